@@ -1,0 +1,196 @@
+/*
+ * libsv -- streaming KV-cache hot path of StreamingVLM (arXiv 2510.09608) for
+ * AMD MI355X (gfx950).  C ABI: plain pointers and sizes only.
+ *
+ * One cache object holds, for each of n_streams independent streams and each
+ * layer, the K and V rows of the tokens that the streaming policy still
+ * retains, in arrival order, in device memory that the CALLER allocates and
+ * owns (one arena, see sv_cache_bytes).  The library owns only the opaque
+ * handle and a little host bookkeeping, and never allocates device memory.
+ *
+ * Conventions
+ *   - "dev" pointers are device (HBM) addresses, "host" pointers are ordinary
+ *     host memory.  Borrowed for the duration of the call, never retained.
+ *   - Every device-touching call is asynchronous on the HIP stream passed as
+ *     `hip_stream` (a hipStream_t, NULL = default stream); all calls on one
+ *     handle must use streams that are ordered with respect to each other.
+ *   - All functions return SV_OK (0) or a negative sv_status; nothing throws
+ *     or aborts across the boundary.  Host-side outputs (slot numbers, counts)
+ *     are valid on return; device outputs after the stream reaches them.
+ *   - A handle is not thread-safe; separate handles are independent.
+ *   - Token rows: Q is [n][n_q_heads][head_dim], K and V are
+ *     [n][n_kv_heads][head_dim], contiguous, in the cache dtype.
+ *   - Query head h reads kv head h / (n_q_heads / n_kv_heads); scores are
+ *     scaled by 1/sqrt(head_dim); softmax is accumulated in fp32.
+ */
+#ifndef SV_H_
+#define SV_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SV_API __attribute__((visibility("default")))
+
+typedef enum sv_status {
+  SV_OK = 0,
+  SV_ERR_INVALID = -1,     /* bad argument: NULL, out of range, inconsistent shapes   */
+  SV_ERR_CAPACITY = -2,    /* append beyond capacity_tokens, or arena too small       */
+  SV_ERR_STATE = -3,       /* call order violated (layers not all appended, ...)      */
+  SV_ERR_HIP = -4,         /* a HIP runtime call or kernel launch failed              */
+  SV_ERR_UNSUPPORTED = -5  /* legal request this build has no kernel for              */
+} sv_status;
+
+enum { SV_DTYPE_F32 = 0, SV_DTYPE_BF16 = 1 };
+enum { SV_ROPE_1D = 0, SV_ROPE_3D = 1, SV_ROPE_NONE = 2 };
+enum { SV_TEXT = 0, SV_VISION = 1 };
+
+/* Budgets equal to SV_WINDOW_INF keep every token of that class (the paper's
+ * "infinity" rows in the sink/window ablation, Table 5). */
+#define SV_WINDOW_INF (-1)
+
+typedef struct sv_config {
+  int32_t n_layers;          /* >= 1                                                   */
+  int32_t n_q_heads;         /* multiple of n_kv_heads                                 */
+  int32_t n_kv_heads;
+  int32_t head_dim;          /* 64 or 128                                              */
+  int32_t dtype;             /* SV_DTYPE_*: storage type of Q, K, V and O              */
+  int32_t rope_mode;         /* SV_ROPE_*                                              */
+  double rope_theta;         /* rotary base; frequency i is theta^(-2i/head_dim)       */
+  int32_t mrope_sections[3]; /* SV_ROPE_3D: frequencies read t, then h, then w; sum = head_dim/2 */
+  int32_t n_streams;         /* independent streams held by this cache, >= 1           */
+  int64_t capacity_tokens;   /* slots per stream                                       */
+  int32_t max_q_tokens;      /* largest n_q given to sv_attn_chunk (sizes its scratch) */
+} sv_config;
+
+typedef struct sv_cache sv_cache;
+
+/* Text for a status code; never NULL. */
+SV_API const char* sv_strerror(int status);
+
+/* Bytes of device memory sv_cache_create needs for this configuration (both
+ * halves of the ping-pong K/V store, per-token metadata, split-KV scratch).
+ * Returns 0 if the configuration is invalid. */
+SV_API size_t sv_cache_bytes(const sv_config* cfg);
+
+/* Create a cache inside caller-owned device memory `dev_arena` (256-byte
+ * aligned, at least sv_cache_bytes(cfg) bytes, must outlive the handle).  The
+ * arena's contents need no initialisation.  Synchronous and cheap: touches the
+ * device only to zero a few counters on `hip_stream`.
+ * Errors: SV_ERR_INVALID (NULLs, n_q_heads % n_kv_heads, head_dim not 64/128,
+ * sections not summing to head_dim/2, sizes < 1), SV_ERR_CAPACITY (arena too
+ * small). */
+SV_API int sv_cache_create(const sv_config* cfg, void* dev_arena, size_t arena_bytes,
+                    void* hip_stream, sv_cache** out);
+
+/* Free the handle (host memory only; the arena stays with the caller). */
+SV_API int sv_cache_destroy(sv_cache* c);
+
+/*
+ * sv_cache_append -- new tokens join the cache in arrival order and their K/V
+ * states are stored for reuse (Sec. 2.1, "Streaming-aware KV Cache").
+ *
+ * Appends n tokens to `stream_id` for one `layer`.  The call with layer == 0
+ * registers the tokens: it assigns slots [slot0, slot0+n), arrival ids, ranks
+ * within their type and contiguous rotary positions that continue from the
+ * last retained token (Sec. 2.1, "Contiguous RoPE").  Calls for layers
+ * 1..n_layers-1 must follow, in any order, with the same n, before attention
+ * on that layer, before the next layer-0 append and before sv_cache_evict
+ * (else SV_ERR_STATE).
+ *
+ *   types_host    [n] SV_TEXT / SV_VISION; read only when layer == 0.
+ *   grid_thw_host NULL, or the (T, H, W) grid of one vision block: then every
+ *                 type must be SV_VISION and n == T*H*W, tokens in row-major
+ *                 (t, h, w) order.  SV_ROPE_3D requires a grid for vision
+ *                 tokens and builds their (t, h, w) indices from it; afterwards
+ *                 the scalar position advances by max(T, H, W).  Each of T, H,
+ *                 W must be <= 32767.
+ *   k_dev, v_dev  [n][n_kv_heads][head_dim], K NOT yet rotated: the library
+ *                 rotates K at the assigned positions while storing it.
+ *   slot0_out     host, optional: first slot assigned.
+ * Errors: SV_ERR_CAPACITY when len + n > capacity_tokens (nothing is changed).
+ */
+SV_API int sv_cache_append(sv_cache* c, int stream_id, int layer, int n,
+                    const uint8_t* types_host, const int32_t* grid_thw_host,
+                    const void* k_dev, const void* v_dev, int64_t* slot0_out,
+                    void* hip_stream);
+
+/*
+ * sv_cache_evict -- cut one stream's cache to the three budgets of Sec. 2.1 /
+ * Fig. 3 and make it compact again.  A text token stays if it is among the
+ * first n_sink text tokens ever appended to the stream or among the last
+ * text_window text tokens; a vision token stays if it is among the last
+ * vision_window vision tokens.  Counts are over tokens present at the call.
+ * Survivors keep their order; their K/V rows of all layers are moved to the
+ * front (stream compaction), they get new contiguous positions (1-D: the slot
+ * index; 3-D: re-walk of the retained list with the block rule, see
+ * sv_cache_append), and cached K is re-rotated by the position shift, which
+ * is one scalar per token.  Budgets are in tokens; SV_WINDOW_INF for a window
+ * keeps the whole class; 0 is legal.  A call that evicts nothing does no
+ * device work.  n_retained_out (host, optional) is valid on return.
+ * Errors: SV_ERR_STATE if some layer has not received the last append.
+ */
+SV_API int sv_cache_evict(sv_cache* c, int stream_id, int64_t n_sink, int64_t vision_window,
+                   int64_t text_window, int64_t* n_retained_out, void* hip_stream);
+
+/*
+ * sv_rope_apply -- rotate fresh Q (and, for callers that keep their own K
+ * copies, K) in place at the contiguous positions of cache slots
+ * [slot0, slot0+n) of `stream_id` (Sec. 2.1, "Contiguous RoPE": 1-D index, or
+ * the 3-D (t, h, w) index where frequency i reads t, h or w by section).
+ * Pairing is (i, i + head_dim/2).  q_dev_inout is [n][n_q_heads][head_dim] or
+ * NULL; k_dev_inout is [n][n_kv_heads][head_dim] or NULL.  The slots must
+ * exist.  With SV_ROPE_NONE this is a no-op.
+ */
+SV_API int sv_rope_apply(sv_cache* c, int stream_id, int64_t slot0, int n,
+                  void* q_dev_inout, void* k_dev_inout, void* hip_stream);
+
+/*
+ * sv_attn_chunk -- chunked prefill: the n_q newest tokens of the stream (the
+ * last n_q slots, K/V already appended for `layer`) attend to the retained
+ * cache and, causally, to their own chunk (Sec. 2.1: new frames reuse the
+ * retained states instead of recomputing them).  q_dev is rotated Q
+ * [n_q][n_q_heads][head_dim]; o_dev receives [n_q][n_q_heads][head_dim].
+ * causal != 0: query i sees slots <= its own; causal == 0: all slots.
+ * n_q <= max_q_tokens.
+ */
+SV_API int sv_attn_chunk(sv_cache* c, int stream_id, int layer, const void* q_dev, int n_q,
+                  void* o_dev, int causal, void* hip_stream);
+
+/*
+ * sv_attn_decode -- one rotated query token per listed stream attends to that
+ * stream's whole cache for `layer`, the newest token (itself) included
+ * (text decoding against the compact cache, Sec. 2.1 / Sec. 3.3).  Streams may
+ * have different lengths (split-KV, variable length).  q_dev and o_dev are
+ * [n_list][n_q_heads][head_dim], row b belongs to stream_ids_host[b].
+ */
+SV_API int sv_attn_decode(sv_cache* c, int layer, const int32_t* stream_ids_host, int n_list,
+                   const void* q_dev, void* o_dev, void* hip_stream);
+
+/* Number of tokens currently in the stream's cache. */
+SV_API int sv_cache_len(sv_cache* c, int stream_id, int64_t* n_out);
+
+/*
+ * Inspection for parity checks; SYNCHRONOUS (waits for hip_stream).  Copies
+ * up to `cap` entries, in slot order: arrival ids (ids_host, [cap]) and
+ * positions (pos3_host, [cap][3] as t, h, w; 1-D mode repeats the index).
+ * Either pointer may be NULL.  n_out receives the cache length.
+ */
+SV_API int sv_cache_retained(sv_cache* c, int stream_id, int64_t* ids_host, int32_t* pos3_host,
+                      int64_t cap, int64_t* n_out, void* hip_stream);
+
+/*
+ * Inspection for parity checks; SYNCHRONOUS.  Copies the stored K (rotated) or
+ * V rows of slots [slot0, slot0+n) of one layer to dst_host as
+ * [n][n_kv_heads][head_dim] in the cache dtype.  which: 0 = K, 1 = V.
+ */
+SV_API int sv_cache_read_kv(sv_cache* c, int stream_id, int layer, int which, int64_t slot0,
+                     int64_t n, void* dst_host, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SV_H_ */

@@ -1,0 +1,394 @@
+// Host side of libsv: argument checking, bookkeeping and kernel sequencing.
+// All device work is done by the kernels in the sibling translation units; this
+// file holds no arithmetic of the method beyond counting which tokens survive.
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <limits>
+#include <new>
+
+#include "sv_internal.h"
+
+namespace {
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+bool config_ok(const sv_config* c) {
+  if (!c) return false;
+  if (c->n_layers < 1 || c->n_kv_heads < 1 || c->n_q_heads < 1 || c->n_streams < 1) return false;
+  if (c->n_q_heads % c->n_kv_heads != 0) return false;
+  if (c->head_dim != 64 && c->head_dim != 128) return false;
+  if (c->dtype != SV_DTYPE_F32 && c->dtype != SV_DTYPE_BF16) return false;
+  if (c->rope_mode != SV_ROPE_1D && c->rope_mode != SV_ROPE_3D && c->rope_mode != SV_ROPE_NONE) return false;
+  if (c->capacity_tokens < 1 || c->capacity_tokens > (int64_t)1 << 30) return false;
+  if (c->max_q_tokens < 1) return false;
+  if (c->rope_mode != SV_ROPE_NONE && !(c->rope_theta > 0.0)) return false;
+  if (c->rope_mode == SV_ROPE_3D) {
+    int64_t s = 0;
+    for (int i = 0; i < 3; ++i) {
+      if (c->mrope_sections[i] < 0) return false;
+      s += c->mrope_sections[i];
+    }
+    if (s != c->head_dim / 2) return false;
+  }
+  return true;
+}
+
+// Byte offsets of every region of the arena, in one place so that
+// sv_cache_bytes and sv_cache_create cannot disagree.
+struct Layout {
+  size_t kv, meta_gid[2], meta_rank[2], meta_pos[2], meta_local[2], meta_blk[2], meta_type[2];
+  size_t src, delta, dtab, next_pos, n_dev, inv_freq, part_o, part_ml, total;
+  int64_t part_rows;
+};
+
+Layout make_layout(const sv_config& c) {
+  Layout L{};
+  const size_t es = c.dtype == SV_DTYPE_F32 ? 4 : 2;
+  const size_t cap = (size_t)c.capacity_tokens, S = (size_t)c.n_streams;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t o = off;
+    off = align_up(off + bytes);
+    return o;
+  };
+  L.kv = take(S * 2 * (size_t)c.n_layers * 2 * (size_t)c.n_kv_heads * cap * (size_t)c.head_dim * es);
+  for (int h = 0; h < 2; ++h) {
+    L.meta_gid[h] = take(S * cap * 8);
+    L.meta_rank[h] = take(S * cap * 8);
+    L.meta_pos[h] = take(S * cap * 16);
+    L.meta_local[h] = take(S * cap * 8);
+    L.meta_blk[h] = take(S * cap * 4);
+    L.meta_type[h] = take(S * cap);
+  }
+  L.src = take(S * cap * 4);
+  L.delta = take(S * cap * 4);
+  L.dtab = take(S * cap * (size_t)(c.head_dim / 2) * 8);
+  L.next_pos = take(S * 2 * 4);
+  L.n_dev = take(S * 4);
+  L.inv_freq = take((size_t)(c.head_dim / 2) * 8);
+  L.part_rows = std::max<int64_t>(64 * (int64_t)c.n_streams, std::max<int64_t>(4096, 4 * (int64_t)c.max_q_tokens));
+  L.part_o = take((size_t)L.part_rows * c.n_q_heads * c.head_dim * 4);
+  L.part_ml = take((size_t)L.part_rows * c.n_q_heads * 2 * 4);
+  L.total = off;
+  return L;
+}
+
+bool stream_ok(const sv_cache* c, int s) { return c && s >= 0 && s < c->cfg.n_streams; }
+
+int64_t iv_count(const std::vector<std::pair<int64_t, int64_t>>& iv) {
+  int64_t n = 0;
+  for (auto& p : iv) n += p.second - p.first;
+  return n;
+}
+
+// Text ranks present after keeping [0, n_sink) and [text_lo, n_text).
+std::vector<std::pair<int64_t, int64_t>> iv_after_evict(
+    const std::vector<std::pair<int64_t, int64_t>>& iv, int64_t n_sink, int64_t text_lo) {
+  if (text_lo <= n_sink) return iv;  // sink and window meet: every text token stays
+  std::vector<std::pair<int64_t, int64_t>> out;
+  auto push = [&](int64_t a, int64_t b) {
+    if (a >= b) return;
+    if (!out.empty() && out.back().second == a) out.back().second = b;
+    else out.emplace_back(a, b);
+  };
+  for (auto& p : iv) {
+    push(p.first, std::min(p.second, n_sink));
+    push(std::max(p.first, text_lo), p.second);
+  }
+  return out;
+}
+
+#define SV_HIP(expr)                         \
+  do {                                       \
+    hipError_t e__ = (expr);                 \
+    if (e__ != hipSuccess) return SV_ERR_HIP; \
+  } while (0)
+
+}  // namespace
+
+extern "C" {
+
+const char* sv_strerror(int status) {
+  switch (status) {
+    case SV_OK: return "ok";
+    case SV_ERR_INVALID: return "invalid argument";
+    case SV_ERR_CAPACITY: return "capacity exceeded";
+    case SV_ERR_STATE: return "call order violated";
+    case SV_ERR_HIP: return "HIP runtime error";
+    case SV_ERR_UNSUPPORTED: return "unsupported configuration";
+    default: return "unknown status";
+  }
+}
+
+size_t sv_cache_bytes(const sv_config* cfg) {
+  if (!config_ok(cfg)) return 0;
+  return make_layout(*cfg).total;
+}
+
+int sv_cache_create(const sv_config* cfg, void* dev_arena, size_t arena_bytes, void* hip_stream,
+                    sv_cache** out) {
+  if (!out) return SV_ERR_INVALID;
+  *out = nullptr;
+  if (!config_ok(cfg) || !dev_arena) return SV_ERR_INVALID;
+  if (((uintptr_t)dev_arena) % kAlign != 0) return SV_ERR_INVALID;
+  Layout L = make_layout(*cfg);
+  if (arena_bytes < L.total) return SV_ERR_CAPACITY;
+  sv_cache* c = new (std::nothrow) sv_cache();
+  if (!c) return SV_ERR_INVALID;
+  c->cfg = *cfg;
+  c->esize = cfg->dtype == SV_DTYPE_F32 ? 4 : 2;
+  c->group = cfg->n_q_heads / cfg->n_kv_heads;
+  c->row_bytes = (size_t)cfg->head_dim * c->esize;
+  c->head_stride = (size_t)cfg->capacity_tokens * c->row_bytes;
+  c->tensor_stride = (size_t)cfg->n_kv_heads * c->head_stride;
+  c->layer_stride = 2 * c->tensor_stride;
+  c->half_stride = (size_t)cfg->n_layers * c->layer_stride;
+  c->stream_kv_stride = 2 * c->half_stride;
+  char* base = (char*)dev_arena;
+  c->kv_base = base + L.kv;
+  for (int h = 0; h < 2; ++h) {
+    c->meta[h].gid = (int64_t*)(base + L.meta_gid[h]);
+    c->meta[h].rank = (int64_t*)(base + L.meta_rank[h]);
+    c->meta[h].pos4 = (int4*)(base + L.meta_pos[h]);
+    c->meta[h].local4 = (short4*)(base + L.meta_local[h]);
+    c->meta[h].blk = (int32_t*)(base + L.meta_blk[h]);
+    c->meta[h].type = (uint8_t*)(base + L.meta_type[h]);
+  }
+  c->src = (int32_t*)(base + L.src);
+  c->delta = (int32_t*)(base + L.delta);
+  c->dtab = (float2*)(base + L.dtab);
+  c->next_pos = (int32_t*)(base + L.next_pos);
+  c->n_dev = (int32_t*)(base + L.n_dev);
+  c->inv_freq = (double*)(base + L.inv_freq);
+  c->part_o = (float*)(base + L.part_o);
+  c->part_ml = (float*)(base + L.part_ml);
+  c->part_rows = L.part_rows;
+  c->st.resize(cfg->n_streams);
+  for (auto& s : c->st) s.layer_len.assign(cfg->n_layers, 0);
+
+  // rotary frequencies theta^(-2i/d), computed once in double
+  const int half = cfg->head_dim / 2;
+  std::vector<double> f(half, 0.0);
+  if (cfg->rope_mode != SV_ROPE_NONE)
+    for (int i = 0; i < half; ++i) f[i] = std::pow(cfg->rope_theta, -2.0 * (double)i / (double)cfg->head_dim);
+  hipStream_t s = (hipStream_t)hip_stream;
+  hipError_t e = hipMemcpyAsync(c->inv_freq, f.data(), half * sizeof(double), hipMemcpyHostToDevice, s);
+  if (e == hipSuccess) e = hipMemsetAsync(c->next_pos, 0, (size_t)cfg->n_streams * 2 * 4, s);
+  if (e == hipSuccess) e = hipMemsetAsync(c->n_dev, 0, (size_t)cfg->n_streams * 4, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);  // f is a local: the copy must have read it
+  if (e != hipSuccess) {
+    delete c;
+    return SV_ERR_HIP;
+  }
+  *out = c;
+  return SV_OK;
+}
+
+int sv_cache_destroy(sv_cache* c) {
+  if (!c) return SV_ERR_INVALID;
+  delete c;
+  return SV_OK;
+}
+
+int sv_cache_len(sv_cache* c, int stream_id, int64_t* n_out) {
+  if (!stream_ok(c, stream_id) || !n_out) return SV_ERR_INVALID;
+  *n_out = c->st[stream_id].len;
+  return SV_OK;
+}
+
+int sv_cache_append(sv_cache* c, int stream_id, int layer, int n, const uint8_t* types_host,
+                    const int32_t* grid_thw_host, const void* k_dev, const void* v_dev,
+                    int64_t* slot0_out, void* hip_stream) {
+  if (!stream_ok(c, stream_id) || layer < 0 || layer >= c->cfg.n_layers || n < 0) return SV_ERR_INVALID;
+  sv::StreamState& st = c->st[stream_id];
+  hipStream_t s = (hipStream_t)hip_stream;
+  if (n == 0) {
+    if (slot0_out) *slot0_out = st.len;
+    return SV_OK;
+  }
+  if (!k_dev || !v_dev) return SV_ERR_INVALID;
+
+  if (layer == 0) {
+    if (!types_host) return SV_ERR_INVALID;
+    for (int l = 0; l < c->cfg.n_layers; ++l)
+      if (st.layer_len[l] != st.len) return SV_ERR_STATE;  // previous append not finished on every layer
+    int n_vis = 0;
+    for (int j = 0; j < n; ++j) {
+      if (types_host[j] != SV_TEXT && types_host[j] != SV_VISION) return SV_ERR_INVALID;
+      n_vis += types_host[j] == SV_VISION;
+    }
+    int gT = 0, gH = 0, gW = 0;
+    if (grid_thw_host) {
+      gT = grid_thw_host[0], gH = grid_thw_host[1], gW = grid_thw_host[2];
+      if (gT < 1 || gH < 1 || gW < 1 || gT > 32767 || gH > 32767 || gW > 32767) return SV_ERR_INVALID;
+      if ((int64_t)gT * gH * gW != n || n_vis != n) return SV_ERR_INVALID;
+    } else if (c->cfg.rope_mode == SV_ROPE_3D && n_vis != 0) {
+      return SV_ERR_INVALID;  // 3-D positions of vision tokens need their grid
+    }
+    const int type_uniform = n_vis == 0 ? SV_TEXT : (n_vis == n ? SV_VISION : -1);
+    if (type_uniform < 0 && n > sv::kMaxMixedAppend) return SV_ERR_UNSUPPORTED;
+    if (st.len + n > c->cfg.capacity_tokens) return SV_ERR_CAPACITY;
+
+    sv::TypeMask mask;
+    if (type_uniform < 0) {
+      std::memset(&mask, 0, sizeof(mask));
+      for (int j = 0; j < n; ++j)
+        if (types_host[j] == SV_VISION) mask.w[j >> 5] |= 1u << (j & 31);
+    }
+    const bool has_blk = grid_thw_host && c->cfg.rope_mode == SV_ROPE_3D;
+    SV_HIP(sv::launch_meta_append(c, stream_id, st.next_parity, st.len, n, st.next_gid, st.n_text,
+                                  st.n_vis, type_uniform, type_uniform < 0 ? &mask : nullptr,
+                                  has_blk ? st.next_blk : -1, gT, gH, gW, s));
+    SV_HIP(sv::launch_append_kv(c, stream_id, 0, st.len, n, k_dev, v_dev, s));
+
+    st.pending_slot0 = st.len;
+    st.pending_n = n;
+    st.next_parity ^= 1;
+    if (has_blk) st.next_blk++;
+    st.next_gid += n;
+    const int n_text_new = n - n_vis;
+    if (n_text_new > 0) {
+      if (!st.text_iv.empty() && st.text_iv.back().second == st.n_text)
+        st.text_iv.back().second += n_text_new;
+      else
+        st.text_iv.emplace_back(st.n_text, st.n_text + n_text_new);
+      st.n_text += n_text_new;
+    }
+    st.n_vis += n_vis;
+    st.len += n;
+    st.layer_len[0] = st.len;
+    if (slot0_out) *slot0_out = st.pending_slot0;
+    return SV_OK;
+  }
+
+  // layers 1..L-1 repeat the append registered by layer 0
+  if (st.layer_len[layer] != st.pending_slot0 || n != st.pending_n ||
+      st.pending_slot0 + n != st.len || st.layer_len[0] != st.len)
+    return SV_ERR_STATE;
+  SV_HIP(sv::launch_append_kv(c, stream_id, layer, st.pending_slot0, n, k_dev, v_dev, s));
+  st.layer_len[layer] = st.len;
+  if (slot0_out) *slot0_out = st.pending_slot0;
+  return SV_OK;
+}
+
+int sv_cache_evict(sv_cache* c, int stream_id, int64_t n_sink, int64_t vision_window,
+                   int64_t text_window, int64_t* n_retained_out, void* hip_stream) {
+  if (!stream_ok(c, stream_id)) return SV_ERR_INVALID;
+  if (n_sink < 0 || vision_window < SV_WINDOW_INF || text_window < SV_WINDOW_INF) return SV_ERR_INVALID;
+  sv::StreamState& st = c->st[stream_id];
+  for (int l = 0; l < c->cfg.n_layers; ++l)
+    if (st.layer_len[l] != st.len) return SV_ERR_STATE;
+  hipStream_t s = (hipStream_t)hip_stream;
+
+  const int64_t kMin = std::numeric_limits<int64_t>::min();
+  const int64_t text_lo = text_window == SV_WINDOW_INF ? kMin : st.n_text - std::min(text_window, st.n_text);
+  const int64_t vis_lo = vision_window == SV_WINDOW_INF ? kMin : st.n_vis - std::min(vision_window, st.n_vis);
+
+  auto iv_new = iv_after_evict(st.text_iv, n_sink, text_lo);
+  const int64_t vis_lo_new = std::max(st.vis_lo, vis_lo);
+  const int64_t n_new = iv_count(iv_new) + (st.n_vis - vis_lo_new);
+  if (n_retained_out) *n_retained_out = n_new;
+  if (n_new == st.len) return SV_OK;  // nothing to evict: no device work
+
+  SV_HIP(sv::launch_evict_scan(c, stream_id, st.next_parity, st.len, n_sink, text_lo, vis_lo, s));
+  if (n_new > 0) SV_HIP(sv::launch_compact(c, stream_id, n_new, s));
+  st.cur ^= 1;
+  st.next_parity ^= 1;
+  st.text_iv.swap(iv_new);
+  st.vis_lo = vis_lo_new;
+  st.len = n_new;
+  for (int l = 0; l < c->cfg.n_layers; ++l) st.layer_len[l] = n_new;
+  st.pending_slot0 = n_new;
+  st.pending_n = 0;
+  return SV_OK;
+}
+
+int sv_rope_apply(sv_cache* c, int stream_id, int64_t slot0, int n, void* q_dev_inout,
+                  void* k_dev_inout, void* hip_stream) {
+  if (!stream_ok(c, stream_id) || n < 0 || slot0 < 0) return SV_ERR_INVALID;
+  if (slot0 + n > c->st[stream_id].len) return SV_ERR_INVALID;
+  if (n == 0 || c->cfg.rope_mode == SV_ROPE_NONE || (!q_dev_inout && !k_dev_inout)) return SV_OK;
+  SV_HIP(sv::launch_rope_apply(c, stream_id, slot0, n, q_dev_inout, k_dev_inout, (hipStream_t)hip_stream));
+  return SV_OK;
+}
+
+int sv_attn_chunk(sv_cache* c, int stream_id, int layer, const void* q_dev, int n_q, void* o_dev,
+                  int causal, void* hip_stream) {
+  if (!stream_ok(c, stream_id) || layer < 0 || layer >= c->cfg.n_layers || !q_dev || !o_dev) return SV_ERR_INVALID;
+  sv::StreamState& st = c->st[stream_id];
+  if (n_q < 1 || n_q > st.len || n_q > c->cfg.max_q_tokens) return SV_ERR_INVALID;
+  if (st.layer_len[layer] != st.len) return SV_ERR_STATE;
+  hipStream_t s = (hipStream_t)hip_stream;
+  if (sv::attn_mfma_supported(c)) {
+    SV_HIP(sv::launch_attn_chunk_mfma(c, stream_id, layer, q_dev, n_q, o_dev, causal, s));
+    return SV_OK;
+  }
+  if (!sv::attn_rows_supported(c)) return SV_ERR_UNSUPPORTED;
+  SV_HIP(sv::launch_attn_rows_chunk(c, stream_id, layer, q_dev, n_q, o_dev, causal, s));
+  return SV_OK;
+}
+
+int sv_attn_decode(sv_cache* c, int layer, const int32_t* stream_ids_host, int n_list,
+                   const void* q_dev, void* o_dev, void* hip_stream) {
+  if (!c || layer < 0 || layer >= c->cfg.n_layers || !stream_ids_host || n_list < 1 || !q_dev || !o_dev)
+    return SV_ERR_INVALID;
+  if ((int64_t)n_list > c->part_rows) return SV_ERR_INVALID;
+  for (int b = 0; b < n_list; ++b) {
+    if (!stream_ok(c, stream_ids_host[b])) return SV_ERR_INVALID;
+    const sv::StreamState& st = c->st[stream_ids_host[b]];
+    if (st.len < 1) return SV_ERR_INVALID;
+    if (st.layer_len[layer] != st.len) return SV_ERR_STATE;
+  }
+  if (!sv::attn_rows_supported(c)) return SV_ERR_UNSUPPORTED;
+  SV_HIP(sv::launch_attn_rows_batch(c, layer, stream_ids_host, n_list, q_dev, o_dev, (hipStream_t)hip_stream));
+  return SV_OK;
+}
+
+int sv_cache_retained(sv_cache* c, int stream_id, int64_t* ids_host, int32_t* pos3_host, int64_t cap,
+                      int64_t* n_out, void* hip_stream) {
+  if (!stream_ok(c, stream_id) || cap < 0) return SV_ERR_INVALID;
+  sv::StreamState& st = c->st[stream_id];
+  hipStream_t s = (hipStream_t)hip_stream;
+  if (n_out) *n_out = st.len;
+  const int64_t n = std::min(cap, st.len);
+  const size_t off = (size_t)stream_id * (size_t)c->cfg.capacity_tokens;
+  std::vector<int4> pos;
+  if (n > 0 && ids_host)
+    SV_HIP(hipMemcpyAsync(ids_host, c->meta[st.cur].gid + off, (size_t)n * 8, hipMemcpyDeviceToHost, s));
+  if (n > 0 && pos3_host) {
+    pos.resize(n);
+    SV_HIP(hipMemcpyAsync(pos.data(), c->meta[st.cur].pos4 + off, (size_t)n * 16, hipMemcpyDeviceToHost, s));
+  }
+  SV_HIP(hipStreamSynchronize(s));
+  if (n > 0 && pos3_host)
+    for (int64_t i = 0; i < n; ++i) {
+      pos3_host[3 * i + 0] = pos[i].x;
+      pos3_host[3 * i + 1] = pos[i].y;
+      pos3_host[3 * i + 2] = pos[i].z;
+    }
+  return SV_OK;
+}
+
+int sv_cache_read_kv(sv_cache* c, int stream_id, int layer, int which, int64_t slot0, int64_t n,
+                     void* dst_host, void* hip_stream) {
+  if (!stream_ok(c, stream_id) || layer < 0 || layer >= c->cfg.n_layers || (which != 0 && which != 1))
+    return SV_ERR_INVALID;
+  sv::StreamState& st = c->st[stream_id];
+  if (slot0 < 0 || n < 0 || slot0 + n > st.layer_len[layer] || (n > 0 && !dst_host)) return SV_ERR_INVALID;
+  hipStream_t s = (hipStream_t)hip_stream;
+  if (n > 0) {
+    const char* src = c->kv_ptr(stream_id, st.cur, layer, which) + (size_t)slot0 * c->row_bytes;
+    const size_t dpitch = (size_t)c->cfg.n_kv_heads * c->row_bytes;
+    for (int h = 0; h < c->cfg.n_kv_heads; ++h)
+      SV_HIP(hipMemcpy2DAsync((char*)dst_host + (size_t)h * c->row_bytes, dpitch,
+                              src + (size_t)h * c->head_stride, c->row_bytes, c->row_bytes, (size_t)n,
+                              hipMemcpyDeviceToHost, s));
+  }
+  SV_HIP(hipStreamSynchronize(s));
+  return SV_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,120 @@
+// Internal declarations shared by the host side of libsv and its kernel launchers.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "sv.h"
+
+namespace sv {
+
+// ---- per-token metadata kept in device memory, structure of arrays -----------------
+// pos4  : (t, h, w, base).  base is the scalar position the token's block starts at
+//         (for text and for 1-D mode it equals t); the shift applied by an eviction
+//         is old base - new base and is common to t, h and w.
+// local4: (lt, lh, lw, extent) of a vision token inside its block; text is (0,0,0,1).
+// blk   : vision block id, -1 for text and for vision tokens appended without a grid.
+struct MetaPtrs {
+  int64_t* gid;
+  int64_t* rank;
+  int4* pos4;
+  short4* local4;
+  int32_t* blk;
+  uint8_t* type;
+};
+
+struct StreamState {
+  int64_t len = 0;        // tokens in cache
+  int64_t n_text = 0;     // text tokens ever appended
+  int64_t n_vis = 0;      // vision tokens ever appended
+  int64_t next_gid = 0;
+  int32_t next_blk = 0;
+  int cur = 0;            // which half of the ping-pong store is live
+  int next_parity = 0;    // which entry of next_pos[stream][2] is live
+  int64_t vis_lo = 0;     // vision ranks present are [vis_lo, n_vis)
+  std::vector<std::pair<int64_t, int64_t>> text_iv;  // text ranks present, disjoint half-open intervals
+  std::vector<int64_t> layer_len;                    // tokens stored per layer
+  int64_t pending_slot0 = 0;                         // first slot of the append in flight
+  int pending_n = 0;
+};
+
+}  // namespace sv
+
+struct sv_cache {
+  sv_config cfg;
+  int esize;                 // bytes per element
+  int group;                 // q heads per kv head
+  size_t row_bytes;          // head_dim * esize
+  size_t head_stride;        // capacity * row_bytes           (one kv head of one tensor)
+  size_t tensor_stride;      // n_kv_heads * head_stride       (K or V of one layer)
+  size_t layer_stride;       // 2 * tensor_stride
+  size_t half_stride;        // n_layers * layer_stride        (one ping-pong half)
+  size_t stream_kv_stride;   // 2 * half_stride
+  char* kv_base;             // device
+  sv::MetaPtrs meta[2];      // device, stream 0; per-stream offset = stream * capacity elements
+  int32_t* src;              // device [n_streams][capacity]   gather list of the last eviction
+  int32_t* delta;            // device [n_streams][capacity]   position shift of the last eviction
+  float2* dtab;              // device [n_streams][capacity][head_dim/2]  cos/sin of the shift
+  int32_t* next_pos;         // device [n_streams][2]          scalar position of the next token (ping-pong)
+  int32_t* n_dev;            // device [n_streams]             retained count written by the scan
+  double* inv_freq;          // device [head_dim/2]
+  float* part_o;             // device split-KV partial outputs
+  float* part_ml;            // device split-KV partial (max, sum)
+  int64_t part_rows;         // capacity of the partial buffers in (token, split) pairs
+  std::vector<sv::StreamState> st;
+
+  char* kv_ptr(int stream, int half, int layer, int which) const {
+    return kv_base + (size_t)stream * stream_kv_stride + (size_t)half * half_stride +
+           (size_t)layer * layer_stride + (size_t)which * tensor_stride;
+  }
+};
+
+namespace sv {
+
+// Kernel launchers (one translation unit each).  All are asynchronous on `s`
+// and return the hipError_t of the launch.
+
+// Types of the tokens of one append as a bit mask (bit j set = vision), passed by value.
+constexpr int kMaxMixedAppend = 2048;
+struct TypeMask {
+  uint32_t w[kMaxMixedAppend / 32];
+};
+
+// type_uniform: SV_TEXT / SV_VISION when all n tokens share it, -1 to read `mask`.
+hipError_t launch_meta_append(const sv_cache* c, int stream, int next_parity, int64_t slot0, int n,
+                              int64_t gid0, int64_t rank_text0, int64_t rank_vis0, int type_uniform,
+                              const TypeMask* mask, int blk, int gT, int gH, int gW, hipStream_t s);
+
+hipError_t launch_append_kv(const sv_cache* c, int stream, int layer, int64_t slot0, int n,
+                            const void* k, const void* v, hipStream_t s);
+
+// Keep rule: text rank < n_sink or rank >= text_lo; vision rank >= vis_lo.
+hipError_t launch_evict_scan(const sv_cache* c, int stream, int next_parity, int64_t n_old,
+                             int64_t n_sink, int64_t text_lo, int64_t vis_lo, hipStream_t s);
+
+hipError_t launch_compact(const sv_cache* c, int stream, int64_t n_new, hipStream_t s);
+
+hipError_t launch_rope_apply(const sv_cache* c, int stream, int64_t slot0, int n, void* q, void* k,
+                             hipStream_t s);
+
+struct RowDesc {           // one query token of the row-wise attention kernel
+  const void* k;           // K of the layer, kv head 0, slot 0
+  const void* v;
+  int32_t len;             // keys visible: slots [0, len)
+};
+
+hipError_t launch_attn_rows_chunk(const sv_cache* c, int stream, int layer, const void* q, int n_q,
+                                  void* o, int causal, hipStream_t s);
+hipError_t launch_attn_rows_batch(const sv_cache* c, int layer, const int32_t* streams, int n_list,
+                                  const void* q, void* o, hipStream_t s);
+bool attn_rows_supported(const sv_cache* c);
+
+bool attn_mfma_supported(const sv_cache* c);
+hipError_t launch_attn_chunk_mfma(const sv_cache* c, int stream, int layer, const void* q, int n_q,
+                                  void* o, int causal, hipStream_t s);
+
+hipError_t launch_attn_combine(const sv_cache* c, int n_rows, int n_splits, void* o, hipStream_t s);
+
+}  // namespace sv

@@ -1,0 +1,193 @@
+// Integer side of the path: registering new tokens, and the eviction scan that
+// turns the three budgets of Sec. 2.1 into a gather list plus new contiguous
+// positions (Sec. 2.1, "Contiguous RoPE").  Everything here is exact integer work.
+
+#include "sv_internal.h"
+
+namespace sv {
+namespace {
+
+// ---------------------------------------------------------------------------------
+// New tokens: slot, arrival id, rank within type, block coordinates and position.
+// The scalar position counter lives in device memory as a two-entry ping-pong
+// (read next_in, write next_out) so that no thread can read a value another
+// block has already advanced.
+// ---------------------------------------------------------------------------------
+__global__ void k_meta_append(MetaPtrs m, const int32_t* __restrict__ next_in, int32_t* __restrict__ next_out,
+                              int64_t slot0, int n, int64_t gid0, int64_t rank_text0, int64_t rank_vis0,
+                              int type_uniform, TypeMask mask, int rope3d, int blk, int gT, int gH, int gW) {
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  const int next = *next_in;
+  if (j == 0) {
+    int adv;
+    if (!rope3d) adv = (int)(slot0 + n) - next;  // 1-D: position == slot
+    else if (blk >= 0) adv = max(gT, max(gH, gW));
+    else adv = n;
+    *next_out = next + adv;
+  }
+  if (j >= n) return;
+  int type;
+  int64_t rank;
+  if (type_uniform >= 0) {
+    type = type_uniform;
+    rank = (type == SV_TEXT ? rank_text0 : rank_vis0) + j;
+  } else {
+    type = (mask.w[j >> 5] >> (j & 31)) & 1;
+    int vis_before = 0;
+    for (int w = 0; w < (j >> 5); ++w) vis_before += __popc(mask.w[w]);
+    vis_before += __popc(mask.w[j >> 5] & ((1u << (j & 31)) - 1u));
+    rank = type == SV_VISION ? rank_vis0 + vis_before : rank_text0 + (j - vis_before);
+  }
+  const int64_t slot = slot0 + j;
+  m.gid[slot] = gid0 + j;
+  m.rank[slot] = rank;
+  m.type[slot] = (uint8_t)type;
+  if (rope3d && blk >= 0) {
+    const int lt = j / (gH * gW), lh = (j / gW) % gH, lw = j % gW;
+    m.blk[slot] = blk;
+    m.local4[slot] = make_short4((short)lt, (short)lh, (short)lw, (short)max(gT, max(gH, gW)));
+    m.pos4[slot] = make_int4(next + lt, next + lh, next + lw, next);
+  } else {
+    const int p = rope3d ? next + j : (int)slot;
+    m.blk[slot] = -1;
+    m.local4[slot] = make_short4(0, 0, 0, 1);
+    m.pos4[slot] = make_int4(p, p, p, p);
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// Eviction scan, one workgroup of 16 wavefronts per stream.
+//
+// keep(i)  : text  -> rank < n_sink or rank >= text_lo     (sink + recent text)
+//            vision-> rank >= vis_lo                         (recent vision)
+// dst(i)   : exclusive prefix count of keep  (wavefront ballot + popcount, then a
+//            16-entry scan across wavefronts, then a running carry across tiles)
+// base'(i) : exclusive prefix sum over kept tokens of the position advance, where a
+//            text token advances by 1 and a vision block advances by its extent at
+//            its last retained token.  With every token its own block of extent 1
+//            (1-D mode) base' equals dst.
+// Survivors' metadata is written compacted to `out`; src[dst] = i is the gather
+// list for the K/V move and delta[dst] = base - base' the shift for the re-rotation.
+// ---------------------------------------------------------------------------------
+constexpr int kScanThreads = 1024;
+constexpr int kScanWaves = kScanThreads / 64;
+
+__device__ __forceinline__ bool keep_rule(int type, int64_t rank, int64_t n_sink, int64_t text_lo, int64_t vis_lo) {
+  return type == SV_TEXT ? (rank < n_sink || rank >= text_lo) : (rank >= vis_lo);
+}
+
+__global__ __launch_bounds__(kScanThreads) void k_evict_scan(MetaPtrs in, MetaPtrs out, int32_t* __restrict__ src,
+                                                             int32_t* __restrict__ delta,
+                                                             int32_t* __restrict__ next_out,
+                                                             int32_t* __restrict__ n_out, int n_old, int64_t n_sink,
+                                                             int64_t text_lo, int64_t vis_lo) {
+  __shared__ int sh_cnt[kScanWaves];
+  __shared__ int sh_adv[kScanWaves];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int carry_cnt = 0, carry_adv = 0;
+  for (int base = 0; base < n_old; base += kScanThreads) {
+    const int i = base + tid;
+    const bool valid = i < n_old;
+    int type = 0, blk = -1, old_base = 0;
+    int64_t rank = 0, gid = 0;
+    short4 loc = make_short4(0, 0, 0, 1);
+    bool keep = false;
+    int adv = 0;
+    if (valid) {
+      type = in.type[i];
+      rank = in.rank[i];
+      keep = keep_rule(type, rank, n_sink, text_lo, vis_lo);
+      if (keep) {
+        gid = in.gid[i];
+        blk = in.blk[i];
+        loc = in.local4[i];
+        old_base = in.pos4[i].w;
+        if (type == SV_TEXT) {
+          adv = 1;
+        } else {
+          bool last = true;  // last retained token of its vision block?
+          if (blk >= 0 && i + 1 < n_old && in.blk[i + 1] == blk)
+            last = !keep_rule(in.type[i + 1], in.rank[i + 1], n_sink, text_lo, vis_lo);
+          adv = last ? (int)loc.w : 0;
+        }
+      }
+    }
+    // wavefront level: ballot/popcount for the count, shuffle scan for the advance
+    const unsigned long long bal = __ballot(keep);
+    const int lane_cnt = __popcll(bal & ((1ull << lane) - 1ull));
+    int incl = adv;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int y = __shfl_up(incl, off);
+      if (lane >= off) incl += y;
+    }
+    if (lane == 63) {
+      sh_cnt[wave] = __popcll(bal);
+      sh_adv[wave] = incl;
+    }
+    __syncthreads();
+    int wave_cnt = 0, wave_adv = 0, tot_cnt = 0, tot_adv = 0;
+#pragma unroll
+    for (int w = 0; w < kScanWaves; ++w) {
+      const int cw = sh_cnt[w], aw = sh_adv[w];
+      if (w < wave) {
+        wave_cnt += cw;
+        wave_adv += aw;
+      }
+      tot_cnt += cw;
+      tot_adv += aw;
+    }
+    if (keep) {
+      const int d = carry_cnt + wave_cnt + lane_cnt;
+      const int nb = carry_adv + wave_adv + (incl - adv);
+      out.gid[d] = gid;
+      out.rank[d] = rank;
+      out.type[d] = (uint8_t)type;
+      out.blk[d] = blk;
+      out.local4[d] = loc;
+      out.pos4[d] = make_int4(nb + loc.x, nb + loc.y, nb + loc.z, nb);
+      src[d] = i;
+      delta[d] = old_base - nb;
+    }
+    carry_cnt += tot_cnt;
+    carry_adv += tot_adv;
+    __syncthreads();
+  }
+  if (tid == 0) {
+    *next_out = carry_adv;
+    *n_out = carry_cnt;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_meta_append(const sv_cache* c, int stream, int next_parity, int64_t slot0, int n,
+                              int64_t gid0, int64_t rank_text0, int64_t rank_vis0, int type_uniform,
+                              const TypeMask* mask, int blk, int gT, int gH, int gW, hipStream_t s) {
+  const size_t off = (size_t)stream * (size_t)c->cfg.capacity_tokens;
+  MetaPtrs m = c->meta[c->st[stream].cur];
+  m.gid += off, m.rank += off, m.pos4 += off, m.local4 += off, m.blk += off, m.type += off;
+  TypeMask mk = {};
+  if (mask) mk = *mask;
+  const int threads = 256, blocks = (n + threads - 1) / threads;
+  const int32_t* nin = c->next_pos + 2 * stream + next_parity;
+  int32_t* nout = c->next_pos + 2 * stream + (next_parity ^ 1);
+  hipLaunchKernelGGL(k_meta_append, dim3(blocks), dim3(threads), 0, s, m, nin, nout, slot0, n, gid0, rank_text0,
+                     rank_vis0, type_uniform, mk, c->cfg.rope_mode == SV_ROPE_3D ? 1 : 0, blk, gT, gH, gW);
+  return hipGetLastError();
+}
+
+hipError_t launch_evict_scan(const sv_cache* c, int stream, int next_parity, int64_t n_old, int64_t n_sink,
+                             int64_t text_lo, int64_t vis_lo, hipStream_t s) {
+  const size_t off = (size_t)stream * (size_t)c->cfg.capacity_tokens;
+  const int cur = c->st[stream].cur;
+  MetaPtrs in = c->meta[cur], out = c->meta[cur ^ 1];
+  in.gid += off, in.rank += off, in.pos4 += off, in.local4 += off, in.blk += off, in.type += off;
+  out.gid += off, out.rank += off, out.pos4 += off, out.local4 += off, out.blk += off, out.type += off;
+  hipLaunchKernelGGL(k_evict_scan, dim3(1), dim3(kScanThreads), 0, s, in, out, c->src + off, c->delta + off,
+                     c->next_pos + 2 * stream + (next_parity ^ 1), c->n_dev + stream, (int)n_old, n_sink, text_lo,
+                     vis_lo);
+  return hipGetLastError();
+}
+
+}  // namespace sv

@@ -1,0 +1,269 @@
+// Bandwidth-bound row movers: storing new K/V (K rotated at its assigned
+// position), rotating fresh Q/K in place, and the compaction gather that moves
+// every surviving K/V row of every layer to its new slot while re-rotating K by
+// the position shift (Sec. 2.1: states are reused, positions stay contiguous).
+//
+// All three share one thread layout.  A row of head_dim elements is split into
+// a low and a high half; the rotary pairing is (i, i + head_dim/2), so a thread
+// that owns 16 bytes of the low half and the matching 16 bytes of the high half
+// holds complete pairs.  Rows are 128-512 bytes, a wavefront therefore covers
+// 4-16 whole rows with two fully coalesced 16-byte accesses per lane.
+
+#include <hip/hip_bf16.h>
+
+#include "sv_internal.h"
+
+namespace sv {
+namespace {
+
+template <typename T>
+struct Vec16;
+template <>
+struct Vec16<float> {
+  static constexpr int N = 4;
+  float4 raw;
+  __device__ float get(int e) const { return ((const float*)&raw)[e]; }
+  __device__ void set(int e, float x) { ((float*)&raw)[e] = x; }
+};
+template <>
+struct Vec16<__hip_bfloat16> {
+  static constexpr int N = 8;
+  uint4 raw;
+  __device__ float get(int e) const {
+    const uint32_t w = ((const uint32_t*)&raw)[e >> 1];
+    return __uint_as_float((e & 1) ? (w & 0xffff0000u) : (w << 16));
+  }
+  __device__ void set(int e, float x) {  // round to nearest even
+    uint32_t u = __float_as_uint(x);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    uint32_t& w = ((uint32_t*)&raw)[e >> 1];
+    w = (e & 1) ? ((w & 0x0000ffffu) | (u & 0xffff0000u)) : ((w & 0xffff0000u) | (u >> 16));
+  }
+};
+
+template <typename T, int D>
+struct RowGeom {
+  static constexpr int EPV = 16 / (int)sizeof(T);  // elements per 16-byte vector
+  static constexpr int TPR = (D / 2) / EPV;        // threads per row
+  static constexpr int ROWS = 256 / TPR;           // rows per 256-thread block
+};
+
+// cos/sin of angle for a rotation by pos * inv_freq; double for fp32 data (the
+// fp32 workload is held to 1e-5), float for bf16 data.
+template <typename T>
+__device__ __forceinline__ void rot_cs(double angle, float& c, float& s) {
+  if constexpr (sizeof(T) == 4) {
+    double sd, cd;
+    sincos(angle, &sd, &cd);
+    c = (float)cd;
+    s = (float)sd;
+  } else {
+    sincosf((float)angle, &s, &c);
+  }
+}
+
+__device__ __forceinline__ int pos_of_freq(const int4& p, int i, int rope_mode, int s0, int s01) {
+  if (rope_mode != SV_ROPE_3D) return p.x;
+  return i < s0 ? p.x : (i < s01 ? p.y : p.z);
+}
+
+template <typename T, int D>
+__device__ __forceinline__ void rotate_pair_vec(Vec16<T>& lo, Vec16<T>& hi, const int4& p, int i0, int rope_mode,
+                                                int s0, int s01, const double* __restrict__ inv_freq) {
+#pragma unroll
+  for (int e = 0; e < Vec16<T>::N; ++e) {
+    const int i = i0 + e;
+    float c, s;
+    rot_cs<T>((double)pos_of_freq(p, i, rope_mode, s0, s01) * inv_freq[i], c, s);
+    const float a = lo.get(e), b = hi.get(e);
+    lo.set(e, a * c - b * s);
+    hi.set(e, b * c + a * s);
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// Store n new tokens of one layer: cache[K|V][h][slot0 + j] = (rotated K | V)[j][h].
+// grid: (ceil(n / ROWS), n_kv_heads, 2)
+// ---------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(256) void k_append_kv(const T* __restrict__ k_in, const T* __restrict__ v_in,
+                                                   T* __restrict__ k_cache, T* __restrict__ v_cache,
+                                                   const int4* __restrict__ pos4, const double* __restrict__ inv_freq,
+                                                   int64_t slot0, int n, int n_kv_heads, size_t head_stride_elems,
+                                                   int rope_mode, int s0, int s01) {
+  using G = RowGeom<T, D>;
+  const int j = blockIdx.x * G::ROWS + threadIdx.x / G::TPR;
+  if (j >= n) return;
+  const int t = threadIdx.x % G::TPR, h = blockIdx.y, which = blockIdx.z;
+  const T* src = (which == 0 ? k_in : v_in) + ((size_t)j * n_kv_heads + h) * D;
+  T* dst = (which == 0 ? k_cache : v_cache) + (size_t)h * head_stride_elems + (size_t)(slot0 + j) * D;
+  Vec16<T> lo, hi;
+  lo.raw = *(const decltype(lo.raw)*)(src + t * G::EPV);
+  hi.raw = *(const decltype(hi.raw)*)(src + D / 2 + t * G::EPV);
+  if (which == 0 && rope_mode != SV_ROPE_NONE)
+    rotate_pair_vec<T, D>(lo, hi, pos4[slot0 + j], t * G::EPV, rope_mode, s0, s01, inv_freq);
+  *(decltype(lo.raw)*)(dst + t * G::EPV) = lo.raw;
+  *(decltype(hi.raw)*)(dst + D / 2 + t * G::EPV) = hi.raw;
+}
+
+// ---------------------------------------------------------------------------------
+// Rotate rows of x [n][n_heads][D] in place at the positions of slots slot0 + j.
+// grid: ceil(n * n_heads / ROWS)
+// ---------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(256) void k_rope_rows(T* __restrict__ x, const int4* __restrict__ pos4,
+                                                   const double* __restrict__ inv_freq, int64_t slot0, int n,
+                                                   int n_heads, int rope_mode, int s0, int s01) {
+  using G = RowGeom<T, D>;
+  const int64_t row = (int64_t)blockIdx.x * G::ROWS + threadIdx.x / G::TPR;
+  if (row >= (int64_t)n * n_heads) return;
+  const int t = threadIdx.x % G::TPR;
+  const int j = (int)(row / n_heads);
+  T* p = x + row * D;
+  Vec16<T> lo, hi;
+  lo.raw = *(const decltype(lo.raw)*)(p + t * G::EPV);
+  hi.raw = *(const decltype(hi.raw)*)(p + D / 2 + t * G::EPV);
+  rotate_pair_vec<T, D>(lo, hi, pos4[slot0 + j], t * G::EPV, rope_mode, s0, s01, inv_freq);
+  *(decltype(lo.raw)*)(p + t * G::EPV) = lo.raw;
+  *(decltype(hi.raw)*)(p + D / 2 + t * G::EPV) = hi.raw;
+}
+
+// ---------------------------------------------------------------------------------
+// cos/sin of the re-rotation of each surviving token: moving from old to new
+// position turns pair i by -(delta * inv_freq[i]); stored as (cos, -sin) so the
+// mover applies the same formula as a forward rotation.  delta is one scalar per
+// token even in 3-D mode because t, h and w shift together.
+// ---------------------------------------------------------------------------------
+__global__ void k_delta_table(const int32_t* __restrict__ delta, const double* __restrict__ inv_freq,
+                              float2* __restrict__ dtab, int n_new, int half) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= n_new * half) return;
+  const int j = idx / half, i = idx % half;
+  const int d = delta[j];
+  float2 cs = make_float2(1.f, 0.f);
+  if (d != 0) {
+    double sd, cd;
+    sincos((double)d * inv_freq[i], &sd, &cd);
+    cs = make_float2((float)cd, (float)-sd);
+  }
+  dtab[idx] = cs;
+}
+
+// ---------------------------------------------------------------------------------
+// Compaction gather over all layers: new[l][K|V][h][j] = old[l][K|V][h][src[j]],
+// K re-rotated when delta[j] != 0.  old and new are the two halves of the
+// ping-pong store, so no row is overwritten before it is read.
+// grid: (ceil(n_new / ROWS), n_kv_heads, 2 * n_layers)
+// ---------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(256) void k_compact(const T* __restrict__ old_base, T* __restrict__ new_base,
+                                                 const int32_t* __restrict__ src, const int32_t* __restrict__ delta,
+                                                 const float2* __restrict__ dtab, int n_new,
+                                                 size_t head_stride_elems, size_t tensor_stride_elems, int rotate) {
+  using G = RowGeom<T, D>;
+  const int j = blockIdx.x * G::ROWS + threadIdx.x / G::TPR;
+  if (j >= n_new) return;
+  const int t = threadIdx.x % G::TPR, h = blockIdx.y;
+  const int which = blockIdx.z & 1;  // z = 2 * layer + which, tensors are laid out in that order
+  const size_t plane = (size_t)blockIdx.z * tensor_stride_elems + (size_t)h * head_stride_elems;
+  const T* s = old_base + plane + (size_t)src[j] * D;
+  T* d = new_base + plane + (size_t)j * D;
+  Vec16<T> lo, hi;
+  lo.raw = *(const decltype(lo.raw)*)(s + t * G::EPV);
+  hi.raw = *(const decltype(hi.raw)*)(s + D / 2 + t * G::EPV);
+  if (which == 0 && rotate && delta[j] != 0) {
+    const float2* cs = dtab + (size_t)j * (D / 2) + t * G::EPV;
+#pragma unroll
+    for (int e = 0; e < Vec16<T>::N; ++e) {
+      const float2 r = cs[e];
+      const float a = lo.get(e), b = hi.get(e);
+      lo.set(e, a * r.x - b * r.y);
+      hi.set(e, b * r.x + a * r.y);
+    }
+  }
+  *(decltype(lo.raw)*)(d + t * G::EPV) = lo.raw;
+  *(decltype(hi.raw)*)(d + D / 2 + t * G::EPV) = hi.raw;
+}
+
+template <typename T, int D>
+hipError_t append_kv_t(const sv_cache* c, int stream, int layer, int64_t slot0, int n, const void* k, const void* v,
+                       hipStream_t s) {
+  using G = RowGeom<T, D>;
+  const int cur = c->st[stream].cur;
+  const size_t off = (size_t)stream * (size_t)c->cfg.capacity_tokens;
+  const int s0 = c->cfg.mrope_sections[0], s01 = s0 + c->cfg.mrope_sections[1];
+  dim3 grid((n + G::ROWS - 1) / G::ROWS, c->cfg.n_kv_heads, 2);
+  hipLaunchKernelGGL((k_append_kv<T, D>), grid, dim3(256), 0, s, (const T*)k, (const T*)v,
+                     (T*)c->kv_ptr(stream, cur, layer, 0), (T*)c->kv_ptr(stream, cur, layer, 1),
+                     c->meta[cur].pos4 + off, c->inv_freq, slot0, n, c->cfg.n_kv_heads,
+                     c->head_stride / sizeof(T), c->cfg.rope_mode, s0, s01);
+  return hipGetLastError();
+}
+
+template <typename T, int D>
+hipError_t rope_apply_t(const sv_cache* c, int stream, int64_t slot0, int n, void* q, void* k, hipStream_t s) {
+  using G = RowGeom<T, D>;
+  const int cur = c->st[stream].cur;
+  const size_t off = (size_t)stream * (size_t)c->cfg.capacity_tokens;
+  const int s0 = c->cfg.mrope_sections[0], s01 = s0 + c->cfg.mrope_sections[1];
+  void* ptrs[2] = {q, k};
+  const int heads[2] = {c->cfg.n_q_heads, c->cfg.n_kv_heads};
+  for (int a = 0; a < 2; ++a) {
+    if (!ptrs[a]) continue;
+    const int64_t rows = (int64_t)n * heads[a];
+    dim3 grid((unsigned)((rows + G::ROWS - 1) / G::ROWS));
+    hipLaunchKernelGGL((k_rope_rows<T, D>), grid, dim3(256), 0, s, (T*)ptrs[a], c->meta[cur].pos4 + off,
+                       c->inv_freq, slot0, n, heads[a], c->cfg.rope_mode, s0, s01);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+template <typename T, int D>
+hipError_t compact_t(const sv_cache* c, int stream, int64_t n_new, hipStream_t s) {
+  using G = RowGeom<T, D>;
+  const int cur = c->st[stream].cur;
+  const size_t off = (size_t)stream * (size_t)c->cfg.capacity_tokens;
+  const int rotate = c->cfg.rope_mode != SV_ROPE_NONE;
+  float2* dtab = c->dtab + off * (D / 2);
+  if (rotate) {
+    const int total = (int)n_new * (D / 2);
+    hipLaunchKernelGGL(k_delta_table, dim3((total + 255) / 256), dim3(256), 0, s, c->delta + off, c->inv_freq, dtab,
+                       (int)n_new, D / 2);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  dim3 grid((unsigned)((n_new + G::ROWS - 1) / G::ROWS), c->cfg.n_kv_heads, 2 * c->cfg.n_layers);
+  hipLaunchKernelGGL((k_compact<T, D>), grid, dim3(256), 0, s, (const T*)c->kv_ptr(stream, cur, 0, 0),
+                     (T*)c->kv_ptr(stream, cur ^ 1, 0, 0), c->src + off, c->delta + off, dtab, (int)n_new,
+                     c->head_stride / sizeof(T), c->tensor_stride / sizeof(T), rotate);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+#define SV_DISPATCH(fn, ...)                                                                   \
+  do {                                                                                         \
+    if (c->cfg.dtype == SV_DTYPE_F32) {                                                        \
+      return c->cfg.head_dim == 64 ? fn<float, 64>(__VA_ARGS__) : fn<float, 128>(__VA_ARGS__); \
+    }                                                                                          \
+    return c->cfg.head_dim == 64 ? fn<__hip_bfloat16, 64>(__VA_ARGS__)                         \
+                                 : fn<__hip_bfloat16, 128>(__VA_ARGS__);                       \
+  } while (0)
+
+hipError_t launch_append_kv(const sv_cache* c, int stream, int layer, int64_t slot0, int n, const void* k,
+                            const void* v, hipStream_t s) {
+  SV_DISPATCH(append_kv_t, c, stream, layer, slot0, n, k, v, s);
+}
+
+hipError_t launch_rope_apply(const sv_cache* c, int stream, int64_t slot0, int n, void* q, void* k,
+                             hipStream_t s) {
+  SV_DISPATCH(rope_apply_t, c, stream, slot0, n, q, k, s);
+}
+
+hipError_t launch_compact(const sv_cache* c, int stream, int64_t n_new, hipStream_t s) {
+  SV_DISPATCH(compact_t, c, stream, n_new, s);
+}
+
+}  // namespace sv

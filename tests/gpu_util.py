@@ -1,0 +1,106 @@
+"""Helpers for the GPU parity tests: build a cache for a workload, feed it the seeded inputs."""
+from __future__ import annotations
+
+from typing import Dict, List, Sequence
+
+import numpy as np
+import torch
+
+import paper_2510_09608_amd as sv
+import sv_inputs as si
+from paper_2510_09608_amd.stream import StreamRunner
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}   # max-abs error bars of the parity contract
+
+
+def tdtype(w: si.Workload):
+    return torch.float32 if w.dtype == "f32" else torch.bfloat16
+
+
+def dev(x: np.ndarray, w: si.Workload) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(x)).to(device="cuda:0", dtype=tdtype(w))
+
+
+def host(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
+
+
+def make_cache(w: si.Workload, n_layers: int = None, capacity: int = None, n_streams: int = 1) -> sv.Cache:
+    return sv.Cache(n_layers or w.n_layers, w.n_q_heads, w.n_kv_heads, w.head_dim,
+                    sv.SV_DTYPE_F32 if w.dtype == "f32" else sv.SV_DTYPE_BF16, w.rope_mode, w.rope_theta,
+                    w.mrope_sections, n_streams, capacity or (w.capacity() + 64), max(w.vision_per_chunk, 16))
+
+
+class GpuStream:
+    """Runs a workload through the library; model layer layers[j] lives in cache layer j."""
+
+    def __init__(self, w: si.Workload, layers: Sequence[int], cache: sv.Cache = None):
+        self.w, self.layers = w, list(layers)
+        self.cache = cache or make_cache(w, n_layers=len(self.layers))
+        self.run = StreamRunner(self.cache, w.n_sink, w.vision_window, w.text_window)
+
+    def preamble(self):
+        w = self.w
+        if w.preamble_text == 0:
+            return
+        gids = np.arange(w.preamble_text)
+        ks, vs = [], []
+        for l in self.layers:
+            _, k, v = w.qkv(l, gids)
+            ks.append(dev(k, w))
+            vs.append(dev(v, w))
+        self.run.preamble(ks, vs)
+
+    def step_chunk(self, c: int) -> Dict[str, object]:
+        w = self.w
+        res: Dict[str, object] = {"n_retained": self.run.evict()}
+        res["gids_after_evict"], res["pos_after_evict"] = self.cache.retained(0)
+        ch = w.chunk(c)
+        nv = ch.vision.n
+        gids = np.arange(ch.vision.gid0, ch.vision.gid0 + nv)
+        qs, ks, vs, os_ = [], [], [], []
+        for l in self.layers:
+            q, k, v = w.qkv(l, gids)
+            qs.append(dev(q, w)), ks.append(dev(k, w)), vs.append(dev(v, w))
+            os_.append(torch.empty_like(qs[-1]))
+        self.run.prefill(qs, ks, vs, os_, ch.vision.grid_thw)
+        res["prefill"] = [host(o) for o in os_]
+        dec: List[List[np.ndarray]] = []
+        for t in range(ch.n_text):
+            gid = np.array([ch.text_gid0 + t])
+            qs, ks, vs, os_ = [], [], [], []
+            for l in self.layers:
+                q, k, v = w.qkv(l, gid)
+                qs.append(dev(q, w)), ks.append(dev(k, w)), vs.append(dev(v, w))
+                os_.append(torch.empty_like(qs[-1]))
+            self.run.decode(qs, ks, vs, os_)
+            dec.append([host(o) for o in os_])
+        res["decode"] = dec
+        res["gids_end"], res["pos_end"] = self.cache.retained(0)
+        return res
+
+
+def assert_int_parity(g: Dict[str, object], o: Dict[str, object], where: str) -> None:
+    assert g["n_retained"] == o["n_retained"], where
+    assert np.array_equal(np.asarray(g["gids_after_evict"]), np.asarray(o["gids_after_evict"], dtype=np.int64)), where
+    assert np.array_equal(np.asarray(g["pos_after_evict"], dtype=np.int64), np.asarray(o["pos_after_evict"])), where
+    assert np.array_equal(np.asarray(g["gids_end"]), np.asarray(o["gids_end"], dtype=np.int64)), where
+    assert np.array_equal(np.asarray(g["pos_end"], dtype=np.int64), np.asarray(o["pos_end"])), where
+
+
+def max_err(a: np.ndarray, b: np.ndarray) -> float:
+    return float(np.max(np.abs(np.asarray(a, dtype=np.float64) - np.asarray(b, dtype=np.float64)))) if a.size else 0.0
+
+
+def assert_attn_parity(g: Dict[str, object], o: Dict[str, object], tol: float, where: str) -> float:
+    worst = 0.0
+    for j, (a, b) in enumerate(zip(g["prefill"], o["prefill"])):
+        e = max_err(a, b)
+        assert e <= tol, f"{where} prefill layer#{j}: max abs err {e:.3e} > {tol}"
+        worst = max(worst, e)
+    for t, (ga, oa) in enumerate(zip(g["decode"], o["decode"])):
+        for j, (a, b) in enumerate(zip(ga, oa)):
+            e = max_err(a, b)
+            assert e <= tol, f"{where} decode step {t} layer#{j}: max abs err {e:.3e} > {tol}"
+            worst = max(worst, e)
+    return worst
