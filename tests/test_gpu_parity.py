@@ -372,7 +372,7 @@ def test_high_frame_rate_chunk_sampled_rows():
                 assert e <= gu.TOL["bf16"], e
         ids, pos = cache.retained(0)
         assert np.array_equal(ids, np.asarray(o.gid)) and np.array_equal(pos.astype(np.int64), o.positions())
-    assert n_ret == 512 + 512 + 16384
+    assert n_ret == 512 + 17 * 16 + 16384      # sink + the text appended so far + the full vision window
 
 
 # ----------------------------------------------------------------------------
@@ -433,7 +433,7 @@ def test_edges_and_errors():
             call()
         assert e.value.status == -3
     c2.append(0, 1, None, None, z(4), z(4))
-    assert c2.evict(0, 1, 1, 1) == 1
+    assert c2.evict(0, 1, 1, 1) == 2                                       # first text token + last text token
     # configuration checks
     for bad in (dict(n_q_heads=3, n_kv_heads=2), dict(head_dim=96), dict(mrope_sections=(1, 2, 3), rope_mode=1)):
         kw = dict(n_layers=1, n_q_heads=2, n_kv_heads=1, head_dim=64, dtype=0, rope_mode=0, rope_theta=1e4,
