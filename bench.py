@@ -31,11 +31,11 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=40, help="untimed chunks; >= 33 reaches steady state")
-    ap.add_argument("--workload", default="qwen7b_256v_28L", choices=["qwen7b_256v_28L", "qwen7b_1024v_28L"])
+    ap.add_argument("--workload", default="qwen7b_256v_28L",
+                    choices=["qwen7b_256v_28L", "qwen7b_1024v_28L", "decode_ragged16", "decode_noevict32k"])
     ap.add_argument("--layers", type=int, default=28)
     ap.add_argument("--pool", type=int, default=6, help="distinct pre-generated chunks cycled through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--roofline-kernel", default="attn_chunk", choices=["attn_chunk", "attn_decode", "compact"])
     return ap.parse_args()
 
 
@@ -60,6 +60,9 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
 
+    if args.workload.startswith("decode_"):
+        print(json.dumps(decode_batch_bench(args)))
+        return
     w = si.workload_qwen_stream() if args.workload == "qwen7b_256v_28L" else si.workload_high_fps(n_layers=28)
     L = args.layers
     Hq, Hkv, d = w.n_q_heads, w.n_kv_heads, w.head_dim
@@ -80,80 +83,31 @@ def main():
     ot = torch.empty(L, 1, Hq, d, device=dev, dtype=torch.bfloat16)
     run.preamble(list(rnd(L, w.preamble_text, Hkv, d)), list(rnd(L, w.preamble_text, Hkv, d)))
 
-    ev = lambda: torch.cuda.Event(enable_timing=True)
-    roof_events = []            # (start, stop) around every launch of the roofline kernel in the timed region
-    roof_units = []             # algorithmic units (flops or bytes) of each of those launches
+    budgets = (w.n_sink, w.vision_window, w.text_window)
 
-    def step(c: int, timed: bool):
+    def step_native(c: int):
         p = pool[c % len(pool)]
-        n_before = cache.len(0)
-        if timed and args.roofline_kernel == "compact":
-            e0, e1 = ev(), ev()
-            e0.record()
-            n_ret = run.evict()
-            e1.record()
-            if n_ret != n_before:
-                roof_events.append((e0, e1))
-                roof_units.append(2.0 * n_ret * 2 * Hkv * d * 2 * L)       # read + write of every retained K and V row
-        else:
-            run.evict()
-        qv, kv, vv = p["qv"], p["kv"], p["vv"]
-        types_v = np.ones(nv, dtype=np.uint8)
-        for l in range(L):
-            slot0 = cache.append(0, l, types_v if l == 0 else None, w.grid_thw if l == 0 else None, kv[l], vv[l])
-            cache.rope_apply(0, slot0, nv, qv[l], None)
-            if timed and args.roofline_kernel == "attn_chunk":
-                e0, e1 = ev(), ev()
-                e0.record()
-                cache.attn_chunk(0, l, qv[l], ov[l], True)
-                e1.record()
-                roof_events.append((e0, e1))
-                roof_units.append(4.0 * d * nv * (slot0 + (nv + 1) / 2.0) * Hq)   # visible (query, key) pairs only
-            else:
-                cache.attn_chunk(0, l, qv[l], ov[l], True)
-        types_t = np.zeros(1, dtype=np.uint8)
-        ids = np.zeros(1, dtype=np.int32)
-        for t in range(nt):
-            qt, kt, vt = p["qt"][t], p["kt"][t], p["vt"][t]
-            for l in range(L):
-                slot = cache.append(0, l, types_t if l == 0 else None, None, kt[l], vt[l])
-                cache.rope_apply(0, slot, 1, qt[l], None)
-                if timed and args.roofline_kernel == "attn_decode":
-                    e0, e1 = ev(), ev()
-                    e0.record()
-                    cache.attn_decode(l, ids, qt[l], ot[l])
-                    e1.record()
-                    roof_events.append((e0, e1))
-                    roof_units.append((slot + 1) * 2.0 * Hkv * d * 2)              # K and V rows of every cached token
-                else:
-                    cache.attn_decode(l, ids, qt[l], ot[l])
+        cache.stream_step(0, *budgets, q_vision=p["qv"], k_vision=p["kv"], v_vision=p["vv"], o_vision=ov,
+                          grid_thw=w.grid_thw, q_text=p["qt"], k_text=p["kt"], v_text=p["vt"], o_text=ot_all)
 
+    ot_all = torch.empty(nt, L, Hq, d, device=dev, dtype=torch.bfloat16)
     for c in range(args.warmup):
-        step(c, False)
+        step_native(c)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for c in range(args.warmup, args.warmup + args.steps):
-        step(c, True)
+        step_native(c)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
     steady = cache.len(0) == R + w.tokens_per_chunk
 
-    # roofline of the chosen kernel from the events recorded in the timed region
-    durs_ms = [a.elapsed_time(b) for a, b in roof_events]
-    avg_ms = sum(durs_ms) / max(len(durs_ms), 1)
-    units = sum(roof_units) / max(len(roof_units), 1)
-    if args.roofline_kernel == "attn_chunk":
-        achieved, peak, unit, bound = units / (avg_ms * 1e-3) / 1e12, MFMA_BF16_PEAK_TFLOPS, "TFLOP/s", "mfma"
-    else:
-        achieved, peak, unit, bound = units / (avg_ms * 1e-3) / 1e9, HBM_PEAK_GBS, "GB/s", "hbm"
-    roofline = {"kernel": args.roofline_kernel, "bound": bound, "achieved": round(achieved, 2), "peak": peak,
-                "unit": unit, "frac": round(achieved / peak, 4), "traffic": None,
-                "avg_launch_us": round(avg_ms * 1e3, 2), "launches": len(durs_ms),
-                "algorithmic_units_per_launch": units}
-
-    # untimed breakdown pass: mean microseconds per call of each class (events around every call)
-    breakdown = breakdown_pass(cache, run, pool, w, L, args.warmup + args.steps, ov, ot)
+    # second region, same work per chunk, driven call by call so that HIP events can bracket each kernel class
+    inst = instrumented_pass(cache, run, pool, w, L, args.warmup + args.steps, ov, ot, n_chunks=min(10, args.steps))
+    roofs = inst["roofline_all"]
+    dominant = max(roofs, key=lambda r: r["total_us_per_chunk"])
+    roofline = {k: dominant[k] for k in ("kernel", "bound", "achieved", "peak", "unit", "frac", "traffic",
+                                         "avg_launch_us", "launches")}
 
     out = {
         "metric": "ms per 1-s video chunk", "value": round(ms_per_step, 4), "unit": "ms", "n_gpus": 1,
@@ -161,26 +115,95 @@ def main():
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.workload}: {L} layers, {Hq}q/{Hkv}kv heads x {d}, M-RoPE (16,24,24); per chunk "
                                f"{nv} vision + {nt} text tokens; budgets sink {w.n_sink} / vision {w.vision_window} / "
-                               f"text {w.text_window}; retained {R}", "steady_state": bool(steady)},
-        "prefill_attn_tflops": breakdown.get("prefill_attn_tflops"),
-        "decode_kv_gbs": breakdown.get("decode_kv_gbs"),
-        "compaction_gbs": breakdown.get("compaction_gbs"),
-        "breakdown_us_per_call": breakdown.get("us"),
+                               f"text {w.text_window}; retained {R}", "steady_state": bool(steady),
+                   "driver": "sv_stream_step (native call sequencing)"},
+        "prefill_attn_tflops": inst["prefill_attn_tflops"],
+        "decode_kv_gbs": inst["decode_kv_gbs"],
+        "compaction_gbs": inst["compaction_gbs"],
+        "ms_per_step_call_by_call": inst["ms_per_chunk"],
+        "breakdown_us_per_call": inst["us"],
         "roofline": roofline,
+        "roofline_all": roofs,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(L)
     print(json.dumps(out))
 
 
-def breakdown_pass(cache, run, pool, w, L, c0, ov, ot, n_chunks: int = 3):
+def decode_batch_bench(args):
+    """16 independent streams, one decode token per stream per step (variable-length split-KV decode).
+
+    decode_ragged16: per-stream budgets drawn as in sv_inputs.workload_ragged_batch (caches of 1.7k-9.7k tokens);
+    decode_noevict32k: the no-eviction baseline, 16 caches of 32768 tokens.  A step = one sweep over the layers;
+    the layers hold distinct data so that a sweep streams more than the 256 MB Infinity Cache from HBM.
+    """
+    import numpy as np
+    import torch
+
+    import paper_2510_09608_amd as sv
+    import sv_inputs as si
+    dev = "cuda:0"
+    rb = si.workload_ragged_batch()
+    lens = rb.lengths() if args.workload == "decode_ragged16" else [32768] * 16
+    L = args.layers if args.layers != 28 else (4 if args.workload == "decode_ragged16" else 2)
+    Hq, Hkv, d = 28, 4, 128
+    cache = sv.Cache(L, Hq, Hkv, d, sv.SV_DTYPE_BF16, sv.SV_ROPE_3D, 1e6, (16, 24, 24), 16, max(lens) + 8, 16)
+    g = torch.Generator(device=dev).manual_seed(5)
+    for s_, n in enumerate(lens):
+        ty = np.zeros(n, dtype=np.uint8)
+        for l in range(L):
+            kv = torch.randn(2, n, Hkv, d, device=dev, generator=g).to(torch.bfloat16)
+            cache.append(s_, l, ty if l == 0 else None, None, kv[0], kv[1])
+    q = torch.randn(L, 16, Hq, d, device=dev, generator=g).to(torch.bfloat16)
+    o = torch.empty_like(q)
+    ids = np.arange(16, dtype=np.int32)
+    qs, os_ = list(q), list(o)
+
+    def sweep():
+        for l in range(L):
+            cache.attn_decode(l, ids, qs[l], os_[l])
+
+    for _ in range(max(args.warmup // 8, 3)):
+        sweep()
+    torch.cuda.synchronize()
+    evs = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        sweep()
+        b.record()
+        evs.append((a, b))
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    us_layer = sum(a.elapsed_time(b) for a, b in evs) * 1e3 / (args.steps * L)
+    bytes_layer = sum(lens) * 2.0 * Hkv * d * 2
+    gbs = bytes_layer / (us_layer * 1e-6) / 1e9
+    return {
+        "metric": "decode KV-read GB/s", "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(wall * 1e3 / args.steps, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: 16 streams, total {sum(lens)} cached tokens, {L} layers per sweep, "
+                               f"{Hq}q/{Hkv}kv heads x {d}; one query token per stream per layer",
+                   "lens": lens},
+        "roofline": {"kernel": "k_decode_mfma + k_decode_merge (per layer, incl. launch gaps)", "bound": "hbm",
+                     "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
+                     "traffic": None, "avg_launch_us": round(us_layer, 2), "launches": args.steps * L,
+                     "algorithmic_bytes_per_launch": bytes_layer},
+    }
+
+
+def instrumented_pass(cache, run, pool, w, L, c0, ov, ot, n_chunks: int):
+    """Same per-chunk work through the individual C calls, HIP events (torch's current stream, the one the
+    kernels are launched on) around every evict, every chunk-prefill attention launch and every 28-layer
+    sweep of the fused decode kernel."""
     import numpy as np
     import torch
     Hq, Hkv, d = w.n_q_heads, w.n_kv_heads, w.head_dim
     nv, nt = w.vision_per_chunk, w.text_per_chunk
     ev = lambda: torch.cuda.Event(enable_timing=True)
-    rec = {k: [] for k in ("evict", "append_chunk", "rope_chunk", "attn_chunk", "append_decode", "rope_decode",
-                           "attn_decode")}
+    rec = {k: [] for k in ("evict", "append_chunk", "rope_chunk", "attn_chunk", "decode_sweep")}
+    units = {"evict": [], "attn_chunk": [], "decode_sweep": []}
 
     def timed(key, fn):
         a, b = ev(), ev()
@@ -190,35 +213,49 @@ def breakdown_pass(cache, run, pool, w, L, c0, ov, ot, n_chunks: int = 3):
         rec[key].append((a, b))
         return r
 
-    slot0_seen, slots_decode, n_ret_seen = [], [], []
+    ids = np.zeros(1, dtype=np.int32)
+    tv = np.ones(nv, dtype=np.uint8)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
     for c in range(c0, c0 + n_chunks):
         p = pool[c % len(pool)]
-        n_ret_seen.append(timed("evict", run.evict))
-        tv, tt, ids = np.ones(nv, dtype=np.uint8), np.zeros(1, dtype=np.uint8), np.zeros(1, dtype=np.int32)
+        n_before = cache.len(0)
+        n_ret = timed("evict", run.evict)
+        units["evict"].append(2.0 * n_ret * 2 * Hkv * d * 2 * L if n_ret != n_before else 0.0)
         for l in range(L):
             slot0 = timed("append_chunk", lambda: cache.append(0, l, tv if l == 0 else None,
                                                                w.grid_thw if l == 0 else None, p["kv"][l], p["vv"][l]))
             timed("rope_chunk", lambda: cache.rope_apply(0, slot0, nv, p["qv"][l], None))
             timed("attn_chunk", lambda: cache.attn_chunk(0, l, p["qv"][l], ov[l], True))
-            slot0_seen.append(slot0)
+            units["attn_chunk"].append(4.0 * d * nv * (slot0 + (nv + 1) / 2.0) * Hq)     # visible (query, key) pairs
         for t in range(nt):
-            for l in range(L):
-                slot = timed("append_decode", lambda: cache.append(0, l, tt if l == 0 else None, None,
-                                                                   p["kt"][t][l], p["vt"][t][l]))
-                timed("rope_decode", lambda: cache.rope_apply(0, slot, 1, p["qt"][t][l], None))
-                timed("attn_decode", lambda: cache.attn_decode(l, ids, p["qt"][t][l], ot[l]))
-                slots_decode.append(slot)
+            def sweep():
+                for l in range(L):
+                    cache.decode_step(l, ids, p["qt"][t][l], p["kt"][t][l], p["vt"][t][l], ot[l])
+            timed("decode_sweep", sweep)
+            units["decode_sweep"].append(cache.len(0) * 2.0 * Hkv * d * 2 * L)           # K and V rows of every token
     torch.cuda.synchronize()
-    us = {k: round(1e3 * sum(a.elapsed_time(b) for a, b in v) / max(len(v), 1), 2) for k, v in rec.items()}
-    flops = [4.0 * d * nv * (s + (nv + 1) / 2.0) * Hq for s in slot0_seen]
-    bytes_dec = [(s + 1) * 2.0 * Hkv * d * 2 for s in slots_decode]
-    bytes_cmp = [2.0 * n * 2 * Hkv * d * 2 * L for n in n_ret_seen]
-    return {
-        "us": us,
-        "prefill_attn_tflops": round(sum(flops) / len(flops) / (us["attn_chunk"] * 1e-6) / 1e12, 2),
-        "decode_kv_gbs": round(sum(bytes_dec) / len(bytes_dec) / (us["attn_decode"] * 1e-6) / 1e9, 2),
-        "compaction_gbs": round(sum(bytes_cmp) / len(bytes_cmp) / (us["evict"] * 1e-6) / 1e9, 2),
-    }
+    ms_per_chunk = (time.perf_counter() - t0) * 1e3 / n_chunks
+    tot = {k: sum(a.elapsed_time(b) for a, b in v) * 1e3 for k, v in rec.items()}      # microseconds
+    us = {k: round(tot[k] / max(len(v), 1), 2) for k, v in rec.items()}
+    us["decode_per_layer"] = round(us.pop("decode_sweep") / L, 2)
+
+    def roof(kernel, key, bound, peak, unit, scale, launches_per_event):
+        n_launch = len(rec[key]) * launches_per_event
+        achieved = sum(units[key]) / (tot[key] * 1e-6) / scale if tot[key] > 0 else 0.0
+        return {"kernel": kernel, "bound": bound, "achieved": round(achieved, 2), "peak": peak, "unit": unit,
+                "frac": round(achieved / peak, 4), "traffic": None,
+                "avg_launch_us": round(tot[key] / max(n_launch, 1), 2), "launches": n_launch,
+                "total_us_per_chunk": round(tot[key] / n_chunks, 1)}
+
+    roofs = [roof("k_attn_chunk_mfma (chunk prefill, incl. split merge)", "attn_chunk", "mfma", MFMA_BF16_PEAK_TFLOPS,
+                  "TFLOP/s", 1e12, 1),
+             roof("k_decode_mfma + k_decode_merge (fused decode step, 28-layer sweeps incl. launch gaps)", "decode_sweep", "hbm",
+                  HBM_PEAK_GBS, "GB/s", 1e9, L),
+             roof("k_compact (+ scan, shift table)", "evict", "hbm", HBM_PEAK_GBS, "GB/s", 1e9, 1)]
+    return {"us": us, "ms_per_chunk": round(ms_per_chunk, 3), "roofline_all": roofs,
+            "prefill_attn_tflops": roofs[0]["achieved"], "decode_kv_gbs": roofs[1]["achieved"],
+            "compaction_gbs": roofs[2]["achieved"]}
 
 
 def cpu_baseline(L: int):

@@ -170,6 +170,56 @@ SV_API int sv_attn_chunk(sv_cache* c, int stream_id, int layer, const void* q_de
 SV_API int sv_attn_decode(sv_cache* c, int layer, const int32_t* stream_ids_host, int n_list,
                    const void* q_dev, void* o_dev, void* hip_stream);
 
+/*
+ * sv_decode_step -- one decoded text token per listed stream in a single
+ * launch per layer: equivalent to sv_cache_append (one SV_TEXT token),
+ * sv_rope_apply on the query and sv_attn_decode, fused (Sec. 2.1: the new
+ * token's state joins the cache, gets the next contiguous position, and its
+ * query attends to everything retained, itself included).  q_dev
+ * [n_list][n_q_heads][head_dim] and k_dev, v_dev [n_list][n_kv_heads][head_dim]
+ * are UN-rotated and are not modified; o_dev receives
+ * [n_list][n_q_heads][head_dim].  Layer order rules are those of
+ * sv_cache_append (layer 0 registers the token).  Streams must be distinct.
+ */
+SV_API int sv_decode_step(sv_cache* c, int layer, const int32_t* stream_ids_host, int n_list,
+                          const void* q_dev, const void* k_dev, const void* v_dev, void* o_dev,
+                          void* hip_stream);
+
+/*
+ * sv_stream_step -- one second of stream for ALL layers, sequenced natively:
+ * sv_cache_evict with the three budgets, then per layer the vision chunk
+ * (append, rotate Q, chunk-prefill attention), then n_text decode steps, each
+ * running every layer (sv_decode_step).  This is the per-chunk loop of the
+ * method (Sec. 2.1) with the projections and MLPs of the model left out: the
+ * caller supplies each layer's Q/K/V up front.  Layouts (all device memory,
+ * cache dtype, K un-rotated):
+ *   q_vision [n_layers][n_vision][n_q_heads][head_dim]   rotated IN PLACE
+ *   k_vision, v_vision [n_layers][n_vision][n_kv_heads][head_dim]
+ *   o_vision [n_layers][n_vision][n_q_heads][head_dim]   output
+ *   q_text [n_text][n_layers][n_q_heads][head_dim], k_text / v_text
+ *   [n_text][n_layers][n_kv_heads][head_dim], o_text like q_text (output)
+ * n_vision == 0 skips the chunk, n_text == 0 the decoding.  grid_thw as in
+ * sv_cache_append (all zeros = no grid).  Errors are those of the calls it
+ * sequences; on error the stream is left as the failing call left it.
+ */
+typedef struct sv_chunk_io {
+  int32_t n_vision;
+  int32_t grid_thw[3];
+  void* q_vision;
+  const void* k_vision;
+  const void* v_vision;
+  void* o_vision;
+  int32_t n_text;
+  const void* q_text;
+  const void* k_text;
+  const void* v_text;
+  void* o_text;
+} sv_chunk_io;
+
+SV_API int sv_stream_step(sv_cache* c, int stream_id, int64_t n_sink, int64_t vision_window,
+                          int64_t text_window, const sv_chunk_io* io, int64_t* n_retained_out,
+                          void* hip_stream);
+
 /* Number of tokens currently in the stream's cache. */
 SV_API int sv_cache_len(sv_cache* c, int stream_id, int64_t* n_out);
 

@@ -40,6 +40,14 @@ class SvConfig(C.Structure):
     ]
 
 
+class SvChunkIO(C.Structure):
+    _fields_ = [
+        ("n_vision", C.c_int32), ("grid_thw", C.c_int32 * 3), ("q_vision", C.c_void_p), ("k_vision", C.c_void_p),
+        ("v_vision", C.c_void_p), ("o_vision", C.c_void_p), ("n_text", C.c_int32), ("q_text", C.c_void_p),
+        ("k_text", C.c_void_p), ("v_text", C.c_void_p), ("o_text", C.c_void_p),
+    ]
+
+
 _lib = None
 
 _SIGNATURES = {
@@ -54,6 +62,10 @@ _SIGNATURES = {
     "sv_rope_apply": (C.c_int, [C.c_void_p, C.c_int, C.c_int64, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]),
     "sv_attn_chunk": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p]),
     "sv_attn_decode": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "sv_decode_step": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
+                                 C.c_void_p, C.c_void_p]),
+    "sv_stream_step": (C.c_int, [C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.POINTER(SvChunkIO),
+                                 C.POINTER(C.c_int64), C.c_void_p]),
     "sv_cache_len": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_int64)]),
     "sv_cache_retained": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int64, C.POINTER(C.c_int64),
                                     C.c_void_p]),
@@ -152,6 +164,28 @@ def sv_attn_decode(handle: int, layer: int, stream_ids, q, o, stream=None) -> No
            "sv_attn_decode")
 
 
+def sv_decode_step(handle: int, layer: int, stream_ids, q, k, v, o, stream=None) -> None:
+    ids = np.ascontiguousarray(stream_ids, dtype=np.int32)
+    _check(lib().sv_decode_step(handle, layer, ids.ctypes.data, int(ids.shape[0]), _ptr(q), _ptr(k), _ptr(v), _ptr(o),
+                                _stream(stream)), "sv_decode_step")
+
+
+def sv_stream_step(handle: int, stream_id: int, n_sink: int, vision_window: int, text_window: int,
+                   q_vision=None, k_vision=None, v_vision=None, o_vision=None, grid_thw=None,
+                   q_text=None, k_text=None, v_text=None, o_text=None, stream=None) -> int:
+    """Tensors as laid out in include/sv.h (leading dimension = layers, resp. decode steps then layers)."""
+    io = SvChunkIO()
+    io.n_vision = 0 if q_vision is None else int(q_vision.shape[1])
+    io.grid_thw = (C.c_int32 * 3)(*(grid_thw or (0, 0, 0)))
+    io.q_vision, io.k_vision, io.v_vision, io.o_vision = _ptr(q_vision), _ptr(k_vision), _ptr(v_vision), _ptr(o_vision)
+    io.n_text = 0 if q_text is None else int(q_text.shape[0])
+    io.q_text, io.k_text, io.v_text, io.o_text = _ptr(q_text), _ptr(k_text), _ptr(v_text), _ptr(o_text)
+    n = C.c_int64(-1)
+    _check(lib().sv_stream_step(handle, stream_id, n_sink, vision_window, text_window, C.byref(io), C.byref(n),
+                                _stream(stream)), "sv_stream_step")
+    return n.value
+
+
 def sv_cache_len(handle: int, stream_id: int) -> int:
     n = C.c_int64(-1)
     _check(lib().sv_cache_len(handle, stream_id, C.byref(n)), "sv_cache_len")
@@ -224,6 +258,12 @@ class Cache:
 
     def attn_decode(self, layer, stream_ids, q, o) -> None:
         sv_attn_decode(self.handle, layer, stream_ids, q, o)
+
+    def decode_step(self, layer, stream_ids, q, k, v, o) -> None:
+        sv_decode_step(self.handle, layer, stream_ids, q, k, v, o)
+
+    def stream_step(self, stream_id, n_sink, vision_window, text_window, **tensors) -> int:
+        return sv_stream_step(self.handle, stream_id, n_sink, vision_window, text_window, **tensors)
 
     def len(self, stream_id=0) -> int:
         return sv_cache_len(self.handle, stream_id)

@@ -40,7 +40,7 @@ bool config_ok(const sv_config* c) {
 // sv_cache_bytes and sv_cache_create cannot disagree.
 struct Layout {
   size_t kv, meta_gid[2], meta_rank[2], meta_pos[2], meta_local[2], meta_blk[2], meta_type[2];
-  size_t src, delta, dtab, next_pos, n_dev, inv_freq, part_o, part_ml, total;
+  size_t src, delta, dtab, next_pos, n_dev, inv_freq, last_cs, part_o, part_ml, counters, total;
   int64_t part_rows;
 };
 
@@ -69,9 +69,11 @@ Layout make_layout(const sv_config& c) {
   L.next_pos = take(S * 2 * 4);
   L.n_dev = take(S * 4);
   L.inv_freq = take((size_t)(c.head_dim / 2) * 8);
+  L.last_cs = take(S * (size_t)(c.head_dim / 2) * 8);
   L.part_rows = std::max<int64_t>(64 * (int64_t)c.n_streams, std::max<int64_t>(4096, 4 * (int64_t)c.max_q_tokens));
   L.part_o = take((size_t)L.part_rows * c.n_q_heads * c.head_dim * 4);
   L.part_ml = take((size_t)L.part_rows * c.n_q_heads * 2 * 4);
+  L.counters = take((size_t)L.part_rows * c.n_kv_heads * 4);
   L.total = off;
   return L;
 }
@@ -163,9 +165,11 @@ int sv_cache_create(const sv_config* cfg, void* dev_arena, size_t arena_bytes, v
   c->next_pos = (int32_t*)(base + L.next_pos);
   c->n_dev = (int32_t*)(base + L.n_dev);
   c->inv_freq = (double*)(base + L.inv_freq);
+  c->last_cs = (float2*)(base + L.last_cs);
   c->part_o = (float*)(base + L.part_o);
   c->part_ml = (float*)(base + L.part_ml);
   c->part_rows = L.part_rows;
+  c->counters = (int32_t*)(base + L.counters);
   c->st.resize(cfg->n_streams);
   for (auto& s : c->st) s.layer_len.assign(cfg->n_layers, 0);
 
@@ -178,6 +182,7 @@ int sv_cache_create(const sv_config* cfg, void* dev_arena, size_t arena_bytes, v
   hipError_t e = hipMemcpyAsync(c->inv_freq, f.data(), half * sizeof(double), hipMemcpyHostToDevice, s);
   if (e == hipSuccess) e = hipMemsetAsync(c->next_pos, 0, (size_t)cfg->n_streams * 2 * 4, s);
   if (e == hipSuccess) e = hipMemsetAsync(c->n_dev, 0, (size_t)cfg->n_streams * 4, s);
+  if (e == hipSuccess) e = hipMemsetAsync(c->counters, 0, (size_t)L.part_rows * cfg->n_kv_heads * 4, s);
   if (e == hipSuccess) e = hipStreamSynchronize(s);  // f is a local: the copy must have read it
   if (e != hipSuccess) {
     delete c;
@@ -342,8 +347,97 @@ int sv_attn_decode(sv_cache* c, int layer, const int32_t* stream_ids_host, int n
     if (st.len < 1) return SV_ERR_INVALID;
     if (st.layer_len[layer] != st.len) return SV_ERR_STATE;
   }
+  if (sv::attn_decode_mfma_supported(c)) {
+    SV_HIP(sv::launch_attn_decode_mfma(c, layer, stream_ids_host, n_list, 0, q_dev, nullptr, nullptr, o_dev,
+                                       (hipStream_t)hip_stream));
+    return SV_OK;
+  }
   if (!sv::attn_rows_supported(c)) return SV_ERR_UNSUPPORTED;
-  SV_HIP(sv::launch_attn_rows_batch(c, layer, stream_ids_host, n_list, q_dev, o_dev, (hipStream_t)hip_stream));
+  SV_HIP(sv::launch_attn_rows_batch(c, layer, stream_ids_host, n_list, 0, q_dev, nullptr, nullptr, o_dev,
+                                    (hipStream_t)hip_stream));
+  return SV_OK;
+}
+
+int sv_decode_step(sv_cache* c, int layer, const int32_t* stream_ids_host, int n_list, const void* q_dev,
+                   const void* k_dev, const void* v_dev, void* o_dev, void* hip_stream) {
+  if (!c || layer < 0 || layer >= c->cfg.n_layers || !stream_ids_host || n_list < 1 || !q_dev || !k_dev || !v_dev ||
+      !o_dev)
+    return SV_ERR_INVALID;
+  if ((int64_t)n_list > c->part_rows) return SV_ERR_INVALID;
+  const bool use_mfma = sv::attn_decode_mfma_supported(c);
+  if (!use_mfma && !sv::attn_rows_supported(c)) return SV_ERR_UNSUPPORTED;
+  hipStream_t s = (hipStream_t)hip_stream;
+  // validate everything before changing anything
+  for (int b = 0; b < n_list; ++b) {
+    if (!stream_ok(c, stream_ids_host[b])) return SV_ERR_INVALID;
+    for (int b2 = 0; b2 < b; ++b2)
+      if (stream_ids_host[b2] == stream_ids_host[b]) return SV_ERR_INVALID;  // one new token per stream
+    const sv::StreamState& st = c->st[stream_ids_host[b]];
+    if (layer == 0) {
+      for (int l = 0; l < c->cfg.n_layers; ++l)
+        if (st.layer_len[l] != st.len) return SV_ERR_STATE;
+      if (st.len + 1 > c->cfg.capacity_tokens) return SV_ERR_CAPACITY;
+    } else if (st.layer_len[layer] != st.pending_slot0 || st.pending_n != 1 || st.pending_slot0 + 1 != st.len ||
+               st.layer_len[0] != st.len) {
+      return SV_ERR_STATE;
+    }
+  }
+  for (int b = 0; b < n_list; ++b) {
+    const int sid = stream_ids_host[b];
+    sv::StreamState& st = c->st[sid];
+    if (layer == 0) {
+      SV_HIP(sv::launch_meta_append(c, sid, st.next_parity, st.len, 1, st.next_gid, st.n_text, st.n_vis, SV_TEXT,
+                                    nullptr, -1, 0, 0, 0, s));
+      st.pending_slot0 = st.len;
+      st.pending_n = 1;
+      st.next_parity ^= 1;
+      st.next_gid += 1;
+      if (!st.text_iv.empty() && st.text_iv.back().second == st.n_text) st.text_iv.back().second += 1;
+      else st.text_iv.emplace_back(st.n_text, st.n_text + 1);
+      st.n_text += 1;
+      st.len += 1;
+    }
+    st.layer_len[layer] = st.len;
+  }
+  if (use_mfma) SV_HIP(sv::launch_attn_decode_mfma(c, layer, stream_ids_host, n_list, 1, q_dev, k_dev, v_dev, o_dev, s));
+  else SV_HIP(sv::launch_attn_rows_batch(c, layer, stream_ids_host, n_list, 1, q_dev, k_dev, v_dev, o_dev, s));
+  return SV_OK;
+}
+
+int sv_stream_step(sv_cache* c, int stream_id, int64_t n_sink, int64_t vision_window, int64_t text_window,
+                   const sv_chunk_io* io, int64_t* n_retained_out, void* hip_stream) {
+  if (!stream_ok(c, stream_id) || !io || io->n_vision < 0 || io->n_text < 0) return SV_ERR_INVALID;
+  if (io->n_vision > 0 && (!io->q_vision || !io->k_vision || !io->v_vision || !io->o_vision)) return SV_ERR_INVALID;
+  if (io->n_text > 0 && (!io->q_text || !io->k_text || !io->v_text || !io->o_text)) return SV_ERR_INVALID;
+  const int L = c->cfg.n_layers;
+  const size_t qrow = (size_t)c->cfg.n_q_heads * c->row_bytes, kvrow = (size_t)c->cfg.n_kv_heads * c->row_bytes;
+  int rc = sv_cache_evict(c, stream_id, n_sink, vision_window, text_window, n_retained_out, hip_stream);
+  if (rc != SV_OK) return rc;
+  if (io->n_vision > 0) {
+    const int n = io->n_vision;
+    std::vector<uint8_t> types((size_t)n, (uint8_t)SV_VISION);
+    const bool has_grid = io->grid_thw[0] > 0 || io->grid_thw[1] > 0 || io->grid_thw[2] > 0;
+    for (int l = 0; l < L; ++l) {
+      int64_t slot0 = 0;
+      char* q = (char*)io->q_vision + (size_t)l * n * qrow;
+      rc = sv_cache_append(c, stream_id, l, n, types.data(), has_grid ? io->grid_thw : nullptr,
+                           (const char*)io->k_vision + (size_t)l * n * kvrow,
+                           (const char*)io->v_vision + (size_t)l * n * kvrow, &slot0, hip_stream);
+      if (rc != SV_OK) return rc;
+      rc = sv_rope_apply(c, stream_id, slot0, n, q, nullptr, hip_stream);
+      if (rc != SV_OK) return rc;
+      rc = sv_attn_chunk(c, stream_id, l, q, n, (char*)io->o_vision + (size_t)l * n * qrow, 1, hip_stream);
+      if (rc != SV_OK) return rc;
+    }
+  }
+  const int32_t sid = stream_id;
+  for (int t = 0; t < io->n_text; ++t)
+    for (int l = 0; l < L; ++l) {
+      const size_t i = (size_t)t * L + l;
+      rc = sv_decode_step(c, l, &sid, 1, (const char*)io->q_text + i * qrow, (const char*)io->k_text + i * kvrow,
+                          (const char*)io->v_text + i * kvrow, (char*)io->o_text + i * qrow, hip_stream);
+      if (rc != SV_OK) return rc;
+    }
   return SV_OK;
 }
 

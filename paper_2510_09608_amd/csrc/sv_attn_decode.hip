@@ -1,0 +1,419 @@
+// Text-decode attention for bf16 / head_dim 128 / up to 8 query heads per kv head
+// (Sec. 2.1, Sec. 3.3: each generated token attends to the compact cache).
+//
+// Bound: K and V of every cached token are read once per layer and step
+// (2 * n_kv_heads * 128 * 2 bytes per token); arithmetic is negligible, so the
+// kernel is organised to keep many 16-byte loads in flight and to spend as few
+// instructions per key as possible:
+//   * both products run on the matrix cores (v_mfma_f32_16x16x32_bf16).  Scores are
+//     computed transposed, S^T[keys][heads] = K Q^T: K rows go from HBM straight into
+//     the A-operand layout, the query heads of the kv head (padded to 16) are the B
+//     operand held in registers, and a lane then owns scores of ONE head, so the tile
+//     max needs two exchanges between lane groups and nothing else crosses lanes;
+//   * the rows of the score MFMAs are assigned to keys such that each lane ends up
+//     with 8 consecutive keys, i.e. the probabilities already sit in the B-operand
+//     layout of the second product O^T = V^T P^T;
+//   * V rows are staged row-major in LDS (coalesced 16-byte loads and stores) and read
+//     back as the V^T operand with the LDS transpose read, so keys are contracted
+//     inside the MFMA: about 4 instructions per key in total;
+//   * in the fused form the query and the new token's K are rotated in registers at
+//     the new token's position (cos/sin from a 64-entry table written when the token
+//     was registered), and K/V of the new token are stored by the lanes that hold them;
+//   * all global loads of a tile are issued before anything else the wavefront does;
+//   * wavefronts of a workgroup take alternate tiles of the workgroup's key range and
+//     are merged through LDS; key ranges are merged by a second, tiny kernel whose
+//     threads issue all their loads at once (an in-kernel merge by the last workgroup
+//     to arrive was measured slower: the device-scope fences it needs cost more than
+//     a launch).
+
+#include <hip/hip_bf16.h>
+
+#include <algorithm>
+#include <cstdlib>
+
+#include "sv_internal.h"
+
+namespace sv {
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+
+constexpr int D = 128;
+constexpr int GMAX = 8;       // query heads per kv head this kernel handles
+constexpr int TK = 32;        // keys per wavefront tile
+constexpr int kMaxSplitsD = 128;
+constexpr int kMaxRowsD = 64;
+
+struct DecRow {
+  const __hip_bfloat16* k;   // K of the layer: kv head 0, slot 0
+  const __hip_bfloat16* v;
+  __hip_bfloat16* k_w;
+  __hip_bfloat16* v_w;
+  const float2* cs;          // cos/sin of the query token's rotary angles, [64]
+  int32_t len;               // visible keys: slots [0, len), the query token is slot len - 1
+};
+struct DecTable {
+  DecRow r[kMaxRowsD];
+};
+
+__device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+__device__ __forceinline__ uint32_t bf_round_bits(float x) {
+  uint32_t a = __float_as_uint(x);
+  a += 0x7fffu + ((a >> 16) & 1u);
+  return a >> 16;
+}
+
+// Rotate, in place, the two 16-byte chunks a lane holds of one row: `lo` covers
+// dims [i0, i0 + 8), `hi` the partner dims [i0 + 64, i0 + 72); c/s are cos/sin of
+// the 8 pairs.  Result is rounded to bf16, as it would be stored.
+__device__ __forceinline__ void rotate_pair_chunks(uint4& lo, uint4& hi, const float (&c)[8], const float (&s)[8]) {
+  uint32_t* a = (uint32_t*)&lo;
+  uint32_t* b = (uint32_t*)&hi;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    const float a0 = bf_lo(a[w]), a1 = bf_hi(a[w]), b0 = bf_lo(b[w]), b1 = bf_hi(b[w]);
+    const float ra0 = a0 * c[2 * w] - b0 * s[2 * w], rb0 = b0 * c[2 * w] + a0 * s[2 * w];
+    const float ra1 = a1 * c[2 * w + 1] - b1 * s[2 * w + 1], rb1 = b1 * c[2 * w + 1] + a1 * s[2 * w + 1];
+    a[w] = bf_round_bits(ra0) | (bf_round_bits(ra1) << 16);
+    b[w] = bf_round_bits(rb0) | (bf_round_bits(rb1) << 16);
+  }
+}
+
+typedef short v4i16 __attribute__((ext_vector_type(4)));
+
+constexpr int VROW = D * 2 + 32;   // bytes per V row in LDS: 4 consecutive rows x 32 bytes fall in distinct banks
+
+// LDS transpose read (ds_read_b64_tr_b16).  Within each group of 16 lanes, lane j hands in the address of 4
+// consecutive 16-bit elements and receives element (j & 3) of the chunks of lanes (j >> 2) + 4 e, e = 0..3.
+// With lane j pointing at row r0 + (j >> 2), columns c0 + 4 (j & 3) .. + 3 of a row-major tile, it therefore
+// receives column c0 + j of rows r0 .. r0 + 3: a column fragment, which is what an MFMA operand holding
+// V^T wants.  (Layout confirmed with an index pattern on the device.)
+__device__ __forceinline__ v4i16 lds_read_tr(const char* lds_base, int byte_off) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (v4i16 __attribute__((address_space(3)))*)((__attribute__((address_space(3))) char*)lds_base + byte_off));
+}
+
+template <int NW>
+__global__ __launch_bounds__(NW * 64) void k_decode_mfma(DecTable tab, int fused, const __hip_bfloat16* __restrict__ q,
+                                                         const __hip_bfloat16* __restrict__ k_new,
+                                                         const __hip_bfloat16* __restrict__ v_new,
+                                                         __hip_bfloat16* __restrict__ out, float* __restrict__ part_o,
+                                                         float* __restrict__ part_ml, int n_splits, int keys_per_split,
+                                                         int n_q_heads, int n_kv_heads, int G,
+                                                         size_t head_stride_elems, float c_log2, int rotate) {
+  __shared__ __attribute__((aligned(16))) char sV[NW][TK * VROW];   // V tile of each wavefront, row-major
+  __shared__ float sO[NW][GMAX][D];                                 // wavefront results (merge)
+  __shared__ float sML[NW][GMAX][2];
+
+  const int sp = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l16 = lane & 15, lg = lane >> 4;
+  const DecRow rd = tab.r[b];
+  const int len = rd.len;
+  const int k0 = sp * keys_per_split, k1 = min(len, k0 + keys_per_split);
+  const __hip_bfloat16* kp = rd.k + (size_t)hk * head_stride_elems;
+  const __hip_bfloat16* vp = rd.v + (size_t)hk * head_stride_elems;
+  const bool rot = fused && rotate;
+  const size_t new_off = ((size_t)b * n_kv_heads + hk) * D;
+  char* myV = sV[wave];
+
+  // Row m = l16 of score MFMA gi carries key 8 (m >> 2) + 4 gi + (m & 3) of the tile, so that the
+  // accumulator of lane group lg holds keys 8 lg + 4 gi + r: eight consecutive keys per lane over the two
+  // MFMAs, which is the B-operand layout of the second product.
+  const int krow[2] = {8 * (l16 >> 2) + (l16 & 3), 8 * (l16 >> 2) + 4 + (l16 & 3)};
+
+  uint4 kreg[2][4];
+  uint4 vreg[8];
+  // K: 8 loads per lane straight into the A-operand layout (dims 8 lg + 32 kk + j of key krow[gi]);
+  // V: 8 loads per lane, 16 lanes per row (key 4 st + lg, dims 8 l16 + e).  The token being decoded comes
+  // from the caller's buffers.
+  auto issue_loads = [&](int kt) {
+#pragma unroll
+    for (int gi = 0; gi < 2; ++gi) {
+      const int key = kt + krow[gi];
+      const bool is_new = fused && key == len - 1;
+      const __hip_bfloat16* src = is_new ? k_new + new_off + 8 * lg : kp + (size_t)key * D + 8 * lg;
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk)
+        kreg[gi][kk] = key < k1 ? *(const uint4*)(src + 32 * kk) : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int st = 0; st < 8; ++st) {
+      const int key = kt + 4 * st + lg;
+      const bool is_new = fused && key == len - 1;
+      const __hip_bfloat16* src = is_new ? v_new + new_off + 8 * l16 : vp + (size_t)key * D + 8 * l16;
+      vreg[st] = key < k1 ? *(const uint4*)src : make_uint4(0, 0, 0, 0);
+    }
+  };
+
+  const int n_tiles = k1 > k0 ? (k1 - k0 + TK - 1) / TK : 0;
+  if (wave < n_tiles) issue_loads(k0 + wave * TK);   // memory first: everything below overlaps its latency
+
+  // cos/sin of the 16 rotary pairs a lane touches (dims 8 lg + 32 kk + j, kk = 0, 1), from the table the
+  // token's registration wrote
+  float rc[2][8], rs[2][8];
+  if (rot) {
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+      for (int j = 0; j < 8; j += 2) {
+        const float4 t4 = *(const float4*)(rd.cs + 8 * lg + 32 * kk + j);
+        rc[kk][j] = t4.x, rs[kk][j] = t4.y, rc[kk][j + 1] = t4.z, rs[kk][j + 1] = t4.w;
+      }
+  }
+
+  // query heads of this kv head as the B operand: lane holds head l16, dims 8 lg + 32 kk + j
+  uint4 qraw[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk)
+    qraw[kk] = l16 < G ? *(const uint4*)(q + ((size_t)b * n_q_heads + hk * G + l16) * D + 8 * lg + 32 * kk)
+                       : make_uint4(0, 0, 0, 0);
+  if (rot) {
+    rotate_pair_chunks(qraw[0], qraw[2], rc[0], rs[0]);
+    rotate_pair_chunks(qraw[1], qraw[3], rc[1], rs[1]);
+  }
+  bf16x8 qf[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) qf[kk] = *(bf16x8*)&qraw[kk];
+
+  // lane (head l16, lane group lg): running max of the head, its share of the sum, and
+  // O^T[dims 16 blk + 4 lg + r][head l16]
+  float m_run = -INFINITY, l_run = 0.f;
+  f32x4 oacc[8];
+#pragma unroll
+  for (int blk = 0; blk < 8; ++blk) oacc[blk] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  for (int t = wave; t < n_tiles; t += NW) {
+    const int kt = k0 + t * TK;
+    if (fused && len - 1 >= kt && len - 1 < kt + TK) {
+      // this tile holds the token being decoded: rotate its K, store K and V to the cache
+      const int rel = len - 1 - kt;
+#pragma unroll
+      for (int gi = 0; gi < 2; ++gi)
+        if (rel == krow[gi]) {
+          if (rot) {
+            rotate_pair_chunks(kreg[gi][0], kreg[gi][2], rc[0], rs[0]);
+            rotate_pair_chunks(kreg[gi][1], kreg[gi][3], rc[1], rs[1]);
+          }
+          __hip_bfloat16* dst = rd.k_w + (size_t)hk * head_stride_elems + (size_t)(len - 1) * D + 8 * lg;
+#pragma unroll
+          for (int kk = 0; kk < 4; ++kk) *(uint4*)(dst + 32 * kk) = kreg[gi][kk];
+        }
+#pragma unroll
+      for (int st = 0; st < 8; ++st)
+        if (rel == 4 * st + lg)
+          *(uint4*)(rd.v_w + (size_t)hk * head_stride_elems + (size_t)(len - 1) * D + 8 * l16) = vreg[st];
+    }
+    // ---- V tile to LDS, row-major
+#pragma unroll
+    for (int st = 0; st < 8; ++st) *(uint4*)(myV + (4 * st + lg) * VROW + l16 * 16) = vreg[st];
+    // ---- scores S^T = K Q^T: register r of MFMA gi is key kt + 8 lg + 4 gi + r, head l16
+    f32x4 sacc[2];
+#pragma unroll
+    for (int gi = 0; gi < 2; ++gi) {
+      sacc[gi] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk)
+        sacc[gi] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(bf16x8*)&kreg[gi][kk], qf[kk], sacc[gi], 0, 0, 0);
+    }
+    // the registers of this tile are consumed: fetch the wavefront's next tile behind the softmax and
+    // the second product
+    if (t + NW < n_tiles) issue_loads(kt + NW * TK);
+    float mx = -INFINITY;
+#pragma unroll
+    for (int gi = 0; gi < 2; ++gi)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        if (kt + 8 * lg + 4 * gi + r >= k1) sacc[gi][r] = -INFINITY;
+        mx = fmaxf(mx, sacc[gi][r]);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));   // every tile holds at least one valid key, so mx is finite
+    const float m_new = fmaxf(m_run, mx);
+    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c_log2);
+    const float mc = m_new * c_log2;
+    float psum = 0.f;
+    bf16x8 pf;
+#pragma unroll
+    for (int gi = 0; gi < 2; ++gi)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float p = __builtin_amdgcn_exp2f(fmaf(sacc[gi][r], c_log2, -mc));
+        psum += p;
+        pf[4 * gi + r] = (__bf16)p;
+      }
+    l_run = l_run * alpha + psum;
+    if (m_new > m_run) {
+#pragma unroll
+      for (int blk = 0; blk < 8; ++blk) oacc[blk] *= alpha;
+    }
+    m_run = m_new;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    // ---- O^T += V^T P^T: A operand = V^T[dims 16 blk + l16][keys 8 lg + j] by two transpose reads
+#pragma unroll
+    for (int blk = 0; blk < 8; ++blk) {
+      const int off = (8 * lg + (l16 >> 2)) * VROW + (16 * blk + 4 * (l16 & 3)) * 2;
+      const v4i16 a0 = lds_read_tr(myV, off), a1 = lds_read_tr(myV, off + 4 * VROW);
+      const short __attribute__((ext_vector_type(8))) a8 = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
+      oacc[blk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(const bf16x8*)&a8, pf, oacc[blk], 0, 0, 0);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();   // the next tile overwrites the V tile
+  }
+
+  // ---- wavefront result to LDS: head l16 < G, dims 16 blk + 4 lg + r; the sum of a head is spread over
+  // the four lane groups
+  l_run += __shfl_xor(l_run, 16);
+  l_run += __shfl_xor(l_run, 32);
+  if (l16 < GMAX) {
+#pragma unroll
+    for (int blk = 0; blk < 8; ++blk)
+      *(float4*)&sO[wave][l16][16 * blk + 4 * lg] = make_float4(oacc[blk][0], oacc[blk][1], oacc[blk][2], oacc[blk][3]);
+    if (lg == 0) {
+      sML[wave][l16][0] = m_run == -INFINITY ? -INFINITY : m_run * c_log2;   // log2 units from here on
+      sML[wave][l16][1] = l_run;
+    }
+  }
+  __syncthreads();
+
+  // ---- merge the wavefronts; with one split this is the result, else a partial for the merge kernel
+  const size_t pbase = ((size_t)b * n_splits + sp) * n_q_heads + (size_t)hk * G;
+  for (int idx = tid; idx < G * D; idx += NW * 64) {
+    const int g = idx / D, d = idx % D;
+    float mn = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) mn = fmaxf(mn, sML[w][g][0]);
+    float acc = 0.f, lsum = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      const float mw = sML[w][g][0];
+      const float a = mw == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mw - mn);
+      acc += sO[w][g][d] * a;
+      lsum += sML[w][g][1] * a;
+    }
+    if (n_splits == 1) {
+      out[((size_t)b * n_q_heads + hk * G + g) * D + d] = __float2bfloat16(acc / lsum);
+    } else {
+      part_o[(pbase + g) * D + d] = acc;
+      if (d == 0) {
+        part_ml[(pbase + g) * 2] = mn;
+        part_ml[(pbase + g) * 2 + 1] = lsum;
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// Merge of the key ranges of one decode step: one thread per (head, 4 output dims),
+// one 32-thread workgroup per head so that the loads spread over many CUs.  Every
+// thread issues 16 (max, sum) pairs and 16 float4 loads before using any of them.
+// grid: (n_q_heads, n_rows), block: 32 threads.
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(32) void k_decode_merge(const float* __restrict__ part_o,
+                                                     const float* __restrict__ part_ml,
+                                                     __hip_bfloat16* __restrict__ out, int n_splits, int n_q_heads) {
+  const int h = blockIdx.x, b = blockIdx.y, d4 = threadIdx.x;
+  const size_t rbase = (size_t)b * n_splits * n_q_heads + h;   // split s adds s * n_q_heads
+  const float4* po = (const float4*)(part_o + rbase * D) + d4;
+  const float2* pml = (const float2*)part_ml + rbase;
+  const size_t ostride = (size_t)n_q_heads * D / 4;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  float lsum = 0.f, m_ref = -INFINITY;
+  for (int s0 = 0; s0 < n_splits; s0 += 16) {
+    float4 v[16];
+    float2 ml[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const bool ok = s0 + j < n_splits;
+      ml[j] = ok ? pml[(size_t)(s0 + j) * n_q_heads] : make_float2(-INFINITY, 0.f);
+      v[j] = ok ? po[(size_t)(s0 + j) * ostride] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    float mx = m_ref;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) mx = fmaxf(mx, ml[j].x);
+    const float resc = m_ref == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_ref - mx);
+    acc.x *= resc, acc.y *= resc, acc.z *= resc, acc.w *= resc;
+    lsum *= resc;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const float w = ml[j].x == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(ml[j].x - mx);
+      acc.x += w * v[j].x, acc.y += w * v[j].y, acc.z += w * v[j].z, acc.w += w * v[j].w;
+      lsum += w * ml[j].y;
+    }
+    m_ref = mx;
+  }
+  const float inv = 1.0f / lsum;
+  __hip_bfloat16* op = out + ((size_t)b * n_q_heads + h) * D + 4 * d4;
+  const uint32_t w0 = bf_round_bits(acc.x * inv) | (bf_round_bits(acc.y * inv) << 16);
+  const uint32_t w1 = bf_round_bits(acc.z * inv) | (bf_round_bits(acc.w * inv) << 16);
+  *(uint2*)op = make_uint2(w0, w1);
+}
+
+int env_int(const char* name, int dflt) {
+  const char* v = std::getenv(name);
+  return v && *v ? std::atoi(v) : dflt;
+}
+
+}  // namespace
+
+bool attn_decode_mfma_supported(const sv_cache* c) {
+  return c->cfg.dtype == SV_DTYPE_BF16 && c->cfg.head_dim == 128 && c->group <= GMAX &&
+         std::getenv("SV_NO_MFMA_DECODE") == nullptr;
+}
+
+template <int NW>
+hipError_t decode_launch(const sv_cache* c, const DecTable& tab, int fused, int nr, int max_len, const void* q,
+                         const void* k_new, const void* v_new, void* o, size_t r0, hipStream_t s) {
+  const int Hq = c->cfg.n_q_heads, Hkv = c->cfg.n_kv_heads;
+  // one 64-key tile per wavefront unless that needs more than kMaxSplitsD key ranges
+  const int tiles_per_wave = std::max(1, env_int("SV_DECODE_TILES_PER_WAVE", 2));
+  int keys_per_split = TK * NW * tiles_per_wave;
+  int n_splits = (max_len + keys_per_split - 1) / keys_per_split;
+  const int cap = (int)std::min<int64_t>(kMaxSplitsD, std::max<int64_t>(1, c->part_rows / nr));
+  if (n_splits > cap) {
+    keys_per_split = ((max_len + cap - 1) / cap + TK - 1) / TK * TK;
+    n_splits = (max_len + keys_per_split - 1) / keys_per_split;
+  }
+  const float c_log2 = 1.4426950408889634f / sqrtf((float)D);
+  hipLaunchKernelGGL((k_decode_mfma<NW>), dim3(n_splits, Hkv, nr), dim3(NW * 64), 0, s, tab, fused,
+                     (const __hip_bfloat16*)q + r0 * Hq * D,
+                     k_new ? (const __hip_bfloat16*)k_new + r0 * Hkv * D : nullptr,
+                     v_new ? (const __hip_bfloat16*)v_new + r0 * Hkv * D : nullptr,
+                     (__hip_bfloat16*)o + r0 * Hq * D, c->part_o, c->part_ml, n_splits, keys_per_split, Hq, Hkv,
+                     c->group, c->head_stride / 2, c_log2, c->cfg.rope_mode != SV_ROPE_NONE ? 1 : 0);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || n_splits == 1) return e;
+  hipLaunchKernelGGL(k_decode_merge, dim3(Hq, nr), dim3(32), 0, s, c->part_o, c->part_ml,
+                     (__hip_bfloat16*)o + r0 * Hq * D, n_splits, Hq);
+  return hipGetLastError();
+}
+
+hipError_t launch_attn_decode_mfma(const sv_cache* c, int layer, const int32_t* streams, int n_list, int fused,
+                                   const void* q, const void* k_new, const void* v_new, void* o, hipStream_t s) {
+  const int nw = env_int("SV_DECODE_NW", 4);
+  for (int r0 = 0; r0 < n_list; r0 += kMaxRowsD) {
+    const int nr = std::min(kMaxRowsD, n_list - r0);
+    DecTable tab = {};
+    int max_len = 1;
+    for (int b = 0; b < nr; ++b) {
+      const int sid = streams[r0 + b];
+      const StreamState& st = c->st[sid];
+      tab.r[b].k = tab.r[b].k_w = (__hip_bfloat16*)c->kv_ptr(sid, st.cur, layer, 0);
+      tab.r[b].v = tab.r[b].v_w = (__hip_bfloat16*)c->kv_ptr(sid, st.cur, layer, 1);
+      tab.r[b].len = (int)st.len;
+      tab.r[b].cs = c->last_cs + (size_t)sid * (D / 2);
+      max_len = std::max(max_len, (int)st.len);
+    }
+    hipError_t e = nw == 2   ? decode_launch<2>(c, tab, fused, nr, max_len, q, k_new, v_new, o, (size_t)r0, s)
+                   : nw == 1 ? decode_launch<1>(c, tab, fused, nr, max_len, q, k_new, v_new, o, (size_t)r0, s)
+                             : decode_launch<4>(c, tab, fused, nr, max_len, q, k_new, v_new, o, (size_t)r0, s);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+}  // namespace sv

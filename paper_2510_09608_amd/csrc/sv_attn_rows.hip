@@ -1,16 +1,24 @@
 // Row-wise split-KV attention: one query token (all its heads) against a cache
 // prefix.  This is the text-decode kernel (Sec. 2.1 / Sec. 3.3: every generated
 // token attends to the compact cache), also used with one row per stream for
-// ragged batches, and with one row per chunk token as the fp32 chunk-prefill path.
+// ragged batches, and with one row per chunk token as the chunk-prefill path of
+// configurations the MFMA kernel does not cover (fp32, head_dim 64).
 //
 // The kernel is bound by reading K and V once from HBM: 2 * n_kv_heads *
 // head_dim * esize bytes per cached token per layer, shared by the n_q_heads /
-// n_kv_heads query heads of each kv head.  A workgroup owns one (row, kv head,
-// key range); 16 lanes share a key row (16-byte loads, fully coalesced), so a
-// wavefront streams 4 keys at a time.  Scores are reduced over the 16 lanes with
-// shuffles, softmax runs online per lane group, and the 16 lane groups of the
-// workgroup are merged with the log-sum-exp rule at the end.  A second small
-// kernel merges the key ranges.
+// n_kv_heads query heads of each kv head.  One launch does the whole decode step
+// of a layer:
+//   * a workgroup owns one (row, kv head, key range); 16 lanes share a key row
+//     (16-byte loads, fully coalesced), so a wavefront streams 4 keys at a time;
+//     keys are taken in batches of 4 per lane group so that 8 loads are in flight
+//     per lane and the running max is updated once per batch;
+//   * in the fused form the query is rotated in registers at the position of the
+//     new token, and the new token's K (rotated) and V are written to the cache by
+//     the workgroup whose range ends at that token, which uses them from registers;
+//   * scores are reduced over the 16 lanes with shuffles, the 16 lane groups are
+//     merged with the log-sum-exp rule, and the key ranges are merged by whichever
+//     workgroup of a (row, kv head) finishes last (a counter in device memory that
+//     the same workgroup resets), so no second launch is needed.
 
 #include <hip/hip_bf16.h>
 
@@ -23,8 +31,24 @@ namespace sv {
 namespace {
 
 constexpr int kMaxRowsPerLaunch = 64;
+constexpr int kMaxSplits = 64;
+constexpr int KB = 4;  // keys per lane group per batch
+
+struct RowDesc {
+  const void* k;      // K of the layer: kv head 0, slot 0
+  const void* v;
+  void* k_w;          // same buffers, writable (fused append)
+  void* v_w;
+  const int4* pos4;   // position of the query token (fused rotation)
+  int32_t len;        // keys visible: slots [0, len); the query token is slot len - 1
+};
 struct RowTable {
   RowDesc r[kMaxRowsPerLaunch];
+};
+
+struct RopeParams {
+  const double* inv_freq;
+  int mode, s0, s01;
 };
 
 template <typename T, int EPL>
@@ -35,24 +59,49 @@ __device__ __forceinline__ void load_chunk(const T* p, float (&f)[EPL]) {
       const float4 v = *(const float4*)(p + e);
       f[e] = v.x, f[e + 1] = v.y, f[e + 2] = v.z, f[e + 3] = v.w;
     }
-  } else {
-    if constexpr (EPL == 8) {
-      const uint4 v = *(const uint4*)p;
-      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+  } else if constexpr (EPL == 8) {
+    const uint4 v = *(const uint4*)p;
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        f[2 * e] = __uint_as_float(w[e] << 16);
-        f[2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u);
-      }
-    } else {
-      const uint2 v = *(const uint2*)p;
-      const uint32_t w[2] = {v.x, v.y};
-#pragma unroll
-      for (int e = 0; e < 2; ++e) {
-        f[2 * e] = __uint_as_float(w[e] << 16);
-        f[2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u);
-      }
+    for (int e = 0; e < 4; ++e) {
+      f[2 * e] = __uint_as_float(w[e] << 16);
+      f[2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u);
     }
+  } else {
+    const uint2 v = *(const uint2*)p;
+    const uint32_t w[2] = {v.x, v.y};
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+      f[2 * e] = __uint_as_float(w[e] << 16);
+      f[2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u);
+    }
+  }
+}
+
+__device__ __forceinline__ uint32_t bf16_bits(float x) {  // round to nearest even, result in the high half
+  uint32_t a = __float_as_uint(x);
+  a += 0x7fffu + ((a >> 16) & 1u);
+  return a & 0xffff0000u;
+}
+
+// Value a stored element will read back as (identity for fp32 storage).
+template <typename T>
+__device__ __forceinline__ float storage_round(float x) {
+  if constexpr (sizeof(T) == 4) return x;
+  else return __uint_as_float(bf16_bits(x));
+}
+
+template <typename T, int EPL>
+__device__ __forceinline__ void store_chunk(T* p, const float (&f)[EPL]) {  // f already storage-rounded
+  if constexpr (sizeof(T) == 4) {
+#pragma unroll
+    for (int e = 0; e < EPL; e += 4) *(float4*)(p + e) = make_float4(f[e], f[e + 1], f[e + 2], f[e + 3]);
+  } else {
+    uint32_t w[EPL / 2];
+#pragma unroll
+    for (int e = 0; e < EPL / 2; ++e) w[e] = (__float_as_uint(f[2 * e]) >> 16) | (__float_as_uint(f[2 * e + 1]) & 0xffff0000u);
+    if constexpr (EPL == 8) *(uint4*)p = make_uint4(w[0], w[1], w[2], w[3]);
+    else *(uint2*)p = make_uint2(w[0], w[1]);
   }
 }
 
@@ -62,14 +111,49 @@ __device__ __forceinline__ void load_chunk(const T* p, float (&f)[EPL]) {
 template <typename T>
 __device__ __forceinline__ float exp_diff(float x) {
   if constexpr (sizeof(T) == 4) return expf(x);
-  else return exp2f(x);
+  else return __builtin_amdgcn_exp2f(x);
+}
+
+// cos/sin of the rotary angles of the EPL pairs a lane owns.  The 16 lanes of a
+// group cover head_dim: lanes 0-7 hold the low halves, lanes 8-15 the high halves
+// of the same pairs, so lane li and lane li ^ 8 share frequencies (li & 7) * EPL + e.
+template <typename T, int EPL>
+__device__ __forceinline__ void lane_cos_sin(const int4 pos, int li, const RopeParams& rp, float (&c)[EPL],
+                                             float (&s)[EPL]) {
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) {
+    const int i = (li & 7) * EPL + e;
+    const int p = rp.mode != SV_ROPE_3D ? pos.x : (i < rp.s0 ? pos.x : (i < rp.s01 ? pos.y : pos.z));
+    const double ang = (double)p * rp.inv_freq[i];
+    if constexpr (sizeof(T) == 4) {
+      double sd, cd;
+      sincos(ang, &sd, &cd);
+      c[e] = (float)cd, s[e] = (float)sd;
+    } else {
+      sincosf((float)ang, &s[e], &c[e]);
+    }
+  }
+}
+
+// Rotate the chunk a lane holds; the partner half lives 8 lanes away.
+template <int EPL>
+__device__ __forceinline__ void rotate_chunk(float (&x)[EPL], int li, const float (&c)[EPL], const float (&s)[EPL]) {
+  const float sign = li < 8 ? -1.f : 1.f;  // low half: lo c - hi s ; high half: hi c + lo s
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) {
+    const float other = __shfl_xor(x[e], 8, 16);
+    x[e] = x[e] * c[e] + sign * other * s[e];
+  }
 }
 
 template <typename T, int D, int G>
 __global__ __launch_bounds__(256) void k_attn_rows(RowTable tab, int chunk_mode, int chunk_len0, int chunk_step,
-                                                   const T* __restrict__ q, float* __restrict__ part_o,
-                                                   float* __restrict__ part_ml, int n_splits, int n_q_heads,
-                                                   size_t head_stride_elems, float qscale) {
+                                                   int fused, const T* __restrict__ q, const T* __restrict__ k_new,
+                                                   const T* __restrict__ v_new, T* __restrict__ out,
+                                                   float* __restrict__ part_o, float* __restrict__ part_ml,
+                                                   int* __restrict__ counters, int n_splits, int n_q_heads,
+                                                   int n_kv_heads, size_t head_stride_elems, float qscale,
+                                                   RopeParams rp, int debug_skip_merge) {
   constexpr int EPL = D / 16;  // elements per lane
   const int sp = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lg = tid >> 4, li = tid & 15, wave = tid >> 6;
@@ -80,10 +164,19 @@ __global__ __launch_bounds__(256) void k_attn_rows(RowTable tab, int chunk_mode,
   const T* kp = (const T*)rd.k + (size_t)hk * head_stride_elems + li * EPL;
   const T* vp = (const T*)rd.v + (size_t)hk * head_stride_elems + li * EPL;
 
+  float rc[EPL], rs[EPL];
+  const bool rot = fused && rp.mode != SV_ROPE_NONE;
+  if (rot) lane_cos_sin<T, EPL>(*rd.pos4, li, rp, rc, rs);
+
   float qr[G][EPL], o[G][EPL], m[G], l[G];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
     load_chunk<T, EPL>(q + ((size_t)b * n_q_heads + hk * G + g) * D + li * EPL, qr[g]);
+    if (rot) {
+      rotate_chunk<EPL>(qr[g], li, rc, rs);
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) qr[g][e] = storage_round<T>(qr[g][e]);  // as sv_rope_apply would store it
+    }
     m[g] = -INFINITY;
     l[g] = 0.f;
 #pragma unroll
@@ -93,27 +186,68 @@ __global__ __launch_bounds__(256) void k_attn_rows(RowTable tab, int chunk_mode,
     }
   }
 
-
-  for (int key = k0 + lg; key < k1; key += 16) {
-    float kf[EPL], vf[EPL];
-    load_chunk<T, EPL>(kp + (size_t)key * D, kf);
-    load_chunk<T, EPL>(vp + (size_t)key * D, vf);
+  for (int key0 = k0 + lg; key0 < k1; key0 += 16 * KB) {
+    float kf[KB][EPL], vf[KB][EPL];
+    bool valid[KB];
+#pragma unroll
+    for (int j = 0; j < KB; ++j) {
+      const int key = key0 + 16 * j;
+      valid[j] = key < k1;
+      const bool is_new = fused && key == len - 1;
+      if (valid[j] && !is_new) {
+        load_chunk<T, EPL>(kp + (size_t)key * D, kf[j]);
+        load_chunk<T, EPL>(vp + (size_t)key * D, vf[j]);
+      } else if (valid[j]) {
+        // the token being decoded: take K/V from the caller, rotate K, store both in the
+        // cache, and attend to exactly what the cache now holds
+        const size_t src = ((size_t)b * n_kv_heads + hk) * D + li * EPL;
+        load_chunk<T, EPL>(k_new + src, kf[j]);
+        load_chunk<T, EPL>(v_new + src, vf[j]);
+        if (rot) {
+          rotate_chunk<EPL>(kf[j], li, rc, rs);
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) kf[j][e] = storage_round<T>(kf[j][e]);
+        }
+        const size_t dst = (size_t)hk * head_stride_elems + (size_t)key * D + li * EPL;
+        store_chunk<T, EPL>((T*)rd.k_w + dst, kf[j]);
+        store_chunk<T, EPL>((T*)rd.v_w + dst, vf[j]);
+      } else {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) kf[j][e] = 0.f, vf[j][e] = 0.f;
+      }
+    }
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-      float s = 0.f;
+      float s[KB];
+      float mx = m[g];
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) s += qr[g][e] * kf[e];
-      s += __shfl_xor(s, 8, 16);
-      s += __shfl_xor(s, 4, 16);
-      s += __shfl_xor(s, 2, 16);
-      s += __shfl_xor(s, 1, 16);
-      const float mn = fmaxf(m[g], s);
-      const float alpha = exp_diff<T>(m[g] - mn);  // exp(-inf) = 0 on the first key
-      const float p = exp_diff<T>(s - mn);
-      l[g] = l[g] * alpha + p;
+      for (int j = 0; j < KB; ++j) {
+        float acc = 0.f;
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) o[g][e] = o[g][e] * alpha + p * vf[e];
-      m[g] = mn;
+        for (int e = 0; e < EPL; ++e) acc += qr[g][e] * kf[j][e];
+        acc += __shfl_xor(acc, 8, 16);
+        acc += __shfl_xor(acc, 4, 16);
+        acc += __shfl_xor(acc, 2, 16);
+        acc += __shfl_xor(acc, 1, 16);
+        s[j] = valid[j] ? acc : -INFINITY;
+        mx = fmaxf(mx, s[j]);
+      }
+      const float alpha = exp_diff<T>(m[g] - mx);  // 0 on the first batch (m = -inf, mx finite)
+      float p[KB], psum = 0.f;
+#pragma unroll
+      for (int j = 0; j < KB; ++j) {
+        p[j] = exp_diff<T>(s[j] - mx);
+        psum += p[j];
+      }
+      l[g] = l[g] * alpha + psum;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) {
+        float acc = o[g][e] * alpha;
+#pragma unroll
+        for (int j = 0; j < KB; ++j) acc += p[j] * vf[j][e];
+        o[g][e] = acc;
+      }
+      m[g] = mx;
     }
   }
 
@@ -133,9 +267,13 @@ __global__ __launch_bounds__(256) void k_attn_rows(RowTable tab, int chunk_mode,
     }
   }
 
-  // merge the 4 wavefronts through LDS and write the partial result of this key range
+  // merge the 4 wavefronts through LDS
   __shared__ float sm_o[4][G][D];
   __shared__ float sm_ml[4][G][2];
+  __shared__ float sm_w[kMaxSplits][G];
+  __shared__ float sm_l[kMaxSplits][G];
+  __shared__ float sm_max[G];
+  __shared__ int sm_last;
   if ((tid & 63) < 16) {
 #pragma unroll
     for (int g = 0; g < G; ++g) {
@@ -162,35 +300,104 @@ __global__ __launch_bounds__(256) void k_attn_rows(RowTable tab, int chunk_mode,
       acc += sm_o[w][g][d] * a;
       lsum += sm_ml[w][g][1] * a;
     }
-    part_o[(pbase + g) * D + d] = acc;
-    if (d == 0) {
-      part_ml[(pbase + g) * 2] = mn;
-      part_ml[(pbase + g) * 2 + 1] = lsum;
+    if (n_splits == 1) {  // nothing to merge: finish here
+      const float r = acc / lsum;
+      T* op = out + ((size_t)b * n_q_heads + hk * G + g) * D + d;
+      if constexpr (sizeof(T) == 4) *op = r;
+      else *op = __float2bfloat16(r);
+    } else {
+      part_o[(pbase + g) * D + d] = acc;
+      if (d == 0) {
+        part_ml[(pbase + g) * 2] = mn;
+        part_ml[(pbase + g) * 2 + 1] = lsum;
+      }
     }
+  }
+  if (n_splits == 1 || debug_skip_merge) return;
+
+  // the workgroup that finishes last for this (row, kv head) merges the key ranges
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) {
+    int* ctr = counters + (size_t)b * n_kv_heads + hk;
+    const int prev = atomicAdd(ctr, 1);
+    sm_last = prev == n_splits - 1;
+    if (sm_last) *ctr = 0;  // ready for the next launch
+  }
+  __syncthreads();
+  if (!sm_last) return;
+  __threadfence();
+  const size_t rbase = (size_t)b * n_splits * n_q_heads + (size_t)hk * G;  // split s adds s * n_q_heads
+  for (int idx = tid; idx < n_splits * G; idx += 256) {
+    const int s = idx / G, g = idx % G;
+    const size_t p = rbase + (size_t)s * n_q_heads + g;
+    sm_w[s][g] = __builtin_nontemporal_load(part_ml + p * 2);
+    sm_l[s][g] = __builtin_nontemporal_load(part_ml + p * 2 + 1);
+  }
+  __syncthreads();
+  if (tid < G) {
+    float mn = -INFINITY;
+    for (int s = 0; s < n_splits; ++s) mn = fmaxf(mn, sm_w[s][tid]);
+    sm_max[tid] = mn;
+  }
+  __syncthreads();
+  for (int idx = tid; idx < n_splits * G; idx += 256) {
+    const int s = idx / G, g = idx % G;
+    const float ms = sm_w[s][g];
+    sm_w[s][g] = ms == -INFINITY ? 0.f : exp_diff<T>(ms - sm_max[g]);
+  }
+  __syncthreads();
+  for (int idx = tid; idx < G * D; idx += 256) {
+    const int g = idx / D, d = idx % D;
+    const float* po = part_o + (rbase + g) * D + d;
+    float acc = 0.f, lsum = 0.f;
+#pragma unroll 8
+    for (int s = 0; s < n_splits; ++s) {
+      const float w = sm_w[s][g];
+      acc += w * __builtin_nontemporal_load(po + (size_t)s * n_q_heads * D);
+      lsum += w * sm_l[s][g];
+    }
+    const float r = acc / lsum;
+    T* op = out + ((size_t)b * n_q_heads + hk * G + g) * D + d;
+    if constexpr (sizeof(T) == 4) *op = r;
+    else *op = __float2bfloat16(r);
   }
 }
 
 // ---------------------------------------------------------------------------------
-// Merge the key ranges of one (row, head): out = sum_s e^(m_s - M) o_s / sum_s e^(m_s - M) l_s.
-// grid: n_rows * n_q_heads blocks of D threads.  Used by both attention kernels.
+// Merge of key ranges as a kernel of its own (used by the MFMA chunk kernel):
+// out = sum_s e^(m_s - M) o_s / sum_s e^(m_s - M) l_s.  One workgroup of 128
+// threads per (row, head); the weights are computed once into LDS, then every
+// thread sums its dimension over the splits with independent loads.
 // ---------------------------------------------------------------------------------
 template <typename T, int D>
-__global__ __launch_bounds__(D) void k_attn_combine(const float* __restrict__ part_o, const float* __restrict__ part_ml,
-                                                    T* __restrict__ out, int n_splits, int n_q_heads) {
-  const int b = blockIdx.x / n_q_heads, h = blockIdx.x % n_q_heads, d = threadIdx.x;
-  float mn = -INFINITY;
-  for (int s = 0; s < n_splits; ++s) mn = fmaxf(mn, part_ml[(((size_t)b * n_splits + s) * n_q_heads + h) * 2]);
-  float acc = 0.f, lsum = 0.f;
-  for (int s = 0; s < n_splits; ++s) {
-    const size_t p = ((size_t)b * n_splits + s) * n_q_heads + h;
-    const float ms = part_ml[p * 2];
-    const float a = ms == -INFINITY ? 0.f : exp_diff<T>(ms - mn);
-    acc += part_o[p * D + d] * a;
-    lsum += part_ml[p * 2 + 1] * a;
+__global__ __launch_bounds__(128) void k_attn_combine(const float* __restrict__ part_o,
+                                                      const float* __restrict__ part_ml, T* __restrict__ out,
+                                                      int n_splits, int n_q_heads) {
+  __shared__ float sw[kMaxSplits], sl[kMaxSplits];
+  const int b = blockIdx.x / n_q_heads, h = blockIdx.x % n_q_heads, t = threadIdx.x;
+  const size_t base = (size_t)b * n_splits * n_q_heads + h;
+  if (t < n_splits) {
+    sw[t] = part_ml[(base + (size_t)t * n_q_heads) * 2];
+    sl[t] = part_ml[(base + (size_t)t * n_q_heads) * 2 + 1];
   }
-  const float r = acc / lsum;
-  if constexpr (sizeof(T) == 4) out[((size_t)b * n_q_heads + h) * D + d] = r;
-  else out[((size_t)b * n_q_heads + h) * D + d] = __float2bfloat16(r);
+  __syncthreads();
+  float mn = -INFINITY;
+  for (int s = 0; s < n_splits; ++s) mn = fmaxf(mn, sw[s]);
+  __syncthreads();
+  if (t < n_splits) sw[t] = sw[t] == -INFINITY ? 0.f : exp_diff<T>(sw[t] - mn);
+  __syncthreads();
+  for (int d = t; d < D; d += 128) {
+    float acc = 0.f, lsum = 0.f;
+#pragma unroll 8
+    for (int s = 0; s < n_splits; ++s) {
+      acc += sw[s] * part_o[(base + (size_t)s * n_q_heads) * D + d];
+      lsum += sw[s] * sl[s];
+    }
+    const float r = acc / lsum;
+    if constexpr (sizeof(T) == 4) out[((size_t)b * n_q_heads + h) * D + d] = r;
+    else out[((size_t)b * n_q_heads + h) * D + d] = __float2bfloat16(r);
+  }
 }
 
 int env_int(const char* name, int dflt) {
@@ -199,67 +406,77 @@ int env_int(const char* name, int dflt) {
 }
 
 int pick_splits(const sv_cache* c, int n_rows, int max_len) {
-  int forced = env_int("SV_DECODE_SPLITS", 0);
-  int64_t want = forced > 0 ? forced : (1024 + (int64_t)c->cfg.n_kv_heads * n_rows - 1) / ((int64_t)c->cfg.n_kv_heads * n_rows);
+  const int forced = env_int("SV_DECODE_SPLITS", 0);
+  int64_t want = forced > 0 ? forced
+                            : (1024 + (int64_t)c->cfg.n_kv_heads * n_rows - 1) / ((int64_t)c->cfg.n_kv_heads * n_rows);
   want = std::min<int64_t>(want, (max_len + 63) / 64);
-  want = std::min<int64_t>(want, 64);
+  want = std::min<int64_t>(want, kMaxSplits);
   want = std::min<int64_t>(want, c->part_rows / n_rows);
   return (int)std::max<int64_t>(want, 1);
 }
 
 template <typename T, int D, int G>
-hipError_t rows_launch(const sv_cache* c, const RowTable& tab, int chunk_mode, int len0, int step, int n_rows,
-                       int n_splits, const void* q, void* o, size_t row_off, hipStream_t s) {
+hipError_t rows_launch(const sv_cache* c, const RowTable& tab, int chunk_mode, int len0, int step, int fused,
+                       int n_rows, int n_splits, const void* q, const void* k_new, const void* v_new, void* o,
+                       size_t row_off, hipStream_t s) {
   const float scale = 1.0f / sqrtf((float)D) * (sizeof(T) == 4 ? 1.0f : 1.4426950408889634f);
-  const int Hq = c->cfg.n_q_heads;
+  const int Hq = c->cfg.n_q_heads, Hkv = c->cfg.n_kv_heads;
+  RopeParams rp{c->inv_freq, c->cfg.rope_mode, c->cfg.mrope_sections[0],
+                c->cfg.mrope_sections[0] + c->cfg.mrope_sections[1]};
+  dim3 grid(n_splits, Hkv, n_rows);
   // launches are ordered on the stream, so each one reuses the partial buffers from the start
-  float* po = c->part_o;
-  float* pml = c->part_ml;
-  dim3 grid(n_splits, c->cfg.n_kv_heads, n_rows);
-  hipLaunchKernelGGL((k_attn_rows<T, D, G>), grid, dim3(256), 0, s, tab, chunk_mode, len0, step,
-                     (const T*)q + row_off * Hq * D, po, pml, n_splits, Hq, c->head_stride / sizeof(T), scale);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((k_attn_combine<T, D>), dim3(n_rows * Hq), dim3(D), 0, s, po, pml,
-                     (T*)o + row_off * Hq * D, n_splits, Hq);
+  hipLaunchKernelGGL((k_attn_rows<T, D, G>), grid, dim3(256), 0, s, tab, chunk_mode, len0, step, fused,
+                     (const T*)q + row_off * Hq * D, k_new ? (const T*)k_new + row_off * Hkv * D : nullptr,
+                     v_new ? (const T*)v_new + row_off * Hkv * D : nullptr, (T*)o + row_off * Hq * D, c->part_o,
+                     c->part_ml, c->counters, n_splits, Hq, Hkv, c->head_stride / sizeof(T), scale, rp,
+                     env_int("SV_DEBUG_SKIP_MERGE", 0));
   return hipGetLastError();
+}
+
+template <typename T, int D>
+hipError_t rows_dispatch_g(const sv_cache* c, const RowTable& tab, int chunk_mode, int len0, int step, int fused,
+                           int n_rows, int n_splits, const void* q, const void* k_new, const void* v_new, void* o,
+                           size_t row_off, hipStream_t s) {
+#define SV_ROWS_CASE(GG)                                                                                       \
+  case GG:                                                                                                     \
+    return rows_launch<T, D, GG>(c, tab, chunk_mode, len0, step, fused, n_rows, n_splits, q, k_new, v_new, o, \
+                                 row_off, s)
+  switch (c->group) {
+    SV_ROWS_CASE(1);
+    SV_ROWS_CASE(2);
+    SV_ROWS_CASE(4);
+    SV_ROWS_CASE(7);
+    SV_ROWS_CASE(8);
+    default: return hipErrorInvalidValue;
+  }
+#undef SV_ROWS_CASE
+}
+
+hipError_t rows_dispatch(const sv_cache* c, const RowTable& tab, int chunk_mode, int len0, int step, int fused,
+                         int n_rows, int n_splits, const void* q, const void* k_new, const void* v_new, void* o,
+                         size_t row_off, hipStream_t s) {
+  if (c->cfg.dtype == SV_DTYPE_F32)
+    return c->cfg.head_dim == 64 ? rows_dispatch_g<float, 64>(c, tab, chunk_mode, len0, step, fused, n_rows, n_splits,
+                                                              q, k_new, v_new, o, row_off, s)
+                                 : rows_dispatch_g<float, 128>(c, tab, chunk_mode, len0, step, fused, n_rows,
+                                                               n_splits, q, k_new, v_new, o, row_off, s);
+  return c->cfg.head_dim == 64 ? rows_dispatch_g<__hip_bfloat16, 64>(c, tab, chunk_mode, len0, step, fused, n_rows,
+                                                                     n_splits, q, k_new, v_new, o, row_off, s)
+                               : rows_dispatch_g<__hip_bfloat16, 128>(c, tab, chunk_mode, len0, step, fused, n_rows,
+                                                                      n_splits, q, k_new, v_new, o, row_off, s);
 }
 
 template <typename T, int D>
 hipError_t combine_launch(const sv_cache* c, int n_rows, int n_splits, void* o, hipStream_t s) {
-  hipLaunchKernelGGL((k_attn_combine<T, D>), dim3(n_rows * c->cfg.n_q_heads), dim3(D), 0, s, c->part_o, c->part_ml,
+  hipLaunchKernelGGL((k_attn_combine<T, D>), dim3(n_rows * c->cfg.n_q_heads), dim3(128), 0, s, c->part_o, c->part_ml,
                      (T*)o, n_splits, c->cfg.n_q_heads);
   return hipGetLastError();
-}
-
-template <typename T, int D>
-hipError_t rows_dispatch_g(const sv_cache* c, const RowTable& tab, int chunk_mode, int len0, int step, int n_rows,
-                           int n_splits, const void* q, void* o, size_t row_off, hipStream_t s) {
-  switch (c->group) {
-    case 1: return rows_launch<T, D, 1>(c, tab, chunk_mode, len0, step, n_rows, n_splits, q, o, row_off, s);
-    case 2: return rows_launch<T, D, 2>(c, tab, chunk_mode, len0, step, n_rows, n_splits, q, o, row_off, s);
-    case 4: return rows_launch<T, D, 4>(c, tab, chunk_mode, len0, step, n_rows, n_splits, q, o, row_off, s);
-    case 7: return rows_launch<T, D, 7>(c, tab, chunk_mode, len0, step, n_rows, n_splits, q, o, row_off, s);
-    case 8: return rows_launch<T, D, 8>(c, tab, chunk_mode, len0, step, n_rows, n_splits, q, o, row_off, s);
-    default: return hipErrorInvalidValue;
-  }
-}
-
-hipError_t rows_dispatch(const sv_cache* c, const RowTable& tab, int chunk_mode, int len0, int step, int n_rows,
-                         int n_splits, const void* q, void* o, size_t row_off, hipStream_t s) {
-  if (c->cfg.dtype == SV_DTYPE_F32)
-    return c->cfg.head_dim == 64
-               ? rows_dispatch_g<float, 64>(c, tab, chunk_mode, len0, step, n_rows, n_splits, q, o, row_off, s)
-               : rows_dispatch_g<float, 128>(c, tab, chunk_mode, len0, step, n_rows, n_splits, q, o, row_off, s);
-  return c->cfg.head_dim == 64
-             ? rows_dispatch_g<__hip_bfloat16, 64>(c, tab, chunk_mode, len0, step, n_rows, n_splits, q, o, row_off, s)
-             : rows_dispatch_g<__hip_bfloat16, 128>(c, tab, chunk_mode, len0, step, n_rows, n_splits, q, o, row_off,
-                                                    s);
 }
 
 }  // namespace
 
 hipError_t launch_attn_combine(const sv_cache* c, int n_rows, int n_splits, void* o, hipStream_t s) {
+  if (n_splits > kMaxSplits) return hipErrorInvalidValue;
   if (c->cfg.dtype == SV_DTYPE_F32)
     return c->cfg.head_dim == 64 ? combine_launch<float, 64>(c, n_rows, n_splits, o, s)
                                  : combine_launch<float, 128>(c, n_rows, n_splits, o, s);
@@ -285,27 +502,30 @@ hipError_t launch_attn_rows_chunk(const sv_cache* c, int stream, int layer, cons
   const int64_t rows_per_launch = std::min<int64_t>(std::min<int64_t>(n_q, c->part_rows / n_splits), 65535);
   for (int64_t r0 = 0; r0 < n_q; r0 += rows_per_launch) {
     const int nr = (int)std::min<int64_t>(rows_per_launch, n_q - r0);
-    hipError_t e = rows_dispatch(c, tab, 1, len0 + (int)r0 * step, step, nr, n_splits, q, o, (size_t)r0, s);
+    hipError_t e = rows_dispatch(c, tab, 1, len0 + (int)r0 * step, step, 0, nr, n_splits, q, nullptr, nullptr, o,
+                                 (size_t)r0, s);
     if (e != hipSuccess) return e;
   }
   return hipSuccess;
 }
 
-hipError_t launch_attn_rows_batch(const sv_cache* c, int layer, const int32_t* streams, int n_list, const void* q,
-                                  void* o, hipStream_t s) {
+hipError_t launch_attn_rows_batch(const sv_cache* c, int layer, const int32_t* streams, int n_list, int fused,
+                                  const void* q, const void* k_new, const void* v_new, void* o, hipStream_t s) {
   for (int r0 = 0; r0 < n_list; r0 += kMaxRowsPerLaunch) {
     const int nr = std::min(kMaxRowsPerLaunch, n_list - r0);
     RowTable tab = {};
     int max_len = 1;
     for (int b = 0; b < nr; ++b) {
-      const StreamState& st = c->st[streams[r0 + b]];
-      tab.r[b].k = c->kv_ptr(streams[r0 + b], st.cur, layer, 0);
-      tab.r[b].v = c->kv_ptr(streams[r0 + b], st.cur, layer, 1);
+      const int sid = streams[r0 + b];
+      const StreamState& st = c->st[sid];
+      tab.r[b].k = tab.r[b].k_w = c->kv_ptr(sid, st.cur, layer, 0);
+      tab.r[b].v = tab.r[b].v_w = c->kv_ptr(sid, st.cur, layer, 1);
       tab.r[b].len = (int)st.len;
+      tab.r[b].pos4 = c->meta[st.cur].pos4 + (size_t)sid * (size_t)c->cfg.capacity_tokens + (st.len - 1);
       max_len = std::max(max_len, (int)st.len);
     }
     const int n_splits = pick_splits(c, nr, max_len);
-    hipError_t e = rows_dispatch(c, tab, 0, 0, 0, nr, n_splits, q, o, (size_t)r0, s);
+    hipError_t e = rows_dispatch(c, tab, 0, 0, 0, fused, nr, n_splits, q, k_new, v_new, o, (size_t)r0, s);
     if (e != hipSuccess) return e;
   }
   return hipSuccess;

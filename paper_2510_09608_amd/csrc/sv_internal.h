@@ -60,9 +60,11 @@ struct sv_cache {
   int32_t* next_pos;         // device [n_streams][2]          scalar position of the next token (ping-pong)
   int32_t* n_dev;            // device [n_streams]             retained count written by the scan
   double* inv_freq;          // device [head_dim/2]
+  float2* last_cs;           // device [n_streams][head_dim/2]  cos/sin at the position of the newest token
   float* part_o;             // device split-KV partial outputs
   float* part_ml;            // device split-KV partial (max, sum)
   int64_t part_rows;         // capacity of the partial buffers in (token, split) pairs
+  int32_t* counters;         // device [part_rows][n_kv_heads]  arrival counters of the split-KV merge (zero between launches)
   std::vector<sv::StreamState> st;
 
   char* kv_ptr(int stream, int half, int layer, int which) const {
@@ -99,17 +101,19 @@ hipError_t launch_compact(const sv_cache* c, int stream, int64_t n_new, hipStrea
 hipError_t launch_rope_apply(const sv_cache* c, int stream, int64_t slot0, int n, void* q, void* k,
                              hipStream_t s);
 
-struct RowDesc {           // one query token of the row-wise attention kernel
-  const void* k;           // K of the layer, kv head 0, slot 0
-  const void* v;
-  int32_t len;             // keys visible: slots [0, len)
-};
-
 hipError_t launch_attn_rows_chunk(const sv_cache* c, int stream, int layer, const void* q, int n_q,
                                   void* o, int causal, hipStream_t s);
-hipError_t launch_attn_rows_batch(const sv_cache* c, int layer, const int32_t* streams, int n_list,
-                                  const void* q, void* o, hipStream_t s);
+// fused != 0: q is un-rotated and k_new / v_new ([n_list][n_kv_heads][head_dim], un-rotated K) are the
+// newest token of each stream, already counted in the stream's length: the kernel rotates q and k_new at
+// that token's position and stores k_new / v_new in the cache before attending.
+hipError_t launch_attn_rows_batch(const sv_cache* c, int layer, const int32_t* streams, int n_list, int fused,
+                                  const void* q, const void* k_new, const void* v_new, void* o, hipStream_t s);
 bool attn_rows_supported(const sv_cache* c);
+
+// Same contract as launch_attn_rows_batch, matrix-core kernel for bf16 / head_dim 128 / group <= 8.
+bool attn_decode_mfma_supported(const sv_cache* c);
+hipError_t launch_attn_decode_mfma(const sv_cache* c, int layer, const int32_t* streams, int n_list, int fused,
+                                   const void* q, const void* k_new, const void* v_new, void* o, hipStream_t s);
 
 bool attn_mfma_supported(const sv_cache* c);
 hipError_t launch_attn_chunk_mfma(const sv_cache* c, int stream, int layer, const void* q, int n_q,

@@ -15,9 +15,29 @@ namespace {
 // ---------------------------------------------------------------------------------
 __global__ void k_meta_append(MetaPtrs m, const int32_t* __restrict__ next_in, int32_t* __restrict__ next_out,
                               int64_t slot0, int n, int64_t gid0, int64_t rank_text0, int64_t rank_vis0,
-                              int type_uniform, TypeMask mask, int rope3d, int blk, int gT, int gH, int gW) {
+                              int type_uniform, TypeMask mask, int rope3d, int blk, int gT, int gH, int gW,
+                              float2* __restrict__ last_cs, const double* __restrict__ inv_freq, int half,
+                              int rope_none, int s0, int s01, int f32_data) {
   const int j = blockIdx.x * blockDim.x + threadIdx.x;
   const int next = *next_in;
+  if (blockIdx.x == 0 && threadIdx.x < half) {
+    // cos/sin of the rotary angles of the LAST token of this append (the decode kernel's query token)
+    const int i = threadIdx.x;
+    int pt, ph, pw;
+    if (rope3d && blk >= 0) pt = next + gT - 1, ph = next + gH - 1, pw = next + gW - 1;
+    else pt = ph = pw = rope3d ? next + n - 1 : (int)(slot0 + n - 1);
+    const int p = !rope3d ? pt : (i < s0 ? pt : (i < s01 ? ph : pw));
+    const double ang = rope_none ? 0.0 : (double)p * inv_freq[i];
+    float2 cs;
+    if (f32_data) {
+      double sd, cd;
+      sincos(ang, &sd, &cd);
+      cs = make_float2((float)cd, (float)sd);
+    } else {
+      sincosf((float)ang, &cs.y, &cs.x);
+    }
+    last_cs[i] = cs;
+  }
   if (j == 0) {
     int adv;
     if (!rope3d) adv = (int)(slot0 + n) - next;  // 1-D: position == slot
@@ -172,8 +192,12 @@ hipError_t launch_meta_append(const sv_cache* c, int stream, int next_parity, in
   const int threads = 256, blocks = (n + threads - 1) / threads;
   const int32_t* nin = c->next_pos + 2 * stream + next_parity;
   int32_t* nout = c->next_pos + 2 * stream + (next_parity ^ 1);
+  const int half = c->cfg.head_dim / 2;
   hipLaunchKernelGGL(k_meta_append, dim3(blocks), dim3(threads), 0, s, m, nin, nout, slot0, n, gid0, rank_text0,
-                     rank_vis0, type_uniform, mk, c->cfg.rope_mode == SV_ROPE_3D ? 1 : 0, blk, gT, gH, gW);
+                     rank_vis0, type_uniform, mk, c->cfg.rope_mode == SV_ROPE_3D ? 1 : 0, blk, gT, gH, gW,
+                     c->last_cs + (size_t)stream * half, c->inv_freq, half, c->cfg.rope_mode == SV_ROPE_NONE ? 1 : 0,
+                     c->cfg.mrope_sections[0], c->cfg.mrope_sections[0] + c->cfg.mrope_sections[1],
+                     c->cfg.dtype == SV_DTYPE_F32 ? 1 : 0);
   return hipGetLastError();
 }
 

@@ -15,8 +15,10 @@ from .binding import Cache, SV_TEXT, SV_VISION
 
 
 class StreamRunner:
-    def __init__(self, cache: Cache, n_sink: int, vision_window: int, text_window: int, stream_id: int = 0):
+    def __init__(self, cache: Cache, n_sink: int, vision_window: int, text_window: int, stream_id: int = 0,
+                 fused_decode: bool = True):
         self.cache = cache
+        self.fused_decode = fused_decode
         self.budgets = (n_sink, vision_window, text_window)
         self.sid = stream_id
         self.L = cache.cfg.n_layers
@@ -46,7 +48,11 @@ class StreamRunner:
         return slot0
 
     def decode(self, q_layers: Sequence, k_layers: Sequence, v_layers: Sequence, o_layers: Sequence) -> int:
-        """One text token: q/k/v per layer are [1, H, d]."""
+        """One text token: q/k/v per layer are [1, H, d].  Fused: one launch per layer, q is left un-rotated."""
+        if self.fused_decode:
+            for l in range(self.L):
+                self.cache.decode_step(l, self._ids, q_layers[l], k_layers[l], v_layers[l], o_layers[l])
+            return self.cache.len(self.sid) - 1
         types = np.zeros(1, dtype=np.uint8)
         slot = -1
         for l in range(self.L):

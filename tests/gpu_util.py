@@ -34,10 +34,10 @@ def make_cache(w: si.Workload, n_layers: int = None, capacity: int = None, n_str
 class GpuStream:
     """Runs a workload through the library; model layer layers[j] lives in cache layer j."""
 
-    def __init__(self, w: si.Workload, layers: Sequence[int], cache: sv.Cache = None):
+    def __init__(self, w: si.Workload, layers: Sequence[int], cache: sv.Cache = None, fused_decode: bool = True):
         self.w, self.layers = w, list(layers)
         self.cache = cache or make_cache(w, n_layers=len(self.layers))
-        self.run = StreamRunner(self.cache, w.n_sink, w.vision_window, w.text_window)
+        self.run = StreamRunner(self.cache, w.n_sink, w.vision_window, w.text_window, fused_decode=fused_decode)
 
     def preamble(self):
         w = self.w

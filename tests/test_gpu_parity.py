@@ -29,9 +29,10 @@ def _say(msg):
 # whole per-chunk step
 # ----------------------------------------------------------------------------
 
-def test_tiny_stream_f32_every_chunk():
+@pytest.mark.parametrize("fused", [True, False])
+def test_tiny_stream_f32_every_chunk(fused):
     w = si.workload_tiny()
-    g, o = gu.GpuStream(w, [0]), sv_step.new_stream(w, [0])
+    g, o = gu.GpuStream(w, [0], fused_decode=fused), sv_step.new_stream(w, [0])
     worst = 0.0
     for c in range(w.n_chunks):
         _say(f"tiny_f32 chunk {c}")
@@ -41,10 +42,11 @@ def test_tiny_stream_f32_every_chunk():
     _say(f"tiny_f32 worst max-abs err {worst:.3e}")
 
 
-def test_qwen_layer_bf16_stream():
+@pytest.mark.parametrize("fused", [True, False])
+def test_qwen_layer_bf16_stream(fused):
     """One Qwen-7B-shaped layer through warm-up into steady state (retained = 5120)."""
     w = si.workload_qwen_layer(n_chunks=35)
-    g, o = gu.GpuStream(w, [0]), sv_step.new_stream(w, [0])
+    g, o = gu.GpuStream(w, [0], fused_decode=fused), sv_step.new_stream(w, [0])
     g.preamble()
     sv_step.append_preamble(o, w, [0])
     check = {0, 1, 31, 32, 33, 34}
@@ -105,6 +107,43 @@ def test_multi_layer_step_sampled_layers():
             for j, l in enumerate(checked):
                 e = gu.max_err(gu.host(os_[l]), ro["decode"][t][j])
                 assert e <= gu.TOL["bf16"], (c, t, l, e)
+        ids, pos = cache.retained(0)
+        assert np.array_equal(ids, np.asarray(ro["gids_end"])) and np.array_equal(pos, ro["pos_end"])
+
+
+def test_native_stream_step_matches_oracle():
+    """sv_stream_step (the whole second sequenced in C, all layers) on a 3-layer cache, every output checked."""
+    w = si.workload_qwen_layer(n_chunks=5, n_layers=3, seed=1003)
+    w.preamble_text, w.vision_window, w.text_window, w.n_sink = 48, 512, 40, 32
+    layers = [0, 1, 2]
+    cache = gu.make_cache(w, n_layers=3, capacity=2048)
+    o = sv_step.new_stream(w, layers)
+    sv_step.append_preamble(o, w, layers)
+    gids = np.arange(w.preamble_text)
+    run = gu.StreamRunner(cache, w.n_sink, w.vision_window, w.text_window)
+    run.preamble([gu.dev(si.normal(w.seed, si.TENSOR_K, l, gids, 4, 128, True), w) for l in layers],
+                 [gu.dev(si.normal(w.seed, si.TENSOR_V, l, gids, 4, 128, True), w) for l in layers])
+    stack = lambda which, g, heads: torch.stack([gu.dev(si.normal(w.seed, which, l, g, heads, 128, True), w)
+                                                 for l in layers])
+    for c in range(w.n_chunks):
+        _say(f"native_step chunk {c}")
+        ro = sv_step.step_chunk(o, w, c, layers)
+        ch = w.chunk(c)
+        gv = np.arange(ch.vision.gid0, ch.vision.gid0 + ch.vision.n)
+        gt = np.arange(ch.text_gid0, ch.text_gid0 + ch.n_text)
+        qv, kv, vv = stack(si.TENSOR_Q, gv, 28), stack(si.TENSOR_K, gv, 4), stack(si.TENSOR_V, gv, 4)
+        # text tensors are [n_text][L][H][d]
+        qt = stack(si.TENSOR_Q, gt, 28).transpose(0, 1).contiguous()
+        kt = stack(si.TENSOR_K, gt, 4).transpose(0, 1).contiguous()
+        vt = stack(si.TENSOR_V, gt, 4).transpose(0, 1).contiguous()
+        ov, ot = torch.empty_like(qv), torch.empty_like(qt)
+        n_ret = cache.stream_step(0, w.n_sink, w.vision_window, w.text_window, q_vision=qv, k_vision=kv, v_vision=vv,
+                                  o_vision=ov, grid_thw=ch.vision.grid_thw, q_text=qt, k_text=kt, v_text=vt, o_text=ot)
+        assert n_ret == ro["n_retained"]
+        for j in range(3):
+            assert gu.max_err(gu.host(ov[j]), ro["prefill"][j]) <= gu.TOL["bf16"]
+            for t in range(ch.n_text):
+                assert gu.max_err(gu.host(ot[t, j]), ro["decode"][t][j][0]) <= gu.TOL["bf16"]
         ids, pos = cache.retained(0)
         assert np.array_equal(ids, np.asarray(ro["gids_end"])) and np.array_equal(pos, ro["pos_end"])
 
@@ -321,6 +360,7 @@ def test_decode_ragged_batch_full_size():
             o.append_meta([ty] * n, grid)
             o.append_kv(0, k, v)
         assert cache.len(s) == len(o)
+        oracles.append(o)
         q, _, _ = ws.qkv(0, np.array([g0 - 1]))
         q_all.append(q)
         ref.append(o.attend(0, q, [len(o) - 1]))
@@ -334,6 +374,26 @@ def test_decode_ragged_batch_full_size():
     err = gu.max_err(gu.host(od), np.concatenate(ref))
     _say(f"ragged decode max-abs err {err:.3e}, total keys {sum(cache.len(s) for s in range(rb.n_streams))}")
     assert err <= gu.TOL["bf16"]
+    # one more token per stream through the fused step (append + rotate + attend in one launch)
+    q2, k2, v2, ref2 = [], [], [], []
+    for s in range(rb.n_streams):
+        gid = np.array([10_000_000 + s])
+        q, k, v = si.normal(7, si.TENSOR_Q, 0, gid, 28, 128, True), si.normal(7, si.TENSOR_K, 0, gid, 4, 128, True), \
+            si.normal(7, si.TENSOR_V, 0, gid, 4, 128, True)
+        q2.append(q), k2.append(k), v2.append(v)
+        oracles_s = oracles[s]
+        oracles_s.append_meta([orc.TEXT])
+        oracles_s.append_kv(0, k, v)
+        ref2.append(oracles_s.attend(0, q, [len(oracles_s) - 1]))
+    od2 = torch.empty_like(qd)
+    cache.decode_step(0, list(range(rb.n_streams)), gu.dev(np.concatenate(q2), w), gu.dev(np.concatenate(k2), w),
+                      gu.dev(np.concatenate(v2), w), od2)
+    err2 = gu.max_err(gu.host(od2), np.concatenate(ref2))
+    _say(f"ragged fused decode step max-abs err {err2:.3e}")
+    assert err2 <= gu.TOL["bf16"]
+    for s in range(rb.n_streams):
+        _, pos = cache.retained(s)
+        assert np.array_equal(pos.astype(np.int64), oracles[s].positions())
 
 
 def test_high_frame_rate_chunk_sampled_rows():
