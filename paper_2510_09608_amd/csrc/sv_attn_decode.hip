@@ -83,7 +83,7 @@ __device__ __forceinline__ void rotate_pair_chunks(uint4& lo, uint4& hi, const f
 
 typedef short v4i16 __attribute__((ext_vector_type(4)));
 
-constexpr int VROW = D * 2 + 32;   // bytes per V row in LDS: 4 consecutive rows x 32 bytes fall in distinct banks
+constexpr int VROW = D * 2 + 64;   // bytes per V row in LDS: rows of one transpose read fall in distinct banks
 
 // LDS transpose read (ds_read_b64_tr_b16).  Within each group of 16 lanes, lane j hands in the address of 4
 // consecutive 16-bit elements and receives element (j & 3) of the chunks of lanes (j >> 2) + 4 e, e = 0..3.

@@ -9,23 +9,23 @@
 // Tiling (64-wide wavefronts, v_mfma_f32_32x32x16_bf16):
 //   * The G query heads that share a kv head are packed into one row space,
 //     row = query * G + head_in_group, so one K/V tile serves all of them.
-//   * A wavefront owns RB blocks of 32 rows; a workgroup of NW wavefronts owns
-//     NW * RB * 32 rows of one kv head and one key range (split-KV); key ranges
-//     are merged afterwards with the log-sum-exp rule.
-//   * Scores are computed transposed, S^T = K Q^T, so that a lane holds scores
-//     of ONE query row: row max and row sum are in-lane plus one exchange
-//     between the two half-wavefronts, and the output O^T = V^T P^T keeps one
-//     query row per lane, so rescaling by the running max is a per-lane scalar.
-//   * K tiles (64 keys) are staged in LDS row-wise with their rows permuted
-//     (bits 2 and 3 of the key index swapped): the accumulator layout of S^T
-//     then hands every lane 8 consecutive keys per 16-key step, which is exactly
-//     the B-operand layout of the second product, so P never moves between lanes.
-//   * V tiles are transposed on the way into LDS (4 keys x 8 dims per thread in
-//     registers), so the A operand of V^T P^T is one 16-byte LDS read.
-//   * Both LDS tiles use a 16-byte-chunk XOR swizzle: every 8 consecutive lanes
-//     of a 16-byte read or an 8-byte write fall in distinct bank groups.
-//   * The next tile's global loads are issued into registers before the current
-//     tile's MFMAs.
+//   * A wavefront owns 32 rows; a workgroup of NW wavefronts owns NW * 32 rows of one
+//     kv head and one key range (split-KV); key ranges are merged afterwards with
+//     the log-sum-exp rule.  Two wavefronts share a SIMD (NW = 8, or two workgroups
+//     of 4 per CU), so one wavefront's softmax overlaps the other's MFMAs and the
+//     vector ALU is fed every cycle (a single wavefront issues at half rate).
+//   * Scores are computed transposed, S^T = K Q^T, so that a lane holds scores of
+//     ONE query row: row max and row sum are in-lane plus one exchange between the
+//     two half-wavefronts, and the output O^T = V^T P^T keeps one query row per
+//     lane, so rescaling by the running max is a per-lane scalar.
+//   * K tiles (64 keys) are staged in LDS with their rows permuted (bits 2 and 3 of
+//     the key index swapped): the accumulator layout of S^T then hands every lane 8
+//     consecutive keys per 16-key step, which is exactly the B-operand layout of
+//     the second product, so P never moves between lanes.
+//   * V tiles are staged row-major, exactly as loaded, and read back as the V^T
+//     operand with the LDS transpose read (ds_read_b64_tr_b16), two per operand.
+//   * LDS is double-buffered: the next tile's global loads are issued into registers
+//     before the current tile's MFMAs and stored after them; one barrier per tile.
 
 #include <hip/hip_bf16.h>
 
@@ -39,37 +39,43 @@ namespace {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef short v4i16 __attribute__((ext_vector_type(4)));
+typedef short v8i16 __attribute__((ext_vector_type(8)));
 
-constexpr int D = 128;          // head_dim
-constexpr int TK = 64;          // keys per tile
-constexpr int KROW = D * 2;     // bytes per K row in LDS
-constexpr int VROW = TK * 2;    // bytes per V^T row in LDS
+constexpr int D = 128;               // head_dim
+constexpr int TK = 64;               // keys per tile
+constexpr int KROW = D * 2;          // bytes per K row in LDS (16-byte chunks XOR-swizzled by row)
+constexpr int VROW = D * 2 + 64;     // bytes per V row in LDS: the 4 rows x 64 bytes that 32 lanes of a transpose read
+                                     // touch fall in distinct banks (64 banks x 4 bytes)
 constexpr int K_BYTES = TK * KROW;
-constexpr int V_BYTES = D * VROW;
+constexpr int V_BYTES = TK * VROW;
+constexpr int BUF_BYTES = K_BYTES + V_BYTES;
 
 __device__ __forceinline__ int perm_key(int key) {  // swap bits 2 and 3
   return (key & ~0xC) | ((key & 4) << 1) | ((key & 8) >> 1);
 }
 __device__ __forceinline__ int k_lds_off(int row, int chunk) {  // row: permuted key, chunk: 16-byte unit of head_dim
-  return row * KROW + ((chunk ^ (row & 7)) << 4);
-}
-__device__ __forceinline__ int v_swz(int dv) { return (dv & 7) ^ ((dv >> 3) & 7); }
-__device__ __forceinline__ int vt_lds_off(int dv, int chunk) {  // chunk: 8 keys
-  return dv * VROW + ((chunk ^ v_swz(dv)) << 4);
+  return row * KROW + ((chunk ^ (row & 15)) << 4);   // 16 consecutive rows read 16 distinct chunks: no bank conflict
 }
 
-template <int NW, int RB>
-__global__ __launch_bounds__(NW * 64) void k_attn_chunk_mfma(
+// LDS transpose read: within each group of 16 lanes, lane j hands in the address of 4 consecutive 16-bit
+// elements and receives element (j & 3) of the chunks of lanes (j >> 2) + 4 e, e = 0..3.  Pointing lane j
+// at row r0 + (j >> 2), columns c0 + 4 (j & 3) .. + 3 of a row-major tile returns column c0 + j of rows
+// r0 .. r0 + 3.  (Layout confirmed with an index pattern on the device.)
+__device__ __forceinline__ v4i16 lds_read_tr(const char* base, int byte_off) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (v4i16 __attribute__((address_space(3)))*)((__attribute__((address_space(3))) char*)base + byte_off));
+}
+
+template <int NW>
+__global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_mfma(
     const __hip_bfloat16* __restrict__ q, const __hip_bfloat16* __restrict__ kc, const __hip_bfloat16* __restrict__ vc,
     __hip_bfloat16* __restrict__ out, float* __restrict__ part_o, float* __restrict__ part_ml, int n_q, int n_kv,
     int causal, int n_splits, int keys_per_split, int n_q_heads, int G, size_t head_stride_elems, float c_log2) {
   constexpr int NT = NW * 64;
-  constexpr int ROWS_WG = NW * RB * 32;
-  constexpr int KLD = (TK * 16) / NT;  // 16-byte K chunks per thread per tile
-  constexpr int VUN = 256 / NT;        // (4 keys x 8 dims) V units per thread per tile
-  __shared__ __attribute__((aligned(16))) char smem[K_BYTES + V_BYTES];
-  char* sK = smem;
-  char* sV = smem + K_BYTES;
+  constexpr int ROWS_WG = NW * 32;
+  constexpr int CH = (TK * 16) / NT;   // 16-byte chunks of K (and of V) per thread per tile
+  extern __shared__ __attribute__((aligned(16))) char smem[];   // two buffers of (K tile, V tile)
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, hh = lane >> 5;
@@ -84,208 +90,169 @@ __global__ __launch_bounds__(NW * 64) void k_attn_chunk_mfma(
   if (causal) k_end = min(k_end, slot0 + row_last / G + 1);
   const int n_tiles = k_end > k_begin ? (k_end - k_begin + TK - 1) / TK : 0;
 
-  // per-lane query rows
-  int qi[RB], hg[RB], limit[RB];
-  bool rvalid[RB];
-  bf16x8 qf[RB][8];
-#pragma unroll
-  for (int rb = 0; rb < RB; ++rb) {
-    const int row = rt * ROWS_WG + (wave * RB + rb) * 32 + l32;
-    rvalid[rb] = row < n_rows;
-    const int rr = rvalid[rb] ? row : n_rows - 1;
-    qi[rb] = rr / G;
-    hg[rb] = rr % G;
-    limit[rb] = min(causal ? slot0 + qi[rb] : n_kv - 1, k_end - 1);
-    const __hip_bfloat16* qp = q + ((size_t)qi[rb] * n_q_heads + hk * G + hg[rb]) * D + hh * 8;
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
-      uint4 raw = rvalid[rb] ? *(const uint4*)(qp + kk * 16) : make_uint4(0, 0, 0, 0);
-      qf[rb][kk] = *(bf16x8*)&raw;
-    }
-  }
-
-  f32x16 oacc[RB][4];
-  float m_run[RB], l_run[RB];
-#pragma unroll
-  for (int rb = 0; rb < RB; ++rb) {
-    m_run[rb] = -INFINITY;
-    l_run[rb] = 0.f;
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) oacc[rb][db][r] = 0.f;
-  }
-
   const __hip_bfloat16* kbase = kc + (size_t)hk * head_stride_elems;
   const __hip_bfloat16* vbase = vc + (size_t)hk * head_stride_elems;
 
-  uint4 kreg[KLD];
-  uint4 vreg[VUN][4];
+  uint4 kreg[CH], vreg[CH];
   auto issue_loads = [&](int t) {
     const int kt0 = k_begin + t * TK;
 #pragma unroll
-    for (int i = 0; i < KLD; ++i) {
+    for (int i = 0; i < CH; ++i) {
       const int cid = tid + i * NT, key = cid >> 4, c16 = cid & 15;
-      kreg[i] = (kt0 + key < k_end) ? *(const uint4*)(kbase + (size_t)(kt0 + key) * D + c16 * 8) : make_uint4(0, 0, 0, 0);
-    }
-#pragma unroll
-    for (int u = 0; u < VUN; ++u) {
-      const int unit = tid + u * NT, dg = unit & 15, kg = unit >> 4;
-#pragma unroll
-      for (int a = 0; a < 4; ++a) {
-        const int key = kt0 + 4 * kg + a;
-        vreg[u][a] = key < k_end ? *(const uint4*)(vbase + (size_t)key * D + dg * 8) : make_uint4(0, 0, 0, 0);
-      }
+      const bool ok = kt0 + key < k_end;   // rows past the range read as zero (finite, masked anyway)
+      kreg[i] = ok ? *(const uint4*)(kbase + (size_t)(kt0 + key) * D + c16 * 8) : make_uint4(0, 0, 0, 0);
+      vreg[i] = ok ? *(const uint4*)(vbase + (size_t)(kt0 + key) * D + c16 * 8) : make_uint4(0, 0, 0, 0);
     }
   };
-  auto store_tile = [&]() {
+  auto store_tile = [&](char* buf) {
 #pragma unroll
-    for (int i = 0; i < KLD; ++i) {
+    for (int i = 0; i < CH; ++i) {
       const int cid = tid + i * NT, key = cid >> 4, c16 = cid & 15;
-      *(uint4*)(sK + k_lds_off(perm_key(key), c16)) = kreg[i];
-    }
-#pragma unroll
-    for (int u = 0; u < VUN; ++u) {
-      const int unit = tid + u * NT, dg = unit & 15, kg = unit >> 4;
-      const uint32_t* r0 = (const uint32_t*)&vreg[u][0];
-      const uint32_t* r1 = (const uint32_t*)&vreg[u][1];
-      const uint32_t* r2 = (const uint32_t*)&vreg[u][2];
-      const uint32_t* r3 = (const uint32_t*)&vreg[u][3];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int w = e >> 1;
-        uint2 t2;
-        if (e & 1) {
-          t2.x = (r0[w] >> 16) | (r1[w] & 0xffff0000u);
-          t2.y = (r2[w] >> 16) | (r3[w] & 0xffff0000u);
-        } else {
-          t2.x = (r0[w] & 0xffffu) | (r1[w] << 16);
-          t2.y = (r2[w] & 0xffffu) | (r3[w] << 16);
-        }
-        const int dv = dg * 8 + e;
-        *(uint2*)(sV + vt_lds_off(dv, kg >> 1) + ((kg & 1) << 3)) = t2;
-      }
+      *(uint4*)(buf + k_lds_off(perm_key(key), c16)) = kreg[i];
+      *(uint4*)(buf + K_BYTES + key * VROW + c16 * 16) = vreg[i];
     }
   };
 
   if (n_tiles > 0) issue_loads(0);
+
+  // this lane's query row
+  const int row = rt * ROWS_WG + wave * 32 + l32;
+  const bool rvalid = row < n_rows;
+  const int rr = rvalid ? row : n_rows - 1;
+  const int qi = rr / G, hg = rr % G;
+  const int limit = min(causal ? slot0 + qi : n_kv - 1, k_end - 1);
+  bf16x8 qf[8];
+  {
+    const __hip_bfloat16* qp = q + ((size_t)qi * n_q_heads + hk * G + hg) * D + hh * 8;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      uint4 raw = rvalid ? *(const uint4*)(qp + kk * 16) : make_uint4(0, 0, 0, 0);
+      qf[kk] = *(bf16x8*)&raw;
+    }
+  }
+
+  f32x16 oacc[4];
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+
+  if (n_tiles > 0) store_tile(smem);
+  __syncthreads();
+
+  // lane geometry of the V^T transpose reads: 16-lane group g16 covers dims 16 (g16 & 1) + j of a 32-dim
+  // block and keys 8 (g16 >> 1) + e (+4 for the second read) of a 16-key step
+  const int j16 = lane & 15, g16 = lane >> 4;
+  const int v_lane_off = (8 * (g16 >> 1) + (j16 >> 2)) * VROW + (16 * (g16 & 1) + 4 * (j16 & 3)) * 2;
+
   for (int t = 0; t < n_tiles; ++t) {
-    __syncthreads();  // everyone is done reading the previous tile
-    store_tile();
-    __syncthreads();
+    const char* sK = smem + (t & 1) * BUF_BYTES;
+    const char* sV = sK + K_BYTES;
     if (t + 1 < n_tiles) issue_loads(t + 1);
     const int kt0 = k_begin + t * TK;
 
-    // S^T = K Q^T for 2 blocks of 32 keys x RB blocks of 32 rows
-    f32x16 sacc[RB][2];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) sacc[rb][kb][r] = 0.f;
+    // S^T = K Q^T for 2 blocks of 32 keys
+    f32x16 sacc[2];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
+      for (int r = 0; r < 16; ++r) sacc[kb][r] = 0.f;
+#pragma unroll
       for (int kk = 0; kk < 8; ++kk) {
         const bf16x8 a = *(const bf16x8*)(sK + k_lds_off(kb * 32 + l32, 2 * kk + hh));
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-          sacc[rb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[rb][kk], sacc[rb][kb], 0, 0, 0);
+        sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk], sacc[kb], 0, 0, 0);
       }
     }
 
     // online softmax, one query row per lane.  Register r of key block kb holds key
     // kt0 + 32 kb + 16 (r / 8) + 8 hh + r % 8.
     const bool need_mask = kt0 + TK - 1 > (causal ? slot0 + (rt * ROWS_WG) / G : n_kv - 1) || kt0 + TK > k_end;
-    bf16x8 pf[RB][4];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-      if (need_mask) {
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int key = kt0 + 32 * kb + 16 * (r >> 3) + 8 * hh + (r & 7);
-            if (key > limit[rb]) sacc[rb][kb][r] = -INFINITY;
-          }
-      }
-      float mx = -INFINITY;
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[rb][kb][r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m_run[rb], mx);
-      const float m_use = m_new == -INFINITY ? 0.f : m_new;
-      const float alpha = exp2f((m_run[rb] - m_use) * c_log2);
-      const float mc = m_use * c_log2;
-      float psum = 0.f;
+    if (need_mask) {
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const float p = exp2f(fmaf(sacc[rb][kb][r], c_log2, -mc));
-          psum += p;
-          pf[rb][kb * 2 + (r >> 3)][r & 7] = (__bf16)p;
+          const int key = kt0 + 32 * kb + 16 * (r >> 3) + 8 * hh + (r & 7);
+          if (key > limit) sacc[kb][r] = -INFINITY;
         }
-      l_run[rb] = l_run[rb] * alpha + psum;
-      if (__any(m_new > m_run[rb])) {
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) oacc[rb][db][r] *= alpha;
-      }
-      m_run[rb] = m_new;
     }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kb][r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m_run, mx);
+    const float m_use = m_new == -INFINITY ? 0.f : m_new;   // a row may be fully masked in this tile
+    const float alpha = __builtin_amdgcn_exp2f((m_run - m_use) * c_log2);
+    const float mc = m_use * c_log2;
+    float psum = 0.f;
+    bf16x8 pf[4];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float p = __builtin_amdgcn_exp2f(fmaf(sacc[kb][r], c_log2, -mc));
+        psum += p;
+        pf[kb * 2 + (r >> 3)][r & 7] = (__bf16)p;
+      }
+    l_run = l_run * alpha + psum;
+    if (__any(m_new > m_run)) {
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+    }
+    m_run = m_new;
 
     // O^T += V^T P^T : 4 blocks of 32 dims, 4 steps of 16 keys
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
 #pragma unroll
       for (int db = 0; db < 4; ++db) {
-        const bf16x8 a = *(const bf16x8*)(sV + vt_lds_off(db * 32 + l32, 2 * ks + hh));
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-          oacc[rb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[rb][ks], oacc[rb][db], 0, 0, 0);
+        const int off = v_lane_off + 16 * ks * VROW + 64 * db;
+        const v4i16 a0 = lds_read_tr(sV, off), a1 = lds_read_tr(sV, off + 4 * VROW);
+        const v8i16 a8 = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
+        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)&a8, pf[ks], oacc[db], 0, 0, 0);
       }
     }
+
+    if (t + 1 < n_tiles) store_tile(smem + ((t + 1) & 1) * BUF_BYTES);
+    __syncthreads();
   }
 
-  // epilogue: lane holds row l32 of each block, dims 32 db + 8 (r / 4) + 4 hh + r % 4
+  // epilogue: lane holds its row, dims 32 db + 8 (r / 4) + 4 hh + r % 4
+  const float l_tot = l_run + __shfl_xor(l_run, 32);
+  if (!rvalid) return;
+  const int h = hk * G + hg;
+  if (n_splits == 1) {
+    const float inv = 1.0f / l_tot;
+    __hip_bfloat16* op = out + ((size_t)qi * n_q_heads + h) * D;
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb) {
-    const float l_tot = l_run[rb] + __shfl_xor(l_run[rb], 32);
-    if (!rvalid[rb]) continue;
-    const int h = hk * G + hg[rb];
-    if (n_splits == 1) {
-      const float inv = 1.0f / l_tot;
-      __hip_bfloat16* op = out + ((size_t)qi[rb] * n_q_heads + h) * D;
+    for (int db = 0; db < 4; ++db)
 #pragma unroll
-      for (int db = 0; db < 4; ++db)
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const int dv = 32 * db + 8 * r4 + 4 * hh;
+        __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 pk;
 #pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          const int dv = 32 * db + 8 * r4 + 4 * hh;
-          __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 pk;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) pk[e] = (__bf16)(oacc[rb][db][r4 * 4 + e] * inv);
-          *(uint2*)(op + dv) = *(uint2*)&pk;
-        }
-    } else {
-      const size_t p = ((size_t)qi[rb] * n_splits + sp) * n_q_heads + h;
-      float* po = part_o + p * D;
-#pragma unroll
-      for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          const int dv = 32 * db + 8 * r4 + 4 * hh;
-          *(float4*)(po + dv) = make_float4(oacc[rb][db][r4 * 4], oacc[rb][db][r4 * 4 + 1], oacc[rb][db][r4 * 4 + 2],
-                                            oacc[rb][db][r4 * 4 + 3]);
-        }
-      if (hh == 0) {
-        part_ml[p * 2] = m_run[rb] == -INFINITY ? -INFINITY : m_run[rb] * c_log2;
-        part_ml[p * 2 + 1] = l_tot;
+        for (int e = 0; e < 4; ++e) pk[e] = (__bf16)(oacc[db][r4 * 4 + e] * inv);
+        *(uint2*)(op + dv) = *(uint2*)&pk;
       }
+  } else {
+    const size_t p = ((size_t)qi * n_splits + sp) * n_q_heads + h;
+    float* po = part_o + p * D;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const int dv = 32 * db + 8 * r4 + 4 * hh;
+        *(float4*)(po + dv) = make_float4(oacc[db][r4 * 4], oacc[db][r4 * 4 + 1], oacc[db][r4 * 4 + 2],
+                                          oacc[db][r4 * 4 + 3]);
+      }
+    if (hh == 0) {
+      part_ml[p * 2] = m_run == -INFINITY ? -INFINITY : m_run * c_log2;
+      part_ml[p * 2 + 1] = l_tot;
     }
   }
 }
@@ -295,17 +262,26 @@ int env_int(const char* name, int dflt) {
   return v && *v ? std::atoi(v) : dflt;
 }
 
-template <int NW, int RB>
+template <int NW>
 hipError_t launch_t(const sv_cache* c, int stream, int layer, const void* q, int n_q, void* o, int causal,
                     hipStream_t s) {
-  constexpr int ROWS_WG = NW * RB * 32;
+  constexpr int ROWS_WG = NW * 32;
+  constexpr int kLds = 2 * BUF_BYTES;
+  static bool attr_set = false;   // more than 64 KB of LDS has to be asked for once per kernel
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)k_attn_chunk_mfma<NW>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       kLds);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
   const StreamState& st = c->st[stream];
   const int n_kv = (int)st.len, G = c->group, Hkv = c->cfg.n_kv_heads;
   const int row_tiles = (n_q * G + ROWS_WG - 1) / ROWS_WG;
   int n_splits = env_int("SV_CHUNK_SPLITS", 0);
   if (n_splits <= 0) {
-    const int n_cu = 256;
-    n_splits = std::max(1, n_cu / std::max(1, row_tiles * Hkv));
+    // fill 256 CUs with 8 wavefronts each (one workgroup of 8 or two of 4)
+    const int slots = 256 * (8 / NW);
+    n_splits = std::max(1, slots / std::max(1, row_tiles * Hkv));
     n_splits = std::min(n_splits, std::max(1, n_kv / (4 * TK)));
   }
   n_splits = std::min<int64_t>(n_splits, std::max<int64_t>(1, c->part_rows / n_q));
@@ -314,7 +290,7 @@ hipError_t launch_t(const sv_cache* c, int stream, int layer, const void* q, int
   n_splits = (n_kv + keys_per_split - 1) / keys_per_split;
   const float c_log2 = 1.4426950408889634f / sqrtf((float)D);
   dim3 grid(row_tiles, Hkv, n_splits);
-  hipLaunchKernelGGL((k_attn_chunk_mfma<NW, RB>), grid, dim3(NW * 64), 0, s, (const __hip_bfloat16*)q,
+  hipLaunchKernelGGL((k_attn_chunk_mfma<NW>), grid, dim3(NW * 64), kLds, s, (const __hip_bfloat16*)q,
                      (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 0),
                      (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 1), (__hip_bfloat16*)o, c->part_o,
                      c->part_ml, n_q, n_kv, causal ? 1 : 0, n_splits, keys_per_split, c->cfg.n_q_heads, G,
@@ -332,12 +308,10 @@ bool attn_mfma_supported(const sv_cache* c) {
 
 hipError_t launch_attn_chunk_mfma(const sv_cache* c, int stream, int layer, const void* q, int n_q, void* o,
                                   int causal, hipStream_t s) {
-  const int variant = env_int("SV_CHUNK_VARIANT", 0);
-  switch (variant) {
-    case 1: return launch_t<2, 2>(c, stream, layer, q, n_q, o, causal, s);
-    case 3: return launch_t<4, 2>(c, stream, layer, q, n_q, o, causal, s);
-    default: return launch_t<4, 1>(c, stream, layer, q, n_q, o, causal, s);
-  }
+  // two workgroups of 4 wavefronts per CU measured a little faster than one of 8 on both chunk sizes
+  const int variant = env_int("SV_CHUNK_VARIANT", 1);
+  if (variant == 0) return launch_t<8>(c, stream, layer, q, n_q, o, causal, s);
+  return launch_t<4>(c, stream, layer, q, n_q, o, causal, s);
 }
 
 }  // namespace sv
