@@ -25,6 +25,12 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on the default workload, scaled by
+# what a plain 1 GiB copy reads on the same counters (fetch x2.00, write x1.00); profiles/hbm_traffic_*.txt.
+MEASURED_TRAFFIC = {
+    "qwen7b_256v_28L": {"attn_chunk": 73.6e6 + 31.6e6, "decode_sweep": 9.3e6 + 0.27e6, "evict": 323.5e6 + 289.8e6},
+}
+
 
 def parse_args():
     ap = argparse.ArgumentParser()
@@ -36,6 +42,9 @@ def parse_args():
     ap.add_argument("--layers", type=int, default=28)
     ap.add_argument("--pool", type=int, default=6, help="distinct pre-generated chunks cycled through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (a kernel of known traffic, for scaling rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE readings)")
     return ap.parse_args()
 
 
@@ -103,7 +112,8 @@ def main():
     steady = cache.len(0) == R + w.tokens_per_chunk
 
     # second region, same work per chunk, driven call by call so that HIP events can bracket each kernel class
-    inst = instrumented_pass(cache, run, pool, w, L, args.warmup + args.steps, ov, ot, n_chunks=min(10, args.steps))
+    inst = instrumented_pass(cache, run, pool, w, L, args.warmup + args.steps, ov, ot, n_chunks=min(10, args.steps),
+                             traffic=MEASURED_TRAFFIC.get(args.workload if L == 28 else "", {}))
     roofs = inst["roofline_all"]
     dominant = max(roofs, key=lambda r: r["total_us_per_chunk"])
     roofline = {k: dominant[k] for k in ("kernel", "bound", "achieved", "peak", "unit", "frac", "traffic",
@@ -125,6 +135,11 @@ def main():
         "roofline": roofline,
         "roofline_all": roofs,
     }
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
+        dst = torch.empty_like(src)
+        dst.copy_(src)                       # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(L)
     print(json.dumps(out))
@@ -193,7 +208,7 @@ def decode_batch_bench(args):
     }
 
 
-def instrumented_pass(cache, run, pool, w, L, c0, ov, ot, n_chunks: int):
+def instrumented_pass(cache, run, pool, w, L, c0, ov, ot, n_chunks: int, traffic=None):
     """Same per-chunk work through the individual C calls, HIP events (torch's current stream, the one the
     kernels are launched on) around every evict, every chunk-prefill attention launch and every 28-layer
     sweep of the fused decode kernel."""
@@ -244,7 +259,7 @@ def instrumented_pass(cache, run, pool, w, L, c0, ov, ot, n_chunks: int):
         n_launch = len(rec[key]) * launches_per_event
         achieved = sum(units[key]) / (tot[key] * 1e-6) / scale if tot[key] > 0 else 0.0
         return {"kernel": kernel, "bound": bound, "achieved": round(achieved, 2), "peak": peak, "unit": unit,
-                "frac": round(achieved / peak, 4), "traffic": None,
+                "frac": round(achieved / peak, 4), "traffic": (traffic or {}).get(key),
                 "avg_launch_us": round(tot[key] / max(n_launch, 1), 2), "launches": n_launch,
                 "total_us_per_chunk": round(tot[key] / n_chunks, 1)}
 
