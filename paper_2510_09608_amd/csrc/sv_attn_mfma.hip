@@ -31,6 +31,7 @@
 
 #include <algorithm>
 #include <cstdlib>
+#include <type_traits>
 
 #include "sv_internal.h"
 
@@ -257,20 +258,286 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_mfma(
   }
 }
 
+// ---------------------------------------------------------------------------------
+// Pipelined variant (8 wavefronts, one workgroup per CU).
+//   * K/V tiles go from HBM to LDS with the direct global -> LDS load (16 bytes per lane, lane L lands at
+//     base + 16 L; confirmed on the device), so staging costs no registers and no LDS store instructions.  The
+//     swizzles are applied on the global side: each lane fetches the chunk that belongs at its LDS position.
+//       K: LDS row m holds key perm_key(m); position p of the row holds chunk p ^ (m & 15).
+//       V: LDS row = key; position p holds chunk p ^ (4 (key & 3)), which puts the 4 rows x 64 bytes that
+//          32 lanes of a transpose read touch into distinct banks without padding.
+//   * Four LDS slots per tensor: in iteration t tiles t-1 .. t+1 may be read while tile t+2 arrives.
+//   * The matrix-core work of an iteration (scores of one tile, output of another) does not depend on the
+//     softmax running in the same iteration; LDS operands are fetched one batch ahead of the MFMAs that use them.
+// ---------------------------------------------------------------------------------
+constexpr int PIPE_SLOTS = 4;
+constexpr int PIPE_TILE = TK * D * 2;   // 16 KB per tile, unpadded
+constexpr int PIPE_LDS = 2 * PIPE_SLOTS * PIPE_TILE;
+
+__device__ __forceinline__ void dma16(const void* gsrc, char* lds_dst) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
+                                   (__attribute__((address_space(3))) void*)(__attribute__((address_space(3))) char*)lds_dst,
+                                   16, 0, 0);
+}
+
+template <int NW>
+__global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
+    const __hip_bfloat16* __restrict__ q, const __hip_bfloat16* __restrict__ kc, const __hip_bfloat16* __restrict__ vc,
+    __hip_bfloat16* __restrict__ out, float* __restrict__ part_o, float* __restrict__ part_ml, int n_q, int n_kv,
+    int causal, int n_splits, int keys_per_split, int n_q_heads, int G, size_t head_stride_elems, float c_log2,
+    int phase_mode) {
+  constexpr int ROWS_WG = NW * 32;
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  char* const sKbase = smem;
+  char* const sVbase = smem + PIPE_SLOTS * PIPE_TILE;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, hh = lane >> 5;
+  const int rt = blockIdx.x, hk = blockIdx.y, sp = blockIdx.z;
+  const int slot0 = n_kv - n_q;
+  const int n_rows = n_q * G;
+
+  const int row_last = min(n_rows, (rt + 1) * ROWS_WG) - 1;
+  const int k_begin = sp * keys_per_split;
+  int k_end = min(n_kv, k_begin + keys_per_split);
+  if (causal) k_end = min(k_end, slot0 + row_last / G + 1);
+  const int n_tiles = k_end > k_begin ? (k_end - k_begin + TK - 1) / TK : 0;
+  if (n_tiles == 0) {   // nothing visible in this key range: an empty partial
+    const int row = rt * ROWS_WG + wave * 32 + l32;
+    if (row < n_rows && n_splits > 1) {
+      const size_t p = ((size_t)(row / G) * n_splits + sp) * n_q_heads + hk * G + row % G;
+      for (int d = hh * 64; d < hh * 64 + 64; d += 4) *(float4*)(part_o + p * D + d) = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (hh == 0) part_ml[p * 2] = -INFINITY, part_ml[p * 2 + 1] = 0.f;
+    }
+    return;
+  }
+
+  const __hip_bfloat16* kbase = kc + (size_t)hk * head_stride_elems;
+  const __hip_bfloat16* vbase = vc + (size_t)hk * head_stride_elems;
+
+  // tile t -> LDS slot t & 3.  Rows past the key range re-read the last row (finite values, masked keys).
+  auto dma_tile = [&](int t) {
+    const int kt0 = k_begin + t * TK;
+    char* kslot = sKbase + (t & (PIPE_SLOTS - 1)) * PIPE_TILE;
+    char* vslot = sVbase + (t & (PIPE_SLOTS - 1)) * PIPE_TILE;
+#pragma unroll
+    for (int i = 0; i < 16 / NW; ++i) {
+      const int wi = wave + i * NW;            // this instruction fills LDS rows 4 wi .. 4 wi + 3
+      const int m = 4 * wi + (lane >> 4), p = lane & 15;
+      const int gk = min(kt0 + perm_key(m), k_end - 1);
+      dma16(kbase + (size_t)gk * D + ((p ^ (m & 15)) << 3), kslot + wi * 1024);
+      const int gv = min(kt0 + m, k_end - 1);
+      dma16(vbase + (size_t)gv * D + ((p ^ ((m & 3) << 2)) << 3), vslot + wi * 1024);
+    }
+  };
+
+  dma_tile(0);
+  dma_tile(1);
+
+  const int row = rt * ROWS_WG + wave * 32 + l32;
+  const bool rvalid = row < n_rows;
+  const int rr = rvalid ? row : n_rows - 1;
+  const int qi = rr / G, hg = rr % G;
+  const int limit = min(causal ? slot0 + qi : n_kv - 1, k_end - 1);
+  const int wg_first_limit = causal ? slot0 + (rt * ROWS_WG) / G : n_kv - 1;
+  bf16x8 qf[8];
+  {
+    const __hip_bfloat16* qp = q + ((size_t)qi * n_q_heads + hk * G + hg) * D + hh * 8;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      uint4 raw = rvalid ? *(const uint4*)(qp + kk * 16) : make_uint4(0, 0, 0, 0);
+      qf[kk] = *(bf16x8*)&raw;
+    }
+  }
+
+  f32x16 oacc[4];
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+
+  // V^T transpose-read geometry: 16-lane group g16 covers dims 16 (g16 & 1) + j of a 32-dim block and keys
+  // 8 (g16 >> 1) + e of a 16-key step; x = row & 3 selects the swizzle of the 64-byte segment
+  const int j16 = lane & 15, g16 = lane >> 4, vx = j16 >> 2;
+  const int v_lane_off = (8 * (g16 >> 1) + vx) * 256 + ((2 * (g16 & 1) + ((j16 & 3) >> 1)) << 4) + (j16 & 1) * 8;
+  int v_db_off[4];
+#pragma unroll
+  for (int db = 0; db < 4; ++db) v_db_off[db] = (db ^ vx) << 6;
+  const bool mfma_first = phase_mode == 0 ? true : (phase_mode == 1 ? ((wave >> 2) & 1) == 0 : (wave & 1) == 0);
+
+  auto softmax = [&](auto masked, int t, f32x16 (&sacc)[2], bf16x8 (&pf)[4], bool& changed) -> float {
+    const int kt0 = k_begin + t * TK;
+    if constexpr (decltype(masked)::value) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = kt0 + 32 * kb + 16 * (r >> 3) + 8 * hh + (r & 7);
+          if (key > limit) sacc[kb][r] = -INFINITY;
+        }
+    }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kb][r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m_run, mx);
+    const float m_use = m_new == -INFINITY ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f((m_run - m_use) * c_log2);
+    const float mc = m_use * c_log2;
+    float psum = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float p = __builtin_amdgcn_exp2f(fmaf(sacc[kb][r], c_log2, -mc));
+        psum += p;
+        pf[kb * 2 + (r >> 3)][r & 7] = (__bf16)p;
+      }
+    l_run = l_run * alpha + psum;
+    changed = __any(m_new > m_run);
+    m_run = m_new;
+    return alpha;
+  };
+  auto rescale = [&](float alpha) {
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+  };
+  auto qk_block = [&](int t, f32x16 (&sacc)[2]) {   // S^T of tile t
+    const char* sK = sKbase + (t & (PIPE_SLOTS - 1)) * PIPE_TILE;
+    bf16x8 fa[2][4];
+    auto fetch = [&](int b, bf16x8 (&f)[4]) {   // fragments kk = 2b, 2b+1 of key blocks 0 and 1
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        f[i] = *(const bf16x8*)(sK + k_lds_off((i & 1) * 32 + l32, 2 * (2 * b + (i >> 1)) + hh));
+    };
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sacc[kb][r] = 0.f;
+    fetch(0, fa[0]);
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+      if (b + 1 < 4) fetch(b + 1, fa[(b + 1) & 1]);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        sacc[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[b & 1][i], qf[2 * b + (i >> 1)], sacc[i & 1], 0, 0, 0);
+    }
+  };
+  auto pv_block = [&](int t, const bf16x8 (&pf)[4]) {   // O^T += V^T(tile t) P^T
+    const char* sV = sVbase + (t & (PIPE_SLOTS - 1)) * PIPE_TILE + v_lane_off;
+    bf16x8 fa[2][4];
+    auto fetch = [&](int ks, bf16x8 (&f)[4]) {
+#pragma unroll
+      for (int db = 0; db < 4; ++db) {
+        const int off = 16 * ks * 256 + v_db_off[db];
+        const v4i16 a0 = lds_read_tr(sV, off), a1 = lds_read_tr(sV, off + 4 * 256);
+        const v8i16 a8 = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
+        f[db] = *(const bf16x8*)&a8;
+      }
+    };
+    fetch(0, fa[0]);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      if (ks + 1 < 4) fetch(ks + 1, fa[(ks + 1) & 1]);
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][db], pf[ks], oacc[db], 0, 0, 0);
+    }
+  };
+  auto arrive = [&]() {   // this wavefront's direct loads have landed; then everybody's
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+    __syncthreads();
+  };
+
+  // "matrix first":  iteration t = [S(t) = QK(t), O += PV(t-1)] then softmax(t)
+  // "softmax first": iteration t = softmax(t) (S(t) from the previous iteration) then [O += PV(t), S(t+1)]
+  f32x16 sacc[2];
+  bf16x8 pf[4];
+  bool changed;
+  const int full_keys = min(wg_first_limit + 1, k_end) - k_begin;   // tiles every row of the workgroup sees whole
+  const int n_full = full_keys > 0 ? min(full_keys / TK, n_tiles) : 0;
+  arrive();
+  if (mfma_first) {
+    auto iter = [&](auto masked, int t) {
+      dma_tile(t + 2);
+      qk_block(t, sacc);
+      if (t > 0) pv_block(t - 1, pf);
+      const float alpha = softmax(masked, t, sacc, pf, changed);
+      if (changed) rescale(alpha);
+      arrive();
+    };
+    int t = 0;
+    for (; t < n_full; ++t) iter(std::false_type{}, t);
+    for (; t < n_tiles; ++t) iter(std::true_type{}, t);
+    pv_block(n_tiles - 1, pf);
+  } else {
+    qk_block(0, sacc);
+    auto iter = [&](auto masked, int t) {
+      dma_tile(t + 2);
+      const float alpha = softmax(masked, t, sacc, pf, changed);
+      if (changed) rescale(alpha);
+      pv_block(t, pf);
+      if (t + 1 < n_tiles) qk_block(t + 1, sacc);
+      arrive();
+    };
+    int t = 0;
+    for (; t < n_full; ++t) iter(std::false_type{}, t);
+    for (; t < n_tiles; ++t) iter(std::true_type{}, t);
+  }
+
+  const float l_tot = l_run + __shfl_xor(l_run, 32);
+  if (!rvalid) return;
+  const int h = hk * G + hg;
+  if (n_splits == 1) {
+    const float inv = 1.0f / l_tot;
+    __hip_bfloat16* op = out + ((size_t)qi * n_q_heads + h) * D;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const int dv = 32 * db + 8 * r4 + 4 * hh;
+        __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 pk;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) pk[e] = (__bf16)(oacc[db][r4 * 4 + e] * inv);
+        *(uint2*)(op + dv) = *(uint2*)&pk;
+      }
+  } else {
+    const size_t p = ((size_t)qi * n_splits + sp) * n_q_heads + h;
+    float* po = part_o + p * D;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const int dv = 32 * db + 8 * r4 + 4 * hh;
+        *(float4*)(po + dv) = make_float4(oacc[db][r4 * 4], oacc[db][r4 * 4 + 1], oacc[db][r4 * 4 + 2],
+                                          oacc[db][r4 * 4 + 3]);
+      }
+    if (hh == 0) {
+      part_ml[p * 2] = m_run == -INFINITY ? -INFINITY : m_run * c_log2;
+      part_ml[p * 2 + 1] = l_tot;
+    }
+  }
+}
+
 int env_int(const char* name, int dflt) {
   const char* v = std::getenv(name);
   return v && *v ? std::atoi(v) : dflt;
 }
 
-template <int NW>
+template <int NW, bool PIPE>
 hipError_t launch_t(const sv_cache* c, int stream, int layer, const void* q, int n_q, void* o, int causal,
                     hipStream_t s) {
   constexpr int ROWS_WG = NW * 32;
-  constexpr int kLds = 2 * BUF_BYTES;
+  constexpr int kLds = PIPE ? PIPE_LDS : 2 * BUF_BYTES;
+  const void* kern = PIPE ? (const void*)k_attn_chunk_pipe<NW> : (const void*)k_attn_chunk_mfma<NW>;
   static bool attr_set = false;   // more than 64 KB of LDS has to be asked for once per kernel
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)k_attn_chunk_mfma<NW>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       kLds);
+    hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
@@ -280,7 +547,7 @@ hipError_t launch_t(const sv_cache* c, int stream, int layer, const void* q, int
   int n_splits = env_int("SV_CHUNK_SPLITS", 0);
   if (n_splits <= 0) {
     // fill 256 CUs with 8 wavefronts each (one workgroup of 8 or two of 4)
-    const int slots = 256 * (8 / NW);
+    const int slots = PIPE ? 256 : 256 * (8 / NW);
     n_splits = std::max(1, slots / std::max(1, row_tiles * Hkv));
     n_splits = std::min(n_splits, std::max(1, n_kv / (4 * TK)));
   }
@@ -290,11 +557,18 @@ hipError_t launch_t(const sv_cache* c, int stream, int layer, const void* q, int
   n_splits = (n_kv + keys_per_split - 1) / keys_per_split;
   const float c_log2 = 1.4426950408889634f / sqrtf((float)D);
   dim3 grid(row_tiles, Hkv, n_splits);
-  hipLaunchKernelGGL((k_attn_chunk_mfma<NW>), grid, dim3(NW * 64), kLds, s, (const __hip_bfloat16*)q,
-                     (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 0),
-                     (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 1), (__hip_bfloat16*)o, c->part_o,
-                     c->part_ml, n_q, n_kv, causal ? 1 : 0, n_splits, keys_per_split, c->cfg.n_q_heads, G,
-                     c->head_stride / 2, c_log2);
+  if constexpr (PIPE)
+    hipLaunchKernelGGL((k_attn_chunk_pipe<NW>), grid, dim3(NW * 64), kLds, s, (const __hip_bfloat16*)q,
+                       (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 0),
+                       (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 1), (__hip_bfloat16*)o, c->part_o,
+                       c->part_ml, n_q, n_kv, causal ? 1 : 0, n_splits, keys_per_split, c->cfg.n_q_heads, G,
+                       c->head_stride / 2, c_log2, env_int("SV_CHUNK_PHASE", 1));
+  else
+    hipLaunchKernelGGL((k_attn_chunk_mfma<NW>), grid, dim3(NW * 64), kLds, s, (const __hip_bfloat16*)q,
+                       (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 0),
+                       (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 1), (__hip_bfloat16*)o, c->part_o,
+                       c->part_ml, n_q, n_kv, causal ? 1 : 0, n_splits, keys_per_split, c->cfg.n_q_heads, G,
+                       c->head_stride / 2, c_log2);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || n_splits == 1) return e;
   return launch_attn_combine(c, n_q, n_splits, o, s);
@@ -310,8 +584,9 @@ hipError_t launch_attn_chunk_mfma(const sv_cache* c, int stream, int layer, cons
                                   int causal, hipStream_t s) {
   // two workgroups of 4 wavefronts per CU measured a little faster than one of 8 on both chunk sizes
   const int variant = env_int("SV_CHUNK_VARIANT", 1);
-  if (variant == 0) return launch_t<8>(c, stream, layer, q, n_q, o, causal, s);
-  return launch_t<4>(c, stream, layer, q, n_q, o, causal, s);
+  if (variant == 0) return launch_t<8, false>(c, stream, layer, q, n_q, o, causal, s);
+  if (variant == 2) return launch_t<8, true>(c, stream, layer, q, n_q, o, causal, s);
+  return launch_t<4, false>(c, stream, layer, q, n_q, o, causal, s);
 }
 
 }  // namespace sv
