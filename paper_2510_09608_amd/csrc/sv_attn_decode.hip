@@ -366,11 +366,18 @@ bool attn_decode_mfma_supported(const sv_cache* c) {
 }
 
 template <int NW>
-hipError_t decode_launch(const sv_cache* c, const DecTable& tab, int fused, int nr, int max_len, const void* q,
-                         const void* k_new, const void* v_new, void* o, size_t r0, hipStream_t s) {
+hipError_t decode_launch(const sv_cache* c, const DecTable& tab, int fused, int nr, int max_len, int64_t total_tiles,
+                         const void* q, const void* k_new, const void* v_new, void* o, size_t r0, hipStream_t s) {
   const int Hq = c->cfg.n_q_heads, Hkv = c->cfg.n_kv_heads;
-  // one 64-key tile per wavefront unless that needs more than kMaxSplitsD key ranges
-  const int tiles_per_wave = std::max(1, env_int("SV_DECODE_TILES_PER_WAVE", 2));
+  // Key tiles per wavefront.  A single stream is latency bound: one tile per wavefront spreads its few
+  // hundred tiles over the most CUs and costs one memory round trip.  A large batch is bandwidth bound:
+  // longer key ranges keep the partial results and their merge small; doubling the range while more than
+  // about 512 workgroups remain was the best point of sweeps at 16 rows of 2k..32k keys.
+  int tiles_per_wave = env_int("SV_DECODE_TILES_PER_WAVE", 0);
+  if (tiles_per_wave <= 0) {
+    tiles_per_wave = 1;
+    while (tiles_per_wave < 16 && total_tiles * Hkv > (int64_t)512 * NW * tiles_per_wave) tiles_per_wave *= 2;
+  }
   int keys_per_split = TK * NW * tiles_per_wave;
   int n_splits = (max_len + keys_per_split - 1) / keys_per_split;
   const int cap = (int)std::min<int64_t>(kMaxSplitsD, std::max<int64_t>(1, c->part_rows / nr));
@@ -399,6 +406,7 @@ hipError_t launch_attn_decode_mfma(const sv_cache* c, int layer, const int32_t* 
     const int nr = std::min(kMaxRowsD, n_list - r0);
     DecTable tab = {};
     int max_len = 1;
+    int64_t total_tiles = 0;
     for (int b = 0; b < nr; ++b) {
       const int sid = streams[r0 + b];
       const StreamState& st = c->st[sid];
@@ -407,10 +415,11 @@ hipError_t launch_attn_decode_mfma(const sv_cache* c, int layer, const int32_t* 
       tab.r[b].len = (int)st.len;
       tab.r[b].cs = c->last_cs + (size_t)sid * (D / 2);
       max_len = std::max(max_len, (int)st.len);
+      total_tiles += (st.len + TK - 1) / TK;
     }
-    hipError_t e = nw == 2   ? decode_launch<2>(c, tab, fused, nr, max_len, q, k_new, v_new, o, (size_t)r0, s)
-                   : nw == 1 ? decode_launch<1>(c, tab, fused, nr, max_len, q, k_new, v_new, o, (size_t)r0, s)
-                             : decode_launch<4>(c, tab, fused, nr, max_len, q, k_new, v_new, o, (size_t)r0, s);
+    hipError_t e = nw == 2   ? decode_launch<2>(c, tab, fused, nr, max_len, total_tiles, q, k_new, v_new, o, (size_t)r0, s)
+                   : nw == 1 ? decode_launch<1>(c, tab, fused, nr, max_len, total_tiles, q, k_new, v_new, o, (size_t)r0, s)
+                             : decode_launch<4>(c, tab, fused, nr, max_len, total_tiles, q, k_new, v_new, o, (size_t)r0, s);
     if (e != hipSuccess) return e;
   }
   return hipSuccess;

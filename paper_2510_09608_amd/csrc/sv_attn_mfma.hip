@@ -582,8 +582,9 @@ bool attn_mfma_supported(const sv_cache* c) {
 
 hipError_t launch_attn_chunk_mfma(const sv_cache* c, int stream, int layer, const void* q, int n_q, void* o,
                                   int causal, hipStream_t s) {
-  // two workgroups of 4 wavefronts per CU measured a little faster than one of 8 on both chunk sizes
-  const int variant = env_int("SV_CHUNK_VARIANT", 1);
+  // the pipelined kernel (tiles brought to LDS by direct loads) measured fastest on both chunk sizes; the
+  // register-staged kernels stay selectable for comparison
+  const int variant = env_int("SV_CHUNK_VARIANT", 2);
   if (variant == 0) return launch_t<8, false>(c, stream, layer, q, n_q, o, causal, s);
   if (variant == 2) return launch_t<8, true>(c, stream, layer, q, n_q, o, causal, s);
   return launch_t<4, false>(c, stream, layer, q, n_q, o, causal, s);
