@@ -40,7 +40,7 @@ bool config_ok(const sv_config* c) {
 // sv_cache_bytes and sv_cache_create cannot disagree.
 struct Layout {
   size_t kv, meta_gid[2], meta_rank[2], meta_pos[2], meta_local[2], meta_blk[2], meta_type[2];
-  size_t src, delta, dtab, next_pos, n_dev, inv_freq, last_cs, part_o, part_ml, counters, total;
+  size_t src, delta, dtab, next_pos, n_dev, inv_freq, last_cs, part_o, part_ml, counters, vt, total;
   int64_t part_rows;
 };
 
@@ -74,6 +74,8 @@ Layout make_layout(const sv_config& c) {
   L.part_o = take((size_t)L.part_rows * c.n_q_heads * c.head_dim * 4);
   L.part_ml = take((size_t)L.part_rows * c.n_q_heads * 2 * 4);
   L.counters = take((size_t)L.part_rows * c.n_kv_heads * 4);
+  // V^T staging of one layer per stream (chunk prefill on the matrix cores): blocks of 64 keys, [head_dim][64]
+  L.vt = take(S * (size_t)c.n_kv_heads * ((cap + 63) / 64) * 64 * (size_t)c.head_dim * es);
   L.total = off;
   return L;
 }
@@ -170,6 +172,8 @@ int sv_cache_create(const sv_config* cfg, void* dev_arena, size_t arena_bytes, v
   c->part_ml = (float*)(base + L.part_ml);
   c->part_rows = L.part_rows;
   c->counters = (int32_t*)(base + L.counters);
+  c->vt = base + L.vt;
+  c->vt_stream_stride = (size_t)cfg->n_kv_heads * (((size_t)cfg->capacity_tokens + 63) / 64) * 64 * (size_t)cfg->head_dim * c->esize;
   c->st.resize(cfg->n_streams);
   for (auto& s : c->st) s.layer_len.assign(cfg->n_layers, 0);
 

@@ -274,10 +274,54 @@ constexpr int PIPE_SLOTS = 4;
 constexpr int PIPE_TILE = TK * D * 2;   // 16 KB per tile, unpadded
 constexpr int PIPE_LDS = 2 * PIPE_SLOTS * PIPE_TILE;
 
-__device__ __forceinline__ void dma16(const void* gsrc, char* lds_dst) {
-  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
-                                   (__attribute__((address_space(3))) void*)(__attribute__((address_space(3))) char*)lds_dst,
-                                   16, 0, 0);
+// ---------------------------------------------------------------------------------
+// V^T staging for the pipelined kernel.  The second product wants V^T fragments (one head dim, 8
+// consecutive keys per lane); read from a row-major V tile that costs two half-rate LDS transpose reads per
+// fragment in EVERY wavefront of every workgroup that shares the tile.  This pass transposes each 64-key
+// block of the layer's V once, into vt[kv head][block][head dim][64 keys]; the attention kernel then
+// brings V^T tiles to LDS with direct loads and reads fragments with plain 16-byte reads.  Keys past the
+// cache length are written as zeros (they are masked, but must be finite).
+// grid: (blocks of 64 keys, kv heads), block: 256 threads.
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_vt_build(const __hip_bfloat16* __restrict__ vc, __hip_bfloat16* __restrict__ vt,
+                                                  int n_kv, size_t head_stride_elems, size_t vt_head_stride_elems) {
+  __shared__ __attribute__((aligned(16))) char sT[TK * VROW];
+  const int blk = blockIdx.x, hk = blockIdx.y, tid = threadIdx.x;
+  const __hip_bfloat16* src = vc + (size_t)hk * head_stride_elems + (size_t)blk * TK * D;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int cid = tid + 256 * i, key = cid >> 4, c16 = cid & 15;
+    const uint4 v = blk * TK + key < n_kv ? *(const uint4*)(src + (size_t)key * D + c16 * 8) : make_uint4(0, 0, 0, 0);
+    *(uint4*)(sT + key * VROW + c16 * 16) = v;
+  }
+  __syncthreads();
+  const int wave = tid >> 6, lane = tid & 63, j16 = lane & 15, g = lane >> 4;
+  __hip_bfloat16* dst = vt + (size_t)hk * vt_head_stride_elems + (size_t)blk * TK * D;
+#pragma unroll
+  for (int ko = 0; ko < 2; ++ko)
+#pragma unroll
+    for (int ds = 0; ds < 2; ++ds) {
+      const int r0 = 16 * wave + 8 * ko, c0 = 64 * ds + 16 * g;
+      const int off = (r0 + (j16 >> 2)) * VROW + (c0 + 4 * (j16 & 3)) * 2;
+      const v4i16 a0 = lds_read_tr(sT, off), a1 = lds_read_tr(sT, off + 4 * VROW);
+      const v8i16 a8 = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
+      *(v8i16*)(dst + (size_t)(c0 + j16) * TK + r0) = a8;   // head dim c0 + j16, keys r0 .. r0 + 7
+    }
+}
+
+// 16 bytes per lane from global memory straight into LDS: lane L's bytes land at lds_dst + 16 L (lds_dst is
+// uniform over the wavefront and travels in M0).  Written as assembly on purpose: the compiler then does not
+// see a pending write to LDS and inserts no wait for ALL outstanding direct loads in front of later LDS
+// reads; the kernel waits itself (vmcnt(0), then a workgroup barrier) before a tile is first read.
+__device__ __forceinline__ void dma16(const void* base, uint32_t lane_off, char* lds_dst) {
+  // base (uniform) travels in a scalar register pair, the lane's byte offset in one VGPR
+  const uint32_t l = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds_dst);
+  const uint64_t b = (uint64_t)base;
+  // (the builtin returns a signed int: convert each half through uint32_t, or the low half sign-extends)
+  const uint64_t bu = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(b >> 32)) << 32) |
+                      (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)b);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(l), "v"(lane_off), "s"(bu)
+               : "memory", "m0");
 }
 
 template <int NW>
@@ -285,13 +329,13 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
     const __hip_bfloat16* __restrict__ q, const __hip_bfloat16* __restrict__ kc, const __hip_bfloat16* __restrict__ vc,
     __hip_bfloat16* __restrict__ out, float* __restrict__ part_o, float* __restrict__ part_ml, int n_q, int n_kv,
     int causal, int n_splits, int keys_per_split, int n_q_heads, int G, size_t head_stride_elems, float c_log2,
-    int phase_mode) {
+    int phase_mode, const __hip_bfloat16* __restrict__ vt, size_t vt_head_stride_elems) {
   constexpr int ROWS_WG = NW * 32;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   char* const sKbase = smem;
   char* const sVbase = smem + PIPE_SLOTS * PIPE_TILE;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hh = lane >> 5;
   const int rt = blockIdx.x, hk = blockIdx.y, sp = blockIdx.z;
   const int slot0 = n_kv - n_q;
@@ -313,26 +357,49 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
   }
 
   const __hip_bfloat16* kbase = kc + (size_t)hk * head_stride_elems;
-  const __hip_bfloat16* vbase = vc + (size_t)hk * head_stride_elems;
+  const __hip_bfloat16* vtbase = vt + (size_t)hk * vt_head_stride_elems;
 
-  // tile t -> LDS slot t & 3.  Rows past the key range re-read the last row (finite values, masked keys).
-  auto dma_tile = [&](int t) {
-    const int kt0 = k_begin + t * TK;
-    char* kslot = sKbase + (t & (PIPE_SLOTS - 1)) * PIPE_TILE;
-    char* vslot = sVbase + (t & (PIPE_SLOTS - 1)) * PIPE_TILE;
+  // tile t -> LDS slot t & 3; each tile is 16 / NW direct-load instructions per wavefront, instruction wi
+  // filling 1 KB of the slot.  The lane's source offset inside a tile does not depend on the tile:
+  //   K:   LDS row m = 4 wi + lane / 16 holds key perm_key(m), its 16-byte chunks XOR-swizzled by m & 15;
+  //   V^T: LDS row d = 8 wi + lane / 8 (128 bytes: 8 chunks of 8 keys); chunk c sits at position
+  //        c ^ ((d >> 1) & 7), so that 16 lanes reading one chunk index of 16 consecutive rows touch 16
+  //        distinct 16-byte bank groups.
+  // Tiles past the range re-read the last one.  The last K tile may run up to 63 rows past the key range:
+  // those rows are other rows of the cache arena (K is never its last tensor), and their scores are
+  // replaced, not scaled, by the mask.  V^T blocks are zero-padded by the staging pass.
+  uint32_t k_lane_off[16 / NW], v_lane_off[16 / NW];
 #pragma unroll
-    for (int i = 0; i < 16 / NW; ++i) {
-      const int wi = wave + i * NW;            // this instruction fills LDS rows 4 wi .. 4 wi + 3
-      const int m = 4 * wi + (lane >> 4), p = lane & 15;
-      const int gk = min(kt0 + perm_key(m), k_end - 1);
-      dma16(kbase + (size_t)gk * D + ((p ^ (m & 15)) << 3), kslot + wi * 1024);
-      const int gv = min(kt0 + m, k_end - 1);
-      dma16(vbase + (size_t)gv * D + ((p ^ ((m & 3) << 2)) << 3), vslot + wi * 1024);
-    }
+  for (int i = 0; i < 16 / NW; ++i) {
+    const int wi = wave + i * NW;
+    const int m = 4 * wi + (lane >> 4), p = lane & 15;
+    k_lane_off[i] = (uint32_t)(perm_key(m) * (D * 2) + ((p ^ (m & 15)) << 4));
+    const int dd = 8 * wi + (lane >> 3), c = (lane & 7) ^ ((dd >> 1) & 7);
+    v_lane_off[i] = (uint32_t)(dd * (TK * 2) + (c << 4));
+  }
+  const char* const k_tiles = (const char*)(kbase + (size_t)k_begin * D);
+  const char* const v_tiles = (const char*)(vtbase + (size_t)(k_begin / TK) * (TK * D));
+  auto dma_tile = [&](int which, int t) {
+    const int te = min(t, n_tiles - 1);
+    char* slot = (which ? sVbase : sKbase) + (t & (PIPE_SLOTS - 1)) * PIPE_TILE;
+    const char* src = (which ? v_tiles : k_tiles) + (size_t)te * PIPE_TILE;
+#pragma unroll
+    for (int i = 0; i < 16 / NW; ++i)
+      dma16(src, which ? v_lane_off[i] : k_lane_off[i], slot + (wave + i * NW) * 1024);
+  };
+  // Iteration t requests K of tile t + 3 and V of tile t + 2 and, at its end, waits only for what iteration
+  // t - 1 requested: every tile has two iterations to arrive.  Slots: K tiles t, t + 1 are read in iteration
+  // t while t + 2, t + 3 are in flight; V tiles t - 1, t are read while t + 1, t + 2 are in flight.
+  auto dma_iter = [&](int t) {
+    dma_tile(0, t + 3);
+    dma_tile(1, t + 2);
   };
 
-  dma_tile(0);
-  dma_tile(1);
+  dma_tile(0, 0);
+  dma_tile(0, 1);
+  dma_tile(0, 2);
+  dma_tile(1, 0);
+  dma_tile(1, 1);
 
   const int row = rt * ROWS_WG + wave * 32 + l32;
   const bool rvalid = row < n_rows;
@@ -357,13 +424,10 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
     for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
 
-  // V^T transpose-read geometry: 16-lane group g16 covers dims 16 (g16 & 1) + j of a 32-dim block and keys
-  // 8 (g16 >> 1) + e of a 16-key step; x = row & 3 selects the swizzle of the 64-byte segment
-  const int j16 = lane & 15, g16 = lane >> 4, vx = j16 >> 2;
-  const int v_lane_off = (8 * (g16 >> 1) + vx) * 256 + ((2 * (g16 & 1) + ((j16 & 3) >> 1)) << 4) + (j16 & 1) * 8;
-  int v_db_off[4];
+  // V^T fragment of head-dim block db, key step ks: row 32 db + l32, chunk 2 ks + hh (swizzled as written)
+  int v_ks_off[4];
 #pragma unroll
-  for (int db = 0; db < 4; ++db) v_db_off[db] = (db ^ vx) << 6;
+  for (int ks = 0; ks < 4; ++ks) v_ks_off[ks] = l32 * 128 + (((2 * ks + hh) ^ ((l32 >> 1) & 7)) << 4);
   const bool mfma_first = phase_mode == 0 ? true : (phase_mode == 1 ? ((wave >> 2) & 1) == 0 : (wave & 1) == 0);
 
   auto softmax = [&](auto masked, int t, f32x16 (&sacc)[2], bf16x8 (&pf)[4], bool& changed) -> float {
@@ -407,50 +471,62 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
 #pragma unroll
       for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
   };
-  auto qk_block = [&](int t, f32x16 (&sacc)[2]) {   // S^T of tile t
-    const char* sK = sKbase + (t & (PIPE_SLOTS - 1)) * PIPE_TILE;
-    bf16x8 fa[2][4];
-    auto fetch = [&](int b, bf16x8 (&f)[4]) {   // fragments kk = 2b, 2b+1 of key blocks 0 and 1
+  // Matrix-core work of one phase: S^T of tile tq (groups 0..3: two 16-dim steps of both 32-key blocks each)
+  // and O^T += V^T(tile tp) P^T (groups 4..7: one 16-key step of all four 32-dim blocks each), 4 MFMAs per
+  // group.  The LDS operands of a group are requested two groups ahead of the MFMAs that use them, into three
+  // rotating register sets; scheduling fences keep the compiler from sinking the reads back to their uses, so
+  // the LDS latency hides behind 8 MFMAs (256 cycles) of this wavefront.
+  auto matrix = [&](auto do_qk, auto do_pv, int tq, int tp, f32x16 (&sacc)[2], const bf16x8 (&pf)[4]) {
+    constexpr int G0 = decltype(do_qk)::value ? 0 : 4, G1 = decltype(do_pv)::value ? 8 : 4;
+    const char* sK = sKbase + (tq & (PIPE_SLOTS - 1)) * PIPE_TILE;
+    const char* sV = sVbase + (tp & (PIPE_SLOTS - 1)) * PIPE_TILE;
+    bf16x8 fb[3][4];
+    auto fetch = [&](int g, bf16x8 (&f)[4]) {
+      if (g < 4) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-        f[i] = *(const bf16x8*)(sK + k_lds_off((i & 1) * 32 + l32, 2 * (2 * b + (i >> 1)) + hh));
-    };
+        for (int i = 0; i < 4; ++i)
+          f[i] = *(const bf16x8*)(sK + k_lds_off((i & 1) * 32 + l32, 2 * (2 * g + (i >> 1)) + hh));
+      } else {
+        const int ks = g - 4;
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) sacc[kb][r] = 0.f;
-    fetch(0, fa[0]);
-#pragma unroll
-    for (int b = 0; b < 4; ++b) {
-      if (b + 1 < 4) fetch(b + 1, fa[(b + 1) & 1]);
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        sacc[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[b & 1][i], qf[2 * b + (i >> 1)], sacc[i & 1], 0, 0, 0);
-    }
-  };
-  auto pv_block = [&](int t, const bf16x8 (&pf)[4]) {   // O^T += V^T(tile t) P^T
-    const char* sV = sVbase + (t & (PIPE_SLOTS - 1)) * PIPE_TILE + v_lane_off;
-    bf16x8 fa[2][4];
-    auto fetch = [&](int ks, bf16x8 (&f)[4]) {
-#pragma unroll
-      for (int db = 0; db < 4; ++db) {
-        const int off = 16 * ks * 256 + v_db_off[db];
-        const v4i16 a0 = lds_read_tr(sV, off), a1 = lds_read_tr(sV, off + 4 * 256);
-        const v8i16 a8 = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
-        f[db] = *(const bf16x8*)&a8;
+        for (int db = 0; db < 4; ++db) f[db] = *(const bf16x8*)(sV + v_ks_off[ks] + db * 4096);
       }
     };
-    fetch(0, fa[0]);
+    auto mm = [&](int g, const bf16x8 (&f)[4]) {
+      if (g == 0) {
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[0], qf[0], zero, 0, 0, 0);
+        sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[1], qf[0], zero, 0, 0, 0);
+        sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[2], qf[1], sacc[0], 0, 0, 0);
+        sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[3], qf[1], sacc[1], 0, 0, 0);
+      } else if (g < 4) {
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      if (ks + 1 < 4) fetch(ks + 1, fa[(ks + 1) & 1]);
+        for (int i = 0; i < 4; ++i)
+          sacc[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i], qf[2 * g + (i >> 1)], sacc[i & 1], 0, 0, 0);
+      } else {
 #pragma unroll
-      for (int db = 0; db < 4; ++db)
-        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][db], pf[ks], oacc[db], 0, 0, 0);
+        for (int db = 0; db < 4; ++db)
+          oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[db], pf[g - 4], oacc[db], 0, 0, 0);
+      }
+    };
+    fetch(G0, fb[G0 % 3]);
+    fetch(G0 + 1, fb[(G0 + 1) % 3]);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int g = G0; g < G1; ++g) {
+      if (g + 2 < G1) fetch(g + 2, fb[(g + 2) % 3]);
+      __builtin_amdgcn_sched_barrier(0);
+      mm(g, fb[g % 3]);
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
-  auto arrive = [&]() {   // this wavefront's direct loads have landed; then everybody's
+  auto arrive_all = [&]() {   // all of this wavefront's direct loads have landed; then everybody's
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+    __syncthreads();
+  };
+  auto arrive = [&]() {   // all but the direct loads this iteration issued (2 * 16 / NW instructions)
+    if constexpr (NW == 8) __builtin_amdgcn_s_waitcnt(0x0F74);   // vmcnt(4)
+    else __builtin_amdgcn_s_waitcnt(0x0F78);                     // vmcnt(8)
     __syncthreads();
   };
 
@@ -461,33 +537,47 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
   bool changed;
   const int full_keys = min(wg_first_limit + 1, k_end) - k_begin;   // tiles every row of the workgroup sees whole
   const int n_full = full_keys > 0 ? min(full_keys / TK, n_tiles) : 0;
-  arrive();
+  arrive_all();
+  constexpr std::true_type yes{};
+  constexpr std::false_type no{};
   if (mfma_first) {
     auto iter = [&](auto masked, int t) {
-      dma_tile(t + 2);
-      qk_block(t, sacc);
-      if (t > 0) pv_block(t - 1, pf);
+      dma_iter(t);
+      matrix(yes, yes, t, t - 1, sacc, pf);
       const float alpha = softmax(masked, t, sacc, pf, changed);
       if (changed) rescale(alpha);
       arrive();
     };
-    int t = 0;
-    for (; t < n_full; ++t) iter(std::false_type{}, t);
-    for (; t < n_tiles; ++t) iter(std::true_type{}, t);
-    pv_block(n_tiles - 1, pf);
+    {   // tile 0: no output product yet
+      dma_iter(0);
+      matrix(yes, no, 0, 0, sacc, pf);
+      const float alpha = n_full > 0 ? softmax(no, 0, sacc, pf, changed) : softmax(yes, 0, sacc, pf, changed);
+      if (changed) rescale(alpha);
+      arrive();
+    }
+    int t = 1;
+    for (; t < n_full; ++t) iter(no, t);
+    for (; t < n_tiles; ++t) iter(yes, t);
+    matrix(no, yes, 0, n_tiles - 1, sacc, pf);
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // no direct load may be in flight when the wavefront ends
   } else {
-    qk_block(0, sacc);
+    matrix(yes, no, 0, 0, sacc, pf);
     auto iter = [&](auto masked, int t) {
-      dma_tile(t + 2);
+      dma_iter(t);
       const float alpha = softmax(masked, t, sacc, pf, changed);
       if (changed) rescale(alpha);
-      pv_block(t, pf);
-      if (t + 1 < n_tiles) qk_block(t + 1, sacc);
+      matrix(yes, yes, t + 1, t, sacc, pf);
       arrive();
     };
     int t = 0;
-    for (; t < n_full; ++t) iter(std::false_type{}, t);
-    for (; t < n_tiles; ++t) iter(std::true_type{}, t);
+    for (; t < n_full && t + 1 < n_tiles; ++t) iter(no, t);
+    for (; t + 1 < n_tiles; ++t) iter(yes, t);
+    {   // last tile: no further scores
+      const float alpha = t < n_full ? softmax(no, t, sacc, pf, changed) : softmax(yes, t, sacc, pf, changed);
+      if (changed) rescale(alpha);
+      matrix(no, yes, 0, t, sacc, pf);
+      arrive_all();   // as many barriers as the wavefronts of the other order execute
+    }
   }
 
   const float l_tot = l_run + __shfl_xor(l_run, 32);
@@ -557,13 +647,19 @@ hipError_t launch_t(const sv_cache* c, int stream, int layer, const void* q, int
   n_splits = (n_kv + keys_per_split - 1) / keys_per_split;
   const float c_log2 = 1.4426950408889634f / sqrtf((float)D);
   dim3 grid(row_tiles, Hkv, n_splits);
-  if constexpr (PIPE)
+  if constexpr (PIPE) {
+    __hip_bfloat16* vt = (__hip_bfloat16*)(c->vt + (size_t)stream * c->vt_stream_stride);
+    const size_t vt_head_stride = c->vt_stream_stride / 2 / Hkv;
+    hipLaunchKernelGGL(k_vt_build, dim3((n_kv + TK - 1) / TK, Hkv), dim3(256), 0, s,
+                       (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 1), vt, n_kv, c->head_stride / 2,
+                       vt_head_stride);
     hipLaunchKernelGGL((k_attn_chunk_pipe<NW>), grid, dim3(NW * 64), kLds, s, (const __hip_bfloat16*)q,
                        (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 0),
                        (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 1), (__hip_bfloat16*)o, c->part_o,
                        c->part_ml, n_q, n_kv, causal ? 1 : 0, n_splits, keys_per_split, c->cfg.n_q_heads, G,
-                       c->head_stride / 2, c_log2, env_int("SV_CHUNK_PHASE", 1));
-  else
+                       c->head_stride / 2, c_log2, env_int("SV_CHUNK_PHASE", 1), (const __hip_bfloat16*)vt,
+                       vt_head_stride);
+  } else
     hipLaunchKernelGGL((k_attn_chunk_mfma<NW>), grid, dim3(NW * 64), kLds, s, (const __hip_bfloat16*)q,
                        (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 0),
                        (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 1), (__hip_bfloat16*)o, c->part_o,

@@ -65,6 +65,8 @@ struct sv_cache {
   float* part_ml;            // device split-KV partial (max, sum)
   int64_t part_rows;         // capacity of the partial buffers in (token, split) pairs
   int32_t* counters;         // device [part_rows][n_kv_heads]  arrival counters of the split-KV merge (zero between launches)
+  char* vt;                  // device [n_streams][n_kv_heads][ceil(capacity/64)][head_dim][64]  V^T staging of one layer
+  size_t vt_stream_stride;   // bytes per stream of vt
   std::vector<sv::StreamState> st;
 
   char* kv_ptr(int stream, int half, int layer, int which) const {
