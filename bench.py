@@ -28,7 +28,11 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on the default workload, scaled by
 # what a plain 1 GiB copy reads on the same counters (fetch x2.00, write x1.00); profiles/hbm_traffic_*.txt.
 MEASURED_TRAFFIC = {
-    "qwen7b_256v_28L": {"attn_chunk": 73.6e6 + 31.6e6, "decode_sweep": 9.3e6 + 0.27e6, "evict": 323.5e6 + 289.8e6},
+    # attn_chunk = k_vt_build + k_attn_chunk_pipe + k_attn_combine; decode_sweep = k_decode_mfma + k_decode_merge;
+    # evict = k_evict_scan + k_delta_table + k_compact (reads + writes, scaled counters)
+    "qwen7b_256v_28L": {"attn_chunk": (4.57e6 + 4.56e6) + (66.5e6 + 31.7e6) + (34.8e6 + 1.8e6),
+                        "decode_sweep": (9.34e6 + 0.52e6) + (0.69e6 + 0.01e6),
+                        "evict": (323.7e6 + 289.8e6) + 3.3e6},
 }
 
 
@@ -263,7 +267,7 @@ def instrumented_pass(cache, run, pool, w, L, c0, ov, ot, n_chunks: int, traffic
                 "avg_launch_us": round(tot[key] / max(n_launch, 1), 2), "launches": n_launch,
                 "total_us_per_chunk": round(tot[key] / n_chunks, 1)}
 
-    roofs = [roof("k_attn_chunk_mfma (chunk prefill, incl. split merge)", "attn_chunk", "mfma", MFMA_BF16_PEAK_TFLOPS,
+    roofs = [roof("k_vt_build + k_attn_chunk_pipe + k_attn_combine (chunk prefill incl. V^T staging and split merge)", "attn_chunk", "mfma", MFMA_BF16_PEAK_TFLOPS,
                   "TFLOP/s", 1e12, 1),
              roof("k_decode_mfma + k_decode_merge (fused decode step, 28-layer sweeps incl. launch gaps)", "decode_sweep", "hbm",
                   HBM_PEAK_GBS, "GB/s", 1e9, L),
