@@ -329,7 +329,7 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
     const __hip_bfloat16* __restrict__ q, const __hip_bfloat16* __restrict__ kc, const __hip_bfloat16* __restrict__ vc,
     __hip_bfloat16* __restrict__ out, float* __restrict__ part_o, float* __restrict__ part_ml, int n_q, int n_kv,
     int causal, int n_splits, int keys_per_split, int n_q_heads, int G, size_t head_stride_elems, float c_log2,
-    int phase_mode, const __hip_bfloat16* __restrict__ vt, size_t vt_head_stride_elems) {
+    int phase_mode, const __hip_bfloat16* __restrict__ vt, size_t vt_head_stride_elems, int n_kv_heads, int pairs_pad) {
   constexpr int ROWS_WG = NW * 32;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   char* const sKbase = smem;
@@ -337,7 +337,12 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hh = lane >> 5;
-  const int rt = blockIdx.x, hk = blockIdx.y, sp = blockIdx.z;
+  // One-dimensional grid: workgroup id = row tile * pairs_pad + pair, pair = key range * kv heads + kv head.
+  // Consecutive ids go to the 8 XCDs in turn and pairs_pad is a multiple of 8, so all row tiles of one
+  // (kv head, key range) pair run on the same XCD and share its L2 copy of the pair's K and V^T tiles.
+  const int pair = blockIdx.x % pairs_pad, rt = blockIdx.x / pairs_pad;
+  if (pair >= n_kv_heads * n_splits) return;   // padding ids
+  const int hk = pair % n_kv_heads, sp = pair / n_kv_heads;
   const int slot0 = n_kv - n_q;
   const int n_rows = n_q * G;
 
@@ -640,6 +645,10 @@ hipError_t launch_t(const sv_cache* c, int stream, int layer, const void* q, int
     const int slots = PIPE ? 256 : 256 * (8 / NW);
     n_splits = std::max(1, slots / std::max(1, row_tiles * Hkv));
     n_splits = std::min(n_splits, std::max(1, n_kv / (4 * TK)));
+    // the pipelined kernel keeps the row tiles of a (kv head, key range) pair on one XCD: a pair count that
+    // is a multiple of 8 loads the 8 XCDs evenly
+    if (PIPE)
+      while (n_splits > 1 && (Hkv * n_splits) % 8 != 0) --n_splits;
   }
   n_splits = std::min<int64_t>(n_splits, std::max<int64_t>(1, c->part_rows / n_q));
   n_splits = std::min(n_splits, 64);
@@ -653,12 +662,13 @@ hipError_t launch_t(const sv_cache* c, int stream, int layer, const void* q, int
     hipLaunchKernelGGL(k_vt_build, dim3((n_kv + TK - 1) / TK, Hkv), dim3(256), 0, s,
                        (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 1), vt, n_kv, c->head_stride / 2,
                        vt_head_stride);
-    hipLaunchKernelGGL((k_attn_chunk_pipe<NW>), grid, dim3(NW * 64), kLds, s, (const __hip_bfloat16*)q,
+    const int pairs_pad = (Hkv * n_splits + 7) / 8 * 8;
+    hipLaunchKernelGGL((k_attn_chunk_pipe<NW>), dim3(row_tiles * pairs_pad), dim3(NW * 64), kLds, s, (const __hip_bfloat16*)q,
                        (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 0),
                        (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 1), (__hip_bfloat16*)o, c->part_o,
                        c->part_ml, n_q, n_kv, causal ? 1 : 0, n_splits, keys_per_split, c->cfg.n_q_heads, G,
                        c->head_stride / 2, c_log2, env_int("SV_CHUNK_PHASE", 1), (const __hip_bfloat16*)vt,
-                       vt_head_stride);
+                       vt_head_stride, Hkv, pairs_pad);
   } else
     hipLaunchKernelGGL((k_attn_chunk_mfma<NW>), grid, dim3(NW * 64), kLds, s, (const __hip_bfloat16*)q,
                        (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 0),
