@@ -42,7 +42,9 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=40, help="untimed chunks; >= 33 reaches steady state")
     ap.add_argument("--workload", default="qwen7b_256v_28L",
-                    choices=["qwen7b_256v_28L", "qwen7b_1024v_28L", "decode_ragged16", "decode_noevict32k"])
+                    choices=["qwen7b_256v_28L", "qwen7b_1024v_28L", "decode_ragged16", "decode_noevict32k",
+                             "noevict_growth", "budget_sweep", "overlap_recompute"])
+    ap.add_argument("--max-tokens", type=int, default=131072, help="noevict_growth: cache length to grow to")
     ap.add_argument("--layers", type=int, default=28)
     ap.add_argument("--pool", type=int, default=6, help="distinct pre-generated chunks cycled through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -75,6 +77,10 @@ def main():
 
     if args.workload.startswith("decode_"):
         print(json.dumps(decode_batch_bench(args)))
+        return
+    if args.workload in ("noevict_growth", "budget_sweep", "overlap_recompute"):
+        print(json.dumps({"noevict_growth": noevict_growth_bench, "budget_sweep": budget_sweep_bench,
+                          "overlap_recompute": overlap_recompute_bench}[args.workload](args)))
         return
     w = si.workload_qwen_stream() if args.workload == "qwen7b_256v_28L" else si.workload_high_fps(n_layers=28)
     L = args.layers
@@ -210,6 +216,171 @@ def decode_batch_bench(args):
                      "traffic": None, "avg_launch_us": round(us_layer, 2), "launches": args.steps * L,
                      "algorithmic_bytes_per_launch": bytes_layer},
     }
+
+
+def _stream_setup(L, cap, w, n_sink, vision_window, text_window, preamble, pool_n, max_q=None):
+    """A one-stream cache of Qwen-7B head shapes with a pool of random chunk inputs (bf16, N(0,1))."""
+    import torch
+
+    import paper_2510_09608_amd as sv
+    from paper_2510_09608_amd.stream import StreamRunner
+    dev = "cuda:0"
+    Hq, Hkv, d = w.n_q_heads, w.n_kv_heads, w.head_dim
+    nv, nt = w.vision_per_chunk, w.text_per_chunk
+    cache = sv.Cache(L, Hq, Hkv, d, sv.SV_DTYPE_BF16, w.rope_mode, w.rope_theta, w.mrope_sections, 1, cap,
+                     max_q or nv)
+    g = torch.Generator(device=dev).manual_seed(w.seed)
+    rnd = lambda *shape: torch.randn(*shape, device=dev, generator=g).to(torch.bfloat16)
+    pool = [dict(qv=rnd(L, nv, Hq, d), kv=rnd(L, nv, Hkv, d), vv=rnd(L, nv, Hkv, d),
+                 qt=rnd(nt, L, 1, Hq, d), kt=rnd(nt, L, 1, Hkv, d), vt=rnd(nt, L, 1, Hkv, d)) for _ in range(pool_n)]
+    ov = torch.empty(L, nv, Hq, d, device=dev, dtype=torch.bfloat16)
+    ot_all = torch.empty(nt, L, Hq, d, device=dev, dtype=torch.bfloat16)
+    run = StreamRunner(cache, n_sink, vision_window, text_window)
+    if preamble:
+        run.preamble(list(rnd(L, preamble, Hkv, d)), list(rnd(L, preamble, Hkv, d)))
+
+    def step(c):
+        p = pool[c % len(pool)]
+        return cache.stream_step(0, n_sink, vision_window, text_window, q_vision=p["qv"], k_vision=p["kv"],
+                                 v_vision=p["vv"], o_vision=ov, grid_thw=w.grid_thw, q_text=p["qt"], k_text=p["kt"],
+                                 v_text=p["vt"], o_text=ot_all)
+    return cache, step
+
+
+def _base_line(args, value, workload, extra):
+    out = {"metric": "ms per 1-s video chunk", "value": round(value, 4), "unit": "ms", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(value, 4), "higher_is_better": False,
+           "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": workload}}
+    out.update(extra)
+    return out
+
+
+def noevict_growth_bench(args):
+    """Full attention without eviction (the paper's Fig. 1a baseline): the same per-chunk step with both windows
+    infinite, so the cache grows by 272 tokens per second and positions stay native.  Reports ms per chunk as the
+    cache passes 8k, 16k, ... tokens; `value` is the figure at the largest length reached."""
+    import torch
+
+    import paper_2510_09608_amd as sv
+    import sv_inputs as si
+    w = si.workload_qwen_stream()
+    L = args.layers
+    n_chunks = (args.max_tokens - w.preamble_text) // w.tokens_per_chunk
+    cap = w.preamble_text + n_chunks * w.tokens_per_chunk + 64
+    cache, step = _stream_setup(L, cap, w, w.n_sink, sv.SV_WINDOW_INF, sv.SV_WINDOW_INF, w.preamble_text, args.pool)
+    marks = [m for m in (8192, 16384, 32768, 65536, 131072, 262144) if m <= args.max_tokens]
+    curve, c = [], 0
+    for m in marks:
+        while cache.len(0) + 9 * w.tokens_per_chunk < m:
+            step(c)
+            c += 1
+        torch.cuda.synchronize()
+        n0 = cache.len(0)
+        t0 = time.perf_counter()
+        for _ in range(8):           # 8 chunks ending at about m tokens
+            step(c)
+            c += 1
+        torch.cuda.synchronize()
+        curve.append({"cache_tokens": [n0, cache.len(0)], "ms_per_chunk": round((time.perf_counter() - t0) * 1e3 / 8, 3)})
+    bytes_kv = cache.len(0) * 2.0 * w.n_kv_heads * w.head_dim * 2 * L
+    return _base_line(args, curve[-1]["ms_per_chunk"],
+                      f"noevict_growth: {L} layers, qwen7b head shapes, 256 vision + 16 text tokens per chunk, no "
+                      f"eviction (windows infinite, native positions), cache grown to {cache.len(0)} tokens",
+                      {"curve": curve, "kv_bytes_live_at_end": bytes_kv,
+                       "note": "compare qwen7b_256v_28L (same step with the 512/4096/512 budgets): flat ms per chunk"})
+
+
+def budget_sweep_bench(args):
+    """Steady-state ms per chunk against the budgets of the paper's ablations: text sink = text window T in
+    {0, 64, 256, 512, 1024} tokens at a 16 s vision window, and vision windows of {0, 1, 4, 8, 16, 32} s at T = 512."""
+    import torch
+
+    import sv_inputs as si
+    w = si.workload_qwen_stream()
+    L = args.layers
+    points = [(t, t, 16) for t in (0, 64, 256, 512, 1024)] + [(512, 512, v) for v in (0, 1, 4, 8, 32)]
+    rows = []
+    for n_sink, tw, vsec in points:
+        vw = vsec * w.vision_per_chunk
+        pre = max(n_sink + tw, 1)                      # text budget full from the start
+        cap = n_sink + tw + vw + w.tokens_per_chunk + pre + 64
+        cache, step = _stream_setup(L, cap, w, n_sink, vw, tw, pre, 3)
+        warm = vsec + 3
+        for c in range(warm):
+            step(c)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for c in range(warm, warm + args.steps):
+            n_ret = step(c)
+        torch.cuda.synchronize()
+        rows.append({"n_sink": n_sink, "text_window": tw, "vision_window_s": vsec, "retained": int(n_ret),
+                     "ms_per_chunk": round((time.perf_counter() - t0) * 1e3 / args.steps, 3)})
+        cache.close()
+        del cache, step
+        torch.cuda.empty_cache()
+    ref = [r for r in rows if (r["n_sink"], r["vision_window_s"]) == (512, 16)][0]
+    return _base_line(args, ref["ms_per_chunk"],
+                      f"budget_sweep: {L} layers, qwen7b head shapes, 256 vision + 16 text tokens per chunk; value = the "
+                      f"512/512/16 s point", {"sweep": rows})
+
+
+def overlap_recompute_bench(args):
+    """Sliding window with overlap (the paper's Fig. 1c baseline): nothing is reused, every second the whole
+    window (512 + 512 text and 16 s of vision plus the new chunk) is prefilled again, all queries against all keys,
+    before the 16 decode steps.  Same kernels, same budgets; the difference to the streaming step is the
+    recomputation the method avoids (the model's projections and MLPs over the window are not even counted here)."""
+    import numpy as np
+    import torch
+
+    import paper_2510_09608_amd as sv
+    import sv_inputs as si
+    dev = "cuda:0"
+    w = si.workload_qwen_stream()
+    L = args.layers
+    Hq, Hkv, d = w.n_q_heads, w.n_kv_heads, w.head_dim
+    W = w.retained_steady() + w.vision_per_chunk          # tokens prefilled per second
+    nt = w.text_per_chunk
+    cache = sv.Cache(L, Hq, Hkv, d, sv.SV_DTYPE_BF16, w.rope_mode, w.rope_theta, w.mrope_sections, 1, W + nt + 64, W)
+    g = torch.Generator(device=dev).manual_seed(7)
+    rnd = lambda *shape: torch.randn(*shape, device=dev, generator=g).to(torch.bfloat16)
+    q, k, v = rnd(L, W, Hq, d), rnd(L, W, Hkv, d), rnd(L, W, Hkv, d)
+    o = torch.empty_like(q)
+    qt, kt, vt = rnd(nt, L, 1, Hq, d), rnd(nt, L, 1, Hkv, d), rnd(nt, L, 1, Hkv, d)
+    ot = torch.empty(L, 1, Hq, d, device=dev, dtype=torch.bfloat16)
+    # window layout: sink + text window, then the 17 s of vision as one block with grid (17, 16, 16)
+    n_text0 = w.n_sink + w.text_window
+    n_vis0 = W - n_text0
+    grid = (n_vis0 // w.vision_per_chunk, w.grid_thw[1], w.grid_thw[2])
+    t_text, t_vis = np.zeros(n_text0, np.uint8), np.ones(n_vis0, np.uint8)
+    ids = np.zeros(1, dtype=np.int32)
+
+    def second():
+        cache.evict(0, 0, 0, 0)                                    # drop everything: nothing is reused
+        for l in range(L):
+            cache.append(0, l, t_text if l == 0 else None, None, k[l][:n_text0], v[l][:n_text0])
+        for l in range(L):
+            cache.append(0, l, t_vis if l == 0 else None, grid if l == 0 else None, k[l][n_text0:], v[l][n_text0:])
+        for l in range(L):
+            cache.rope_apply(0, 0, W, q[l], None)
+            cache.attn_chunk(0, l, q[l], o[l], True)
+        for t in range(nt):
+            for l in range(L):
+                cache.decode_step(l, ids, qt[t, l], kt[t, l], vt[t, l], ot[l])
+
+    for _ in range(2):
+        second()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        second()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    flops = 4.0 * d * W * (W + 1) / 2.0 * Hq * L
+    return _base_line(args, ms,
+                      f"overlap_recompute: {L} layers, qwen7b head shapes; every second the whole window of {W} tokens "
+                      f"is prefilled again (causal, {flops / 1e12:.2f} TFLOP of attention), then 16 decode steps",
+                      {"window_tokens": W, "note": "compare qwen7b_256v_28L: the streaming step prefills 256 tokens"})
 
 
 def instrumented_pass(cache, run, pool, w, L, c0, ov, ot, n_chunks: int, traffic=None):

@@ -146,6 +146,8 @@ class Workload:
         total = self.preamble_text + self.n_chunks * self.tokens_per_chunk
         steady = self.retained_steady() + self.tokens_per_chunk
         # before steady state nothing beyond the budgets is held either
+        if self.vision_window < 0 or self.text_window < 0:   # an infinite window: nothing of that class is dropped
+            return total
         return min(total, steady + self.preamble_text)
 
     def qkv(self, layer: int, gids: np.ndarray):

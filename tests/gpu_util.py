@@ -3,6 +3,8 @@ from __future__ import annotations
 
 from typing import Dict, List, Sequence
 
+import os
+
 import numpy as np
 import torch
 
@@ -88,8 +90,14 @@ def assert_int_parity(g: Dict[str, object], o: Dict[str, object], where: str) ->
     assert np.array_equal(np.asarray(g["pos_end"], dtype=np.int64), np.asarray(o["pos_end"])), where
 
 
+WORST: Dict[str, float] = {}   # test id -> largest max-abs error it compared (reported at the end of the session)
+
+
 def max_err(a: np.ndarray, b: np.ndarray) -> float:
-    return float(np.max(np.abs(np.asarray(a, dtype=np.float64) - np.asarray(b, dtype=np.float64)))) if a.size else 0.0
+    e = float(np.max(np.abs(np.asarray(a, dtype=np.float64) - np.asarray(b, dtype=np.float64)))) if a.size else 0.0
+    test = os.environ.get("PYTEST_CURRENT_TEST", "?").split(" ")[0].split("::")[-1]
+    WORST[test] = max(WORST.get(test, 0.0), e)
+    return e
 
 
 def assert_attn_parity(g: Dict[str, object], o: Dict[str, object], tol: float, where: str) -> float:

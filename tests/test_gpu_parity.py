@@ -501,3 +501,30 @@ def test_edges_and_errors():
         kw.update(bad)
         with pytest.raises(sv.SvError):
             sv.Cache(**kw)
+
+
+# ---------------------------------------------------------------------------------------------------------
+# Budget sweep and the no-eviction mode (the sink / window ablations and the full-attention baseline):
+# zero-length windows, infinite windows (cache grows, positions stay native), mixed.
+# ---------------------------------------------------------------------------------------------------------
+INF = sv.SV_WINDOW_INF
+
+
+@pytest.mark.parametrize("n_sink,vision_window,text_window", [
+    (0, 0, 0), (0, 128, 16), (16, 0, 16), (16, 128, 0), (16, INF, INF), (64, 256, 64), (0, INF, 0), (8, 64, INF)])
+def test_budget_sweep_and_no_evict_mode(n_sink, vision_window, text_window):
+    w = si.Workload("qwen7b_64v_sweep", 1, 28, 4, 128, "bf16", 1, 1.0e6, (16, 24, 24),
+                    n_sink, vision_window, text_window, 24, 64, 8, (1, 8, 8), 9, 1006)
+    g, o = gu.GpuStream(w, [0]), sv_step.new_stream(w, [0])
+    g.preamble()
+    sv_step.append_preamble(o, w, [0])
+    for c in range(w.n_chunks):
+        _say(f"budget sweep ({n_sink},{vision_window},{text_window}) chunk {c}")
+        rg, ro = g.step_chunk(c), sv_step.step_chunk(o, w, c, [0], want_outputs=c in (0, 1, 4, 8))
+        gu.assert_int_parity(rg, ro, f"chunk {c}")
+        if c in (0, 1, 4, 8):
+            gu.assert_attn_parity(rg, ro, gu.TOL["bf16"], f"chunk {c}")
+    if vision_window == INF and text_window == INF:
+        # nothing was ever dropped: every token still sits at its arrival slot
+        n = w.preamble_text + w.n_chunks * w.tokens_per_chunk
+        assert rg["gids_end"].tolist() == list(range(n))
