@@ -308,29 +308,33 @@ __global__ __launch_bounds__(NW * 64) void k_decode_mfma(DecTable tab, int fused
 }
 
 // ---------------------------------------------------------------------------------
-// Merge of the key ranges of one decode step: one thread per (head, 4 output dims),
-// one 32-thread workgroup per head so that the loads spread over many CUs.  Every
-// thread issues 16 (max, sum) pairs and 16 float4 loads before using any of them.
-// grid: (n_q_heads, n_rows), block: 32 threads.
+// Merge of the key ranges of one decode step.  One workgroup of 128 threads per (head, row): thread
+// (g, d4) = (tid / 32, tid % 32) takes the key ranges s = g, g + 4, g + 8, ... and 4 output dims, issues
+// ALL its loads (up to 16 (max, sum) pairs and 16 float4) before using any of them, so the kernel costs
+// one memory round trip for up to 64 key ranges; the four partial merges meet in LDS.
+// grid: (n_q_heads, n_rows), block: 128 threads.
 // ---------------------------------------------------------------------------------
-__global__ __launch_bounds__(32) void k_decode_merge(const float* __restrict__ part_o,
-                                                     const float* __restrict__ part_ml,
-                                                     __hip_bfloat16* __restrict__ out, int n_splits, int n_q_heads) {
-  const int h = blockIdx.x, b = blockIdx.y, d4 = threadIdx.x;
+__global__ __launch_bounds__(128) void k_decode_merge(const float* __restrict__ part_o,
+                                                      const float* __restrict__ part_ml,
+                                                      __hip_bfloat16* __restrict__ out, int n_splits, int n_q_heads) {
+  __shared__ float4 s_acc[4][32];
+  __shared__ float2 s_ml[4];
+  const int h = blockIdx.x, b = blockIdx.y, g = threadIdx.x >> 5, d4 = threadIdx.x & 31;
   const size_t rbase = (size_t)b * n_splits * n_q_heads + h;   // split s adds s * n_q_heads
   const float4* po = (const float4*)(part_o + rbase * D) + d4;
   const float2* pml = (const float2*)part_ml + rbase;
   const size_t ostride = (size_t)n_q_heads * D / 4;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   float lsum = 0.f, m_ref = -INFINITY;
-  for (int s0 = 0; s0 < n_splits; s0 += 16) {
+  for (int s0 = g; s0 < n_splits; s0 += 64) {
     float4 v[16];
     float2 ml[16];
 #pragma unroll
     for (int j = 0; j < 16; ++j) {
-      const bool ok = s0 + j < n_splits;
-      ml[j] = ok ? pml[(size_t)(s0 + j) * n_q_heads] : make_float2(-INFINITY, 0.f);
-      v[j] = ok ? po[(size_t)(s0 + j) * ostride] : make_float4(0.f, 0.f, 0.f, 0.f);
+      const int sidx = s0 + 4 * j;
+      const bool ok = sidx < n_splits;
+      ml[j] = ok ? pml[(size_t)sidx * n_q_heads] : make_float2(-INFINITY, 0.f);
+      v[j] = ok ? po[(size_t)sidx * ostride] : make_float4(0.f, 0.f, 0.f, 0.f);
     }
     float mx = m_ref;
 #pragma unroll
@@ -346,10 +350,27 @@ __global__ __launch_bounds__(32) void k_decode_merge(const float* __restrict__ p
     }
     m_ref = mx;
   }
-  const float inv = 1.0f / lsum;
+  s_acc[g][d4] = acc;
+  if (d4 == 0) s_ml[g] = make_float2(m_ref, lsum);
+  __syncthreads();
+  if (g != 0) return;
+  float mx = -INFINITY;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) mx = fmaxf(mx, s_ml[k].x);
+  float4 tot = make_float4(0.f, 0.f, 0.f, 0.f);
+  float ltot = 0.f;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const float2 mlk = s_ml[k];
+    const float w = mlk.x == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mlk.x - mx);
+    const float4 a = s_acc[k][d4];
+    tot.x += w * a.x, tot.y += w * a.y, tot.z += w * a.z, tot.w += w * a.w;
+    ltot += w * mlk.y;
+  }
+  const float inv = 1.0f / ltot;
   __hip_bfloat16* op = out + ((size_t)b * n_q_heads + h) * D + 4 * d4;
-  const uint32_t w0 = bf_round_bits(acc.x * inv) | (bf_round_bits(acc.y * inv) << 16);
-  const uint32_t w1 = bf_round_bits(acc.z * inv) | (bf_round_bits(acc.w * inv) << 16);
+  const uint32_t w0 = bf_round_bits(tot.x * inv) | (bf_round_bits(tot.y * inv) << 16);
+  const uint32_t w1 = bf_round_bits(tot.z * inv) | (bf_round_bits(tot.w * inv) << 16);
   *(uint2*)op = make_uint2(w0, w1);
 }
 
@@ -394,7 +415,7 @@ hipError_t decode_launch(const sv_cache* c, const DecTable& tab, int fused, int 
                      c->group, c->head_stride / 2, c_log2, c->cfg.rope_mode != SV_ROPE_NONE ? 1 : 0);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || n_splits == 1) return e;
-  hipLaunchKernelGGL(k_decode_merge, dim3(Hq, nr), dim3(32), 0, s, c->part_o, c->part_ml,
+  hipLaunchKernelGGL(k_decode_merge, dim3(Hq, nr), dim3(128), 0, s, c->part_o, c->part_ml,
                      (__hip_bfloat16*)o + r0 * Hq * D, n_splits, Hq);
   return hipGetLastError();
 }
