@@ -22,10 +22,11 @@
 //     the key index swapped): the accumulator layout of S^T then hands every lane 8
 //     consecutive keys per 16-key step, which is exactly the B-operand layout of
 //     the second product, so P never moves between lanes.
-//   * V tiles are staged row-major, exactly as loaded, and read back as the V^T
-//     operand with the LDS transpose read (ds_read_b64_tr_b16), two per operand.
-//   * LDS is double-buffered: the next tile's global loads are issued into registers
-//     before the current tile's MFMAs and stored after them; one barrier per tile.
+//   * Two kernels share this tiling.  k_attn_chunk_mfma (the first one, kept for comparison) stages tiles
+//     through registers: V row-major exactly as loaded, read back as the V^T operand with the LDS transpose read
+//     (ds_read_b64_tr_b16, two per operand), LDS double-buffered, one barrier per tile.  k_attn_chunk_pipe (the
+//     default) brings K and V^T tiles to LDS with direct loads, four slots per tensor, and reads V^T fragments
+//     with plain 16-byte reads from tiles that k_vt_build transposed once per launch; see its own header.
 
 #include <hip/hip_bf16.h>
 
