@@ -208,9 +208,11 @@ int sv_cache_len(sv_cache* c, int stream_id, int64_t* n_out) {
   return SV_OK;
 }
 
-int sv_cache_append(sv_cache* c, int stream_id, int layer, int n, const uint8_t* types_host,
-                    const int32_t* grid_thw_host, const void* k_dev, const void* v_dev,
-                    int64_t* slot0_out, void* hip_stream) {
+// sv_cache_append, with the option of leaving the K/V store to the caller (the fused chunk prologue of
+// sv_stream_step stores K/V, rotates Q and stages V^T in one launch): all checks and bookkeeping are the same.
+static int append_impl(sv_cache* c, int stream_id, int layer, int n, const uint8_t* types_host,
+                       const int32_t* grid_thw_host, const void* k_dev, const void* v_dev,
+                       int64_t* slot0_out, void* hip_stream, bool launch_kv) {
   if (!stream_ok(c, stream_id) || layer < 0 || layer >= c->cfg.n_layers || n < 0) return SV_ERR_INVALID;
   sv::StreamState& st = c->st[stream_id];
   hipStream_t s = (hipStream_t)hip_stream;
@@ -251,7 +253,7 @@ int sv_cache_append(sv_cache* c, int stream_id, int layer, int n, const uint8_t*
     SV_HIP(sv::launch_meta_append(c, stream_id, st.next_parity, st.len, n, st.next_gid, st.n_text,
                                   st.n_vis, type_uniform, type_uniform < 0 ? &mask : nullptr,
                                   has_blk ? st.next_blk : -1, gT, gH, gW, s));
-    SV_HIP(sv::launch_append_kv(c, stream_id, 0, st.len, n, k_dev, v_dev, s));
+    if (launch_kv) SV_HIP(sv::launch_append_kv(c, stream_id, 0, st.len, n, k_dev, v_dev, s));
 
     st.pending_slot0 = st.len;
     st.pending_n = n;
@@ -277,10 +279,16 @@ int sv_cache_append(sv_cache* c, int stream_id, int layer, int n, const uint8_t*
   if (st.layer_len[layer] != st.pending_slot0 || n != st.pending_n ||
       st.pending_slot0 + n != st.len || st.layer_len[0] != st.len)
     return SV_ERR_STATE;
-  SV_HIP(sv::launch_append_kv(c, stream_id, layer, st.pending_slot0, n, k_dev, v_dev, s));
+  if (launch_kv) SV_HIP(sv::launch_append_kv(c, stream_id, layer, st.pending_slot0, n, k_dev, v_dev, s));
   st.layer_len[layer] = st.len;
   if (slot0_out) *slot0_out = st.pending_slot0;
   return SV_OK;
+}
+
+int sv_cache_append(sv_cache* c, int stream_id, int layer, int n, const uint8_t* types_host,
+                    const int32_t* grid_thw_host, const void* k_dev, const void* v_dev,
+                    int64_t* slot0_out, void* hip_stream) {
+  return append_impl(c, stream_id, layer, n, types_host, grid_thw_host, k_dev, v_dev, slot0_out, hip_stream, true);
 }
 
 int sv_cache_evict(sv_cache* c, int stream_id, int64_t n_sink, int64_t vision_window,
@@ -332,7 +340,7 @@ int sv_attn_chunk(sv_cache* c, int stream_id, int layer, const void* q_dev, int 
   if (st.layer_len[layer] != st.len) return SV_ERR_STATE;
   hipStream_t s = (hipStream_t)hip_stream;
   if (sv::attn_mfma_supported(c)) {
-    SV_HIP(sv::launch_attn_chunk_mfma(c, stream_id, layer, q_dev, n_q, o_dev, causal, s));
+    SV_HIP(sv::launch_attn_chunk_mfma(c, stream_id, layer, q_dev, n_q, o_dev, causal, false, s));
     return SV_OK;
   }
   if (!sv::attn_rows_supported(c)) return SV_ERR_UNSUPPORTED;
@@ -421,17 +429,26 @@ int sv_stream_step(sv_cache* c, int stream_id, int64_t n_sink, int64_t vision_wi
     const int n = io->n_vision;
     std::vector<uint8_t> types((size_t)n, (uint8_t)SV_VISION);
     const bool has_grid = io->grid_thw[0] > 0 || io->grid_thw[1] > 0 || io->grid_thw[2] > 0;
+    // bf16 / head_dim 128: K/V store, Q rotation and V^T staging of a layer go out as ONE launch
+    const bool fused = sv::attn_chunk_wants_vt(c) && n <= c->cfg.max_q_tokens;
     for (int l = 0; l < L; ++l) {
       int64_t slot0 = 0;
       char* q = (char*)io->q_vision + (size_t)l * n * qrow;
-      rc = sv_cache_append(c, stream_id, l, n, types.data(), has_grid ? io->grid_thw : nullptr,
-                           (const char*)io->k_vision + (size_t)l * n * kvrow,
-                           (const char*)io->v_vision + (size_t)l * n * kvrow, &slot0, hip_stream);
+      const char* k = (const char*)io->k_vision + (size_t)l * n * kvrow;
+      const char* v = (const char*)io->v_vision + (size_t)l * n * kvrow;
+      char* o = (char*)io->o_vision + (size_t)l * n * qrow;
+      rc = append_impl(c, stream_id, l, n, types.data(), has_grid ? io->grid_thw : nullptr, k, v, &slot0, hip_stream,
+                       !fused);
       if (rc != SV_OK) return rc;
-      rc = sv_rope_apply(c, stream_id, slot0, n, q, nullptr, hip_stream);
-      if (rc != SV_OK) return rc;
-      rc = sv_attn_chunk(c, stream_id, l, q, n, (char*)io->o_vision + (size_t)l * n * qrow, 1, hip_stream);
-      if (rc != SV_OK) return rc;
+      if (fused) {
+        SV_HIP(sv::launch_chunk_prologue(c, stream_id, l, slot0, n, q, k, v, (hipStream_t)hip_stream));
+        SV_HIP(sv::launch_attn_chunk_mfma(c, stream_id, l, q, n, o, 1, true, (hipStream_t)hip_stream));
+      } else {
+        rc = sv_rope_apply(c, stream_id, slot0, n, q, nullptr, hip_stream);
+        if (rc != SV_OK) return rc;
+        rc = sv_attn_chunk(c, stream_id, l, q, n, o, 1, hip_stream);
+        if (rc != SV_OK) return rc;
+      }
     }
   }
   const int32_t sid = stream_id;

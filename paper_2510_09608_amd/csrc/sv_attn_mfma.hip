@@ -275,41 +275,6 @@ constexpr int PIPE_SLOTS = 4;
 constexpr int PIPE_TILE = TK * D * 2;   // 16 KB per tile, unpadded
 constexpr int PIPE_LDS = 2 * PIPE_SLOTS * PIPE_TILE;
 
-// ---------------------------------------------------------------------------------
-// V^T staging for the pipelined kernel.  The second product wants V^T fragments (one head dim, 8
-// consecutive keys per lane); read from a row-major V tile that costs two half-rate LDS transpose reads per
-// fragment in EVERY wavefront of every workgroup that shares the tile.  This pass transposes each 64-key
-// block of the layer's V once, into vt[kv head][block][head dim][64 keys]; the attention kernel then
-// brings V^T tiles to LDS with direct loads and reads fragments with plain 16-byte reads.  Keys past the
-// cache length are written as zeros (they are masked, but must be finite).
-// grid: (blocks of 64 keys, kv heads), block: 256 threads.
-// ---------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_vt_build(const __hip_bfloat16* __restrict__ vc, __hip_bfloat16* __restrict__ vt,
-                                                  int n_kv, size_t head_stride_elems, size_t vt_head_stride_elems) {
-  __shared__ __attribute__((aligned(16))) char sT[TK * VROW];
-  const int blk = blockIdx.x, hk = blockIdx.y, tid = threadIdx.x;
-  const __hip_bfloat16* src = vc + (size_t)hk * head_stride_elems + (size_t)blk * TK * D;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int cid = tid + 256 * i, key = cid >> 4, c16 = cid & 15;
-    const uint4 v = blk * TK + key < n_kv ? *(const uint4*)(src + (size_t)key * D + c16 * 8) : make_uint4(0, 0, 0, 0);
-    *(uint4*)(sT + key * VROW + c16 * 16) = v;
-  }
-  __syncthreads();
-  const int wave = tid >> 6, lane = tid & 63, j16 = lane & 15, g = lane >> 4;
-  __hip_bfloat16* dst = vt + (size_t)hk * vt_head_stride_elems + (size_t)blk * TK * D;
-#pragma unroll
-  for (int ko = 0; ko < 2; ++ko)
-#pragma unroll
-    for (int ds = 0; ds < 2; ++ds) {
-      const int r0 = 16 * wave + 8 * ko, c0 = 64 * ds + 16 * g;
-      const int off = (r0 + (j16 >> 2)) * VROW + (c0 + 4 * (j16 & 3)) * 2;
-      const v4i16 a0 = lds_read_tr(sT, off), a1 = lds_read_tr(sT, off + 4 * VROW);
-      const v8i16 a8 = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
-      *(v8i16*)(dst + (size_t)(c0 + j16) * TK + r0) = a8;   // head dim c0 + j16, keys r0 .. r0 + 7
-    }
-}
-
 // 16 bytes per lane from global memory straight into LDS: lane L's bytes land at lds_dst + 16 L (lds_dst is
 // uniform over the wavefront and travels in M0).  Written as assembly on purpose: the compiler then does not
 // see a pending write to LDS and inserts no wait for ALL outstanding direct loads in front of later LDS
@@ -627,7 +592,7 @@ int env_int(const char* name, int dflt) {
 
 template <int NW, bool PIPE>
 hipError_t launch_t(const sv_cache* c, int stream, int layer, const void* q, int n_q, void* o, int causal,
-                    hipStream_t s) {
+                    bool vt_ready, hipStream_t s) {
   constexpr int ROWS_WG = NW * 32;
   constexpr int kLds = PIPE ? PIPE_LDS : 2 * BUF_BYTES;
   const void* kern = PIPE ? (const void*)k_attn_chunk_pipe<NW> : (const void*)k_attn_chunk_mfma<NW>;
@@ -660,9 +625,10 @@ hipError_t launch_t(const sv_cache* c, int stream, int layer, const void* q, int
   if constexpr (PIPE) {
     __hip_bfloat16* vt = (__hip_bfloat16*)(c->vt + (size_t)stream * c->vt_stream_stride);
     const size_t vt_head_stride = c->vt_stream_stride / 2 / Hkv;
-    hipLaunchKernelGGL(k_vt_build, dim3((n_kv + TK - 1) / TK, Hkv), dim3(256), 0, s,
-                       (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 1), vt, n_kv, c->head_stride / 2,
-                       vt_head_stride);
+    if (!vt_ready) {
+      hipError_t ev = launch_vt_build(c, stream, layer, n_kv, s);
+      if (ev != hipSuccess) return ev;
+    }
     const int pairs_pad = (Hkv * n_splits + 7) / 8 * 8;
     hipLaunchKernelGGL((k_attn_chunk_pipe<NW>), dim3(row_tiles * pairs_pad), dim3(NW * 64), kLds, s, (const __hip_bfloat16*)q,
                        (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 0),
@@ -687,14 +653,16 @@ bool attn_mfma_supported(const sv_cache* c) {
   return c->cfg.dtype == SV_DTYPE_BF16 && c->cfg.head_dim == 128 && std::getenv("SV_NO_MFMA") == nullptr;
 }
 
+bool attn_chunk_wants_vt(const sv_cache* c) { return attn_mfma_supported(c) && env_int("SV_CHUNK_VARIANT", 2) == 2; }
+
 hipError_t launch_attn_chunk_mfma(const sv_cache* c, int stream, int layer, const void* q, int n_q, void* o,
-                                  int causal, hipStream_t s) {
+                                  int causal, bool vt_ready, hipStream_t s) {
   // the pipelined kernel (tiles brought to LDS by direct loads) measured fastest on both chunk sizes; the
   // register-staged kernels stay selectable for comparison
   const int variant = env_int("SV_CHUNK_VARIANT", 2);
-  if (variant == 0) return launch_t<8, false>(c, stream, layer, q, n_q, o, causal, s);
-  if (variant == 2) return launch_t<8, true>(c, stream, layer, q, n_q, o, causal, s);
-  return launch_t<4, false>(c, stream, layer, q, n_q, o, causal, s);
+  if (variant == 0) return launch_t<8, false>(c, stream, layer, q, n_q, o, causal, false, s);
+  if (variant == 2) return launch_t<8, true>(c, stream, layer, q, n_q, o, causal, vt_ready, s);
+  return launch_t<4, false>(c, stream, layer, q, n_q, o, causal, false, s);
 }
 
 }  // namespace sv

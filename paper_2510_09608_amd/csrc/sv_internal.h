@@ -118,8 +118,14 @@ hipError_t launch_attn_decode_mfma(const sv_cache* c, int layer, const int32_t* 
                                    const void* q, const void* k_new, const void* v_new, void* o, hipStream_t s);
 
 bool attn_mfma_supported(const sv_cache* c);
+// V^T staging of one layer for the pipelined chunk-prefill kernel, alone or fused with the chunk's append and Q
+// rotation (bf16, head_dim 128); vt_ready tells the attention launch that the staging is already done.
+hipError_t launch_vt_build(const sv_cache* c, int stream, int layer, int n_kv, hipStream_t s);
+hipError_t launch_chunk_prologue(const sv_cache* c, int stream, int layer, int64_t slot0, int n, void* q, const void* k,
+                                 const void* v, hipStream_t s);
+bool attn_chunk_wants_vt(const sv_cache* c);
 hipError_t launch_attn_chunk_mfma(const sv_cache* c, int stream, int layer, const void* q, int n_q,
-                                  void* o, int causal, hipStream_t s);
+                                  void* o, int causal, bool vt_ready, hipStream_t s);
 
 hipError_t launch_attn_combine(const sv_cache* c, int n_rows, int n_splits, void* o, hipStream_t s);
 

@@ -83,18 +83,18 @@ __device__ __forceinline__ void rotate_pair_vec(Vec16<T>& lo, Vec16<T>& hi, cons
 
 // ---------------------------------------------------------------------------------
 // Store n new tokens of one layer: cache[K|V][h][slot0 + j] = (rotated K | V)[j][h].
-// grid: (ceil(n / ROWS), n_kv_heads, 2)
+// bx: block of ROWS tokens, h: kv head, which: 0 = K, 1 = V.
 // ---------------------------------------------------------------------------------
 template <typename T, int D>
-__global__ __launch_bounds__(256) void k_append_kv(const T* __restrict__ k_in, const T* __restrict__ v_in,
-                                                   T* __restrict__ k_cache, T* __restrict__ v_cache,
-                                                   const int4* __restrict__ pos4, const double* __restrict__ inv_freq,
-                                                   int64_t slot0, int n, int n_kv_heads, size_t head_stride_elems,
-                                                   int rope_mode, int s0, int s01) {
+__device__ __forceinline__ void append_rows(int bx, int h, int which, const T* __restrict__ k_in,
+                                            const T* __restrict__ v_in, T* __restrict__ k_cache, T* __restrict__ v_cache,
+                                            const int4* __restrict__ pos4, const double* __restrict__ inv_freq,
+                                            int64_t slot0, int n, int n_kv_heads, size_t head_stride_elems,
+                                            int rope_mode, int s0, int s01) {
   using G = RowGeom<T, D>;
-  const int j = blockIdx.x * G::ROWS + threadIdx.x / G::TPR;
+  const int j = bx * G::ROWS + threadIdx.x / G::TPR;
   if (j >= n) return;
-  const int t = threadIdx.x % G::TPR, h = blockIdx.y, which = blockIdx.z;
+  const int t = threadIdx.x % G::TPR;
   const T* src = (which == 0 ? k_in : v_in) + ((size_t)j * n_kv_heads + h) * D;
   T* dst = (which == 0 ? k_cache : v_cache) + (size_t)h * head_stride_elems + (size_t)(slot0 + j) * D;
   Vec16<T> lo, hi;
@@ -106,16 +106,27 @@ __global__ __launch_bounds__(256) void k_append_kv(const T* __restrict__ k_in, c
   *(decltype(hi.raw)*)(dst + D / 2 + t * G::EPV) = hi.raw;
 }
 
+// grid: (ceil(n / ROWS), n_kv_heads, 2)
+template <typename T, int D>
+__global__ __launch_bounds__(256) void k_append_kv(const T* __restrict__ k_in, const T* __restrict__ v_in,
+                                                   T* __restrict__ k_cache, T* __restrict__ v_cache,
+                                                   const int4* __restrict__ pos4, const double* __restrict__ inv_freq,
+                                                   int64_t slot0, int n, int n_kv_heads, size_t head_stride_elems,
+                                                   int rope_mode, int s0, int s01) {
+  append_rows<T, D>(blockIdx.x, blockIdx.y, blockIdx.z, k_in, v_in, k_cache, v_cache, pos4, inv_freq, slot0, n,
+                    n_kv_heads, head_stride_elems, rope_mode, s0, s01);
+}
+
 // ---------------------------------------------------------------------------------
 // Rotate rows of x [n][n_heads][D] in place at the positions of slots slot0 + j.
-// grid: ceil(n * n_heads / ROWS)
+// bx: block of ROWS (token, head) rows.
 // ---------------------------------------------------------------------------------
 template <typename T, int D>
-__global__ __launch_bounds__(256) void k_rope_rows(T* __restrict__ x, const int4* __restrict__ pos4,
-                                                   const double* __restrict__ inv_freq, int64_t slot0, int n,
-                                                   int n_heads, int rope_mode, int s0, int s01) {
+__device__ __forceinline__ void rope_rows(int bx, T* __restrict__ x, const int4* __restrict__ pos4,
+                                          const double* __restrict__ inv_freq, int64_t slot0, int n, int n_heads,
+                                          int rope_mode, int s0, int s01) {
   using G = RowGeom<T, D>;
-  const int64_t row = (int64_t)blockIdx.x * G::ROWS + threadIdx.x / G::TPR;
+  const int64_t row = (int64_t)bx * G::ROWS + threadIdx.x / G::TPR;
   if (row >= (int64_t)n * n_heads) return;
   const int t = threadIdx.x % G::TPR;
   const int j = (int)(row / n_heads);
@@ -126,6 +137,111 @@ __global__ __launch_bounds__(256) void k_rope_rows(T* __restrict__ x, const int4
   rotate_pair_vec<T, D>(lo, hi, pos4[slot0 + j], t * G::EPV, rope_mode, s0, s01, inv_freq);
   *(decltype(lo.raw)*)(p + t * G::EPV) = lo.raw;
   *(decltype(hi.raw)*)(p + D / 2 + t * G::EPV) = hi.raw;
+}
+
+// grid: ceil(n * n_heads / ROWS)
+template <typename T, int D>
+__global__ __launch_bounds__(256) void k_rope_rows(T* __restrict__ x, const int4* __restrict__ pos4,
+                                                   const double* __restrict__ inv_freq, int64_t slot0, int n,
+                                                   int n_heads, int rope_mode, int s0, int s01) {
+  rope_rows<T, D>(blockIdx.x, x, pos4, inv_freq, slot0, n, n_heads, rope_mode, s0, s01);
+}
+
+// ---------------------------------------------------------------------------------
+// V^T staging for the pipelined chunk-prefill kernel (bf16, head_dim 128).  That kernel's second product
+// wants V^T fragments (one head dim, 8 consecutive keys per lane); read from a row-major V tile that costs two
+// half-rate LDS transpose reads per fragment in EVERY wavefront of every workgroup that shares the tile.  This
+// pass transposes each 64-key block of the layer's V once, into vt[kv head][block][head dim][64 keys]; the
+// attention kernel then brings V^T tiles to LDS with direct loads and reads fragments with plain 16-byte
+// reads.  Rows [new0, new0 + n_new) may come from the caller's buffer v_new [n_new][n_kv_heads][128] instead of
+// the cache (they are being appended by other workgroups of the same launch); keys past n_kv are written as
+// zeros (they are masked, but must be finite).  One 256-thread workgroup per (block, kv head).
+//
+// LDS transpose read (ds_read_b64_tr_b16): within each group of 16 lanes, lane j hands in the address of 4
+// consecutive 16-bit elements and receives element (j & 3) of the chunks of lanes (j >> 2) + 4 e, e = 0..3;
+// pointing lane j at row r0 + (j >> 2), columns c0 + 4 (j & 3) .. + 3 of a row-major tile returns column
+// c0 + j of rows r0 .. r0 + 3.
+// ---------------------------------------------------------------------------------
+constexpr int VT_KEYS = 64;              // keys per block
+constexpr int VT_D = 128;
+constexpr int VT_ROW = VT_D * 2 + 64;    // LDS row stride in bytes: transpose reads fall in distinct banks
+typedef short v4i16 __attribute__((ext_vector_type(4)));
+typedef short v8i16 __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ void vt_block(char* sT, int blk, int hk, const __hip_bfloat16* __restrict__ v_cache,
+                                         const __hip_bfloat16* __restrict__ v_new, int64_t new0, int n_new, int n_kv,
+                                         int n_kv_heads, size_t head_stride_elems, __hip_bfloat16* __restrict__ vt,
+                                         size_t vt_head_stride_elems) {
+  const int tid = threadIdx.x;
+  const __hip_bfloat16* src = v_cache + (size_t)hk * head_stride_elems;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int cid = tid + 256 * i, key = cid >> 4, c16 = cid & 15;
+    const int64_t kk = (int64_t)blk * VT_KEYS + key;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (kk < n_kv) {
+      const bool fresh = v_new != nullptr && kk >= new0 && kk < new0 + n_new;
+      const __hip_bfloat16* row = fresh ? v_new + ((size_t)(kk - new0) * n_kv_heads + hk) * VT_D : src + (size_t)kk * VT_D;
+      v = *(const uint4*)(row + c16 * 8);
+    }
+    *(uint4*)(sT + key * VT_ROW + c16 * 16) = v;
+  }
+  __syncthreads();
+  const int wave = tid >> 6, lane = tid & 63, j16 = lane & 15, g = lane >> 4;
+  __hip_bfloat16* dst = vt + (size_t)hk * vt_head_stride_elems + (size_t)blk * VT_KEYS * VT_D;
+#pragma unroll
+  for (int ko = 0; ko < 2; ++ko)
+#pragma unroll
+    for (int ds = 0; ds < 2; ++ds) {
+      const int r0 = 16 * wave + 8 * ko, c0 = 64 * ds + 16 * g;
+      const int off = (r0 + (j16 >> 2)) * VT_ROW + (c0 + 4 * (j16 & 3)) * 2;
+      auto rd = [&](int o) {
+        return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (v4i16 __attribute__((address_space(3)))*)((__attribute__((address_space(3))) char*)sT + o));
+      };
+      const v4i16 a0 = rd(off), a1 = rd(off + 4 * VT_ROW);
+      const v8i16 a8 = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
+      *(v8i16*)(dst + (size_t)(c0 + j16) * VT_KEYS + r0) = a8;   // head dim c0 + j16, keys r0 .. r0 + 7
+    }
+}
+
+// grid: (blocks of 64 keys, kv heads)
+__global__ __launch_bounds__(256) void k_vt_build(const __hip_bfloat16* __restrict__ v_cache,
+                                                  __hip_bfloat16* __restrict__ vt, int n_kv, int n_kv_heads,
+                                                  size_t head_stride_elems, size_t vt_head_stride_elems) {
+  __shared__ __attribute__((aligned(16))) char sT[VT_KEYS * VT_ROW];
+  vt_block(sT, blockIdx.x, blockIdx.y, v_cache, nullptr, 0, 0, n_kv, n_kv_heads, head_stride_elems, vt,
+           vt_head_stride_elems);
+}
+
+// ---------------------------------------------------------------------------------
+// Everything a layer needs before the chunk-prefill attention of a new chunk, in ONE launch (bf16, head_dim
+// 128): store the chunk's K (rotated) and V, rotate its Q in place, and stage V^T of the whole layer (old rows
+// from the cache, the chunk's rows from the caller's buffer).  The three jobs are independent; workgroup ids
+// [0, nb_kv) do the first, [nb_kv, nb_kv + nb_q) the second, the rest the third.
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_chunk_prologue(
+    __hip_bfloat16* __restrict__ q, const __hip_bfloat16* __restrict__ k_in, const __hip_bfloat16* __restrict__ v_in,
+    __hip_bfloat16* __restrict__ k_cache, __hip_bfloat16* __restrict__ v_cache, const int4* __restrict__ pos4,
+    const double* __restrict__ inv_freq, int64_t slot0, int n, int n_q_heads, int n_kv_heads, size_t head_stride_elems,
+    int rope_mode, int s0, int s01, int gx_kv, int nb_kv, int nb_q, __hip_bfloat16* __restrict__ vt,
+    size_t vt_head_stride_elems, int n_blk) {
+  __shared__ __attribute__((aligned(16))) char sT[VT_KEYS * VT_ROW];
+  using T = __hip_bfloat16;
+  int b = blockIdx.x;
+  if (b < nb_kv) {
+    append_rows<T, VT_D>(b % gx_kv, (b / gx_kv) % n_kv_heads, b / (gx_kv * n_kv_heads), k_in, v_in, k_cache, v_cache,
+                         pos4, inv_freq, slot0, n, n_kv_heads, head_stride_elems, rope_mode, s0, s01);
+    return;
+  }
+  b -= nb_kv;
+  if (b < nb_q) {
+    if (rope_mode != SV_ROPE_NONE) rope_rows<T, VT_D>(b, q, pos4, inv_freq, slot0, n, n_q_heads, rope_mode, s0, s01);
+    return;
+  }
+  b -= nb_q;
+  vt_block(sT, b % n_blk, b / n_blk, v_cache, v_in, slot0, n, (int)(slot0 + n), n_kv_heads, head_stride_elems, vt,
+           vt_head_stride_elems);
 }
 
 // ---------------------------------------------------------------------------------
@@ -264,6 +380,32 @@ hipError_t launch_rope_apply(const sv_cache* c, int stream, int64_t slot0, int n
 
 hipError_t launch_compact(const sv_cache* c, int stream, int64_t n_new, hipStream_t s) {
   SV_DISPATCH(compact_t, c, stream, n_new, s);
+}
+
+hipError_t launch_vt_build(const sv_cache* c, int stream, int layer, int n_kv, hipStream_t s) {
+  const int Hkv = c->cfg.n_kv_heads;
+  __hip_bfloat16* vt = (__hip_bfloat16*)(c->vt + (size_t)stream * c->vt_stream_stride);
+  hipLaunchKernelGGL(k_vt_build, dim3((n_kv + VT_KEYS - 1) / VT_KEYS, Hkv), dim3(256), 0, s,
+                     (const __hip_bfloat16*)c->kv_ptr(stream, c->st[stream].cur, layer, 1), vt, n_kv, Hkv,
+                     c->head_stride / 2, c->vt_stream_stride / 2 / Hkv);
+  return hipGetLastError();
+}
+
+hipError_t launch_chunk_prologue(const sv_cache* c, int stream, int layer, int64_t slot0, int n, void* q, const void* k,
+                                 const void* v, hipStream_t s) {
+  using G = RowGeom<__hip_bfloat16, VT_D>;
+  const int Hq = c->cfg.n_q_heads, Hkv = c->cfg.n_kv_heads, cur = c->st[stream].cur;
+  const size_t off = (size_t)stream * (size_t)c->cfg.capacity_tokens;
+  const int gx_kv = (n + G::ROWS - 1) / G::ROWS, nb_kv = gx_kv * Hkv * 2;
+  const int nb_q = (int)(((int64_t)n * Hq + G::ROWS - 1) / G::ROWS);
+  const int n_blk = (int)((slot0 + n + VT_KEYS - 1) / VT_KEYS);
+  hipLaunchKernelGGL(k_chunk_prologue, dim3(nb_kv + nb_q + n_blk * Hkv), dim3(256), 0, s, (__hip_bfloat16*)q,
+                     (const __hip_bfloat16*)k, (const __hip_bfloat16*)v, (__hip_bfloat16*)c->kv_ptr(stream, cur, layer, 0),
+                     (__hip_bfloat16*)c->kv_ptr(stream, cur, layer, 1), c->meta[cur].pos4 + off, c->inv_freq, slot0, n, Hq,
+                     Hkv, c->head_stride / 2, c->cfg.rope_mode, c->cfg.mrope_sections[0],
+                     c->cfg.mrope_sections[0] + c->cfg.mrope_sections[1], gx_kv, nb_kv, nb_q,
+                     (__hip_bfloat16*)(c->vt + (size_t)stream * c->vt_stream_stride), c->vt_stream_stride / 2 / Hkv, n_blk);
+  return hipGetLastError();
 }
 
 }  // namespace sv
