@@ -46,10 +46,8 @@ constexpr int kMaxSplitsD = 128;
 constexpr int kMaxRowsD = 64;
 
 struct DecRow {
-  const __hip_bfloat16* k;   // K of the layer: kv head 0, slot 0
-  const __hip_bfloat16* v;
-  __hip_bfloat16* k_w;
-  __hip_bfloat16* v_w;
+  __hip_bfloat16* k;         // K of the layer: kv head 0, slot 0 (written only at the slot of a fused new token)
+  __hip_bfloat16* v;
   const float2* cs;          // cos/sin of the query token's rotary angles, [64]
   int32_t len;               // visible keys: slots [0, len), the query token is slot len - 1
 };
@@ -95,14 +93,19 @@ __device__ __forceinline__ v4i16 lds_read_tr(const char* lds_base, int byte_off)
       (v4i16 __attribute__((address_space(3)))*)((__attribute__((address_space(3))) char*)lds_base + byte_off));
 }
 
-template <int NW>
-__global__ __launch_bounds__(NW * 64) void k_decode_mfma(DecTable tab, int fused, const __hip_bfloat16* __restrict__ q,
+// ONE: a single row (one stream).  Its cache pointers, length and everything else needed to issue the first
+// loads are the leading 16 dwords of the argument list, which reach the wavefront in SGPRs at launch (kernel
+// argument preload) instead of through a first dependent fetch; the by-value table, at the end, is not read.
+template <int NW, bool ONE>
+__global__ __launch_bounds__(NW * 64) void k_decode_mfma(__hip_bfloat16* k0_, __hip_bfloat16* v0_, const float2* cs0_,
+                                                         int len0_, int keys_per_split,
+                                                         const __hip_bfloat16* __restrict__ q,
                                                          const __hip_bfloat16* __restrict__ k_new,
                                                          const __hip_bfloat16* __restrict__ v_new,
+                                                         size_t head_stride_elems, int fused, int rotate,
                                                          __hip_bfloat16* __restrict__ out, float* __restrict__ part_o,
-                                                         float* __restrict__ part_ml, int n_splits, int keys_per_split,
-                                                         int n_q_heads, int n_kv_heads, int G,
-                                                         size_t head_stride_elems, float c_log2, int rotate) {
+                                                         float* __restrict__ part_ml, int n_splits, int n_q_heads,
+                                                         int n_kv_heads, int G, float c_log2, DecTable tab) {
   __shared__ __attribute__((aligned(16))) char sV[NW][TK * VROW];   // V tile of each wavefront, row-major
   __shared__ float sO[NW][GMAX][D];                                 // wavefront results (merge)
   __shared__ float sML[NW][GMAX][2];
@@ -110,7 +113,9 @@ __global__ __launch_bounds__(NW * 64) void k_decode_mfma(DecTable tab, int fused
   const int sp = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, lg = lane >> 4;
-  const DecRow rd = tab.r[b];
+  DecRow rd;
+  if constexpr (ONE) rd = DecRow{k0_, v0_, cs0_, len0_};
+  else rd = tab.r[b];
   const int len = rd.len;
   const int k0 = sp * keys_per_split, k1 = min(len, k0 + keys_per_split);
   const __hip_bfloat16* kp = rd.k + (size_t)hk * head_stride_elems;
@@ -197,14 +202,14 @@ __global__ __launch_bounds__(NW * 64) void k_decode_mfma(DecTable tab, int fused
             rotate_pair_chunks(kreg[gi][0], kreg[gi][2], rc[0], rs[0]);
             rotate_pair_chunks(kreg[gi][1], kreg[gi][3], rc[1], rs[1]);
           }
-          __hip_bfloat16* dst = rd.k_w + (size_t)hk * head_stride_elems + (size_t)(len - 1) * D + 8 * lg;
+          __hip_bfloat16* dst = rd.k + (size_t)hk * head_stride_elems + (size_t)(len - 1) * D + 8 * lg;
 #pragma unroll
           for (int kk = 0; kk < 4; ++kk) *(uint4*)(dst + 32 * kk) = kreg[gi][kk];
         }
 #pragma unroll
       for (int st = 0; st < 8; ++st)
         if (rel == 4 * st + lg)
-          *(uint4*)(rd.v_w + (size_t)hk * head_stride_elems + (size_t)(len - 1) * D + 8 * l16) = vreg[st];
+          *(uint4*)(rd.v + (size_t)hk * head_stride_elems + (size_t)(len - 1) * D + 8 * l16) = vreg[st];
     }
     // ---- V tile to LDS, row-major
 #pragma unroll
@@ -407,12 +412,20 @@ hipError_t decode_launch(const sv_cache* c, const DecTable& tab, int fused, int 
     n_splits = (max_len + keys_per_split - 1) / keys_per_split;
   }
   const float c_log2 = 1.4426950408889634f / sqrtf((float)D);
-  hipLaunchKernelGGL((k_decode_mfma<NW>), dim3(n_splits, Hkv, nr), dim3(NW * 64), 0, s, tab, fused,
-                     (const __hip_bfloat16*)q + r0 * Hq * D,
-                     k_new ? (const __hip_bfloat16*)k_new + r0 * Hkv * D : nullptr,
-                     v_new ? (const __hip_bfloat16*)v_new + r0 * Hkv * D : nullptr,
-                     (__hip_bfloat16*)o + r0 * Hq * D, c->part_o, c->part_ml, n_splits, keys_per_split, Hq, Hkv,
-                     c->group, c->head_stride / 2, c_log2, c->cfg.rope_mode != SV_ROPE_NONE ? 1 : 0);
+  const __hip_bfloat16* qp = (const __hip_bfloat16*)q + r0 * Hq * D;
+  const __hip_bfloat16* knp = k_new ? (const __hip_bfloat16*)k_new + r0 * Hkv * D : nullptr;
+  const __hip_bfloat16* vnp = v_new ? (const __hip_bfloat16*)v_new + r0 * Hkv * D : nullptr;
+  __hip_bfloat16* op = (__hip_bfloat16*)o + r0 * Hq * D;
+  const int rotate = c->cfg.rope_mode != SV_ROPE_NONE ? 1 : 0;
+  const DecRow& r = tab.r[0];
+  if (nr == 1)
+    hipLaunchKernelGGL((k_decode_mfma<NW, true>), dim3(n_splits, Hkv, 1), dim3(NW * 64), 0, s, r.k, r.v, r.cs, r.len,
+                       keys_per_split, qp, knp, vnp, c->head_stride / 2, fused, rotate, op, c->part_o, c->part_ml,
+                       n_splits, Hq, Hkv, c->group, c_log2, tab);
+  else
+    hipLaunchKernelGGL((k_decode_mfma<NW, false>), dim3(n_splits, Hkv, nr), dim3(NW * 64), 0, s, r.k, r.v, r.cs, r.len,
+                       keys_per_split, qp, knp, vnp, c->head_stride / 2, fused, rotate, op, c->part_o, c->part_ml,
+                       n_splits, Hq, Hkv, c->group, c_log2, tab);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || n_splits == 1) return e;
   hipLaunchKernelGGL(k_decode_merge, dim3(Hq, nr), dim3(128), 0, s, c->part_o, c->part_ml,
@@ -431,8 +444,8 @@ hipError_t launch_attn_decode_mfma(const sv_cache* c, int layer, const int32_t* 
     for (int b = 0; b < nr; ++b) {
       const int sid = streams[r0 + b];
       const StreamState& st = c->st[sid];
-      tab.r[b].k = tab.r[b].k_w = (__hip_bfloat16*)c->kv_ptr(sid, st.cur, layer, 0);
-      tab.r[b].v = tab.r[b].v_w = (__hip_bfloat16*)c->kv_ptr(sid, st.cur, layer, 1);
+      tab.r[b].k = (__hip_bfloat16*)c->kv_ptr(sid, st.cur, layer, 0);
+      tab.r[b].v = (__hip_bfloat16*)c->kv_ptr(sid, st.cur, layer, 1);
       tab.r[b].len = (int)st.len;
       tab.r[b].cs = c->last_cs + (size_t)sid * (D / 2);
       max_len = std::max(max_len, (int)st.len);
