@@ -28,11 +28,11 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on the default workload, scaled by
 # what a plain 1 GiB copy reads on the same counters (fetch x2.00, write x1.00); profiles/hbm_traffic_*.txt.
 MEASURED_TRAFFIC = {
-    # attn_chunk = k_vt_build + k_attn_chunk_pipe + k_attn_combine; decode_sweep = k_decode_mfma + k_decode_merge;
+    # attn_chunk = k_chunk_prologue + k_attn_chunk_pipe + k_attn_combine; decode_sweep = k_decode_mfma + k_decode_merge;
     # evict = k_evict_scan + k_delta_table + k_compact (reads + writes, scaled counters)
-    "qwen7b_256v_28L": {"attn_chunk": (4.57e6 + 4.56e6) + (66.5e6 + 31.7e6) + (34.8e6 + 1.8e6),
-                        "decode_sweep": (9.34e6 + 0.52e6) + (0.69e6 + 0.01e6),
-                        "evict": (323.7e6 + 289.8e6) + 3.3e6},
+    "qwen7b_256v_28L": {"attn_chunk": (7.1e6 + 6.8e6) + (13.1e6 + 28.4e6) + (31.2e6 + 1.8e6),
+                        "decode_sweep": (9.32e6 + 0.52e6) + (0.65e6 + 0.01e6),
+                        "evict": (323.8e6 + 289.8e6) + 3.3e6},
 }
 
 
@@ -122,7 +122,7 @@ def main():
     steady = cache.len(0) == R + w.tokens_per_chunk
 
     # second region, same work per chunk, driven call by call so that HIP events can bracket each kernel class
-    inst = instrumented_pass(cache, run, pool, w, L, args.warmup + args.steps, ov, ot, n_chunks=min(10, args.steps),
+    inst = instrumented_pass(cache, run, pool, w, L, args.warmup + args.steps, ov, ot_all, n_chunks=min(10, args.steps),
                              traffic=MEASURED_TRAFFIC.get(args.workload if L == 28 else "", {}))
     roofs = inst["roofline_all"]
     dominant = max(roofs, key=lambda r: r["total_us_per_chunk"])
@@ -140,8 +140,8 @@ def main():
         "prefill_attn_tflops": inst["prefill_attn_tflops"],
         "decode_kv_gbs": inst["decode_kv_gbs"],
         "compaction_gbs": inst["compaction_gbs"],
-        "ms_per_step_call_by_call": inst["ms_per_chunk"],
-        "breakdown_us_per_call": inst["us"],
+        "ms_per_step_three_calls": inst["ms_per_chunk"],
+        "breakdown_us": inst["us"],
         "roofline": roofline,
         "roofline_all": roofs,
     }
@@ -412,17 +412,22 @@ def overlap_recompute_bench(args):
                       {"window_tokens": W, "note": "compare qwen7b_256v_28L: the streaming step prefills 256 tokens"})
 
 
-def instrumented_pass(cache, run, pool, w, L, c0, ov, ot, n_chunks: int, traffic=None):
-    """Same per-chunk work through the individual C calls, HIP events (torch's current stream, the one the
-    kernels are launched on) around every evict, every chunk-prefill attention launch and every 28-layer
-    sweep of the fused decode kernel."""
-    import numpy as np
+def instrumented_pass(cache, run, pool, w, L, c0, ov, ot_all, n_chunks: int, traffic=None):
+    """The same per-chunk work as three native calls, each bracketed by HIP events on the launch stream (torch's
+    current stream): the eviction, the chunk prefill of all layers (sv_stream_step with the vision half only:
+    per layer one prologue, one attention and one merge launch) and the 16 decode steps of all layers
+    (sv_stream_step with the text half only: per step and layer one attention and one merge launch).  The
+    launches of a region are enqueued by one C call, so the GPU runs them back to back and the event time per
+    launch is the kernels' own duration plus the dispatch gap between dependent launches."""
     import torch
+
+    import paper_2510_09608_amd as sv
     Hq, Hkv, d = w.n_q_heads, w.n_kv_heads, w.head_dim
     nv, nt = w.vision_per_chunk, w.text_per_chunk
     ev = lambda: torch.cuda.Event(enable_timing=True)
-    rec = {k: [] for k in ("evict", "append_chunk", "rope_chunk", "attn_chunk", "decode_sweep")}
+    rec = {k: [] for k in ("evict", "attn_chunk", "decode_sweep")}
     units = {"evict": [], "attn_chunk": [], "decode_sweep": []}
+    INF = sv.SV_WINDOW_INF
 
     def timed(key, fn):
         a, b = ev(), ev()
@@ -432,8 +437,6 @@ def instrumented_pass(cache, run, pool, w, L, c0, ov, ot, n_chunks: int, traffic
         rec[key].append((a, b))
         return r
 
-    ids = np.zeros(1, dtype=np.int32)
-    tv = np.ones(nv, dtype=np.uint8)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for c in range(c0, c0 + n_chunks):
@@ -441,23 +444,19 @@ def instrumented_pass(cache, run, pool, w, L, c0, ov, ot, n_chunks: int, traffic
         n_before = cache.len(0)
         n_ret = timed("evict", run.evict)
         units["evict"].append(2.0 * n_ret * 2 * Hkv * d * 2 * L if n_ret != n_before else 0.0)
-        for l in range(L):
-            slot0 = timed("append_chunk", lambda: cache.append(0, l, tv if l == 0 else None,
-                                                               w.grid_thw if l == 0 else None, p["kv"][l], p["vv"][l]))
-            timed("rope_chunk", lambda: cache.rope_apply(0, slot0, nv, p["qv"][l], None))
-            timed("attn_chunk", lambda: cache.attn_chunk(0, l, p["qv"][l], ov[l], True))
-            units["attn_chunk"].append(4.0 * d * nv * (slot0 + (nv + 1) / 2.0) * Hq)     # visible (query, key) pairs
-        for t in range(nt):
-            def sweep():
-                for l in range(L):
-                    cache.decode_step(l, ids, p["qt"][t][l], p["kt"][t][l], p["vt"][t][l], ot[l])
-            timed("decode_sweep", sweep)
-            units["decode_sweep"].append(cache.len(0) * 2.0 * Hkv * d * 2 * L)           # K and V rows of every token
+        # the two halves of the second; infinite windows: the eviction inside these calls has nothing to do
+        timed("attn_chunk", lambda: cache.stream_step(0, w.n_sink, INF, INF, q_vision=p["qv"], k_vision=p["kv"],
+                                                       v_vision=p["vv"], o_vision=ov, grid_thw=w.grid_thw))
+        units["attn_chunk"].append(L * 4.0 * d * nv * (n_ret + (nv + 1) / 2.0) * Hq)      # visible (query, key) pairs
+        n0 = cache.len(0)
+        timed("decode_sweep", lambda: cache.stream_step(0, w.n_sink, INF, INF, q_text=p["qt"], k_text=p["kt"],
+                                                         v_text=p["vt"], o_text=ot_all))
+        units["decode_sweep"].append(sum((n0 + t + 1) * 2.0 * Hkv * d * 2 * L for t in range(nt)))   # K and V rows
     torch.cuda.synchronize()
     ms_per_chunk = (time.perf_counter() - t0) * 1e3 / n_chunks
     tot = {k: sum(a.elapsed_time(b) for a, b in v) * 1e3 for k, v in rec.items()}      # microseconds
-    us = {k: round(tot[k] / max(len(v), 1), 2) for k, v in rec.items()}
-    us["decode_per_layer"] = round(us.pop("decode_sweep") / L, 2)
+    us = {"evict": round(tot["evict"] / n_chunks, 2), "prefill_per_layer": round(tot["attn_chunk"] / (n_chunks * L), 2),
+          "decode_per_layer_step": round(tot["decode_sweep"] / (n_chunks * L * nt), 2)}
 
     def roof(kernel, key, bound, peak, unit, scale, launches_per_event):
         n_launch = len(rec[key]) * launches_per_event
@@ -467,10 +466,10 @@ def instrumented_pass(cache, run, pool, w, L, c0, ov, ot, n_chunks: int, traffic
                 "avg_launch_us": round(tot[key] / max(n_launch, 1), 2), "launches": n_launch,
                 "total_us_per_chunk": round(tot[key] / n_chunks, 1)}
 
-    roofs = [roof("k_vt_build + k_attn_chunk_pipe + k_attn_combine (chunk prefill incl. V^T staging and split merge)", "attn_chunk", "mfma", MFMA_BF16_PEAK_TFLOPS,
-                  "TFLOP/s", 1e12, 1),
-             roof("k_decode_mfma + k_decode_merge (fused decode step, 28-layer sweeps incl. launch gaps)", "decode_sweep", "hbm",
-                  HBM_PEAK_GBS, "GB/s", 1e9, L),
+    roofs = [roof("k_chunk_prologue + k_attn_chunk_pipe + k_attn_combine (chunk prefill of one layer: K/V store, Q rotation "
+                  "and V^T staging, attention, split merge)", "attn_chunk", "mfma", MFMA_BF16_PEAK_TFLOPS, "TFLOP/s", 1e12, L),
+             roof("k_decode_mfma + k_decode_merge (fused decode step of one layer)", "decode_sweep", "hbm",
+                  HBM_PEAK_GBS, "GB/s", 1e9, L * nt),
              roof("k_compact (+ scan, shift table)", "evict", "hbm", HBM_PEAK_GBS, "GB/s", 1e9, 1)]
     return {"us": us, "ms_per_chunk": round(ms_per_chunk, 3), "roofline_all": roofs,
             "prefill_attn_tflops": roofs[0]["achieved"], "decode_kv_gbs": roofs[1]["achieved"],

@@ -153,7 +153,7 @@ __global__ __launch_bounds__(256) void k_attn_rows(RowTable tab, int chunk_mode,
                                                    float* __restrict__ part_o, float* __restrict__ part_ml,
                                                    int* __restrict__ counters, int n_splits, int n_q_heads,
                                                    int n_kv_heads, size_t head_stride_elems, float qscale,
-                                                   RopeParams rp, int debug_skip_merge) {
+                                                   RopeParams rp) {
   constexpr int EPL = D / 16;  // elements per lane
   const int sp = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x, lg = tid >> 4, li = tid & 15, wave = tid >> 6;
@@ -313,7 +313,7 @@ __global__ __launch_bounds__(256) void k_attn_rows(RowTable tab, int chunk_mode,
       }
     }
   }
-  if (n_splits == 1 || debug_skip_merge) return;
+  if (n_splits == 1) return;
 
   // the workgroup that finishes last for this (row, kv head) merges the key ranges
   __threadfence();
@@ -428,8 +428,7 @@ hipError_t rows_launch(const sv_cache* c, const RowTable& tab, int chunk_mode, i
   hipLaunchKernelGGL((k_attn_rows<T, D, G>), grid, dim3(256), 0, s, tab, chunk_mode, len0, step, fused,
                      (const T*)q + row_off * Hq * D, k_new ? (const T*)k_new + row_off * Hkv * D : nullptr,
                      v_new ? (const T*)v_new + row_off * Hkv * D : nullptr, (T*)o + row_off * Hq * D, c->part_o,
-                     c->part_ml, c->counters, n_splits, Hq, Hkv, c->head_stride / sizeof(T), scale, rp,
-                     env_int("SV_DEBUG_SKIP_MERGE", 0));
+                     c->part_ml, c->counters, n_splits, Hq, Hkv, c->head_stride / sizeof(T), scale, rp);
   return hipGetLastError();
 }
 
