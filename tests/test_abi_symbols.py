@@ -57,3 +57,11 @@ def test_host_only_calls():
     out = ctypes.c_int64(0)
     assert lib.sv_cache_len(None, 0, ctypes.byref(out)) == -1
     assert lib.sv_cache_destroy(None) == -1
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py is a one-GPU program: any other --gpus exits with a message before touching a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr

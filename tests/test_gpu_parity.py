@@ -528,3 +528,13 @@ def test_budget_sweep_and_no_evict_mode(n_sink, vision_window, text_window):
         # nothing was ever dropped: every token still sits at its arrival slot
         n = w.preamble_text + w.n_chunks * w.tokens_per_chunk
         assert rg["gids_end"].tolist() == list(range(n))
+
+
+def test_probe_rates_are_plausible():
+    """The measurement aid returns the device's sustained rates: below the published peaks, well above zero."""
+    buf = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0").fill_(1.0)      # 1 GiB
+    tflops, gbs = sv.sv_probe_rates(buf)
+    assert 500.0 < tflops <= 2600.0, tflops
+    assert 1000.0 < gbs <= 8200.0, gbs
+    with pytest.raises(sv.SvError):
+        sv.sv_probe_rates(buf[:16])            # smaller than the 1 MiB the probe asks for
