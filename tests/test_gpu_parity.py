@@ -538,3 +538,68 @@ def test_probe_rates_are_plausible():
     assert 1000.0 < gbs <= 8200.0, gbs
     with pytest.raises(sv.SvError):
         sv.sv_probe_rates(buf[:16])            # smaller than the 1 MiB the probe asks for
+
+
+class _PooledWorkload(si.Workload):
+    """Qwen-shaped stream whose Q/K/V of a token depend on its arrival id modulo a pool of 32 chunks (the preamble
+    keeps its own ids): throughput and parity do not depend on the data, and a late chunk of a long stream stays
+    reachable for both sides without generating an hour of samples."""
+    POOL_CHUNKS = 32
+
+    def key(self, gids):
+        g = np.asarray(gids, dtype=np.int64)
+        period = self.POOL_CHUNKS * self.tokens_per_chunk
+        return np.where(g < self.preamble_text, g, self.preamble_text + (g - self.preamble_text) % period)
+
+    def tables(self, layer):
+        cache = self.__dict__.setdefault("_tables", {})
+        if layer not in cache:
+            keys = np.arange(self.preamble_text + self.POOL_CHUNKS * self.tokens_per_chunk)
+            cache[layer] = si.Workload.qkv(self, layer, keys)
+        return cache[layer]
+
+    def qkv(self, layer, gids):
+        q, k, v = self.tables(layer)
+        kk = self.key(gids)
+        return q[kk], k[kk], v[kk]
+
+
+def test_long_stream_attention_at_late_chunks():
+    """Attention parity deep into a one-hour stream (chunks 64, 1800 and 3599 of the 28q/4kv x 128 M-RoPE stream,
+    three layers), driven by the native per-second call; retained counts checked at every chunk."""
+    base = si.workload_qwen_layer(n_chunks=3600, n_layers=3, seed=1003)
+    w = _PooledWorkload(**{f: getattr(base, f) for f in base.__dataclass_fields__})
+    layers = [0, 13, 27]
+    L, nv, nt = 3, w.vision_per_chunk, w.text_per_chunk
+    cache = gu.make_cache(w, n_layers=L, capacity=w.retained_steady() + w.tokens_per_chunk + 64)
+    dev_tab = [[torch.from_numpy(np.ascontiguousarray(t, dtype=np.float32)).to("cuda:0").to(torch.bfloat16)
+                for t in w.tables(l)] for l in layers]                 # [layer][q|k|v] -> [keys, H, d]
+    Q, K, V = (torch.stack([dev_tab[j][i] for j in range(L)]) for i in range(3))   # [L, keys, H, d]
+    run = gu.StreamRunner(cache, w.n_sink, w.vision_window, w.text_window)
+    pre = torch.arange(w.preamble_text, device="cuda:0")
+    run.preamble(list(K[:, pre]), list(V[:, pre]))
+    o = sv_step.new_stream(w, layers)
+    sv_step.append_preamble(o, w, layers)
+    ov = torch.empty(L, nv, w.n_q_heads, w.head_dim, device="cuda:0", dtype=torch.bfloat16)
+    ot = torch.empty(nt, L, w.n_q_heads, w.head_dim, device="cuda:0", dtype=torch.bfloat16)
+    samples = {64, 1800, 3599}
+    for c in range(w.n_chunks):
+        ch = w.chunk(c)
+        kv_ = torch.from_numpy(w.key(np.arange(ch.vision.gid0, ch.vision.gid0 + nv))).to("cuda:0")
+        kt_ = torch.from_numpy(w.key(np.arange(ch.text_gid0, ch.text_gid0 + nt))).to("cuda:0")
+        text = lambda X: X[:, kt_].permute(1, 0, 2, 3).unsqueeze(2).contiguous()      # [nt, L, 1, H, d]
+        n_ret = cache.stream_step(0, w.n_sink, w.vision_window, w.text_window, q_vision=Q[:, kv_].contiguous(),
+                                  k_vision=K[:, kv_].contiguous(), v_vision=V[:, kv_].contiguous(), o_vision=ov,
+                                  grid_thw=w.grid_thw, q_text=text(Q), k_text=text(K), v_text=text(V), o_text=ot)
+        ro = sv_step.step_chunk(o, w, c, layers, want_outputs=c in samples)
+        assert n_ret == ro["n_retained"], c
+        if c in samples:
+            _say(f"late-chunk attention parity, chunk {c}")
+            gids, pos = cache.retained(0)
+            assert np.array_equal(gids, np.asarray(ro["gids_end"], dtype=np.int64))
+            assert np.array_equal(pos.astype(np.int64), ro["pos_end"])
+            gv, gt = gu.host(ov), gu.host(ot)
+            for j in range(L):
+                assert gu.max_err(gv[j], ro["prefill"][j]) <= gu.TOL["bf16"], (c, j)
+                for t in range(nt):
+                    assert gu.max_err(gt[t, j], ro["decode"][t][j][0]) <= gu.TOL["bf16"], (c, j, t)
