@@ -121,8 +121,27 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
     steady = cache.len(0) == R + w.tokens_per_chunk
 
+    # the same step with each decode step as ONE launch over all layers (sv_decode_step_layers): possible here
+    # because the benchmark holds every layer's query up front; a sequential transformer cannot, so this is an
+    # extra figure, never `value`
+    c1 = args.warmup + args.steps
+    def step_batched(c: int):
+        p = pool[c % len(pool)]
+        cache.stream_step(0, *budgets, q_vision=p["qv"], k_vision=p["kv"], v_vision=p["vv"], o_vision=ov,
+                          grid_thw=w.grid_thw, q_text=p["qt"], k_text=p["kt"], v_text=p["vt"], o_text=ot_all,
+                          decode_layers_batched=True)
+    for c in range(c1, c1 + 3):
+        step_batched(c)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for c in range(c1 + 3, c1 + 3 + args.steps):
+        step_batched(c)
+    torch.cuda.synchronize()
+    ms_layer_batched = (time.perf_counter() - t0) * 1e3 / args.steps
+    args.warmup_total = c1 + 3 + args.steps
+
     # second region, same work per chunk, driven call by call so that HIP events can bracket each kernel class
-    inst = instrumented_pass(cache, run, pool, w, L, args.warmup + args.steps, ov, ot_all, n_chunks=min(10, args.steps),
+    inst = instrumented_pass(cache, run, pool, w, L, args.warmup_total, ov, ot_all, n_chunks=min(10, args.steps),
                              traffic=MEASURED_TRAFFIC.get(args.workload if L == 28 else "", {}))
     roofs = inst["roofline_all"]
     dominant = max(roofs, key=lambda r: r["total_us_per_chunk"])
@@ -141,6 +160,7 @@ def main():
         "decode_kv_gbs": inst["decode_kv_gbs"],
         "compaction_gbs": inst["compaction_gbs"],
         "ms_per_step_three_calls": inst["ms_per_chunk"],
+        "ms_per_step_decode_layers_batched": round(ms_layer_batched, 4),
         "breakdown_us": inst["us"],
         "roofline": roofline,
         "roofline_all": roofs,

@@ -186,6 +186,22 @@ SV_API int sv_decode_step(sv_cache* c, int layer, const int32_t* stream_ids_host
                           void* hip_stream);
 
 /*
+ * sv_decode_step_layers -- sv_decode_step of ONE stream for ALL layers in a
+ * single launch: layer l is one row of a batched variable-length decode, with
+ * q_dev [n_layers][n_q_heads][head_dim], k_dev / v_dev
+ * [n_layers][n_kv_heads][head_dim] (un-rotated, not modified) and o_dev
+ * [n_layers][n_q_heads][head_dim].  Same result as n_layers calls of
+ * sv_decode_step (Sec. 2.1), and only usable where every layer's query exists
+ * before any layer's attention runs: attention-only measurement, as here, or a
+ * model with parallel layers; a sequential transformer produces layer l + 1's
+ * query from layer l's output and has to call sv_decode_step layer by layer.
+ * Errors: as sv_decode_step at layer 0; SV_ERR_UNSUPPORTED where only the
+ * generic kernels apply (not bf16 / head_dim 128).
+ */
+SV_API int sv_decode_step_layers(sv_cache* c, int stream_id, const void* q_dev, const void* k_dev,
+                                 const void* v_dev, void* o_dev, void* hip_stream);
+
+/*
  * sv_stream_step -- one second of stream for ALL layers, sequenced natively:
  * sv_cache_evict with the three budgets, then per layer the vision chunk
  * (append, rotate Q, chunk-prefill attention), then n_text decode steps, each
@@ -198,7 +214,10 @@ SV_API int sv_decode_step(sv_cache* c, int layer, const int32_t* stream_ids_host
  *   o_vision [n_layers][n_vision][n_q_heads][head_dim]   output
  *   q_text [n_text][n_layers][n_q_heads][head_dim], k_text / v_text
  *   [n_text][n_layers][n_kv_heads][head_dim], o_text like q_text (output)
- * n_vision == 0 skips the chunk, n_text == 0 the decoding.  grid_thw as in
+ * n_vision == 0 skips the chunk, n_text == 0 the decoding.  decode_layers_batched
+ * != 0 runs each decode step as ONE sv_decode_step_layers launch instead of
+ * n_layers sv_decode_step launches (see there for when that is legitimate).
+ * grid_thw as in
  * sv_cache_append (all zeros = no grid).  Errors are those of the calls it
  * sequences; on error the stream is left as the failing call left it.
  */
@@ -214,6 +233,7 @@ typedef struct sv_chunk_io {
   const void* k_text;
   const void* v_text;
   void* o_text;
+  int32_t decode_layers_batched;
 } sv_chunk_io;
 
 SV_API int sv_stream_step(sv_cache* c, int stream_id, int64_t n_sink, int64_t vision_window,

@@ -44,7 +44,7 @@ class SvChunkIO(C.Structure):
     _fields_ = [
         ("n_vision", C.c_int32), ("grid_thw", C.c_int32 * 3), ("q_vision", C.c_void_p), ("k_vision", C.c_void_p),
         ("v_vision", C.c_void_p), ("o_vision", C.c_void_p), ("n_text", C.c_int32), ("q_text", C.c_void_p),
-        ("k_text", C.c_void_p), ("v_text", C.c_void_p), ("o_text", C.c_void_p),
+        ("k_text", C.c_void_p), ("v_text", C.c_void_p), ("o_text", C.c_void_p), ("decode_layers_batched", C.c_int32),
     ]
 
 
@@ -64,6 +64,8 @@ _SIGNATURES = {
     "sv_attn_decode": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]),
     "sv_decode_step": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
                                  C.c_void_p, C.c_void_p]),
+    "sv_decode_step_layers": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                        C.c_void_p]),
     "sv_stream_step": (C.c_int, [C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.POINTER(SvChunkIO),
                                  C.POINTER(C.c_int64), C.c_void_p]),
     "sv_cache_len": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_int64)]),
@@ -171,9 +173,14 @@ def sv_decode_step(handle: int, layer: int, stream_ids, q, k, v, o, stream=None)
                                 _stream(stream)), "sv_decode_step")
 
 
+def sv_decode_step_layers(handle: int, stream_id: int, q, k, v, o, stream=None) -> None:
+    _check(lib().sv_decode_step_layers(handle, stream_id, _ptr(q), _ptr(k), _ptr(v), _ptr(o), _stream(stream)),
+           "sv_decode_step_layers")
+
+
 def sv_stream_step(handle: int, stream_id: int, n_sink: int, vision_window: int, text_window: int,
                    q_vision=None, k_vision=None, v_vision=None, o_vision=None, grid_thw=None,
-                   q_text=None, k_text=None, v_text=None, o_text=None, stream=None) -> int:
+                   q_text=None, k_text=None, v_text=None, o_text=None, decode_layers_batched=False, stream=None) -> int:
     """Tensors as laid out in include/sv.h (leading dimension = layers, resp. decode steps then layers)."""
     io = SvChunkIO()
     io.n_vision = 0 if q_vision is None else int(q_vision.shape[1])
@@ -181,6 +188,7 @@ def sv_stream_step(handle: int, stream_id: int, n_sink: int, vision_window: int,
     io.q_vision, io.k_vision, io.v_vision, io.o_vision = _ptr(q_vision), _ptr(k_vision), _ptr(v_vision), _ptr(o_vision)
     io.n_text = 0 if q_text is None else int(q_text.shape[0])
     io.q_text, io.k_text, io.v_text, io.o_text = _ptr(q_text), _ptr(k_text), _ptr(v_text), _ptr(o_text)
+    io.decode_layers_batched = 1 if decode_layers_batched else 0
     n = C.c_int64(-1)
     _check(lib().sv_stream_step(handle, stream_id, n_sink, vision_window, text_window, C.byref(io), C.byref(n),
                                 _stream(stream)), "sv_stream_step")
@@ -270,6 +278,9 @@ class Cache:
 
     def decode_step(self, layer, stream_ids, q, k, v, o) -> None:
         sv_decode_step(self.handle, layer, stream_ids, q, k, v, o)
+
+    def decode_step_layers(self, stream_id, q, k, v, o) -> None:
+        sv_decode_step_layers(self.handle, stream_id, q, k, v, o)
 
     def stream_step(self, stream_id, n_sink, vision_window, text_window, **tensors) -> int:
         return sv_stream_step(self.handle, stream_id, n_sink, vision_window, text_window, **tensors)

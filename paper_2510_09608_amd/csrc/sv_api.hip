@@ -416,6 +416,33 @@ int sv_decode_step(sv_cache* c, int layer, const int32_t* stream_ids_host, int n
   return SV_OK;
 }
 
+int sv_decode_step_layers(sv_cache* c, int stream_id, const void* q_dev, const void* k_dev, const void* v_dev,
+                          void* o_dev, void* hip_stream) {
+  if (!stream_ok(c, stream_id) || !q_dev || !k_dev || !v_dev || !o_dev) return SV_ERR_INVALID;
+  if (!sv::attn_decode_mfma_supported(c)) return SV_ERR_UNSUPPORTED;
+  const int L = c->cfg.n_layers;
+  if ((int64_t)L > c->part_rows) return SV_ERR_INVALID;
+  sv::StreamState& st = c->st[stream_id];
+  for (int l = 0; l < L; ++l)
+    if (st.layer_len[l] != st.len) return SV_ERR_STATE;
+  if (st.len + 1 > c->cfg.capacity_tokens) return SV_ERR_CAPACITY;
+  hipStream_t s = (hipStream_t)hip_stream;
+  SV_HIP(sv::launch_meta_append(c, stream_id, st.next_parity, st.len, 1, st.next_gid, st.n_text, st.n_vis, SV_TEXT,
+                                nullptr, -1, 0, 0, 0, s));
+  st.pending_slot0 = st.len;
+  st.pending_n = 1;
+  st.next_parity ^= 1;
+  st.next_gid += 1;
+  if (!st.text_iv.empty() && st.text_iv.back().second == st.n_text) st.text_iv.back().second += 1;
+  else st.text_iv.emplace_back(st.n_text, st.n_text + 1);
+  st.n_text += 1;
+  st.len += 1;
+  for (int l = 0; l < L; ++l) st.layer_len[l] = st.len;
+  const int32_t sid = stream_id;
+  SV_HIP(sv::launch_attn_decode_mfma(c, -1, &sid, L, 1, q_dev, k_dev, v_dev, o_dev, s));
+  return SV_OK;
+}
+
 int sv_stream_step(sv_cache* c, int stream_id, int64_t n_sink, int64_t vision_window, int64_t text_window,
                    const sv_chunk_io* io, int64_t* n_retained_out, void* hip_stream) {
   if (!stream_ok(c, stream_id) || !io || io->n_vision < 0 || io->n_text < 0) return SV_ERR_INVALID;
@@ -452,6 +479,15 @@ int sv_stream_step(sv_cache* c, int stream_id, int64_t n_sink, int64_t vision_wi
     }
   }
   const int32_t sid = stream_id;
+  if (io->decode_layers_batched) {
+    for (int t = 0; t < io->n_text; ++t) {
+      const size_t i = (size_t)t * L;
+      rc = sv_decode_step_layers(c, stream_id, (const char*)io->q_text + i * qrow, (const char*)io->k_text + i * kvrow,
+                                 (const char*)io->v_text + i * kvrow, (char*)io->o_text + i * qrow, hip_stream);
+      if (rc != SV_OK) return rc;
+    }
+    return SV_OK;
+  }
   for (int t = 0; t < io->n_text; ++t)
     for (int l = 0; l < L; ++l) {
       const size_t i = (size_t)t * L + l;

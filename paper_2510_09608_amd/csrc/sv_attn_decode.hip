@@ -442,10 +442,12 @@ hipError_t launch_attn_decode_mfma(const sv_cache* c, int layer, const int32_t* 
     int max_len = 1;
     int64_t total_tiles = 0;
     for (int b = 0; b < nr; ++b) {
-      const int sid = streams[r0 + b];
+      // layer >= 0: row b is stream streams[b] at that layer; layer < 0: row b is layer b of stream streams[0]
+      const int sid = layer >= 0 ? streams[r0 + b] : streams[0];
+      const int lay = layer >= 0 ? layer : r0 + b;
       const StreamState& st = c->st[sid];
-      tab.r[b].k = (__hip_bfloat16*)c->kv_ptr(sid, st.cur, layer, 0);
-      tab.r[b].v = (__hip_bfloat16*)c->kv_ptr(sid, st.cur, layer, 1);
+      tab.r[b].k = (__hip_bfloat16*)c->kv_ptr(sid, st.cur, lay, 0);
+      tab.r[b].v = (__hip_bfloat16*)c->kv_ptr(sid, st.cur, lay, 1);
       tab.r[b].len = (int)st.len;
       tab.r[b].cs = c->last_cs + (size_t)sid * (D / 2);
       max_len = std::max(max_len, (int)st.len);

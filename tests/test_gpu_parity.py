@@ -111,8 +111,10 @@ def test_multi_layer_step_sampled_layers():
         assert np.array_equal(ids, np.asarray(ro["gids_end"])) and np.array_equal(pos, ro["pos_end"])
 
 
-def test_native_stream_step_matches_oracle():
-    """sv_stream_step (the whole second sequenced in C, all layers) on a 3-layer cache, every output checked."""
+@pytest.mark.parametrize("layers_batched", [False, True])
+def test_native_stream_step_matches_oracle(layers_batched):
+    """sv_stream_step (the whole second sequenced in C, all layers) on a 3-layer cache, every output checked;
+    decode steps as one launch per layer, or as one launch for all layers (sv_decode_step_layers)."""
     w = si.workload_qwen_layer(n_chunks=5, n_layers=3, seed=1003)
     w.preamble_text, w.vision_window, w.text_window, w.n_sink = 48, 512, 40, 32
     layers = [0, 1, 2]
@@ -138,7 +140,8 @@ def test_native_stream_step_matches_oracle():
         vt = stack(si.TENSOR_V, gt, 4).transpose(0, 1).contiguous()
         ov, ot = torch.empty_like(qv), torch.empty_like(qt)
         n_ret = cache.stream_step(0, w.n_sink, w.vision_window, w.text_window, q_vision=qv, k_vision=kv, v_vision=vv,
-                                  o_vision=ov, grid_thw=ch.vision.grid_thw, q_text=qt, k_text=kt, v_text=vt, o_text=ot)
+                                  o_vision=ov, grid_thw=ch.vision.grid_thw, q_text=qt, k_text=kt, v_text=vt, o_text=ot,
+                                  decode_layers_batched=layers_batched)
         assert n_ret == ro["n_retained"]
         for j in range(3):
             assert gu.max_err(gu.host(ov[j]), ro["prefill"][j]) <= gu.TOL["bf16"]
