@@ -8,7 +8,7 @@ re-index, then per layer append + RoPE + chunk-prefill attention for the 256
 new vision tokens, then 16 decode steps of append + RoPE + decode attention.
 Inputs are synthetic N(0,1) bf16 tensors already resident in HBM.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line.
 """
 from __future__ import annotations
 
