@@ -397,12 +397,18 @@ hipError_t decode_launch(const sv_cache* c, const DecTable& tab, int fused, int 
   const int Hq = c->cfg.n_q_heads, Hkv = c->cfg.n_kv_heads;
   // Key tiles per wavefront.  A single stream is latency bound: one tile per wavefront spreads its few
   // hundred tiles over the most CUs and costs one memory round trip.  A large batch is bandwidth bound:
-  // longer key ranges keep the partial results and their merge small; doubling the range while more than
-  // about 512 workgroups remain was the best point of sweeps at 16 rows of 2k..32k keys.
+  // longer key ranges keep the partial results and their merge small.  Two workgroups fit a CU (LDS), so the
+  // smallest count for which all non-empty workgroups are resident at once (<= 512) is taken: one workgroup
+  // more than that and a second, nearly empty round follows the first (measured on 16 ragged rows: 516
+  // workgroups 3.6 TB/s, 440 workgroups 4.2 TB/s).
   int tiles_per_wave = env_int("SV_DECODE_TILES_PER_WAVE", 0);
   if (tiles_per_wave <= 0) {
-    tiles_per_wave = 1;
-    while (tiles_per_wave < 16 && total_tiles * Hkv > (int64_t)512 * NW * tiles_per_wave) tiles_per_wave *= 2;
+    for (tiles_per_wave = 1; tiles_per_wave < 16; ++tiles_per_wave) {
+      const int keys = TK * NW * tiles_per_wave;
+      int64_t wgs = 0;
+      for (int b = 0; b < nr; ++b) wgs += (tab.r[b].len + keys - 1) / keys;
+      if (wgs * Hkv <= 512) break;
+    }
   }
   int keys_per_split = TK * NW * tiles_per_wave;
   int n_splits = (max_len + keys_per_split - 1) / keys_per_split;
