@@ -82,7 +82,14 @@ SV_API size_t sv_cache_bytes(const sv_config* cfg);
  * device only to zero a few counters on `hip_stream`.
  * Errors: SV_ERR_INVALID (NULLs, n_q_heads % n_kv_heads, head_dim not 64/128,
  * sections not summing to head_dim/2, sizes < 1), SV_ERR_CAPACITY (arena too
- * small). */
+ * small).
+ * Test seam: if the environment variable SV_HOST_LOGIC_ONLY is set (not "0")
+ * when a cache is created, that cache launches nothing and never touches the
+ * arena: argument checks, call-order rules, lengths, retained counts and error
+ * codes behave as usual (they are host bookkeeping), attention outputs are not
+ * produced, and sv_cache_retained / sv_cache_read_kv return SV_ERR_UNSUPPORTED.
+ * It exists so that the host logic can be tested on a machine without a GPU.
+ */
 SV_API int sv_cache_create(const sv_config* cfg, void* dev_arena, size_t arena_bytes,
                     void* hip_stream, sv_cache** out);
 

@@ -3,6 +3,7 @@
 // file holds no arithmetic of the method beyond counting which tokens survive.
 
 #include <algorithm>
+#include <cstdlib>
 #include <cmath>
 #include <cstring>
 #include <limits>
@@ -111,6 +112,12 @@ std::vector<std::pair<int64_t, int64_t>> iv_after_evict(
     if (e__ != hipSuccess) return SV_ERR_HIP; \
   } while (0)
 
+// Device work of a call: skipped for a cache created with SV_HOST_LOGIC_ONLY set (see sv_cache_create).
+#define SV_DEV(expr)                 \
+  do {                               \
+    if (!c->host_logic_only) SV_HIP(expr); \
+  } while (0)
+
 }  // namespace
 
 extern "C" {
@@ -183,6 +190,12 @@ int sv_cache_create(const sv_config* cfg, void* dev_arena, size_t arena_bytes, v
   if (cfg->rope_mode != SV_ROPE_NONE)
     for (int i = 0; i < half; ++i) f[i] = std::pow(cfg->rope_theta, -2.0 * (double)i / (double)cfg->head_dim);
   hipStream_t s = (hipStream_t)hip_stream;
+  const char* dry = std::getenv("SV_HOST_LOGIC_ONLY");
+  c->host_logic_only = dry && *dry && *dry != '0';
+  if (c->host_logic_only) {   // test seam: bookkeeping and checks only, the arena is never touched
+    *out = c;
+    return SV_OK;
+  }
   hipError_t e = hipMemcpyAsync(c->inv_freq, f.data(), half * sizeof(double), hipMemcpyHostToDevice, s);
   if (e == hipSuccess) e = hipMemsetAsync(c->next_pos, 0, (size_t)cfg->n_streams * 2 * 4, s);
   if (e == hipSuccess) e = hipMemsetAsync(c->n_dev, 0, (size_t)cfg->n_streams * 4, s);
@@ -250,10 +263,10 @@ static int append_impl(sv_cache* c, int stream_id, int layer, int n, const uint8
         if (types_host[j] == SV_VISION) mask.w[j >> 5] |= 1u << (j & 31);
     }
     const bool has_blk = grid_thw_host && c->cfg.rope_mode == SV_ROPE_3D;
-    SV_HIP(sv::launch_meta_append(c, stream_id, st.next_parity, st.len, n, st.next_gid, st.n_text,
+    SV_DEV(sv::launch_meta_append(c, stream_id, st.next_parity, st.len, n, st.next_gid, st.n_text,
                                   st.n_vis, type_uniform, type_uniform < 0 ? &mask : nullptr,
                                   has_blk ? st.next_blk : -1, gT, gH, gW, s));
-    if (launch_kv) SV_HIP(sv::launch_append_kv(c, stream_id, 0, st.len, n, k_dev, v_dev, s));
+    if (launch_kv) SV_DEV(sv::launch_append_kv(c, stream_id, 0, st.len, n, k_dev, v_dev, s));
 
     st.pending_slot0 = st.len;
     st.pending_n = n;
@@ -279,7 +292,7 @@ static int append_impl(sv_cache* c, int stream_id, int layer, int n, const uint8
   if (st.layer_len[layer] != st.pending_slot0 || n != st.pending_n ||
       st.pending_slot0 + n != st.len || st.layer_len[0] != st.len)
     return SV_ERR_STATE;
-  if (launch_kv) SV_HIP(sv::launch_append_kv(c, stream_id, layer, st.pending_slot0, n, k_dev, v_dev, s));
+  if (launch_kv) SV_DEV(sv::launch_append_kv(c, stream_id, layer, st.pending_slot0, n, k_dev, v_dev, s));
   st.layer_len[layer] = st.len;
   if (slot0_out) *slot0_out = st.pending_slot0;
   return SV_OK;
@@ -310,8 +323,8 @@ int sv_cache_evict(sv_cache* c, int stream_id, int64_t n_sink, int64_t vision_wi
   if (n_retained_out) *n_retained_out = n_new;
   if (n_new == st.len) return SV_OK;  // nothing to evict: no device work
 
-  SV_HIP(sv::launch_evict_scan(c, stream_id, st.next_parity, st.len, n_sink, text_lo, vis_lo, s));
-  if (n_new > 0) SV_HIP(sv::launch_compact(c, stream_id, n_new, s));
+  SV_DEV(sv::launch_evict_scan(c, stream_id, st.next_parity, st.len, n_sink, text_lo, vis_lo, s));
+  if (n_new > 0) SV_DEV(sv::launch_compact(c, stream_id, n_new, s));
   st.cur ^= 1;
   st.next_parity ^= 1;
   st.text_iv.swap(iv_new);
@@ -328,7 +341,7 @@ int sv_rope_apply(sv_cache* c, int stream_id, int64_t slot0, int n, void* q_dev_
   if (!stream_ok(c, stream_id) || n < 0 || slot0 < 0) return SV_ERR_INVALID;
   if (slot0 + n > c->st[stream_id].len) return SV_ERR_INVALID;
   if (n == 0 || c->cfg.rope_mode == SV_ROPE_NONE || (!q_dev_inout && !k_dev_inout)) return SV_OK;
-  SV_HIP(sv::launch_rope_apply(c, stream_id, slot0, n, q_dev_inout, k_dev_inout, (hipStream_t)hip_stream));
+  SV_DEV(sv::launch_rope_apply(c, stream_id, slot0, n, q_dev_inout, k_dev_inout, (hipStream_t)hip_stream));
   return SV_OK;
 }
 
@@ -340,11 +353,11 @@ int sv_attn_chunk(sv_cache* c, int stream_id, int layer, const void* q_dev, int 
   if (st.layer_len[layer] != st.len) return SV_ERR_STATE;
   hipStream_t s = (hipStream_t)hip_stream;
   if (sv::attn_mfma_supported(c)) {
-    SV_HIP(sv::launch_attn_chunk_mfma(c, stream_id, layer, q_dev, n_q, o_dev, causal, false, s));
+    SV_DEV(sv::launch_attn_chunk_mfma(c, stream_id, layer, q_dev, n_q, o_dev, causal, false, s));
     return SV_OK;
   }
   if (!sv::attn_rows_supported(c)) return SV_ERR_UNSUPPORTED;
-  SV_HIP(sv::launch_attn_rows_chunk(c, stream_id, layer, q_dev, n_q, o_dev, causal, s));
+  SV_DEV(sv::launch_attn_rows_chunk(c, stream_id, layer, q_dev, n_q, o_dev, causal, s));
   return SV_OK;
 }
 
@@ -360,12 +373,12 @@ int sv_attn_decode(sv_cache* c, int layer, const int32_t* stream_ids_host, int n
     if (st.layer_len[layer] != st.len) return SV_ERR_STATE;
   }
   if (sv::attn_decode_mfma_supported(c)) {
-    SV_HIP(sv::launch_attn_decode_mfma(c, layer, stream_ids_host, n_list, 0, q_dev, nullptr, nullptr, o_dev,
+    SV_DEV(sv::launch_attn_decode_mfma(c, layer, stream_ids_host, n_list, 0, q_dev, nullptr, nullptr, o_dev,
                                        (hipStream_t)hip_stream));
     return SV_OK;
   }
   if (!sv::attn_rows_supported(c)) return SV_ERR_UNSUPPORTED;
-  SV_HIP(sv::launch_attn_rows_batch(c, layer, stream_ids_host, n_list, 0, q_dev, nullptr, nullptr, o_dev,
+  SV_DEV(sv::launch_attn_rows_batch(c, layer, stream_ids_host, n_list, 0, q_dev, nullptr, nullptr, o_dev,
                                     (hipStream_t)hip_stream));
   return SV_OK;
 }
@@ -398,7 +411,7 @@ int sv_decode_step(sv_cache* c, int layer, const int32_t* stream_ids_host, int n
     const int sid = stream_ids_host[b];
     sv::StreamState& st = c->st[sid];
     if (layer == 0) {
-      SV_HIP(sv::launch_meta_append(c, sid, st.next_parity, st.len, 1, st.next_gid, st.n_text, st.n_vis, SV_TEXT,
+      SV_DEV(sv::launch_meta_append(c, sid, st.next_parity, st.len, 1, st.next_gid, st.n_text, st.n_vis, SV_TEXT,
                                     nullptr, -1, 0, 0, 0, s));
       st.pending_slot0 = st.len;
       st.pending_n = 1;
@@ -411,8 +424,8 @@ int sv_decode_step(sv_cache* c, int layer, const int32_t* stream_ids_host, int n
     }
     st.layer_len[layer] = st.len;
   }
-  if (use_mfma) SV_HIP(sv::launch_attn_decode_mfma(c, layer, stream_ids_host, n_list, 1, q_dev, k_dev, v_dev, o_dev, s));
-  else SV_HIP(sv::launch_attn_rows_batch(c, layer, stream_ids_host, n_list, 1, q_dev, k_dev, v_dev, o_dev, s));
+  if (use_mfma) SV_DEV(sv::launch_attn_decode_mfma(c, layer, stream_ids_host, n_list, 1, q_dev, k_dev, v_dev, o_dev, s));
+  else SV_DEV(sv::launch_attn_rows_batch(c, layer, stream_ids_host, n_list, 1, q_dev, k_dev, v_dev, o_dev, s));
   return SV_OK;
 }
 
@@ -427,7 +440,7 @@ int sv_decode_step_layers(sv_cache* c, int stream_id, const void* q_dev, const v
     if (st.layer_len[l] != st.len) return SV_ERR_STATE;
   if (st.len + 1 > c->cfg.capacity_tokens) return SV_ERR_CAPACITY;
   hipStream_t s = (hipStream_t)hip_stream;
-  SV_HIP(sv::launch_meta_append(c, stream_id, st.next_parity, st.len, 1, st.next_gid, st.n_text, st.n_vis, SV_TEXT,
+  SV_DEV(sv::launch_meta_append(c, stream_id, st.next_parity, st.len, 1, st.next_gid, st.n_text, st.n_vis, SV_TEXT,
                                 nullptr, -1, 0, 0, 0, s));
   st.pending_slot0 = st.len;
   st.pending_n = 1;
@@ -439,7 +452,7 @@ int sv_decode_step_layers(sv_cache* c, int stream_id, const void* q_dev, const v
   st.len += 1;
   for (int l = 0; l < L; ++l) st.layer_len[l] = st.len;
   const int32_t sid = stream_id;
-  SV_HIP(sv::launch_attn_decode_mfma(c, -1, &sid, L, 1, q_dev, k_dev, v_dev, o_dev, s));
+  SV_DEV(sv::launch_attn_decode_mfma(c, -1, &sid, L, 1, q_dev, k_dev, v_dev, o_dev, s));
   return SV_OK;
 }
 
@@ -468,8 +481,8 @@ int sv_stream_step(sv_cache* c, int stream_id, int64_t n_sink, int64_t vision_wi
                        !fused);
       if (rc != SV_OK) return rc;
       if (fused) {
-        SV_HIP(sv::launch_chunk_prologue(c, stream_id, l, slot0, n, q, k, v, (hipStream_t)hip_stream));
-        SV_HIP(sv::launch_attn_chunk_mfma(c, stream_id, l, q, n, o, 1, true, (hipStream_t)hip_stream));
+        SV_DEV(sv::launch_chunk_prologue(c, stream_id, l, slot0, n, q, k, v, (hipStream_t)hip_stream));
+        SV_DEV(sv::launch_attn_chunk_mfma(c, stream_id, l, q, n, o, 1, true, (hipStream_t)hip_stream));
       } else {
         rc = sv_rope_apply(c, stream_id, slot0, n, q, nullptr, hip_stream);
         if (rc != SV_OK) return rc;
@@ -504,6 +517,7 @@ int sv_cache_retained(sv_cache* c, int stream_id, int64_t* ids_host, int32_t* po
   sv::StreamState& st = c->st[stream_id];
   hipStream_t s = (hipStream_t)hip_stream;
   if (n_out) *n_out = st.len;
+  if (c->host_logic_only) return SV_ERR_UNSUPPORTED;   // ids and positions live in device memory
   const int64_t n = std::min(cap, st.len);
   const size_t off = (size_t)stream_id * (size_t)c->cfg.capacity_tokens;
   std::vector<int4> pos;
@@ -529,6 +543,7 @@ int sv_cache_read_kv(sv_cache* c, int stream_id, int layer, int which, int64_t s
     return SV_ERR_INVALID;
   sv::StreamState& st = c->st[stream_id];
   if (slot0 < 0 || n < 0 || slot0 + n > st.layer_len[layer] || (n > 0 && !dst_host)) return SV_ERR_INVALID;
+  if (c->host_logic_only) return SV_ERR_UNSUPPORTED;
   hipStream_t s = (hipStream_t)hip_stream;
   if (n > 0) {
     const char* src = c->kv_ptr(stream_id, st.cur, layer, which) + (size_t)slot0 * c->row_bytes;

@@ -67,6 +67,7 @@ struct sv_cache {
   int32_t* counters;         // device [part_rows][n_kv_heads]  arrival counters of the split-KV merge (zero between launches)
   char* vt;                  // device [n_streams][n_kv_heads][ceil(capacity/64)][head_dim][64]  V^T staging of one layer
   size_t vt_stream_stride;   // bytes per stream of vt
+  bool host_logic_only = false;   // created with SV_HOST_LOGIC_ONLY: no device work, bookkeeping only
   std::vector<sv::StreamState> st;
 
   char* kv_ptr(int stream, int half, int layer, int which) const {
