@@ -279,6 +279,10 @@ constexpr int PIPE_LDS = 2 * PIPE_SLOTS * PIPE_TILE;
 // uniform over the wavefront and travels in M0).  Written as assembly on purpose: the compiler then does not
 // see a pending write to LDS and inserts no wait for ALL outstanding direct loads in front of later LDS
 // reads; the kernel waits itself (vmcnt(0), then a workgroup barrier) before a tile is first read.
+// (M0 is named as clobbered on purpose: nothing else in these kernels uses it, and the compiler must not assume it
+// survives; clang notes that M0 is a reserved register, which is the point.)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void dma16(const void* base, uint32_t lane_off, char* lds_dst) {
   // base (uniform) travels in a scalar register pair, the lane's byte offset in one VGPR
   const uint32_t l = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds_dst);
@@ -289,6 +293,7 @@ __device__ __forceinline__ void dma16(const void* base, uint32_t lane_off, char*
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(l), "v"(lane_off), "s"(bu)
                : "memory", "m0");
 }
+#pragma clang diagnostic pop
 
 template <int NW>
 __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
