@@ -470,7 +470,7 @@ int sv_stream_step(sv_cache* c, int stream_id, int64_t n_sink, int64_t vision_wi
     std::vector<uint8_t> types((size_t)n, (uint8_t)SV_VISION);
     const bool has_grid = io->grid_thw[0] > 0 || io->grid_thw[1] > 0 || io->grid_thw[2] > 0;
     // bf16 / head_dim 128: K/V store, Q rotation and V^T staging of a layer go out as ONE launch
-    const bool fused = sv::attn_chunk_wants_vt(c) && n <= c->cfg.max_q_tokens;
+    const bool fused = sv::attn_chunk_wants_vt(c, n) && n <= c->cfg.max_q_tokens;
     for (int l = 0; l < L; ++l) {
       int64_t slot0 = 0;
       char* q = (char*)io->q_vision + (size_t)l * n * qrow;

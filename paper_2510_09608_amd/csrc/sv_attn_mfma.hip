@@ -271,9 +271,7 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_mfma(
 //   * The matrix-core work of an iteration (scores of one tile, output of another) does not depend on the
 //     softmax running in the same iteration; LDS operands are fetched one batch ahead of the MFMAs that use them.
 // ---------------------------------------------------------------------------------
-constexpr int PIPE_SLOTS = 4;
 constexpr int PIPE_TILE = TK * D * 2;   // 16 KB per tile, unpadded
-constexpr int PIPE_LDS = 2 * PIPE_SLOTS * PIPE_TILE;
 
 // 16 bytes per lane from global memory straight into LDS: lane L's bytes land at lds_dst + 16 L (lds_dst is
 // uniform over the wavefront and travels in M0).  Written as assembly on purpose: the compiler then does not
@@ -295,7 +293,7 @@ __device__ __forceinline__ void dma16(const void* base, uint32_t lane_off, char*
 }
 #pragma clang diagnostic pop
 
-template <int NW>
+template <int NW, int KS, int VS>
 __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
     const __hip_bfloat16* __restrict__ q, const __hip_bfloat16* __restrict__ kc, const __hip_bfloat16* __restrict__ vc,
     __hip_bfloat16* __restrict__ out, float* __restrict__ part_o, float* __restrict__ part_ml, int n_q, int n_kv,
@@ -304,7 +302,7 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
   constexpr int ROWS_WG = NW * 32;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   char* const sKbase = smem;
-  char* const sVbase = smem + PIPE_SLOTS * PIPE_TILE;
+  char* const sVbase = smem + KS * PIPE_TILE;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hh = lane >> 5;
@@ -357,7 +355,7 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
   const char* const v_tiles = (const char*)(vtbase + (size_t)(k_begin / TK) * (TK * D));
   auto dma_tile = [&](int which, int t) {
     const int te = min(t, n_tiles - 1);
-    char* slot = (which ? sVbase : sKbase) + (t & (PIPE_SLOTS - 1)) * PIPE_TILE;
+    char* slot = (which ? sVbase : sKbase) + (t % (which ? VS : KS)) * PIPE_TILE;
     const char* src = (which ? v_tiles : k_tiles) + (size_t)te * PIPE_TILE;
 #pragma unroll
     for (int i = 0; i < 16 / NW; ++i)
@@ -367,15 +365,14 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
   // t - 1 requested: every tile has two iterations to arrive.  Slots: K tiles t, t + 1 are read in iteration
   // t while t + 2, t + 3 are in flight; V tiles t - 1, t are read while t + 1, t + 2 are in flight.
   auto dma_iter = [&](int t) {
-    dma_tile(0, t + 3);
-    dma_tile(1, t + 2);
+    dma_tile(1, t + VS - 2);
+    dma_tile(0, t + KS - 1);
   };
 
-  dma_tile(0, 0);
-  dma_tile(0, 1);
-  dma_tile(0, 2);
-  dma_tile(1, 0);
-  dma_tile(1, 1);
+#pragma unroll
+  for (int t = 0; t < KS - 1; ++t) dma_tile(0, t);
+#pragma unroll
+  for (int t = 0; t < VS - 2; ++t) dma_tile(1, t);
 
   const int row = rt * ROWS_WG + wave * 32 + l32;
   const bool rvalid = row < n_rows;
@@ -404,7 +401,8 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
   int v_ks_off[4];
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) v_ks_off[ks] = l32 * 128 + (((2 * ks + hh) ^ ((l32 >> 1) & 7)) << 4);
-  const bool mfma_first = phase_mode == 0 ? true : (phase_mode == 1 ? ((wave >> 2) & 1) == 0 : (wave & 1) == 0);
+  const bool mfma_first =
+      NW != 8 || phase_mode == 0 ? true : (phase_mode == 1 ? ((wave >> 2) & 1) == 0 : (wave & 1) == 0);
 
   auto softmax = [&](auto masked, int t, f32x16 (&sacc)[2], bf16x8 (&pf)[4], bool& changed) -> float {
     const int kt0 = k_begin + t * TK;
@@ -454,8 +452,8 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
   // the LDS latency hides behind 8 MFMAs (256 cycles) of this wavefront.
   auto matrix = [&](auto do_qk, auto do_pv, int tq, int tp, f32x16 (&sacc)[2], const bf16x8 (&pf)[4]) {
     constexpr int G0 = decltype(do_qk)::value ? 0 : 4, G1 = decltype(do_pv)::value ? 8 : 4;
-    const char* sK = sKbase + (tq & (PIPE_SLOTS - 1)) * PIPE_TILE;
-    const char* sV = sVbase + (tp & (PIPE_SLOTS - 1)) * PIPE_TILE;
+    const char* sK = sKbase + (tq % KS) * PIPE_TILE;
+    const char* sV = sVbase + (tp % VS) * PIPE_TILE;
     bf16x8 fb[3][4];
     auto fetch = [&](int g, bf16x8 (&f)[4]) {
       if (g < 4) {
@@ -500,9 +498,14 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
     __syncthreads();
   };
-  auto arrive = [&]() {   // all but the direct loads this iteration issued (2 * 16 / NW instructions)
-    if constexpr (NW == 8) __builtin_amdgcn_s_waitcnt(0x0F74);   // vmcnt(4)
-    else __builtin_amdgcn_s_waitcnt(0x0F78);                     // vmcnt(8)
+  // End of an iteration: everything the next one reads has landed.  With two V^T slots that includes the
+  // V^T tile this iteration asked for (issued before the K tile, so only the K tile's 16 / NW instructions
+  // may stay in flight); with more slots all of this iteration's 2 * 16 / NW instructions may.
+  auto arrive = [&]() {
+    constexpr int pending = (VS > 2 ? 2 : 1) * 16 / NW;
+    static_assert(pending == 4 || pending == 8, "wait immediates below");
+    if constexpr (pending == 4) __builtin_amdgcn_s_waitcnt(0x0F74);   // vmcnt(4)
+    else __builtin_amdgcn_s_waitcnt(0x0F78);                          // vmcnt(8)
     __syncthreads();
   };
 
@@ -536,7 +539,7 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
     for (; t < n_tiles; ++t) iter(yes, t);
     matrix(no, yes, 0, n_tiles - 1, sacc, pf);
     __builtin_amdgcn_s_waitcnt(0x0F70);   // no direct load may be in flight when the wavefront ends
-  } else {
+  } else if constexpr (NW == 8 && KS == 4 && VS == 4) {   // (this order reads one tile further ahead)
     matrix(yes, no, 0, 0, sacc, pf);
     auto iter = [&](auto masked, int t) {
       dma_iter(t);
@@ -599,8 +602,11 @@ template <int NW, bool PIPE>
 hipError_t launch_t(const sv_cache* c, int stream, int layer, const void* q, int n_q, void* o, int causal,
                     bool vt_ready, hipStream_t s) {
   constexpr int ROWS_WG = NW * 32;
-  constexpr int kLds = PIPE ? PIPE_LDS : 2 * BUF_BYTES;
-  const void* kern = PIPE ? (const void*)k_attn_chunk_pipe<NW> : (const void*)k_attn_chunk_mfma<NW>;
+  // pipelined kernel: 8 wavefronts with 4 + 4 tile slots (128 KB, one workgroup per CU) or 4 wavefronts with
+  // 3 + 2 (80 KB, two independent workgroups per CU)
+  constexpr int KS = NW == 8 ? 4 : 3, VS = NW == 8 ? 4 : 2;
+  constexpr int kLds = PIPE ? (KS + VS) * PIPE_TILE : 2 * BUF_BYTES;
+  const void* kern = PIPE ? (const void*)k_attn_chunk_pipe<NW, KS, VS> : (const void*)k_attn_chunk_mfma<NW>;
   static bool attr_set = false;   // more than 64 KB of LDS has to be asked for once per kernel
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
@@ -613,7 +619,7 @@ hipError_t launch_t(const sv_cache* c, int stream, int layer, const void* q, int
   int n_splits = env_int("SV_CHUNK_SPLITS", 0);
   if (n_splits <= 0) {
     // fill 256 CUs with 8 wavefronts each (one workgroup of 8 or two of 4)
-    const int slots = PIPE ? 256 : 256 * (8 / NW);
+    const int slots = 256 * (8 / NW);
     n_splits = std::max(1, slots / std::max(1, row_tiles * Hkv));
     n_splits = std::min(n_splits, std::max(1, n_kv / (4 * TK)));
     // the pipelined kernel keeps the row tiles of a (kv head, key range) pair on one XCD: a pair count that
@@ -635,7 +641,7 @@ hipError_t launch_t(const sv_cache* c, int stream, int layer, const void* q, int
       if (ev != hipSuccess) return ev;
     }
     const int pairs_pad = (Hkv * n_splits + 7) / 8 * 8;
-    hipLaunchKernelGGL((k_attn_chunk_pipe<NW>), dim3(row_tiles * pairs_pad), dim3(NW * 64), kLds, s, (const __hip_bfloat16*)q,
+    hipLaunchKernelGGL((k_attn_chunk_pipe<NW, KS, VS>), dim3(row_tiles * pairs_pad), dim3(NW * 64), kLds, s, (const __hip_bfloat16*)q,
                        (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 0),
                        (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 1), (__hip_bfloat16*)o, c->part_o,
                        c->part_ml, n_q, n_kv, causal ? 1 : 0, n_splits, keys_per_split, c->cfg.n_q_heads, G,
@@ -658,15 +664,24 @@ bool attn_mfma_supported(const sv_cache* c) {
   return c->cfg.dtype == SV_DTYPE_BF16 && c->cfg.head_dim == 128 && std::getenv("SV_NO_MFMA") == nullptr;
 }
 
-bool attn_chunk_wants_vt(const sv_cache* c) { return attn_mfma_supported(c) && env_int("SV_CHUNK_VARIANT", 2) == 2; }
+// Which chunk-prefill kernel runs (SV_CHUNK_VARIANT overrides): 2 = pipelined, 8 wavefronts, one workgroup per
+// CU, the two wavefronts of a SIMD in opposite phase order; 3 = pipelined, 4 wavefronts, two independent
+// workgroups per CU; 0 / 1 = register-staged kernels kept for comparison.  Measured: 3 is ahead on short key
+// ranges per workgroup (256-token chunk over 5.4k keys: 44.9 vs 46.6 us with merge), 2 on long ones
+// (1024-token chunk over 18k keys: 304 vs 308 us).
+static int chunk_variant(int n_q) {
+  const int v = env_int("SV_CHUNK_VARIANT", -1);
+  return v >= 0 ? v : (n_q <= 512 ? 3 : 2);
+}
+
+bool attn_chunk_wants_vt(const sv_cache* c, int n_q) { return attn_mfma_supported(c) && chunk_variant(n_q) >= 2; }
 
 hipError_t launch_attn_chunk_mfma(const sv_cache* c, int stream, int layer, const void* q, int n_q, void* o,
                                   int causal, bool vt_ready, hipStream_t s) {
-  // the pipelined kernel (tiles brought to LDS by direct loads) measured fastest on both chunk sizes; the
-  // register-staged kernels stay selectable for comparison
-  const int variant = env_int("SV_CHUNK_VARIANT", 2);
+  const int variant = chunk_variant(n_q);
   if (variant == 0) return launch_t<8, false>(c, stream, layer, q, n_q, o, causal, false, s);
   if (variant == 2) return launch_t<8, true>(c, stream, layer, q, n_q, o, causal, vt_ready, s);
+  if (variant == 3) return launch_t<4, true>(c, stream, layer, q, n_q, o, causal, vt_ready, s);
   return launch_t<4, false>(c, stream, layer, q, n_q, o, causal, false, s);
 }
 

@@ -124,7 +124,7 @@ bool attn_mfma_supported(const sv_cache* c);
 hipError_t launch_vt_build(const sv_cache* c, int stream, int layer, int n_kv, hipStream_t s);
 hipError_t launch_chunk_prologue(const sv_cache* c, int stream, int layer, int64_t slot0, int n, void* q, const void* k,
                                  const void* v, hipStream_t s);
-bool attn_chunk_wants_vt(const sv_cache* c);
+bool attn_chunk_wants_vt(const sv_cache* c, int n_q);
 hipError_t launch_attn_chunk_mfma(const sv_cache* c, int stream, int layer, const void* q, int n_q,
                                   void* o, int causal, bool vt_ready, hipStream_t s);
 
