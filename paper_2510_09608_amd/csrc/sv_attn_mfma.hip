@@ -404,6 +404,7 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
   const bool mfma_first =
       NW != 8 || phase_mode == 0 ? true : (phase_mode == 1 ? ((wave >> 2) & 1) == 0 : (wave & 1) == 0);
 
+  const float tau = 8.0f / c_log2;   // 8 binary orders, in score units
   auto softmax = [&](auto masked, int t, f32x16 (&sacc)[2], bf16x8 (&pf)[4], bool& changed) -> float {
     const int kt0 = k_begin + t * TK;
     if constexpr (decltype(masked)::value) {
@@ -421,10 +422,20 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
 #pragma unroll
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kb][r]);
     mx = fmaxf(mx, __shfl_xor(mx, 32));
+    // The reference maximum m_run only moves when some row's maximum grew by more than 8 binary orders (then
+    // every row takes its exact new maximum and the accumulators are rescaled); smaller growth stays inside
+    // p <= 2^8, which bf16 P and the fp32 sums hold just as well, and m_run, l_run and O stay consistent, so
+    // the result is the same softmax.  After the first few tiles almost no tile pays the 64-multiply rescale
+    // (with exact tracking a wavefront's 32 rows made about every second tile pay it over 140 tiles).
     const float m_new = fmaxf(m_run, mx);
-    const float m_use = m_new == -INFINITY ? 0.f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f((m_run - m_use) * c_log2);
-    const float mc = m_use * c_log2;
+    changed = __any(m_new > m_run + tau);
+    float alpha = 1.f;
+    if (changed) {
+      const float m_use = m_new == -INFINITY ? 0.f : m_new;
+      alpha = __builtin_amdgcn_exp2f((m_run - m_use) * c_log2);
+      m_run = m_new;
+    }
+    const float mc = (m_run == -INFINITY ? 0.f : m_run) * c_log2;
     float psum = 0.f;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
@@ -435,8 +446,6 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
         pf[kb * 2 + (r >> 3)][r & 7] = (__bf16)p;
       }
     l_run = l_run * alpha + psum;
-    changed = __any(m_new > m_run);
-    m_run = m_new;
     return alpha;
   };
   auto rescale = [&](float alpha) {
