@@ -293,7 +293,7 @@ __device__ __forceinline__ void dma16(const void* base, uint32_t lane_off, char*
 }
 #pragma clang diagnostic pop
 
-template <int NW, int KS, int VS>
+template <int NW, int KS, int VS, bool INTER>
 __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
     const __hip_bfloat16* __restrict__ q, const __hip_bfloat16* __restrict__ kc, const __hip_bfloat16* __restrict__ vc,
     __hip_bfloat16* __restrict__ out, float* __restrict__ part_o, float* __restrict__ part_ml, int n_q, int n_kv,
@@ -369,10 +369,16 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
     dma_tile(0, t + KS - 1);
   };
 
+  if constexpr (INTER) {   // the first pair of tiles
+    dma_tile(0, 0);
+    dma_tile(0, 1);
+    dma_tile(1, 0);
+  } else {
 #pragma unroll
-  for (int t = 0; t < KS - 1; ++t) dma_tile(0, t);
+    for (int t = 0; t < KS - 1; ++t) dma_tile(0, t);
 #pragma unroll
-  for (int t = 0; t < VS - 2; ++t) dma_tile(1, t);
+    for (int t = 0; t < VS - 2; ++t) dma_tile(1, t);
+  }
 
   const int row = rt * ROWS_WG + wave * 32 + l32;
   const bool rvalid = row < n_rows;
@@ -528,7 +534,128 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
   arrive_all();
   constexpr std::true_type yes{};
   constexpr std::false_type no{};
-  if (mfma_first) {
+  if constexpr (INTER) {
+    // Interleaved order: iteration t = S(t) = QK(t), then the softmax of tile t with the 16 MFMAs of
+    // O += P(t-1) V(t-1) spread through it (one MFMA, then the exp / pack / sum of two scores).  Inside one
+    // wavefront an MFMA and the vector instructions behind it do not overlap, but the other wavefront of the
+    // SIMD runs the same mix, and two such streams keep the matrix pipe busy where long separate phases do not.
+    bf16x8 pfb[4];
+    auto mixed = [&](auto do_pv, int t, const bf16x8 (&pp)[4], bf16x8 (&pc)[4]) {
+      const char* sV = sVbase + ((t + VS - 1) % VS) * PIPE_TILE;   // tile t - 1
+      bf16x8 fb[3][4];
+      auto fetch = [&](int ks, bf16x8 (&f)[4]) {
+#pragma unroll
+        for (int db = 0; db < 4; ++db) f[db] = *(const bf16x8*)(sV + v_ks_off[ks] + db * 4096);
+      };
+      if constexpr (decltype(do_pv)::value) {
+        fetch(0, fb[0]);
+        fetch(1, fb[1]);
+      }
+      if (t >= n_full) {
+        const int kt0 = k_begin + t * TK;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int key = kt0 + 32 * kb + 16 * (r >> 3) + 8 * hh + (r & 7);
+            if (key > limit) sacc[kb][r] = -INFINITY;
+          }
+      }
+      // The probabilities are taken against the reference maximum as it stands (see softmax above: it moves
+      // only in steps of more than 8 binary orders), so nothing waits for this tile's row maxima.  They are
+      // not even computed unless a row's sum of the tile exceeds 2^8 (no p above 2^8 can hide under that) or a
+      // row has no reference yet; then the exact maxima decide, and on a step the tile is redone.
+      float mc = (m_run == -INFINITY ? 0.f : m_run) * c_log2;
+      float psum = 0.f;
+      typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+      bf16x2 ones;
+      ones[0] = (__bf16)1.0f, ones[1] = (__bf16)1.0f;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+#pragma unroll
+        for (int db = 0; db < 4; ++db) {
+          // One unit = one MFMA + the exp / pack / sum of two scores.  Empty volatile statements that
+          // name a unit's input before it and its outputs (for the MFMA: the fragment it has read) after it
+          // tie the units to this order; the scheduler otherwise gathers the 16 MFMAs behind the vector work.
+          const int kb = ks >> 1, r = (ks & 1) * 8 + 2 * db;
+          if constexpr (decltype(do_pv)::value) {
+            asm volatile("" : "+v"(mc), "+v"(v_ks_off[(ks + 2) & 3]));
+            if (db == 0 && ks + 2 < 4) fetch(ks + 2, fb[(ks + 2) % 3]);
+            oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ks % 3][db], pp[ks], oacc[db], 0, 0, 0);
+          }
+          bf16x2 pk;
+          pk[0] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sacc[kb][r], c_log2, -mc));
+          pk[1] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sacc[kb][r + 1], c_log2, -mc));
+          psum = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, psum, false);   // row sum of the rounded P, as the MFMA sees it
+          if constexpr (decltype(do_pv)::value)
+            asm volatile("" : "+v"(pk), "+v"(psum), "+v"(fb[ks % 3][db]));
+          pc[ks][2 * db] = pk[0], pc[ks][2 * db + 1] = pk[1];
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      float alpha = 1.f;
+      if (__any(!(psum <= 256.f) || m_run == -INFINITY)) {
+        float mx = -INFINITY;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kb][r]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run, mx);
+        if (__any(m_new > m_run + tau)) {   // a step of the reference maximum: exact new maxima, tile redone, O rescaled
+        const float m_use = m_new == -INFINITY ? 0.f : m_new;
+        alpha = __builtin_amdgcn_exp2f((m_run - m_use) * c_log2);
+        m_run = m_new;
+        mc = m_use * c_log2;
+        psum = 0.f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int e = 0; e < 8; e += 2) {
+            const int kb = j >> 1, r = (j & 1) * 8 + e;
+            bf16x2 pk;
+            pk[0] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sacc[kb][r], c_log2, -mc));
+            pk[1] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sacc[kb][r + 1], c_log2, -mc));
+            psum = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, psum, false);
+            pc[j][e] = pk[0], pc[j][e + 1] = pk[1];
+          }
+        rescale(alpha);
+        }
+      }
+      l_run = l_run * alpha + psum;
+    };
+    // Tiles go in pairs: at the start of pair (t0, t0 + 1) the direct loads of the next pair's tiles are issued
+    // (K t0 + 2, t0 + 3 and V^T t0 + 1, t0 + 2 land in the slots the previous pair read), at its end one
+    // wait + barrier: half the barriers of a per-tile scheme and twice the slack between the wavefronts.
+    static_assert(KS == 4 && VS == 4, "pair schedule uses four slots per tensor");
+    auto dma_pair = [&](int t0) {
+      dma_tile(0, t0 + 2);
+      dma_tile(0, t0 + 3);
+      dma_tile(1, t0 + 1);
+      dma_tile(1, t0 + 2);
+    };
+    dma_pair(0);
+    matrix(yes, no, 0, 0, sacc, pf);
+    mixed(no, 0, pfb, pf);
+    if (n_tiles > 1) {
+      matrix(yes, no, 1, 0, sacc, pf);
+      mixed(yes, 1, pf, pfb);
+    }
+    arrive_all();
+    for (int t0 = 2; t0 < n_tiles; t0 += 2) {   // even tiles leave P in pf, odd ones in pfb
+      dma_pair(t0);
+      matrix(yes, no, t0, 0, sacc, pf);
+      mixed(yes, t0, pfb, pf);
+      if (t0 + 1 < n_tiles) {
+        matrix(yes, no, t0 + 1, 0, sacc, pf);
+        mixed(yes, t0 + 1, pf, pfb);
+      }
+      arrive_all();
+    }
+    if (n_tiles & 1) matrix(no, yes, 0, n_tiles - 1, sacc, pf);
+    else matrix(no, yes, 0, n_tiles - 1, sacc, pfb);
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // no direct load may be in flight when the wavefront ends
+  } else if (mfma_first) {
     auto iter = [&](auto masked, int t) {
       dma_iter(t);
       matrix(yes, yes, t, t - 1, sacc, pf);
@@ -607,7 +734,7 @@ int env_int(const char* name, int dflt) {
   return v && *v ? std::atoi(v) : dflt;
 }
 
-template <int NW, bool PIPE>
+template <int NW, bool PIPE, bool INTER = false>
 hipError_t launch_t(const sv_cache* c, int stream, int layer, const void* q, int n_q, void* o, int causal,
                     bool vt_ready, hipStream_t s) {
   constexpr int ROWS_WG = NW * 32;
@@ -615,7 +742,7 @@ hipError_t launch_t(const sv_cache* c, int stream, int layer, const void* q, int
   // 3 + 2 (80 KB, two independent workgroups per CU)
   constexpr int KS = NW == 8 ? 4 : 3, VS = NW == 8 ? 4 : 2;
   constexpr int kLds = PIPE ? (KS + VS) * PIPE_TILE : 2 * BUF_BYTES;
-  const void* kern = PIPE ? (const void*)k_attn_chunk_pipe<NW, KS, VS> : (const void*)k_attn_chunk_mfma<NW>;
+  const void* kern = PIPE ? (const void*)k_attn_chunk_pipe<NW, KS, VS, INTER> : (const void*)k_attn_chunk_mfma<NW>;
   static bool attr_set = false;   // more than 64 KB of LDS has to be asked for once per kernel
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
@@ -650,7 +777,7 @@ hipError_t launch_t(const sv_cache* c, int stream, int layer, const void* q, int
       if (ev != hipSuccess) return ev;
     }
     const int pairs_pad = (Hkv * n_splits + 7) / 8 * 8;
-    hipLaunchKernelGGL((k_attn_chunk_pipe<NW, KS, VS>), dim3(row_tiles * pairs_pad), dim3(NW * 64), kLds, s, (const __hip_bfloat16*)q,
+    hipLaunchKernelGGL((k_attn_chunk_pipe<NW, KS, VS, INTER>), dim3(row_tiles * pairs_pad), dim3(NW * 64), kLds, s, (const __hip_bfloat16*)q,
                        (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 0),
                        (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 1), (__hip_bfloat16*)o, c->part_o,
                        c->part_ml, n_q, n_kv, causal ? 1 : 0, n_splits, keys_per_split, c->cfg.n_q_heads, G,
@@ -673,14 +800,14 @@ bool attn_mfma_supported(const sv_cache* c) {
   return c->cfg.dtype == SV_DTYPE_BF16 && c->cfg.head_dim == 128 && std::getenv("SV_NO_MFMA") == nullptr;
 }
 
-// Which chunk-prefill kernel runs (SV_CHUNK_VARIANT overrides): 2 = pipelined, 8 wavefronts, one workgroup per
-// CU, the two wavefronts of a SIMD in opposite phase order; 3 = pipelined, 4 wavefronts, two independent
-// workgroups per CU; 0 / 1 = register-staged kernels kept for comparison.  Measured: 3 is ahead on short key
-// ranges per workgroup (256-token chunk over 5.4k keys: 44.9 vs 46.6 us with merge), 2 on long ones
-// (1024-token chunk over 18k keys: 304 vs 308 us).
+// Which chunk-prefill kernel runs (SV_CHUNK_VARIANT overrides).  4 (default) = pipelined, 8 wavefronts, softmax of a
+// tile interleaved with the output MFMAs of the tile before; 2 = same staging, matrix and softmax phases kept apart,
+// the two wavefronts of a SIMD in opposite phase order; 3 = as 2 with 4 wavefronts and two independent workgroups
+// per CU; 0 / 1 = register-staged kernels.  Measured with merge, 256 / 512 / 1024-token chunk over 5.4k / 9.7k /
+// 18.4k keys: 4: 40.9 / 87.8 / 262 us; 2: 44.0 / 93.8 / 284 us; 3: 44.4 / 95.8 / 291 us.
 static int chunk_variant(int n_q) {
-  const int v = env_int("SV_CHUNK_VARIANT", -1);
-  return v >= 0 ? v : (n_q <= 512 ? 3 : 2);
+  (void)n_q;
+  return env_int("SV_CHUNK_VARIANT", 4);
 }
 
 bool attn_chunk_wants_vt(const sv_cache* c, int n_q) { return attn_mfma_supported(c) && chunk_variant(n_q) >= 2; }
@@ -691,6 +818,7 @@ hipError_t launch_attn_chunk_mfma(const sv_cache* c, int stream, int layer, cons
   if (variant == 0) return launch_t<8, false>(c, stream, layer, q, n_q, o, causal, false, s);
   if (variant == 2) return launch_t<8, true>(c, stream, layer, q, n_q, o, causal, vt_ready, s);
   if (variant == 3) return launch_t<4, true>(c, stream, layer, q, n_q, o, causal, vt_ready, s);
+  if (variant == 4) return launch_t<8, true, true>(c, stream, layer, q, n_q, o, causal, vt_ready, s);
   return launch_t<4, false>(c, stream, layer, q, n_q, o, causal, false, s);
 }
 

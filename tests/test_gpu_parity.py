@@ -294,7 +294,7 @@ def _attn_case(dtype, Hq, Hkv, d, n_kv, n_q, causal, seed):
     return gu.max_err(gu.host(od), ref), cache, w, q, k, v
 
 
-@pytest.mark.parametrize("variant", ["0", "1", "2", "3"])
+@pytest.mark.parametrize("variant", ["0", "1", "2", "3", "4"])
 @pytest.mark.parametrize("n_kv,n_q,causal,splits", [
     (64, 64, True, "0"), (200, 37, True, "0"), (1000, 256, True, "0"), (1333, 300, True, "3"),
     (777, 100, False, "2"), (5392, 256, True, "0"), (130, 1, True, "0")])
