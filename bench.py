@@ -30,9 +30,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 MEASURED_TRAFFIC = {
     # attn_chunk = k_chunk_prologue + k_attn_chunk_pipe + k_attn_combine; decode_sweep = k_decode_mfma + k_decode_merge;
     # evict = k_evict_scan + k_delta_table + k_compact (reads + writes, scaled counters)
-    "qwen7b_256v_28L": {"attn_chunk": (7.1e6 + 6.8e6) + (13.1e6 + 28.4e6) + (31.2e6 + 1.8e6),
-                        "decode_sweep": (9.32e6 + 0.52e6) + (0.65e6 + 0.01e6),
-                        "evict": (323.8e6 + 289.8e6) + 3.3e6},
+    "qwen7b_256v_28L": {"attn_chunk": (7.4e6 + 7.1e6) + (13.3e6 + 28.6e6) + (31.5e6 + 1.8e6),
+                        "decode_sweep": (9.32e6 + 0.52e6) + (0.66e6 + 0.01e6),
+                        "evict": (317.9e6 + 290.6e6) + 3.3e6},
 }
 
 
