@@ -308,6 +308,41 @@ def test_attn_chunk_mfma_shapes(variant, n_kv, n_q, causal, splits):
         os.environ.pop("SV_CHUNK_VARIANT"), os.environ.pop("SV_CHUNK_SPLITS")
 
 
+@pytest.mark.parametrize("variant", ["0", "2", "4"])
+def test_attn_chunk_wide_score_range(variant):
+    """Scores whose row maxima jump by tens to hundreds of binary orders from one key tile to the next (key blocks
+    scaled by exact powers of two, one late key by 128): the running-maximum logic of the chunk kernels (steps of
+    the reference maximum, probabilities taken before the tile's maxima are known, redo on overflow) must still
+    reproduce the plain softmax, which is then nearly one-hot."""
+    Hq, Hkv, d, n_kv, n_q, seed = 28, 4, 128, 1100, 200, 4242
+    w = si.Workload("a", 1, Hq, Hkv, d, "bf16", 2, 1e4, (0, 0, 0), 0, 0, 0, 0, 0, 0, None, 0, seed)
+    gids = np.arange(n_kv)
+    k = si.normal(seed, si.TENSOR_K, 0, gids, Hkv, d, True)
+    v = si.normal(seed, si.TENSOR_V, 0, gids, Hkv, d, True)
+    q = si.normal(seed, si.TENSOR_Q, 0, gids[n_kv - n_q:], Hq, d, True)
+    k[0:64] *= 1.0 / 64          # a first tile far below what follows
+    k[192:256] *= 16
+    k[640:704] *= 32
+    k[901] *= 128
+    k[1000:1010] *= 8            # inside the causal part of the chunk
+    os.environ["SV_CHUNK_VARIANT"] = variant
+    try:
+        _say(f"attn_chunk wide score range variant={variant}")
+        for causal in (True, False):
+            cache = sv.Cache(1, Hq, Hkv, d, sv.SV_DTYPE_BF16, sv.SV_ROPE_NONE, 1e4, (0, 0, 0), 1, n_kv + 8, n_q)
+            cache.append(0, 0, np.zeros(n_kv, dtype=np.uint8), None, gu.dev(k, w), gu.dev(v, w))
+            qd = gu.dev(q, w)
+            od = torch.empty_like(qd)
+            cache.attn_chunk(0, 0, qd, od, causal)
+            ref = orc.gqa_attention(q.astype(np.float64), k.astype(np.float64), v.astype(np.float64),
+                                    np.arange(n_kv - n_q, n_kv), causal)
+            got = gu.host(od)
+            assert np.isfinite(got).all()
+            assert gu.max_err(got, ref) <= gu.TOL["bf16"], (causal, gu.max_err(got, ref))
+    finally:
+        os.environ.pop("SV_CHUNK_VARIANT")
+
+
 @pytest.mark.parametrize("dtype,Hq,Hkv,d", [("f32", 2, 1, 64), ("f32", 8, 2, 128), ("bf16", 4, 4, 64), ("bf16", 16, 2, 64)])
 @pytest.mark.parametrize("n_kv,n_q,causal", [(72, 16, True), (300, 41, False), (1, 1, True)])
 def test_attn_chunk_rows_path(dtype, Hq, Hkv, d, n_kv, n_q, causal):
