@@ -150,7 +150,7 @@ def main():
     if dominant["bound"] == "hbm" and "decode" in dominant["kernel"]:
         roofline["note"] = ("one stream, one token: about 11 MB per launch, i.e. 1.4 us at 8 TB/s against a 1.6 us empty "
                             "launch and a 2.3 us memory round trip; the same kernel on 16 streams: --workload "
-                            "decode_noevict32k (0.71 of peak), decode_ragged16 (0.53)")
+                            "decode_noevict32k (0.80 of peak), decode_ragged16 (0.54)")
 
     out = {
         "metric": "ms per 1-s video chunk", "value": round(ms_per_step, 4), "unit": "ms", "n_gpus": 1,

@@ -66,6 +66,16 @@ __device__ __forceinline__ uint32_t bf_round_bits(float x) {
 // Rotate, in place, the two 16-byte chunks a lane holds of one row: `lo` covers
 // dims [i0, i0 + 8), `hi` the partner dims [i0 + 64, i0 + 72); c/s are cos/sin of
 // the 8 pairs.  Result is rounded to bf16, as it would be stored.
+// 16 bytes of K or V for launches that read far more than the caches hold (many long streams), every byte once:
+// a non-temporal load keeps the stream from displacing itself through L2 and the Infinity Cache (measured
+// 16 x 32k tokens: 5.7 -> 6.4 TB/s with merge).  A single stream's 11 MB per layer are partly still cached from
+// the step before, and there the plain load is the faster one (10.3 vs 10.9 us per layer-step).
+__device__ __forceinline__ uint4 stream_load(const __hip_bfloat16* p) {
+  typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4;
+  const u32x4 v = __builtin_nontemporal_load((const u32x4*)p);
+  return make_uint4(v[0], v[1], v[2], v[3]);
+}
+
 __device__ __forceinline__ void rotate_pair_chunks(uint4& lo, uint4& hi, const float (&c)[8], const float (&s)[8]) {
   uint32_t* a = (uint32_t*)&lo;
   uint32_t* b = (uint32_t*)&hi;
@@ -96,7 +106,7 @@ __device__ __forceinline__ v4i16 lds_read_tr(const char* lds_base, int byte_off)
 // ONE: a single row (one stream).  Its cache pointers, length and everything else needed to issue the first
 // loads are the leading 16 dwords of the argument list, which reach the wavefront in SGPRs at launch (kernel
 // argument preload) instead of through a first dependent fetch; the by-value table, at the end, is not read.
-template <int NW, bool ONE>
+template <int NW, bool ONE, bool STREAM>
 __global__ __launch_bounds__(NW * 64) void k_decode_mfma(__hip_bfloat16* k0_, __hip_bfloat16* v0_, const float2* cs0_,
                                                          int len0_, int keys_per_split,
                                                          const __hip_bfloat16* __restrict__ q,
@@ -142,14 +152,16 @@ __global__ __launch_bounds__(NW * 64) void k_decode_mfma(__hip_bfloat16* k0_, __
       const __hip_bfloat16* src = is_new ? k_new + new_off + 8 * lg : kp + (size_t)key * D + 8 * lg;
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk)
-        kreg[gi][kk] = key < k1 ? *(const uint4*)(src + 32 * kk) : make_uint4(0, 0, 0, 0);
+        if constexpr (STREAM) kreg[gi][kk] = key < k1 ? stream_load(src + 32 * kk) : make_uint4(0, 0, 0, 0);
+        else kreg[gi][kk] = key < k1 ? *(const uint4*)(src + 32 * kk) : make_uint4(0, 0, 0, 0);
     }
 #pragma unroll
     for (int st = 0; st < 8; ++st) {
       const int key = kt + 4 * st + lg;
       const bool is_new = fused && key == len - 1;
       const __hip_bfloat16* src = is_new ? v_new + new_off + 8 * l16 : vp + (size_t)key * D + 8 * l16;
-      vreg[st] = key < k1 ? *(const uint4*)src : make_uint4(0, 0, 0, 0);
+      if constexpr (STREAM) vreg[st] = key < k1 ? stream_load(src) : make_uint4(0, 0, 0, 0);
+      else vreg[st] = key < k1 ? *(const uint4*)src : make_uint4(0, 0, 0, 0);
     }
   };
 
@@ -425,11 +437,17 @@ hipError_t decode_launch(const sv_cache* c, const DecTable& tab, int fused, int 
   const int rotate = c->cfg.rope_mode != SV_ROPE_NONE ? 1 : 0;
   const DecRow& r = tab.r[0];
   if (nr == 1)
-    hipLaunchKernelGGL((k_decode_mfma<NW, true>), dim3(n_splits, Hkv, 1), dim3(NW * 64), 0, s, r.k, r.v, r.cs, r.len,
+    hipLaunchKernelGGL((k_decode_mfma<NW, true, false>), dim3(n_splits, Hkv, 1), dim3(NW * 64), 0, s, r.k, r.v, r.cs, r.len,
+                       keys_per_split, qp, knp, vnp, c->head_stride / 2, fused, rotate, op, c->part_o, c->part_ml,
+                       n_splits, Hq, Hkv, c->group, c_log2, tab);
+  // many streams, more than 96 MB of K and V in this launch (rows that are the layers of ONE stream keep the plain
+  // loads: their 308 MB are read again at the next token and the Infinity Cache still holds most of them)
+  else if (total_tiles * (int64_t)(TK * D * 2 * 2) * Hkv >= ((int64_t)96 << 20))
+    hipLaunchKernelGGL((k_decode_mfma<NW, false, true>), dim3(n_splits, Hkv, nr), dim3(NW * 64), 0, s, r.k, r.v, r.cs, r.len,
                        keys_per_split, qp, knp, vnp, c->head_stride / 2, fused, rotate, op, c->part_o, c->part_ml,
                        n_splits, Hq, Hkv, c->group, c_log2, tab);
   else
-    hipLaunchKernelGGL((k_decode_mfma<NW, false>), dim3(n_splits, Hkv, nr), dim3(NW * 64), 0, s, r.k, r.v, r.cs, r.len,
+    hipLaunchKernelGGL((k_decode_mfma<NW, false, false>), dim3(n_splits, Hkv, nr), dim3(NW * 64), 0, s, r.k, r.v, r.cs, r.len,
                        keys_per_split, qp, knp, vnp, c->head_stride / 2, fused, rotate, op, c->part_o, c->part_ml,
                        n_splits, Hq, Hkv, c->group, c_log2, tab);
   hipError_t e = hipGetLastError();
@@ -446,7 +464,7 @@ hipError_t launch_attn_decode_mfma(const sv_cache* c, int layer, const int32_t* 
     const int nr = std::min(kMaxRowsD, n_list - r0);
     DecTable tab = {};
     int max_len = 1;
-    int64_t total_tiles = 0;
+    int64_t total_tiles = 0;   // of the rows that are different streams: what decides the non-temporal loads
     for (int b = 0; b < nr; ++b) {
       // layer >= 0: row b is stream streams[b] at that layer; layer < 0: row b is layer b of stream streams[0]
       const int sid = layer >= 0 ? streams[r0 + b] : streams[0];
@@ -457,7 +475,7 @@ hipError_t launch_attn_decode_mfma(const sv_cache* c, int layer, const int32_t* 
       tab.r[b].len = (int)st.len;
       tab.r[b].cs = c->last_cs + (size_t)sid * (D / 2);
       max_len = std::max(max_len, (int)st.len);
-      total_tiles += (st.len + TK - 1) / TK;
+      if (layer >= 0) total_tiles += (st.len + TK - 1) / TK;
     }
     hipError_t e = nw == 2   ? decode_launch<2>(c, tab, fused, nr, max_len, total_tiles, q, k_new, v_new, o, (size_t)r0, s)
                    : nw == 1 ? decode_launch<1>(c, tab, fused, nr, max_len, total_tiles, q, k_new, v_new, o, (size_t)r0, s)

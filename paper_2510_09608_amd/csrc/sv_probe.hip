@@ -37,17 +37,19 @@ __global__ __launch_bounds__(256) void k_probe_mfma(int iters, float* sink) {
 
 // grid-stride read of `n16` 16-byte words; one word per lane and step, 8 steps in flight
 __global__ __launch_bounds__(256) void k_probe_read(const u32x4* __restrict__ src, size_t n16, float* sink) {
-  const size_t stride = (size_t)gridDim.x * blockDim.x;
-  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  // every workgroup streams its own contiguous span, 8 independent 16-byte non-temporal loads per lane in flight
+  const size_t span = (n16 + gridDim.x - 1) / gridDim.x;
+  const size_t i0 = (size_t)blockIdx.x * span, i1 = i0 + span < n16 ? i0 + span : n16;
+  size_t i = i0 + threadIdx.x;
   uint32_t acc = 0;
-  for (; i + 7 * stride < n16; i += 8 * stride) {
+  for (; i + 7 * 256 < i1; i += 8 * 256) {
     u32x4 v[8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) v[j] = __builtin_nontemporal_load(src + i + j * stride);
+    for (int j = 0; j < 8; ++j) v[j] = __builtin_nontemporal_load(src + i + j * 256);
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc ^= v[j][0] ^ v[j][1] ^ v[j][2] ^ v[j][3];
   }
-  for (; i < n16; i += stride) {
+  for (; i < i1; i += 256) {
     const u32x4 v = src[i];
     acc ^= v[0] ^ v[1] ^ v[2] ^ v[3];
   }

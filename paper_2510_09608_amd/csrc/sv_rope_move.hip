@@ -285,8 +285,16 @@ __global__ __launch_bounds__(256) void k_compact(const T* __restrict__ old_base,
   const T* s = old_base + plane + (size_t)src[j] * D;
   T* d = new_base + plane + (size_t)j * D;
   Vec16<T> lo, hi;
-  lo.raw = *(const decltype(lo.raw)*)(s + t * G::EPV);
-  hi.raw = *(const decltype(hi.raw)*)(s + D / 2 + t * G::EPV);
+  // the old buffer is read once and dead afterwards: non-temporal loads (16 bytes as a native vector); measured
+  // 92.8 -> 90 us for 28 layers at 5.1k retained tokens, non-temporal stores on top of that: no change
+  typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4;
+  static_assert(sizeof(lo.raw) == sizeof(u32x4), "16-byte vectors");
+  {
+    const u32x4 a = __builtin_nontemporal_load((const u32x4*)(s + t * G::EPV));
+    const u32x4 b = __builtin_nontemporal_load((const u32x4*)(s + D / 2 + t * G::EPV));
+    __builtin_memcpy(&lo.raw, &a, 16);
+    __builtin_memcpy(&hi.raw, &b, 16);
+  }
   if (which == 0 && rotate && delta[j] != 0) {
     const float2* cs = dtab + (size_t)j * (D / 2) + t * G::EPV;
 #pragma unroll
