@@ -436,13 +436,15 @@ hipError_t decode_launch(const sv_cache* c, const DecTable& tab, int fused, int 
   __hip_bfloat16* op = (__hip_bfloat16*)o + r0 * Hq * D;
   const int rotate = c->cfg.rope_mode != SV_ROPE_NONE ? 1 : 0;
   const DecRow& r = tab.r[0];
-  if (nr == 1)
+  // More than 96 MB of K and V in this launch, one long stream or many: non-temporal loads (rows that are the layers
+  // of ONE stream keep the plain loads: their 308 MB are read again at the next token and the Infinity Cache still
+  // holds most of them).
+  const bool stream_loads = total_tiles * (int64_t)(TK * D * 2 * 2) * Hkv >= ((int64_t)96 << 20);
+  if (nr == 1 && !stream_loads)
     hipLaunchKernelGGL((k_decode_mfma<NW, true, false>), dim3(n_splits, Hkv, 1), dim3(NW * 64), 0, s, r.k, r.v, r.cs, r.len,
                        keys_per_split, qp, knp, vnp, c->head_stride / 2, fused, rotate, op, c->part_o, c->part_ml,
                        n_splits, Hq, Hkv, c->group, c_log2, tab);
-  // many streams, more than 96 MB of K and V in this launch (rows that are the layers of ONE stream keep the plain
-  // loads: their 308 MB are read again at the next token and the Infinity Cache still holds most of them)
-  else if (total_tiles * (int64_t)(TK * D * 2 * 2) * Hkv >= ((int64_t)96 << 20))
+  else if (stream_loads)
     hipLaunchKernelGGL((k_decode_mfma<NW, false, true>), dim3(n_splits, Hkv, nr), dim3(NW * 64), 0, s, r.k, r.v, r.cs, r.len,
                        keys_per_split, qp, knp, vnp, c->head_stride / 2, fused, rotate, op, c->part_o, c->part_ml,
                        n_splits, Hq, Hkv, c->group, c_log2, tab);
