@@ -434,6 +434,38 @@ def test_decode_ragged_batch_full_size():
         assert np.array_equal(pos.astype(np.int64), oracles[s].positions())
 
 
+def test_decode_long_single_stream():
+    """One stream long enough (50k tokens, 102 MB of K and V per layer) that its decode launch takes the
+    non-temporal-load instantiation of the single-stream kernel; plain decode and the fused step against the oracle."""
+    n = 50_000
+    w = si.Workload("l", 1, 28, 4, 128, "bf16", 2, 1e6, (16, 24, 24), 0, 0, 0, 0, 0, 0, None, 0, 77)
+    cache = sv.Cache(1, 28, 4, 128, sv.SV_DTYPE_BF16, sv.SV_ROPE_3D, w.rope_theta, w.mrope_sections, 1, n + 8, 16)
+    o = orc.OracleStream(1, 28, 4, 128, orc.ROPE_3D, w.rope_theta, w.mrope_sections)
+    _say(f"long single stream decode, {n} tokens")
+    for g0 in range(0, n, 10_000):
+        gids = np.arange(g0, g0 + 10_000)
+        k = si.normal(w.seed, si.TENSOR_K, 0, gids, 4, 128, True)
+        v = si.normal(w.seed, si.TENSOR_V, 0, gids, 4, 128, True)
+        cache.append(0, 0, np.full(len(gids), orc.TEXT, dtype=np.uint8), None, gu.dev(k, w), gu.dev(v, w))
+        o.append_meta([orc.TEXT] * len(gids))
+        o.append_kv(0, k, v)
+    q, _, _ = w.qkv(0, np.array([n - 1]))
+    qd = gu.dev(q, w)
+    cache.rope_apply(0, n - 1, 1, qd, None)
+    od = torch.empty_like(qd)
+    cache.attn_decode(0, [0], qd, od)
+    err = gu.max_err(gu.host(od), o.attend(0, q, [n - 1]))
+    assert err <= gu.TOL["bf16"], err
+    gid = np.array([n])
+    q2, k2, v2 = w.qkv(0, gid)
+    o.append_meta([orc.TEXT])
+    o.append_kv(0, k2, v2)
+    od2 = torch.empty_like(qd)
+    cache.decode_step(0, [0], gu.dev(q2, w), gu.dev(k2, w), gu.dev(v2, w), od2)
+    err2 = gu.max_err(gu.host(od2), o.attend(0, q2, [n]))
+    assert err2 <= gu.TOL["bf16"], err2
+
+
 def test_high_frame_rate_chunk_sampled_rows():
     """1024 vision tokens per chunk against ~17.4k retained tokens; oracle evaluates sampled query rows."""
     w = si.workload_high_fps(n_chunks=18)
