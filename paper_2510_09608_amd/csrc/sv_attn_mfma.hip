@@ -12,8 +12,10 @@
 //   * A wavefront owns 32 rows; a workgroup of NW wavefronts owns NW * 32 rows of one
 //     kv head and one key range (split-KV); key ranges are merged afterwards with
 //     the log-sum-exp rule.  Two wavefronts share a SIMD (NW = 8, or two workgroups
-//     of 4 per CU), so one wavefront's softmax overlaps the other's MFMAs and the
-//     vector ALU is fed every cycle (a single wavefront issues at half rate).
+//     of 4 per CU): inside ONE wavefront an MFMA and the vector instructions behind it
+//     do not overlap (1 MFMA + 8 FMA measure 62 cycles, not 32), across two they do, as
+//     long as the vector work sits in small pieces behind the MFMAs (about 20 cycles of
+//     it per MFMA are hidden; the default kernel interleaves accordingly).
 //   * Scores are computed transposed, S^T = K Q^T, so that a lane holds scores of
 //     ONE query row: row max and row sum are in-lane plus one exchange between the
 //     two half-wavefronts, and the output O^T = V^T P^T keeps one query row per
@@ -26,7 +28,8 @@
 //     through registers: V row-major exactly as loaded, read back as the V^T operand with the LDS transpose read
 //     (ds_read_b64_tr_b16, two per operand), LDS double-buffered, one barrier per tile.  k_attn_chunk_pipe (the
 //     default) brings K and V^T tiles to LDS with direct loads, four slots per tensor, and reads V^T fragments
-//     with plain 16-byte reads from tiles that k_vt_build transposed once per launch; see its own header.
+//     with plain 16-byte reads from tiles that a staging pass transposed once per launch; see its own header.
+//     Its default order of work spreads the softmax of a tile through the output MFMAs of the tile before.
 
 #include <hip/hip_bf16.h>
 
