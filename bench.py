@@ -169,6 +169,8 @@ def main():
         "roofline": roofline,
         "roofline_all": roofs,
     }
+    if args.workload == "qwen7b_256v_28L":
+        out["extra_prefill_1024v"] = prefill_1024v_figure(Hq, Hkv, d)
     out["empirical_ceiling"] = empirical_ceiling()
     for r in [out["roofline"]] + out["roofline_all"]:
         ceil = out["empirical_ceiling"]["mfma_bf16_tflops" if r["bound"] == "mfma" else "hbm_read_gbs"]
@@ -181,6 +183,42 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(L)
     print(json.dumps(out))
+
+
+def prefill_1024v_figure(Hq, Hkv, d, n_kv=18432, n_q=1024, layers=4, reps=40):
+    """Extra figure, never `value`: chunk-prefill attention alone at the high-frame-rate shape (1024-token chunk over
+    a 17.4k-token retained cache, the shape of --workload qwen7b_1024v_28L), where the MFMA kernel has its longest key
+    ranges.  One `sv_attn_chunk` call per layer = V^T staging + attention + split merge, timed with events on the
+    launch stream; the kernel-only duration is in profiles/kernel_trace_qwen7b_1024v_28L.txt."""
+    import numpy as np
+    import torch
+
+    import paper_2510_09608_amd as sv
+    dev = "cuda:0"
+    cache = sv.Cache(layers, Hq, Hkv, d, sv.SV_DTYPE_BF16, sv.SV_ROPE_NONE, 1e6, (0, 0, 0), 1, n_kv + 64, n_q)
+    g = torch.Generator(device=dev).manual_seed(4)
+    rnd = lambda *shape: torch.randn(*shape, device=dev, generator=g).to(torch.bfloat16)
+    types = np.zeros(n_kv, dtype=np.uint8)
+    for l in range(layers):
+        cache.append(0, l, types if l == 0 else None, None, rnd(n_kv, Hkv, d), rnd(n_kv, Hkv, d))
+    q = rnd(layers, n_q, Hq, d)
+    o = torch.empty_like(q)
+    for l in range(layers):
+        cache.attn_chunk(0, l, q[l], o[l], True)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        for l in range(layers):
+            cache.attn_chunk(0, l, q[l], o[l], True)
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / (reps * layers)
+    flops = 4.0 * d * n_q * ((n_kv - n_q) + (n_q + 1) / 2.0) * Hq
+    tf = flops / us / 1e6
+    return {"shape": f"{n_q}-token chunk, {n_kv} keys, {Hq}q/{Hkv}kv x {d}", "us_per_layer": round(us, 2),
+            "tflops": round(tf, 1), "frac_of_peak": round(tf / 2500.0, 4),
+            "includes": "V^T staging + k_attn_chunk_pipe + k_attn_combine and the launch gaps"}
 
 
 def empirical_ceiling():
