@@ -343,6 +343,51 @@ def test_attn_chunk_wide_score_range(variant):
         os.environ.pop("SV_CHUNK_VARIANT")
 
 
+def test_attn_randomized_shapes():
+    """Seeded sweep over cache lengths 1..2600, chunk lengths 1..300, both masks, forced split counts and key blocks
+    scaled by powers of two (row maxima that drift or jump between tiles): chunk attention of the default kernel and
+    the decode of the last token, each against the oracle."""
+    rng = np.random.default_rng(20251009)
+    for case in range(120):
+        n_kv = int(rng.choice([rng.integers(1, 130), rng.integers(130, 700), rng.integers(700, 2600)]))
+        n_q = int(min(n_kv, rng.choice([1, rng.integers(1, 40), rng.integers(40, 300)])))
+        causal = bool(rng.integers(0, 2))
+        splits = str(int(rng.choice([0, 0, 1, 2, 3, 5])))
+        scale_mode = int(rng.integers(0, 3))
+        seed = 7000 + case
+        w = si.Workload("a", 1, 28, 4, 128, "bf16", 2, 1e4, (0, 0, 0), 0, 0, 0, 0, 0, 0, None, 0, seed)
+        gids = np.arange(n_kv)
+        k = si.normal(seed, si.TENSOR_K, 0, gids, 4, 128, True)
+        v = si.normal(seed, si.TENSOR_V, 0, gids, 4, 128, True)
+        q = si.normal(seed, si.TENSOR_Q, 0, gids[n_kv - n_q:], 28, 128, True)
+        if scale_mode == 1:      # magnitudes growing along the keys (powers of two keep bf16 exact)
+            for b in range(0, n_kv, 48):
+                k[b:b + 48] *= 2.0 ** min(6, b // 96)
+        elif scale_mode == 2:    # blocks scaled up or down at random
+            for b in range(0, n_kv, 32):
+                k[b:b + 32] *= 2.0 ** int(rng.integers(-5, 6))
+        _say(f"randomized case {case}: n_kv={n_kv} n_q={n_q} causal={causal} splits={splits} scale_mode={scale_mode}")
+        os.environ["SV_CHUNK_SPLITS"] = splits
+        try:
+            cache = sv.Cache(1, 28, 4, 128, sv.SV_DTYPE_BF16, sv.SV_ROPE_NONE, 1e4, (0, 0, 0), 1, n_kv + 8, n_q)
+            cache.append(0, 0, np.zeros(n_kv, dtype=np.uint8), None, gu.dev(k, w), gu.dev(v, w))
+            qd = gu.dev(q, w)
+            od = torch.empty_like(qd)
+            cache.attn_chunk(0, 0, qd, od, causal)
+        finally:
+            os.environ.pop("SV_CHUNK_SPLITS")
+        k64, v64 = k.astype(np.float64), v.astype(np.float64)
+        ref = orc.gqa_attention(q.astype(np.float64), k64, v64, np.arange(n_kv - n_q, n_kv), causal)
+        got = gu.host(od)
+        assert np.isfinite(got).all(), case
+        assert gu.max_err(got, ref) <= gu.TOL["bf16"], (case, gu.max_err(got, ref))
+        qd1 = gu.dev(q[-1:], w)
+        od1 = torch.empty_like(qd1)
+        cache.attn_decode(0, [0], qd1, od1)
+        ref1 = orc.gqa_attention(q[-1:].astype(np.float64), k64, v64, np.array([n_kv - 1]), True)
+        assert gu.max_err(gu.host(od1), ref1) <= gu.TOL["bf16"], (case, "decode")
+
+
 @pytest.mark.parametrize("dtype,Hq,Hkv,d", [("f32", 2, 1, 64), ("f32", 8, 2, 128), ("bf16", 4, 4, 64), ("bf16", 16, 2, 64)])
 @pytest.mark.parametrize("n_kv,n_q,causal", [(72, 16, True), (300, 41, False), (1, 1, True)])
 def test_attn_chunk_rows_path(dtype, Hq, Hkv, d, n_kv, n_q, causal):
