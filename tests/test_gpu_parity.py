@@ -229,6 +229,53 @@ def test_long_stream_integer_state():
     assert cache.len(0) == 5392
 
 
+def test_randomized_streams_integer_state():
+    """Seeded sweep: streams of random vision grids (1..3 x 1..12 x 1..16) and text runs, random budgets (0, infinite,
+    windows that cut blocks in the middle), evictions skipped now and then, 1-D and 3-D positions: retained ids and
+    positions after every eviction equal the oracle's, bit for bit."""
+    rng = np.random.default_rng(2510_09608)
+    z = lambda n: np.zeros((n, 1, 2))
+    zt = torch.zeros(640, 1, 64, device="cuda:0")
+    for case in range(100):
+        mode3d = bool(rng.integers(0, 2))
+        n_sink = int(rng.choice([0, 1, 5, 64]))
+        vw = int(rng.choice([-1, 0, 7, 100, 300, 1000]))
+        tw = int(rng.choice([-1, 0, 3, 40, 200]))
+        n_chunks = int(rng.integers(3, 25))
+        ncmp = 3 if mode3d else 1
+        _say(f"randomized stream {case}: 3d={mode3d} budgets=({n_sink},{vw},{tw}) chunks={n_chunks}")
+        cache = sv.Cache(1, 1, 1, 64, sv.SV_DTYPE_F32, sv.SV_ROPE_3D if mode3d else sv.SV_ROPE_1D, 1e4,
+                         (8, 12, 12) if mode3d else (0, 0, 0), 1, 64 + n_chunks * 700, 640)
+        o = orc.OracleStream(1, 1, 1, 2, orc.ROPE_3D if mode3d else orc.ROPE_1D, 1e4, (1, 0, 0))
+
+        def check():
+            assert cache.evict(0, n_sink, vw, tw) == o.evict(n_sink, vw, tw)
+            ids, pos = cache.retained(0)
+            assert np.array_equal(ids, np.asarray(o.gid, dtype=np.int64))
+            assert np.array_equal(pos.astype(np.int64)[:, :ncmp], o.positions()[:, :ncmp])
+
+        pre = int(rng.choice([0, 3, 50]))
+        if pre:
+            cache.append(0, 0, np.zeros(pre, dtype=np.uint8), None, zt[:pre], zt[:pre])
+            o.append_meta([orc.TEXT] * pre)
+            o.append_kv(0, z(pre), z(pre))
+        for _ in range(n_chunks):
+            if rng.integers(0, 4) != 0:
+                check()
+            T, H, W = int(rng.integers(1, 4)), int(rng.integers(1, 13)), int(rng.integers(1, 17))
+            nv = T * H * W
+            if rng.integers(0, 5) != 0:
+                cache.append(0, 0, np.ones(nv, dtype=np.uint8), (T, H, W), zt[:nv], zt[:nv])
+                o.append_meta([orc.VISION] * nv, (T, H, W))
+                o.append_kv(0, z(nv), z(nv))
+            nt = int(rng.integers(0, 20))
+            if nt:
+                cache.append(0, 0, np.zeros(nt, dtype=np.uint8), None, zt[:nt], zt[:nt])
+                o.append_meta([orc.TEXT] * nt)
+                o.append_kv(0, z(nt), z(nt))
+        check()
+
+
 # ----------------------------------------------------------------------------
 # single operations
 # ----------------------------------------------------------------------------
