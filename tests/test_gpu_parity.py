@@ -276,6 +276,57 @@ def test_randomized_streams_integer_state():
         check()
 
 
+def test_randomized_streams_stored_kv():
+    """Seeded sweep, two layers, fp32 (d 64) and bf16 (d 128), 1-D and 3-D positions, random grids / text runs /
+    budgets: after every step V as stored is the appended V bit for bit and K as stored is the raw K rotated at the
+    token's CURRENT position (appended rotated, re-rotated by every compaction that moved it: one rounding each)."""
+    rng = np.random.default_rng(96082510)
+    worst = {"f32": 0.0, "bf16": 0.0}
+    for case in range(40):
+        dtype = "f32" if rng.integers(0, 2) else "bf16"
+        mode = int(rng.integers(0, 2))
+        d, Hq, Hkv = (64, 2, 1) if dtype == "f32" else (128, 28, 4)
+        sec = (0, 0, 0) if mode == 0 else ((8, 12, 12) if d == 64 else (16, 24, 24))
+        theta = 1e4 if dtype == "f32" else 1e6
+        n_sink, vw, tw = int(rng.choice([0, 2, 9])), int(rng.choice([0, 17, 90, 200])), int(rng.choice([0, 4, 30]))
+        w = si.Workload("t", 2, Hq, Hkv, d, dtype, mode, theta, sec, n_sink, vw, tw, 0, 0, 0, None, 0, 100 + case)
+        cache = gu.make_cache(w, capacity=4096)
+        o = orc.OracleStream(2, Hq, Hkv, d, mode, theta, sec)
+        _say(f"randomized stored K/V {case}: {dtype} mode={mode} budgets=({n_sink},{vw},{tw})")
+        g0 = 0
+        for c in range(int(rng.integers(3, 9))):
+            spans = []
+            if rng.integers(0, 4):
+                T, H, W = int(rng.integers(1, 3)), int(rng.integers(1, 7)), int(rng.integers(1, 9))
+                spans.append((orc.VISION, T * H * W, (T, H, W)))
+            nt = int(rng.integers(0, 12))
+            if nt:
+                spans.append((orc.TEXT, nt, None))
+            for ty, n, grid in spans:
+                gids = np.arange(g0, g0 + n)
+                g0 += n
+                o.append_meta([ty] * n, grid)
+                for l in range(2):
+                    _, k, v = w.qkv(l, gids)
+                    cache.append(0, l, np.full(n, ty, dtype=np.uint8) if l == 0 else None, grid if l == 0 else None,
+                                 gu.dev(k, w), gu.dev(v, w))
+                    o.append_kv(l, k, v)
+            if rng.integers(0, 3):
+                assert cache.evict(0, n_sink, vw, tw) == o.evict(n_sink, vw, tw)
+            n = len(o)
+            if n == 0:
+                continue
+            pos = o.positions()
+            tol = (1e-5 if dtype == "f32" else 4e-2) * (1 + c)      # one rounding per compaction so far
+            for l in range(2):
+                K, V = np.stack(o.k[l]), np.stack(o.v[l])
+                assert np.array_equal(cache.read_kv(0, l, 1, 0, n).astype(np.float64), V), (case, c, l)
+                e = gu.max_err(cache.read_kv(0, l, 0, 0, n), orc.rope(K, pos, mode, theta, sec))
+                worst[dtype] = max(worst[dtype], e)
+                assert e <= tol, (case, c, l, e)
+    _say(f"stored K worst error {worst}")
+
+
 # ----------------------------------------------------------------------------
 # single operations
 # ----------------------------------------------------------------------------
