@@ -165,6 +165,8 @@ __global__ __launch_bounds__(256) void k_rope_rows(T* __restrict__ x, const int4
 constexpr int VT_KEYS = 64;              // keys per block
 constexpr int VT_D = 128;
 constexpr int VT_ROW = VT_D * 2 + 64;    // LDS row stride in bytes: transpose reads fall in distinct banks
+constexpr int VT_OROW = VT_KEYS * 2 + 16;   // row stride of the transposed block on its way out
+static_assert(VT_D * VT_OROW <= VT_KEYS * VT_ROW, "the transposed block reuses the staging buffer");
 typedef short v4i16 __attribute__((ext_vector_type(4)));
 typedef short v8i16 __attribute__((ext_vector_type(8)));
 
@@ -189,6 +191,8 @@ __device__ __forceinline__ void vt_block(char* sT, int blk, int hk, const __hip_
   __syncthreads();
   const int wave = tid >> 6, lane = tid & 63, j16 = lane & 15, g = lane >> 4;
   __hip_bfloat16* dst = vt + (size_t)hk * vt_head_stride_elems + (size_t)blk * VT_KEYS * VT_D;
+  // transposing reads: 8 keys (r0 .. r0 + 7) of head dim c0 + j16 per lane
+  v8i16 a8[2][2];
 #pragma unroll
   for (int ko = 0; ko < 2; ++ko)
 #pragma unroll
@@ -200,9 +204,25 @@ __device__ __forceinline__ void vt_block(char* sT, int blk, int hk, const __hip_
             (v4i16 __attribute__((address_space(3)))*)((__attribute__((address_space(3))) char*)sT + o));
       };
       const v4i16 a0 = rd(off), a1 = rd(off + 4 * VT_ROW);
-      const v8i16 a8 = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
-      *(v8i16*)(dst + (size_t)(c0 + j16) * VT_KEYS + r0) = a8;   // head dim c0 + j16, keys r0 .. r0 + 7
+      a8[ko][ds] = v8i16{a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
     }
+  // A lane's 16 bytes belong to a row of V^T of their own (64 different 128-byte rows per store instruction), so
+  // the block goes back through LDS in V^T layout (rows of 64 keys, 144-byte stride: conflict-free for the 16-byte
+  // writes) and leaves as full 128-byte rows, 8 lanes per row.
+  __syncthreads();
+#pragma unroll
+  for (int ko = 0; ko < 2; ++ko)
+#pragma unroll
+    for (int ds = 0; ds < 2; ++ds) {
+      const int r0 = 16 * wave + 8 * ko, c0 = 64 * ds + 16 * g;
+      *(v8i16*)(sT + (c0 + j16) * VT_OROW + r0 * 2) = a8[ko][ds];
+    }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = (tid >> 3) + 32 * i, ch = tid & 7;
+    *(uint4*)(dst + (size_t)row * VT_KEYS + ch * 8) = *(const uint4*)(sT + row * VT_OROW + ch * 16);
+  }
 }
 
 // grid: (blocks of 64 keys, kv heads)
