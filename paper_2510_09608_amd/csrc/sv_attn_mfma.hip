@@ -275,6 +275,7 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_mfma(
 //     softmax running in the same iteration; LDS operands are fetched one batch ahead of the MFMAs that use them.
 // ---------------------------------------------------------------------------------
 constexpr int PIPE_TILE = TK * D * 2;   // 16 KB per tile, unpadded
+constexpr int PIPE_OROW = D + 4;         // floats per row of a wavefront's partial result on its way out through LDS
 
 // 16 bytes per lane from global memory straight into LDS: lane L's bytes land at lds_dst + 16 L (lds_dst is
 // uniform over the wavefront and travels in M0).  Written as assembly on purpose: the compiler then does not
@@ -699,9 +700,9 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
   }
 
   const float l_tot = l_run + __shfl_xor(l_run, 32);
-  if (!rvalid) return;
   const int h = hk * G + hg;
   if (n_splits == 1) {
+    if (!rvalid) return;
     const float inv = 1.0f / l_tot;
     __hip_bfloat16* op = out + ((size_t)qi * n_q_heads + h) * D;
 #pragma unroll
@@ -714,20 +715,34 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
         for (int e = 0; e < 4; ++e) pk[e] = (__bf16)(oacc[db][r4 * 4 + e] * inv);
         *(uint2*)(op + dv) = *(uint2*)&pk;
       }
-  } else {
-    const size_t p = ((size_t)qi * n_splits + sp) * n_q_heads + h;
-    float* po = part_o + p * D;
+    return;
+  }
+  // Partial result: a lane holds one row (512 bytes of fp32) in 16-byte pieces, so stored directly every
+  // instruction would touch 32 rows with 32 bytes each.  The wavefront's 32 rows go through LDS (its own 16.5 KB,
+  // rows padded to 132 floats: conflict-free both ways) and leave as whole rows, 32 lanes per row.
+  __syncthreads();   // every wavefront is past its last read of the tile slots
+  float* so = (float*)smem + wave * (32 * PIPE_OROW);
+  if (rvalid) {
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
         const int dv = 32 * db + 8 * r4 + 4 * hh;
-        *(float4*)(po + dv) = make_float4(oacc[db][r4 * 4], oacc[db][r4 * 4 + 1], oacc[db][r4 * 4 + 2],
-                                          oacc[db][r4 * 4 + 3]);
+        *(float4*)(so + l32 * PIPE_OROW + dv) = make_float4(oacc[db][r4 * 4], oacc[db][r4 * 4 + 1],
+                                                            oacc[db][r4 * 4 + 2], oacc[db][r4 * 4 + 3]);
       }
     if (hh == 0) {
+      const size_t p = ((size_t)qi * n_splits + sp) * n_q_heads + h;
       part_ml[p * 2] = m_run == -INFINITY ? -INFINITY : m_run * c_log2;
       part_ml[p * 2 + 1] = l_tot;
+    }
+  }
+#pragma unroll 4
+  for (int i = 0; i < 16; ++i) {
+    const int r = 2 * i + hh, row2 = rt * ROWS_WG + wave * 32 + r;
+    if (row2 < n_rows) {
+      const size_t p2 = ((size_t)(row2 / G) * n_splits + sp) * n_q_heads + hk * G + row2 % G;
+      *(float4*)(part_o + p2 * D + 4 * l32) = *(const float4*)(so + r * PIPE_OROW + 4 * l32);
     }
   }
 }
@@ -744,7 +759,7 @@ hipError_t launch_t(const sv_cache* c, int stream, int layer, const void* q, int
   // pipelined kernel: 8 wavefronts with 4 + 4 tile slots (128 KB, one workgroup per CU) or 4 wavefronts with
   // 3 + 2 (80 KB, two independent workgroups per CU)
   constexpr int KS = NW == 8 ? 4 : 3, VS = NW == 8 ? 4 : 2;
-  constexpr int kLds = PIPE ? (KS + VS) * PIPE_TILE : 2 * BUF_BYTES;
+  constexpr int kLds = PIPE ? std::max((KS + VS) * PIPE_TILE, NW * 32 * PIPE_OROW * 4) : 2 * BUF_BYTES;
   const void* kern = PIPE ? (const void*)k_attn_chunk_pipe<NW, KS, VS, INTER> : (const void*)k_attn_chunk_mfma<NW>;
   static bool attr_set = false;   // more than 64 KB of LDS has to be asked for once per kernel
   if (!attr_set) {
