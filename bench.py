@@ -38,6 +38,8 @@ MEASURED_TRAFFIC = {
 
 def parse_args():
     ap = argparse.ArgumentParser()
+    ap.add_argument("--no-extra-figures", action="store_true",
+                    help="skip the figures that run other shapes (keeps a kernel trace of the workload clean)")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=40, help="untimed chunks; >= 33 reaches steady state")
@@ -169,7 +171,7 @@ def main():
         "roofline": roofline,
         "roofline_all": roofs,
     }
-    if args.workload == "qwen7b_256v_28L":
+    if args.workload == "qwen7b_256v_28L" and not args.no_extra_figures:
         out["extra_prefill_1024v"] = prefill_1024v_figure(Hq, Hkv, d)
     out["empirical_ceiling"] = empirical_ceiling()
     for r in [out["roofline"]] + out["roofline_all"]:
