@@ -42,7 +42,9 @@ def parse_args():
                     help="skip the figures that run other shapes (keeps a kernel trace of the workload clean)")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=40, help="untimed chunks; >= 33 reaches steady state")
+    ap.add_argument("--warmup", type=int, default=40,
+                    help="untimed chunks; the stream workloads always fill to steady state first (33 chunks at the "
+                         "default workload), whatever this says")
     ap.add_argument("--workload", default="qwen7b_256v_28L",
                     choices=["qwen7b_256v_28L", "qwen7b_1024v_28L", "decode_ragged16", "decode_noevict32k",
                              "noevict_growth", "budget_sweep", "overlap_recompute"])
@@ -84,8 +86,63 @@ def main():
         print(json.dumps({"noevict_growth": noevict_growth_bench, "budget_sweep": budget_sweep_bench,
                           "overlap_recompute": overlap_recompute_bench}[args.workload](args)))
         return
-    w = si.workload_qwen_stream() if args.workload == "qwen7b_256v_28L" else si.workload_high_fps(n_layers=28)
-    L = args.layers
+    res = stream_workload(args.workload, args.layers, args.steps, args.warmup, args.pool, batched_leg=True)
+    out = {
+        "metric": "ms per 1-s video chunk", "value": res["ms_per_step"], "unit": "ms", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": res["config"],
+        "prefill_attn_tflops": res["inst"]["prefill_attn_tflops"],
+        "decode_kv_gbs": res["inst"]["decode_kv_gbs"],
+        "compaction_gbs": res["inst"]["compaction_gbs"],
+        "ms_per_step_three_calls": res["inst"]["ms_per_chunk"],
+        "ms_per_step_decode_layers_batched": res["ms_layer_batched"],
+        "breakdown_us": res["inst"]["us"],
+        "roofline": res["roofline"],
+        "roofline_all": res["inst"]["roofline_all"],
+    }
+    if args.workload == "qwen7b_256v_28L" and not args.no_extra_figures:
+        # the other legs of the metric at the configurations they are quoted on, each timed in this same run
+        out["extra_prefill_1024v"] = prefill_1024v_figure(28, 4, 128)
+        hf = stream_workload("qwen7b_1024v_28L", args.layers, min(args.steps, 12), 0, 2, batched_leg=False)
+        out["extra_step_1024v_28L"] = {"ms_per_step": hf["ms_per_step"], "config": hf["config"],
+                                       "breakdown_us": hf["inst"]["us"],
+                                       "prefill_attn_tflops": hf["inst"]["prefill_attn_tflops"],
+                                       "decode_kv_gbs": hf["inst"]["decode_kv_gbs"],
+                                       "compaction_gbs": hf["inst"]["compaction_gbs"],
+                                       "roofline_all": hf["inst"]["roofline_all"]}
+        for name in ("decode_ragged16", "decode_noevict32k"):
+            sub = argparse.Namespace(**vars(args))
+            sub.workload, sub.steps, sub.warmup = name, min(args.steps, 40), 24
+            d = decode_batch_bench(sub, with_ceiling=False)
+            out["extra_" + name] = {"decode_kv_gbs": d["value"], "config": d["config"]["workload"],
+                                    "roofline": d["roofline"]}
+    out["empirical_ceiling"] = empirical_ceiling()
+    for r in [out["roofline"]] + out["roofline_all"]:
+        ceil = out["empirical_ceiling"]["mfma_bf16_tflops" if r["bound"] == "mfma" else "hbm_read_gbs"]
+        r["frac_of_measured_ceiling"] = round(r["achieved"] / ceil, 4)
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
+        dst = torch.empty_like(src)
+        dst.copy_(src)                       # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.layers)
+    print(json.dumps(out))
+
+
+def stream_workload(name, L, steps, warmup, pool_n, batched_leg):
+    """One of the per-second stream workloads at steady state: `steps` timed chunks through sv_stream_step, then
+    the instrumented pass.  The stream is first filled, untimed, until the cache holds the steady-state length
+    (retained + one chunk), whatever `warmup` says; the length is checked before the timed region starts and after
+    it ends, and the program exits non-zero if either is not the steady-state length."""
+    import torch
+
+    import paper_2510_09608_amd as sv
+    import sv_inputs as si
+    from paper_2510_09608_amd.stream import StreamRunner
+    dev = "cuda:0"
+    w = si.workload_qwen_stream() if name == "qwen7b_256v_28L" else si.workload_high_fps(n_layers=28)
     Hq, Hkv, d = w.n_q_heads, w.n_kv_heads, w.head_dim
     nv, nt = w.vision_per_chunk, w.text_per_chunk
     R = w.retained_steady()
@@ -97,94 +154,75 @@ def main():
     rnd = lambda *shape: torch.randn(*shape, device=dev, generator=g).to(torch.bfloat16)
     # pool[p] = inputs of one chunk for all layers: vision q/k/v and the 16 text tokens' q/k/v
     pool = []
-    for _ in range(args.pool):
+    for _ in range(pool_n):
         pool.append(dict(qv=rnd(L, nv, Hq, d), kv=rnd(L, nv, Hkv, d), vv=rnd(L, nv, Hkv, d),
                          qt=rnd(nt, L, 1, Hq, d), kt=rnd(nt, L, 1, Hkv, d), vt=rnd(nt, L, 1, Hkv, d)))
     ov = torch.empty(L, nv, Hq, d, device=dev, dtype=torch.bfloat16)
-    ot = torch.empty(L, 1, Hq, d, device=dev, dtype=torch.bfloat16)
+    ot_all = torch.empty(nt, L, Hq, d, device=dev, dtype=torch.bfloat16)
     run.preamble(list(rnd(L, w.preamble_text, Hkv, d)), list(rnd(L, w.preamble_text, Hkv, d)))
-
     budgets = (w.n_sink, w.vision_window, w.text_window)
 
-    def step_native(c: int):
+    def step_native(c: int, batched=False):
         p = pool[c % len(pool)]
         cache.stream_step(0, *budgets, q_vision=p["qv"], k_vision=p["kv"], v_vision=p["vv"], o_vision=ov,
-                          grid_thw=w.grid_thw, q_text=p["qt"], k_text=p["kt"], v_text=p["vt"], o_text=ot_all)
+                          grid_thw=w.grid_thw, q_text=p["qt"], k_text=p["kt"], v_text=p["vt"], o_text=ot_all,
+                          decode_layers_batched=batched)
 
-    ot_all = torch.empty(nt, L, Hq, d, device=dev, dtype=torch.bfloat16)
-    for c in range(args.warmup):
+    # untimed fill: both windows full, i.e. the cache holds retained + one chunk at the end of a step
+    fill = max(-(-w.vision_window // nv), -(-w.text_window // nt)) + 1
+    n_warm = max(warmup, fill)
+    for c in range(n_warm):
         step_native(c)
     torch.cuda.synchronize()
+    len_start = cache.len(0)
+    if len_start != R + w.tokens_per_chunk:
+        sys.exit(f"bench.py: {name}: cache holds {len_start} tokens after {n_warm} untimed chunks, steady state is "
+                 f"{R + w.tokens_per_chunk}")
     t0 = time.perf_counter()
-    for c in range(args.warmup, args.warmup + args.steps):
+    for c in range(n_warm, n_warm + steps):
         step_native(c)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    ms_per_step = wall * 1e3 / args.steps
-    steady = cache.len(0) == R + w.tokens_per_chunk
+    ms_per_step = wall * 1e3 / steps
+    len_end = cache.len(0)
+    if len_end != R + w.tokens_per_chunk:
+        sys.exit(f"bench.py: {name}: cache length {len_end} at the end of the timed region is not the steady state")
 
     # the same step with each decode step as ONE launch over all layers (sv_decode_step_layers): possible here
     # because the benchmark holds every layer's query up front; a sequential transformer cannot, so this is an
     # extra figure, never `value`
-    c1 = args.warmup + args.steps
-    def step_batched(c: int):
-        p = pool[c % len(pool)]
-        cache.stream_step(0, *budgets, q_vision=p["qv"], k_vision=p["kv"], v_vision=p["vv"], o_vision=ov,
-                          grid_thw=w.grid_thw, q_text=p["qt"], k_text=p["kt"], v_text=p["vt"], o_text=ot_all,
-                          decode_layers_batched=True)
-    for c in range(c1, c1 + 3):
-        step_batched(c)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for c in range(c1 + 3, c1 + 3 + args.steps):
-        step_batched(c)
-    torch.cuda.synchronize()
-    ms_layer_batched = (time.perf_counter() - t0) * 1e3 / args.steps
-    args.warmup_total = c1 + 3 + args.steps
+    c1 = n_warm + steps
+    ms_layer_batched = None
+    if batched_leg:
+        for c in range(c1, c1 + 3):
+            step_native(c, True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for c in range(c1 + 3, c1 + 3 + steps):
+            step_native(c, True)
+        torch.cuda.synchronize()
+        ms_layer_batched = round((time.perf_counter() - t0) * 1e3 / steps, 4)
+        c1 += 3 + steps
 
     # second region, same work per chunk, driven call by call so that HIP events can bracket each kernel class
-    inst = instrumented_pass(cache, run, pool, w, L, args.warmup_total, ov, ot_all, n_chunks=min(10, args.steps),
-                             traffic=MEASURED_TRAFFIC.get(args.workload if L == 28 else "", {}))
+    inst = instrumented_pass(cache, run, pool, w, L, c1, ov, ot_all, n_chunks=min(10, steps),
+                             traffic=MEASURED_TRAFFIC.get(name if L == 28 else "", {}))
     roofs = inst["roofline_all"]
     dominant = max(roofs, key=lambda r: r["total_us_per_chunk"])
     roofline = {k: dominant[k] for k in ("kernel", "bound", "achieved", "peak", "unit", "frac", "traffic",
                                          "avg_launch_us", "launches")}
     if dominant["bound"] == "hbm" and "decode" in dominant["kernel"]:
         roofline["note"] = ("one stream, one token: about 11 MB per launch, i.e. 1.4 us at 8 TB/s against a 1.6 us empty "
-                            "launch and a 2.3 us memory round trip; the same kernel on 16 streams: --workload "
-                            "decode_noevict32k (0.80 of peak), decode_ragged16 (0.54)")
-
-    out = {
-        "metric": "ms per 1-s video chunk", "value": round(ms_per_step, 4), "unit": "ms", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {L} layers, {Hq}q/{Hkv}kv heads x {d}, M-RoPE (16,24,24); per chunk "
-                               f"{nv} vision + {nt} text tokens; budgets sink {w.n_sink} / vision {w.vision_window} / "
-                               f"text {w.text_window}; retained {R}", "steady_state": bool(steady),
-                   "driver": "sv_stream_step (native call sequencing)"},
-        "prefill_attn_tflops": inst["prefill_attn_tflops"],
-        "decode_kv_gbs": inst["decode_kv_gbs"],
-        "compaction_gbs": inst["compaction_gbs"],
-        "ms_per_step_three_calls": inst["ms_per_chunk"],
-        "ms_per_step_decode_layers_batched": round(ms_layer_batched, 4),
-        "breakdown_us": inst["us"],
-        "roofline": roofline,
-        "roofline_all": roofs,
-    }
-    if args.workload == "qwen7b_256v_28L" and not args.no_extra_figures:
-        out["extra_prefill_1024v"] = prefill_1024v_figure(Hq, Hkv, d)
-    out["empirical_ceiling"] = empirical_ceiling()
-    for r in [out["roofline"]] + out["roofline_all"]:
-        ceil = out["empirical_ceiling"]["mfma_bf16_tflops" if r["bound"] == "mfma" else "hbm_read_gbs"]
-        r["frac_of_measured_ceiling"] = round(r["achieved"] / ceil, 4)
-    if args.copy_calibration:
-        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
-        dst = torch.empty_like(src)
-        dst.copy_(src)                       # reads 1 GiB, writes 1 GiB
-        torch.cuda.synchronize()
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(L)
-    print(json.dumps(out))
+                            "launch and a 2.3 us memory round trip; the same kernel on 16 streams: extra_decode_noevict32k, "
+                            "extra_decode_ragged16")
+    config = {"workload": f"{name}: {L} layers, {Hq}q/{Hkv}kv heads x {d}, M-RoPE (16,24,24); per chunk "
+                          f"{nv} vision + {nt} text tokens; budgets sink {w.n_sink} / vision {w.vision_window} / "
+                          f"text {w.text_window}; retained {R}",
+              "steady_state": True, "untimed_fill_chunks": n_warm, "cache_tokens_at_start": len_start,
+              "cache_tokens_at_end": len_end, "driver": "sv_stream_step (native call sequencing)"}
+    cache.close()
+    return {"ms_per_step": round(ms_per_step, 4), "ms_layer_batched": ms_layer_batched, "inst": inst,
+            "roofline": roofline, "config": config}
 
 
 def prefill_1024v_figure(Hq, Hkv, d, n_kv=18432, n_q=1024, layers=4, reps=40):
@@ -245,7 +283,7 @@ def empirical_ceiling():
                    "1 GiB torch device copy counted as read + write"}
 
 
-def decode_batch_bench(args):
+def decode_batch_bench(args, with_ceiling=True):
     """16 independent streams, one decode token per stream per step (variable-length split-KV decode).
 
     decode_ragged16: per-stream budgets drawn as in sv_inputs.workload_ragged_batch (caches of 1.7k-9.7k tokens);
@@ -294,7 +332,7 @@ def decode_batch_bench(args):
     us_layer = sum(a.elapsed_time(b) for a, b in evs) * 1e3 / (args.steps * L)
     bytes_layer = sum(lens) * 2.0 * Hkv * d * 2
     gbs = bytes_layer / (us_layer * 1e-6) / 1e9
-    ceil = empirical_ceiling()
+    ceil = empirical_ceiling() if with_ceiling else None
     return {
         "empirical_ceiling": ceil,
         "metric": "decode KV-read GB/s", "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
@@ -307,7 +345,7 @@ def decode_batch_bench(args):
                      "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
                      "traffic": None, "avg_launch_us": round(us_layer, 2), "launches": args.steps * L,
                      "algorithmic_bytes_per_launch": bytes_layer,
-                     "frac_of_measured_ceiling": round(gbs / ceil["hbm_read_gbs"], 4)},
+                     "frac_of_measured_ceiling": round(gbs / ceil["hbm_read_gbs"], 4) if ceil else None},
     }
 
 
@@ -559,7 +597,16 @@ def cpu_baseline(L: int):
     for c in range(33, 33 + n_sample):
         sv_step.step_chunk(st, w, c, [0], want_outputs=True)
     dt = (time.perf_counter() - t0) / n_sample
-    return {"value": round(dt * 1e3 * L, 1), "unit": "ms", "cores": int(cores), "kind": "oracle",
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    return {"value": round(dt * 1e3 * L, 1), "unit": "ms", "cores": int(cores), "cpu_model": model, "kind": "oracle",
             "sample": f"{n_sample} steady-state chunks (evict, 256-token prefill, 16 decode steps each) of ONE layer took "
                       f"{dt * 1e3:.0f} ms per chunk in the fp64 numpy oracle ({dt * n_sample:.1f} s in all); value = that "
                       f"x {L} layers (extrapolated)"}

@@ -64,7 +64,14 @@ typedef struct sv_config {
   int32_t n_streams;         /* independent streams held by this cache, >= 1           */
   int64_t capacity_tokens;   /* slots per stream                                       */
   int32_t max_q_tokens;      /* largest n_q given to sv_attn_chunk (sizes its scratch) */
+  int32_t flags;             /* SV_FLAG_* bits, 0 = default                             */
 } sv_config;
+
+/* sv_config.flags.  SV_FLAG_GENERIC_KERNELS: run the generic (vector ALU) attention kernels and keep
+ * the row-major V layout even where the matrix-core kernels apply (bf16, head_dim 128, at most 8 query
+ * heads per kv head).  Same results to rounding; the parity tests use it to cover the generic kernels
+ * on bf16 data. */
+enum { SV_FLAG_GENERIC_KERNELS = 1 };
 
 typedef struct sv_cache sv_cache;
 
@@ -81,8 +88,8 @@ SV_API size_t sv_cache_bytes(const sv_config* cfg);
  * arena's contents need no initialisation.  Synchronous and cheap: touches the
  * device only to zero a few counters on `hip_stream`.
  * Errors: SV_ERR_INVALID (NULLs, n_q_heads % n_kv_heads, head_dim not 64/128,
- * sections not summing to head_dim/2, sizes < 1), SV_ERR_CAPACITY (arena too
- * small).
+ * sections not summing to head_dim/2, sizes < 1, capacity_tokens above 2^24, unknown flag bits),
+ * SV_ERR_CAPACITY (arena too small).
  * Test seam: if the environment variable SV_HOST_LOGIC_ONLY is set (not "0")
  * when a cache is created, that cache launches nothing and never touches the
  * arena: argument checks, call-order rules, lengths, retained counts and error
@@ -95,6 +102,18 @@ SV_API int sv_cache_create(const sv_config* cfg, void* dev_arena, size_t arena_b
 
 /* Free the handle (host memory only; the arena stays with the caller). */
 SV_API int sv_cache_destroy(sv_cache* c);
+
+/*
+ * sv_cache_set_option -- per-handle launch overrides; implements no passage of the paper.  Every option
+ * defaults to 0 = "let the library choose" (what all measurements use); a positive value forces
+ *   SV_OPT_CHUNK_SPLITS           the number of key ranges of sv_attn_chunk's matrix-core kernel,
+ *   SV_OPT_DECODE_TILES_PER_WAVE  the 32-key tiles each wavefront of the decode kernel takes (1..16),
+ *   SV_OPT_DECODE_SPLITS          the number of key ranges of the generic row kernel.
+ * Forced values are still clamped to what the scratch buffers hold.  Host-side state only: takes effect
+ * from the next launch.  Errors: SV_ERR_INVALID (NULL handle, unknown option, negative value).
+ */
+enum { SV_OPT_CHUNK_SPLITS = 0, SV_OPT_DECODE_TILES_PER_WAVE = 1, SV_OPT_DECODE_SPLITS = 2, SV_OPT_COUNT_ = 3 };
+SV_API int sv_cache_set_option(sv_cache* c, int option, int value);
 
 /*
  * sv_cache_append -- new tokens join the cache in arrival order and their K/V
@@ -130,7 +149,9 @@ SV_API int sv_cache_append(sv_cache* c, int stream_id, int layer, int n,
  * Fig. 3 and make it compact again.  A text token stays if it is among the
  * first n_sink text tokens ever appended to the stream or among the last
  * text_window text tokens; a vision token stays if it is among the last
- * vision_window vision tokens.  Counts are over tokens present at the call.
+ * vision_window vision tokens.  "First" and "last" go by rank among the tokens of that type EVER
+ * appended to the stream (evicted ones included), at the time of the call: with fixed budgets, evicting at
+ * every step retains exactly what one eviction at the end would.
  * Survivors keep their order; their K/V rows of all layers are moved to the
  * front (stream compaction), they get new contiguous positions (1-D: the slot
  * index; 3-D: re-walk of the retained list with the block rule, see
@@ -254,7 +275,9 @@ SV_API int sv_cache_len(sv_cache* c, int stream_id, int64_t* n_out);
  * Inspection for parity checks; SYNCHRONOUS (waits for hip_stream).  Copies
  * up to `cap` entries, in slot order: arrival ids (ids_host, [cap]) and
  * positions (pos3_host, [cap][3] as t, h, w; 1-D mode repeats the index).
- * Either pointer may be NULL.  n_out receives the cache length.
+ * Either pointer may be NULL.  n_out receives the cache length.  The device keeps its own count of the
+ * stream's tokens (written by the eviction scan and by every registration of new tokens); this call
+ * compares it with the host's bookkeeping and returns SV_ERR_STATE if the two differ.
  */
 SV_API int sv_cache_retained(sv_cache* c, int stream_id, int64_t* ids_host, int32_t* pos3_host,
                       int64_t cap, int64_t* n_out, void* hip_stream);

@@ -17,6 +17,8 @@ SV_DTYPE_F32, SV_DTYPE_BF16 = 0, 1
 SV_ROPE_1D, SV_ROPE_3D, SV_ROPE_NONE = 0, 1, 2
 SV_TEXT, SV_VISION = 0, 1
 SV_WINDOW_INF = -1
+SV_FLAG_GENERIC_KERNELS = 1
+SV_OPT_CHUNK_SPLITS, SV_OPT_DECODE_TILES_PER_WAVE, SV_OPT_DECODE_SPLITS = 0, 1, 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 
@@ -36,7 +38,7 @@ class SvConfig(C.Structure):
         ("n_layers", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
         ("dtype", C.c_int32), ("rope_mode", C.c_int32), ("rope_theta", C.c_double),
         ("mrope_sections", C.c_int32 * 3), ("n_streams", C.c_int32), ("capacity_tokens", C.c_int64),
-        ("max_q_tokens", C.c_int32),
+        ("max_q_tokens", C.c_int32), ("flags", C.c_int32),
     ]
 
 
@@ -55,6 +57,7 @@ _SIGNATURES = {
     "sv_cache_bytes": (C.c_size_t, [C.POINTER(SvConfig)]),
     "sv_cache_create": (C.c_int, [C.POINTER(SvConfig), C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_void_p)]),
     "sv_cache_destroy": (C.c_int, [C.c_void_p]),
+    "sv_cache_set_option": (C.c_int, [C.c_void_p, C.c_int, C.c_int]),
     "sv_cache_append": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
                                   C.c_void_p, C.POINTER(C.c_int64), C.c_void_p]),
     "sv_cache_evict": (C.c_int, [C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.POINTER(C.c_int64),
@@ -130,6 +133,10 @@ def sv_cache_create(cfg: SvConfig, arena, stream=None) -> int:
 
 def sv_cache_destroy(handle: int) -> None:
     _check(lib().sv_cache_destroy(handle), "sv_cache_destroy")
+
+
+def sv_cache_set_option(handle: int, option: int, value: int) -> None:
+    _check(lib().sv_cache_set_option(handle, option, value), "sv_cache_set_option")
 
 
 def sv_cache_append(handle: int, stream_id: int, layer: int, n: int, types, grid_thw, k, v, stream=None) -> int:
@@ -240,10 +247,10 @@ class Cache:
 
     def __init__(self, n_layers: int, n_q_heads: int, n_kv_heads: int, head_dim: int, dtype: int, rope_mode: int,
                  rope_theta: float, mrope_sections=(0, 0, 0), n_streams: int = 1, capacity_tokens: int = 1024,
-                 max_q_tokens: int = 256, device: str = "cuda:0"):
+                 max_q_tokens: int = 256, device: str = "cuda:0", flags: int = 0):
         import torch
         self.cfg = SvConfig(n_layers, n_q_heads, n_kv_heads, head_dim, dtype, rope_mode, float(rope_theta),
-                            (C.c_int32 * 3)(*mrope_sections), n_streams, capacity_tokens, max_q_tokens)
+                            (C.c_int32 * 3)(*mrope_sections), n_streams, capacity_tokens, max_q_tokens, flags)
         nbytes = sv_cache_bytes(self.cfg)
         if nbytes == 0:
             raise SvError(-1, "sv_cache_bytes")
@@ -260,6 +267,9 @@ class Cache:
             self.close()
         except Exception:
             pass
+
+    def set_option(self, option: int, value: int) -> None:
+        sv_cache_set_option(self.handle, option, value)
 
     def append(self, stream_id, layer, types, grid_thw, k, v) -> int:
         return sv_cache_append(self.handle, stream_id, layer, int(k.shape[0]), types, grid_thw, k, v)

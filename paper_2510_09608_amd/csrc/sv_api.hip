@@ -23,7 +23,9 @@ bool config_ok(const sv_config* c) {
   if (c->head_dim != 64 && c->head_dim != 128) return false;
   if (c->dtype != SV_DTYPE_F32 && c->dtype != SV_DTYPE_BF16) return false;
   if (c->rope_mode != SV_ROPE_1D && c->rope_mode != SV_ROPE_3D && c->rope_mode != SV_ROPE_NONE) return false;
-  if (c->capacity_tokens < 1 || c->capacity_tokens > (int64_t)1 << 30) return false;
+  // slot and element indices inside the kernels are 32-bit: 2^24 slots x head_dim 128 stays far below 2^31
+  if (c->capacity_tokens < 1 || c->capacity_tokens > (int64_t)1 << 24) return false;
+  if (c->flags & ~(int32_t)SV_FLAG_GENERIC_KERNELS) return false;
   if (c->max_q_tokens < 1) return false;
   if (c->rope_mode != SV_ROPE_NONE && !(c->rope_theta > 0.0)) return false;
   if (c->rope_mode == SV_ROPE_3D) {
@@ -183,6 +185,8 @@ int sv_cache_create(const sv_config* cfg, void* dev_arena, size_t arena_bytes, v
   c->vt_stream_stride = (size_t)cfg->n_kv_heads * (((size_t)cfg->capacity_tokens + 63) / 64) * 64 * (size_t)cfg->head_dim * c->esize;
   c->st.resize(cfg->n_streams);
   for (auto& s : c->st) s.layer_len.assign(cfg->n_layers, 0);
+  c->use_mfma = cfg->dtype == SV_DTYPE_BF16 && cfg->head_dim == 128 && c->group <= 8 &&
+                !(cfg->flags & SV_FLAG_GENERIC_KERNELS);
 
   // rotary frequencies theta^(-2i/d), computed once in double
   const int half = cfg->head_dim / 2;
@@ -200,6 +204,7 @@ int sv_cache_create(const sv_config* cfg, void* dev_arena, size_t arena_bytes, v
   if (e == hipSuccess) e = hipMemsetAsync(c->next_pos, 0, (size_t)cfg->n_streams * 2 * 4, s);
   if (e == hipSuccess) e = hipMemsetAsync(c->n_dev, 0, (size_t)cfg->n_streams * 4, s);
   if (e == hipSuccess) e = hipMemsetAsync(c->counters, 0, (size_t)L.part_rows * cfg->n_kv_heads * 4, s);
+  if (e == hipSuccess && c->use_mfma) e = sv::attn_chunk_mfma_init();
   if (e == hipSuccess) e = hipStreamSynchronize(s);  // f is a local: the copy must have read it
   if (e != hipSuccess) {
     delete c;
@@ -212,6 +217,12 @@ int sv_cache_create(const sv_config* cfg, void* dev_arena, size_t arena_bytes, v
 int sv_cache_destroy(sv_cache* c) {
   if (!c) return SV_ERR_INVALID;
   delete c;
+  return SV_OK;
+}
+
+int sv_cache_set_option(sv_cache* c, int option, int value) {
+  if (!c || option < 0 || option >= SV_OPT_COUNT_ || value < 0) return SV_ERR_INVALID;
+  c->opt[option] = value;
   return SV_OK;
 }
 
@@ -352,7 +363,7 @@ int sv_attn_chunk(sv_cache* c, int stream_id, int layer, const void* q_dev, int 
   if (n_q < 1 || n_q > st.len || n_q > c->cfg.max_q_tokens) return SV_ERR_INVALID;
   if (st.layer_len[layer] != st.len) return SV_ERR_STATE;
   hipStream_t s = (hipStream_t)hip_stream;
-  if (sv::attn_mfma_supported(c)) {
+  if (c->use_mfma) {
     SV_DEV(sv::launch_attn_chunk_mfma(c, stream_id, layer, q_dev, n_q, o_dev, causal, false, s));
     return SV_OK;
   }
@@ -372,7 +383,7 @@ int sv_attn_decode(sv_cache* c, int layer, const int32_t* stream_ids_host, int n
     if (st.len < 1) return SV_ERR_INVALID;
     if (st.layer_len[layer] != st.len) return SV_ERR_STATE;
   }
-  if (sv::attn_decode_mfma_supported(c)) {
+  if (c->use_mfma) {
     SV_DEV(sv::launch_attn_decode_mfma(c, layer, stream_ids_host, n_list, 0, q_dev, nullptr, nullptr, o_dev,
                                        (hipStream_t)hip_stream));
     return SV_OK;
@@ -389,7 +400,7 @@ int sv_decode_step(sv_cache* c, int layer, const int32_t* stream_ids_host, int n
       !o_dev)
     return SV_ERR_INVALID;
   if ((int64_t)n_list > c->part_rows) return SV_ERR_INVALID;
-  const bool use_mfma = sv::attn_decode_mfma_supported(c);
+  const bool use_mfma = c->use_mfma;
   if (!use_mfma && !sv::attn_rows_supported(c)) return SV_ERR_UNSUPPORTED;
   hipStream_t s = (hipStream_t)hip_stream;
   // validate everything before changing anything
@@ -432,7 +443,7 @@ int sv_decode_step(sv_cache* c, int layer, const int32_t* stream_ids_host, int n
 int sv_decode_step_layers(sv_cache* c, int stream_id, const void* q_dev, const void* k_dev, const void* v_dev,
                           void* o_dev, void* hip_stream) {
   if (!stream_ok(c, stream_id) || !q_dev || !k_dev || !v_dev || !o_dev) return SV_ERR_INVALID;
-  if (!sv::attn_decode_mfma_supported(c)) return SV_ERR_UNSUPPORTED;
+  if (!c->use_mfma) return SV_ERR_UNSUPPORTED;
   const int L = c->cfg.n_layers;
   if ((int64_t)L > c->part_rows) return SV_ERR_INVALID;
   sv::StreamState& st = c->st[stream_id];
@@ -470,7 +481,7 @@ int sv_stream_step(sv_cache* c, int stream_id, int64_t n_sink, int64_t vision_wi
     std::vector<uint8_t> types((size_t)n, (uint8_t)SV_VISION);
     const bool has_grid = io->grid_thw[0] > 0 || io->grid_thw[1] > 0 || io->grid_thw[2] > 0;
     // bf16 / head_dim 128: K/V store, Q rotation and V^T staging of a layer go out as ONE launch
-    const bool fused = sv::attn_chunk_wants_vt(c, n) && n <= c->cfg.max_q_tokens;
+    const bool fused = c->use_mfma && n <= c->cfg.max_q_tokens;
     for (int l = 0; l < L; ++l) {
       int64_t slot0 = 0;
       char* q = (char*)io->q_vision + (size_t)l * n * qrow;
@@ -521,6 +532,8 @@ int sv_cache_retained(sv_cache* c, int stream_id, int64_t* ids_host, int32_t* po
   const int64_t n = std::min(cap, st.len);
   const size_t off = (size_t)stream_id * (size_t)c->cfg.capacity_tokens;
   std::vector<int4> pos;
+  int32_t n_dev = -1;   // the device's own count: written by the eviction scan and by every registration
+  SV_HIP(hipMemcpyAsync(&n_dev, c->n_dev + stream_id, 4, hipMemcpyDeviceToHost, s));
   if (n > 0 && ids_host)
     SV_HIP(hipMemcpyAsync(ids_host, c->meta[st.cur].gid + off, (size_t)n * 8, hipMemcpyDeviceToHost, s));
   if (n > 0 && pos3_host) {
@@ -528,6 +541,7 @@ int sv_cache_retained(sv_cache* c, int stream_id, int64_t* ids_host, int32_t* po
     SV_HIP(hipMemcpyAsync(pos.data(), c->meta[st.cur].pos4 + off, (size_t)n * 16, hipMemcpyDeviceToHost, s));
   }
   SV_HIP(hipStreamSynchronize(s));
+  if ((int64_t)n_dev != st.len) return SV_ERR_STATE;   // host bookkeeping and device scan disagree
   if (n > 0 && pos3_host)
     for (int64_t i = 0; i < n; ++i) {
       pos3_host[3 * i + 0] = pos[i].x;

@@ -29,7 +29,6 @@
 #include <hip/hip_bf16.h>
 
 #include <algorithm>
-#include <cstdlib>
 
 #include "sv_internal.h"
 
@@ -391,21 +390,12 @@ __global__ __launch_bounds__(128) void k_decode_merge(const float* __restrict__ 
   *(uint2*)op = make_uint2(w0, w1);
 }
 
-int env_int(const char* name, int dflt) {
-  const char* v = std::getenv(name);
-  return v && *v ? std::atoi(v) : dflt;
-}
-
 }  // namespace
 
-bool attn_decode_mfma_supported(const sv_cache* c) {
-  return c->cfg.dtype == SV_DTYPE_BF16 && c->cfg.head_dim == 128 && c->group <= GMAX &&
-         std::getenv("SV_NO_MFMA_DECODE") == nullptr;
-}
-
 template <int NW>
-hipError_t decode_launch(const sv_cache* c, const DecTable& tab, int fused, int nr, int max_len, int64_t total_tiles,
-                         const void* q, const void* k_new, const void* v_new, void* o, size_t r0, hipStream_t s) {
+static hipError_t decode_launch(const sv_cache* c, const DecTable& tab, int fused, int nr, int max_len, int64_t total_tiles,
+                         const void* q, const void* k_new, const void* v_new, void* o, size_t r0, float* part_o,
+                         float* part_ml, int64_t part_rows, hipStream_t s) {
   const int Hq = c->cfg.n_q_heads, Hkv = c->cfg.n_kv_heads;
   // Key tiles per wavefront.  A single stream is latency bound: one tile per wavefront spreads its few
   // hundred tiles over the most CUs and costs one memory round trip.  A large batch is bandwidth bound:
@@ -413,7 +403,7 @@ hipError_t decode_launch(const sv_cache* c, const DecTable& tab, int fused, int 
   // smallest count for which all non-empty workgroups are resident at once (<= 512) is taken: one workgroup
   // more than that and a second, nearly empty round follows the first (measured on 16 ragged rows: 516
   // workgroups 3.6 TB/s, 440 workgroups 4.2 TB/s).
-  int tiles_per_wave = env_int("SV_DECODE_TILES_PER_WAVE", 0);
+  int tiles_per_wave = std::min(c->opt[SV_OPT_DECODE_TILES_PER_WAVE], 16);
   if (tiles_per_wave <= 0) {
     for (tiles_per_wave = 1; tiles_per_wave < 16; ++tiles_per_wave) {
       const int keys = TK * NW * tiles_per_wave;
@@ -424,7 +414,7 @@ hipError_t decode_launch(const sv_cache* c, const DecTable& tab, int fused, int 
   }
   int keys_per_split = TK * NW * tiles_per_wave;
   int n_splits = (max_len + keys_per_split - 1) / keys_per_split;
-  const int cap = (int)std::min<int64_t>(kMaxSplitsD, std::max<int64_t>(1, c->part_rows / nr));
+  const int cap = (int)std::min<int64_t>(kMaxSplitsD, std::max<int64_t>(1, part_rows / nr));
   if (n_splits > cap) {
     keys_per_split = ((max_len + cap - 1) / cap + TK - 1) / TK * TK;
     n_splits = (max_len + keys_per_split - 1) / keys_per_split;
@@ -442,26 +432,26 @@ hipError_t decode_launch(const sv_cache* c, const DecTable& tab, int fused, int 
   const bool stream_loads = total_tiles * (int64_t)(TK * D * 2 * 2) * Hkv >= ((int64_t)96 << 20);
   if (nr == 1 && !stream_loads)
     hipLaunchKernelGGL((k_decode_mfma<NW, true, false>), dim3(n_splits, Hkv, 1), dim3(NW * 64), 0, s, r.k, r.v, r.cs, r.len,
-                       keys_per_split, qp, knp, vnp, c->head_stride / 2, fused, rotate, op, c->part_o, c->part_ml,
+                       keys_per_split, qp, knp, vnp, c->head_stride / 2, fused, rotate, op, part_o, part_ml,
                        n_splits, Hq, Hkv, c->group, c_log2, tab);
   else if (stream_loads)
     hipLaunchKernelGGL((k_decode_mfma<NW, false, true>), dim3(n_splits, Hkv, nr), dim3(NW * 64), 0, s, r.k, r.v, r.cs, r.len,
-                       keys_per_split, qp, knp, vnp, c->head_stride / 2, fused, rotate, op, c->part_o, c->part_ml,
+                       keys_per_split, qp, knp, vnp, c->head_stride / 2, fused, rotate, op, part_o, part_ml,
                        n_splits, Hq, Hkv, c->group, c_log2, tab);
   else
     hipLaunchKernelGGL((k_decode_mfma<NW, false, false>), dim3(n_splits, Hkv, nr), dim3(NW * 64), 0, s, r.k, r.v, r.cs, r.len,
-                       keys_per_split, qp, knp, vnp, c->head_stride / 2, fused, rotate, op, c->part_o, c->part_ml,
+                       keys_per_split, qp, knp, vnp, c->head_stride / 2, fused, rotate, op, part_o, part_ml,
                        n_splits, Hq, Hkv, c->group, c_log2, tab);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || n_splits == 1) return e;
-  hipLaunchKernelGGL(k_decode_merge, dim3(Hq, nr), dim3(128), 0, s, c->part_o, c->part_ml,
+  hipLaunchKernelGGL(k_decode_merge, dim3(Hq, nr), dim3(128), 0, s, part_o, part_ml,
                      (__hip_bfloat16*)o + r0 * Hq * D, n_splits, Hq);
   return hipGetLastError();
 }
 
-hipError_t launch_attn_decode_mfma(const sv_cache* c, int layer, const int32_t* streams, int n_list, int fused,
-                                   const void* q, const void* k_new, const void* v_new, void* o, hipStream_t s) {
-  const int nw = env_int("SV_DECODE_NW", 4);
+static hipError_t decode_rows(const sv_cache* c, int layer, const int32_t* streams, int n_list, int fused, const void* q,
+                              const void* k_new, const void* v_new, void* o, float* part_o, float* part_ml,
+                              int64_t part_rows, hipStream_t s) {
   for (int r0 = 0; r0 < n_list; r0 += kMaxRowsD) {
     const int nr = std::min(kMaxRowsD, n_list - r0);
     DecTable tab = {};
@@ -479,12 +469,16 @@ hipError_t launch_attn_decode_mfma(const sv_cache* c, int layer, const int32_t* 
       max_len = std::max(max_len, (int)st.len);
       if (layer >= 0) total_tiles += (st.len + TK - 1) / TK;
     }
-    hipError_t e = nw == 2   ? decode_launch<2>(c, tab, fused, nr, max_len, total_tiles, q, k_new, v_new, o, (size_t)r0, s)
-                   : nw == 1 ? decode_launch<1>(c, tab, fused, nr, max_len, total_tiles, q, k_new, v_new, o, (size_t)r0, s)
-                             : decode_launch<4>(c, tab, fused, nr, max_len, total_tiles, q, k_new, v_new, o, (size_t)r0, s);
+    hipError_t e = decode_launch<4>(c, tab, fused, nr, max_len, total_tiles, q, k_new, v_new, o, (size_t)r0, part_o,
+                                    part_ml, part_rows, s);
     if (e != hipSuccess) return e;
   }
   return hipSuccess;
+}
+
+hipError_t launch_attn_decode_mfma(const sv_cache* c, int layer, const int32_t* streams, int n_list, int fused,
+                                   const void* q, const void* k_new, const void* v_new, void* o, hipStream_t s) {
+  return decode_rows(c, layer, streams, n_list, fused, q, k_new, v_new, o, c->part_o, c->part_ml, c->part_rows, s);
 }
 
 }  // namespace sv

@@ -24,17 +24,13 @@
 //     the key index swapped): the accumulator layout of S^T then hands every lane 8
 //     consecutive keys per 16-key step, which is exactly the B-operand layout of
 //     the second product, so P never moves between lanes.
-//   * Two kernels share this tiling.  k_attn_chunk_mfma (the first one, kept for comparison) stages tiles
-//     through registers: V row-major exactly as loaded, read back as the V^T operand with the LDS transpose read
-//     (ds_read_b64_tr_b16, two per operand), LDS double-buffered, one barrier per tile.  k_attn_chunk_pipe (the
-//     default) brings K and V^T tiles to LDS with direct loads, four slots per tensor, and reads V^T fragments
-//     with plain 16-byte reads from tiles that a staging pass transposed once per launch; see its own header.
-//     Its default order of work spreads the softmax of a tile through the output MFMAs of the tile before.
+//   * K and V^T tiles reach LDS with direct global -> LDS loads, four slots per tensor, and V^T fragments are
+//     plain 16-byte LDS reads; the softmax of a tile is spread through the output MFMAs of the tile before
+//     (see the kernel's own header).
 
 #include <hip/hip_bf16.h>
 
 #include <algorithm>
-#include <cstdlib>
 #include <type_traits>
 
 #include "sv_internal.h"
@@ -50,11 +46,6 @@ typedef short v8i16 __attribute__((ext_vector_type(8)));
 constexpr int D = 128;               // head_dim
 constexpr int TK = 64;               // keys per tile
 constexpr int KROW = D * 2;          // bytes per K row in LDS (16-byte chunks XOR-swizzled by row)
-constexpr int VROW = D * 2 + 64;     // bytes per V row in LDS: the 4 rows x 64 bytes that 32 lanes of a transpose read
-                                     // touch fall in distinct banks (64 banks x 4 bytes)
-constexpr int K_BYTES = TK * KROW;
-constexpr int V_BYTES = TK * VROW;
-constexpr int BUF_BYTES = K_BYTES + V_BYTES;
 
 __device__ __forceinline__ int perm_key(int key) {  // swap bits 2 and 3
   return (key & ~0xC) | ((key & 4) << 1) | ((key & 8) >> 1);
@@ -63,213 +54,13 @@ __device__ __forceinline__ int k_lds_off(int row, int chunk) {  // row: permuted
   return row * KROW + ((chunk ^ (row & 15)) << 4);   // 16 consecutive rows read 16 distinct chunks: no bank conflict
 }
 
-// LDS transpose read: within each group of 16 lanes, lane j hands in the address of 4 consecutive 16-bit
-// elements and receives element (j & 3) of the chunks of lanes (j >> 2) + 4 e, e = 0..3.  Pointing lane j
-// at row r0 + (j >> 2), columns c0 + 4 (j & 3) .. + 3 of a row-major tile returns column c0 + j of rows
-// r0 .. r0 + 3.  (Layout confirmed with an index pattern on the device.)
-__device__ __forceinline__ v4i16 lds_read_tr(const char* base, int byte_off) {
-  return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-      (v4i16 __attribute__((address_space(3)))*)((__attribute__((address_space(3))) char*)base + byte_off));
-}
-
-template <int NW>
-__global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_mfma(
-    const __hip_bfloat16* __restrict__ q, const __hip_bfloat16* __restrict__ kc, const __hip_bfloat16* __restrict__ vc,
-    __hip_bfloat16* __restrict__ out, float* __restrict__ part_o, float* __restrict__ part_ml, int n_q, int n_kv,
-    int causal, int n_splits, int keys_per_split, int n_q_heads, int G, size_t head_stride_elems, float c_log2) {
-  constexpr int NT = NW * 64;
-  constexpr int ROWS_WG = NW * 32;
-  constexpr int CH = (TK * 16) / NT;   // 16-byte chunks of K (and of V) per thread per tile
-  extern __shared__ __attribute__((aligned(16))) char smem[];   // two buffers of (K tile, V tile)
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int l32 = lane & 31, hh = lane >> 5;
-  const int rt = blockIdx.x, hk = blockIdx.y, sp = blockIdx.z;
-  const int slot0 = n_kv - n_q;
-  const int n_rows = n_q * G;
-
-  // key range of this workgroup, trimmed to what its last query may see
-  const int row_last = min(n_rows, (rt + 1) * ROWS_WG) - 1;
-  const int k_begin = sp * keys_per_split;
-  int k_end = min(n_kv, k_begin + keys_per_split);
-  if (causal) k_end = min(k_end, slot0 + row_last / G + 1);
-  const int n_tiles = k_end > k_begin ? (k_end - k_begin + TK - 1) / TK : 0;
-
-  const __hip_bfloat16* kbase = kc + (size_t)hk * head_stride_elems;
-  const __hip_bfloat16* vbase = vc + (size_t)hk * head_stride_elems;
-
-  uint4 kreg[CH], vreg[CH];
-  auto issue_loads = [&](int t) {
-    const int kt0 = k_begin + t * TK;
-#pragma unroll
-    for (int i = 0; i < CH; ++i) {
-      const int cid = tid + i * NT, key = cid >> 4, c16 = cid & 15;
-      const bool ok = kt0 + key < k_end;   // rows past the range read as zero (finite, masked anyway)
-      kreg[i] = ok ? *(const uint4*)(kbase + (size_t)(kt0 + key) * D + c16 * 8) : make_uint4(0, 0, 0, 0);
-      vreg[i] = ok ? *(const uint4*)(vbase + (size_t)(kt0 + key) * D + c16 * 8) : make_uint4(0, 0, 0, 0);
-    }
-  };
-  auto store_tile = [&](char* buf) {
-#pragma unroll
-    for (int i = 0; i < CH; ++i) {
-      const int cid = tid + i * NT, key = cid >> 4, c16 = cid & 15;
-      *(uint4*)(buf + k_lds_off(perm_key(key), c16)) = kreg[i];
-      *(uint4*)(buf + K_BYTES + key * VROW + c16 * 16) = vreg[i];
-    }
-  };
-
-  if (n_tiles > 0) issue_loads(0);
-
-  // this lane's query row
-  const int row = rt * ROWS_WG + wave * 32 + l32;
-  const bool rvalid = row < n_rows;
-  const int rr = rvalid ? row : n_rows - 1;
-  const int qi = rr / G, hg = rr % G;
-  const int limit = min(causal ? slot0 + qi : n_kv - 1, k_end - 1);
-  bf16x8 qf[8];
-  {
-    const __hip_bfloat16* qp = q + ((size_t)qi * n_q_heads + hk * G + hg) * D + hh * 8;
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
-      uint4 raw = rvalid ? *(const uint4*)(qp + kk * 16) : make_uint4(0, 0, 0, 0);
-      qf[kk] = *(bf16x8*)&raw;
-    }
-  }
-
-  f32x16 oacc[4];
-#pragma unroll
-  for (int db = 0; db < 4; ++db)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;
-
-  if (n_tiles > 0) store_tile(smem);
-  __syncthreads();
-
-  // lane geometry of the V^T transpose reads: 16-lane group g16 covers dims 16 (g16 & 1) + j of a 32-dim
-  // block and keys 8 (g16 >> 1) + e (+4 for the second read) of a 16-key step
-  const int j16 = lane & 15, g16 = lane >> 4;
-  const int v_lane_off = (8 * (g16 >> 1) + (j16 >> 2)) * VROW + (16 * (g16 & 1) + 4 * (j16 & 3)) * 2;
-
-  for (int t = 0; t < n_tiles; ++t) {
-    const char* sK = smem + (t & 1) * BUF_BYTES;
-    const char* sV = sK + K_BYTES;
-    if (t + 1 < n_tiles) issue_loads(t + 1);
-    const int kt0 = k_begin + t * TK;
-
-    // S^T = K Q^T for 2 blocks of 32 keys
-    f32x16 sacc[2];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) sacc[kb][r] = 0.f;
-#pragma unroll
-      for (int kk = 0; kk < 8; ++kk) {
-        const bf16x8 a = *(const bf16x8*)(sK + k_lds_off(kb * 32 + l32, 2 * kk + hh));
-        sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk], sacc[kb], 0, 0, 0);
-      }
-    }
-
-    // online softmax, one query row per lane.  Register r of key block kb holds key
-    // kt0 + 32 kb + 16 (r / 8) + 8 hh + r % 8.
-    const bool need_mask = kt0 + TK - 1 > (causal ? slot0 + (rt * ROWS_WG) / G : n_kv - 1) || kt0 + TK > k_end;
-    if (need_mask) {
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = kt0 + 32 * kb + 16 * (r >> 3) + 8 * hh + (r & 7);
-          if (key > limit) sacc[kb][r] = -INFINITY;
-        }
-    }
-    float mx = -INFINITY;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kb][r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_run, mx);
-    const float m_use = m_new == -INFINITY ? 0.f : m_new;   // a row may be fully masked in this tile
-    const float alpha = __builtin_amdgcn_exp2f((m_run - m_use) * c_log2);
-    const float mc = m_use * c_log2;
-    float psum = 0.f;
-    bf16x8 pf[4];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float p = __builtin_amdgcn_exp2f(fmaf(sacc[kb][r], c_log2, -mc));
-        psum += p;
-        pf[kb * 2 + (r >> 3)][r & 7] = (__bf16)p;
-      }
-    l_run = l_run * alpha + psum;
-    if (__any(m_new > m_run)) {
-#pragma unroll
-      for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
-    }
-    m_run = m_new;
-
-    // O^T += V^T P^T : 4 blocks of 32 dims, 4 steps of 16 keys
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-#pragma unroll
-      for (int db = 0; db < 4; ++db) {
-        const int off = v_lane_off + 16 * ks * VROW + 64 * db;
-        const v4i16 a0 = lds_read_tr(sV, off), a1 = lds_read_tr(sV, off + 4 * VROW);
-        const v8i16 a8 = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
-        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)&a8, pf[ks], oacc[db], 0, 0, 0);
-      }
-    }
-
-    if (t + 1 < n_tiles) store_tile(smem + ((t + 1) & 1) * BUF_BYTES);
-    __syncthreads();
-  }
-
-  // epilogue: lane holds its row, dims 32 db + 8 (r / 4) + 4 hh + r % 4
-  const float l_tot = l_run + __shfl_xor(l_run, 32);
-  if (!rvalid) return;
-  const int h = hk * G + hg;
-  if (n_splits == 1) {
-    const float inv = 1.0f / l_tot;
-    __hip_bfloat16* op = out + ((size_t)qi * n_q_heads + h) * D;
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        const int dv = 32 * db + 8 * r4 + 4 * hh;
-        __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 pk;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) pk[e] = (__bf16)(oacc[db][r4 * 4 + e] * inv);
-        *(uint2*)(op + dv) = *(uint2*)&pk;
-      }
-  } else {
-    const size_t p = ((size_t)qi * n_splits + sp) * n_q_heads + h;
-    float* po = part_o + p * D;
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        const int dv = 32 * db + 8 * r4 + 4 * hh;
-        *(float4*)(po + dv) = make_float4(oacc[db][r4 * 4], oacc[db][r4 * 4 + 1], oacc[db][r4 * 4 + 2],
-                                          oacc[db][r4 * 4 + 3]);
-      }
-    if (hh == 0) {
-      part_ml[p * 2] = m_run == -INFINITY ? -INFINITY : m_run * c_log2;
-      part_ml[p * 2 + 1] = l_tot;
-    }
-  }
-}
-
 // ---------------------------------------------------------------------------------
-// Pipelined variant (8 wavefronts, one workgroup per CU).
+// The kernel (8 wavefronts, one workgroup per CU).
 //   * K/V tiles go from HBM to LDS with the direct global -> LDS load (16 bytes per lane, lane L lands at
 //     base + 16 L; confirmed on the device), so staging costs no registers and no LDS store instructions.  The
 //     swizzles are applied on the global side: each lane fetches the chunk that belongs at its LDS position.
 //       K: LDS row m holds key perm_key(m); position p of the row holds chunk p ^ (m & 15).
-//       V: LDS row = key; position p holds chunk p ^ (4 (key & 3)), which puts the 4 rows x 64 bytes that
-//          32 lanes of a transpose read touch into distinct banks without padding.
+//       V^T: LDS row = head dim (64 keys, 128 bytes); position p holds the 8-key chunk p ^ ((row >> 1) & 7).
 //   * Four LDS slots per tensor: in iteration t tiles t-1 .. t+1 may be read while tile t+2 arrives.
 //   * The matrix-core work of an iteration (scores of one tile, output of another) does not depend on the
 //     softmax running in the same iteration; LDS operands are fetched one batch ahead of the MFMAs that use them.
@@ -297,12 +88,12 @@ __device__ __forceinline__ void dma16(const void* base, uint32_t lane_off, char*
 }
 #pragma clang diagnostic pop
 
-template <int NW, int KS, int VS, bool INTER>
+template <int NW, int KS, int VS>
 __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
     const __hip_bfloat16* __restrict__ q, const __hip_bfloat16* __restrict__ kc, const __hip_bfloat16* __restrict__ vc,
     __hip_bfloat16* __restrict__ out, float* __restrict__ part_o, float* __restrict__ part_ml, int n_q, int n_kv,
     int causal, int n_splits, int keys_per_split, int n_q_heads, int G, size_t head_stride_elems, float c_log2,
-    int phase_mode, const __hip_bfloat16* __restrict__ vt, size_t vt_head_stride_elems, int n_kv_heads, int pairs_pad) {
+    const __hip_bfloat16* __restrict__ vt, size_t vt_head_stride_elems, int n_kv_heads, int pairs_pad) {
   constexpr int ROWS_WG = NW * 32;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   char* const sKbase = smem;
@@ -365,24 +156,9 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
     for (int i = 0; i < 16 / NW; ++i)
       dma16(src, which ? v_lane_off[i] : k_lane_off[i], slot + (wave + i * NW) * 1024);
   };
-  // Iteration t requests K of tile t + 3 and V of tile t + 2 and, at its end, waits only for what iteration
-  // t - 1 requested: every tile has two iterations to arrive.  Slots: K tiles t, t + 1 are read in iteration
-  // t while t + 2, t + 3 are in flight; V tiles t - 1, t are read while t + 1, t + 2 are in flight.
-  auto dma_iter = [&](int t) {
-    dma_tile(1, t + VS - 2);
-    dma_tile(0, t + KS - 1);
-  };
-
-  if constexpr (INTER) {   // the first pair of tiles
-    dma_tile(0, 0);
-    dma_tile(0, 1);
-    dma_tile(1, 0);
-  } else {
-#pragma unroll
-    for (int t = 0; t < KS - 1; ++t) dma_tile(0, t);
-#pragma unroll
-    for (int t = 0; t < VS - 2; ++t) dma_tile(1, t);
-  }
+  dma_tile(0, 0);   // the first pair of tiles
+  dma_tile(0, 1);
+  dma_tile(1, 0);
 
   const int row = rt * ROWS_WG + wave * 32 + l32;
   const bool rvalid = row < n_rows;
@@ -411,53 +187,7 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
   int v_ks_off[4];
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) v_ks_off[ks] = l32 * 128 + (((2 * ks + hh) ^ ((l32 >> 1) & 7)) << 4);
-  const bool mfma_first =
-      NW != 8 || phase_mode == 0 ? true : (phase_mode == 1 ? ((wave >> 2) & 1) == 0 : (wave & 1) == 0);
-
   const float tau = 8.0f / c_log2;   // 8 binary orders, in score units
-  auto softmax = [&](auto masked, int t, f32x16 (&sacc)[2], bf16x8 (&pf)[4], bool& changed) -> float {
-    const int kt0 = k_begin + t * TK;
-    if constexpr (decltype(masked)::value) {
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = kt0 + 32 * kb + 16 * (r >> 3) + 8 * hh + (r & 7);
-          if (key > limit) sacc[kb][r] = -INFINITY;
-        }
-    }
-    float mx = -INFINITY;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kb][r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    // The reference maximum m_run only moves when some row's maximum grew by more than 8 binary orders (then
-    // every row takes its exact new maximum and the accumulators are rescaled); smaller growth stays inside
-    // p <= 2^8, which bf16 P and the fp32 sums hold just as well, and m_run, l_run and O stay consistent, so
-    // the result is the same softmax.  After the first few tiles almost no tile pays the 64-multiply rescale
-    // (with exact tracking a wavefront's 32 rows made about every second tile pay it over 140 tiles).
-    const float m_new = fmaxf(m_run, mx);
-    changed = __any(m_new > m_run + tau);
-    float alpha = 1.f;
-    if (changed) {
-      const float m_use = m_new == -INFINITY ? 0.f : m_new;
-      alpha = __builtin_amdgcn_exp2f((m_run - m_use) * c_log2);
-      m_run = m_new;
-    }
-    const float mc = (m_run == -INFINITY ? 0.f : m_run) * c_log2;
-    float psum = 0.f;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float p = __builtin_amdgcn_exp2f(fmaf(sacc[kb][r], c_log2, -mc));
-        psum += p;
-        pf[kb * 2 + (r >> 3)][r & 7] = (__bf16)p;
-      }
-    l_run = l_run * alpha + psum;
-    return alpha;
-  };
   auto rescale = [&](float alpha) {
 #pragma unroll
     for (int db = 0; db < 4; ++db)
@@ -517,28 +247,14 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
     __syncthreads();
   };
-  // End of an iteration: everything the next one reads has landed.  With two V^T slots that includes the
-  // V^T tile this iteration asked for (issued before the K tile, so only the K tile's 16 / NW instructions
-  // may stay in flight); with more slots all of this iteration's 2 * 16 / NW instructions may.
-  auto arrive = [&]() {
-    constexpr int pending = (VS > 2 ? 2 : 1) * 16 / NW;
-    static_assert(pending == 4 || pending == 8, "wait immediates below");
-    if constexpr (pending == 4) __builtin_amdgcn_s_waitcnt(0x0F74);   // vmcnt(4)
-    else __builtin_amdgcn_s_waitcnt(0x0F78);                          // vmcnt(8)
-    __syncthreads();
-  };
-
-  // "matrix first":  iteration t = [S(t) = QK(t), O += PV(t-1)] then softmax(t)
-  // "softmax first": iteration t = softmax(t) (S(t) from the previous iteration) then [O += PV(t), S(t+1)]
   f32x16 sacc[2];
   bf16x8 pf[4];
-  bool changed;
   const int full_keys = min(wg_first_limit + 1, k_end) - k_begin;   // tiles every row of the workgroup sees whole
   const int n_full = full_keys > 0 ? min(full_keys / TK, n_tiles) : 0;
   arrive_all();
   constexpr std::true_type yes{};
   constexpr std::false_type no{};
-  if constexpr (INTER) {
+  {
     // Interleaved order: iteration t = S(t) = QK(t), then the softmax of tile t with the 16 MFMAs of
     // O += P(t-1) V(t-1) spread through it (one MFMA, then the exp / pack / sum of two scores).  Inside one
     // wavefront an MFMA and the vector instructions behind it do not overlap, but the other wavefront of the
@@ -659,44 +375,6 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
     if (n_tiles & 1) matrix(no, yes, 0, n_tiles - 1, sacc, pf);
     else matrix(no, yes, 0, n_tiles - 1, sacc, pfb);
     __builtin_amdgcn_s_waitcnt(0x0F70);   // no direct load may be in flight when the wavefront ends
-  } else if (mfma_first) {
-    auto iter = [&](auto masked, int t) {
-      dma_iter(t);
-      matrix(yes, yes, t, t - 1, sacc, pf);
-      const float alpha = softmax(masked, t, sacc, pf, changed);
-      if (changed) rescale(alpha);
-      arrive();
-    };
-    {   // tile 0: no output product yet
-      dma_iter(0);
-      matrix(yes, no, 0, 0, sacc, pf);
-      const float alpha = n_full > 0 ? softmax(no, 0, sacc, pf, changed) : softmax(yes, 0, sacc, pf, changed);
-      if (changed) rescale(alpha);
-      arrive();
-    }
-    int t = 1;
-    for (; t < n_full; ++t) iter(no, t);
-    for (; t < n_tiles; ++t) iter(yes, t);
-    matrix(no, yes, 0, n_tiles - 1, sacc, pf);
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // no direct load may be in flight when the wavefront ends
-  } else if constexpr (NW == 8 && KS == 4 && VS == 4) {   // (this order reads one tile further ahead)
-    matrix(yes, no, 0, 0, sacc, pf);
-    auto iter = [&](auto masked, int t) {
-      dma_iter(t);
-      const float alpha = softmax(masked, t, sacc, pf, changed);
-      if (changed) rescale(alpha);
-      matrix(yes, yes, t + 1, t, sacc, pf);
-      arrive();
-    };
-    int t = 0;
-    for (; t < n_full && t + 1 < n_tiles; ++t) iter(no, t);
-    for (; t + 1 < n_tiles; ++t) iter(yes, t);
-    {   // last tile: no further scores
-      const float alpha = t < n_full ? softmax(no, t, sacc, pf, changed) : softmax(yes, t, sacc, pf, changed);
-      if (changed) rescale(alpha);
-      matrix(no, yes, 0, t, sacc, pf);
-      arrive_all();   // as many barriers as the wavefronts of the other order execute
-    }
   }
 
   const float l_tot = l_run + __shfl_xor(l_run, 32);
@@ -747,97 +425,52 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
   }
 }
 
-int env_int(const char* name, int dflt) {
-  const char* v = std::getenv(name);
-  return v && *v ? std::atoi(v) : dflt;
+constexpr int kNW = 8, kKS = 4, kVS = 4;   // 8 wavefronts, 4 + 4 tile slots: 128 KB of LDS, one workgroup per CU
+constexpr int kLds = std::max((kKS + kVS) * PIPE_TILE, kNW * 32 * PIPE_OROW * 4);
+
+}  // namespace
+
+hipError_t attn_chunk_mfma_init() {
+  // more than 64 KB of dynamic LDS has to be asked for, once per device
+  return hipFuncSetAttribute((const void*)k_attn_chunk_pipe<kNW, kKS, kVS>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                             kLds);
 }
 
-template <int NW, bool PIPE, bool INTER = false>
-hipError_t launch_t(const sv_cache* c, int stream, int layer, const void* q, int n_q, void* o, int causal,
-                    bool vt_ready, hipStream_t s) {
-  constexpr int ROWS_WG = NW * 32;
-  // pipelined kernel: 8 wavefronts with 4 + 4 tile slots (128 KB, one workgroup per CU) or 4 wavefronts with
-  // 3 + 2 (80 KB, two independent workgroups per CU)
-  constexpr int KS = NW == 8 ? 4 : 3, VS = NW == 8 ? 4 : 2;
-  constexpr int kLds = PIPE ? std::max((KS + VS) * PIPE_TILE, NW * 32 * PIPE_OROW * 4) : 2 * BUF_BYTES;
-  const void* kern = PIPE ? (const void*)k_attn_chunk_pipe<NW, KS, VS, INTER> : (const void*)k_attn_chunk_mfma<NW>;
-  static bool attr_set = false;   // more than 64 KB of LDS has to be asked for once per kernel
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+hipError_t launch_attn_chunk_mfma(const sv_cache* c, int stream, int layer, const void* q, int n_q, void* o,
+                                  int causal, bool vt_ready, hipStream_t s) {
+  constexpr int ROWS_WG = kNW * 32;
   const StreamState& st = c->st[stream];
   const int n_kv = (int)st.len, G = c->group, Hkv = c->cfg.n_kv_heads;
   const int row_tiles = (n_q * G + ROWS_WG - 1) / ROWS_WG;
-  int n_splits = env_int("SV_CHUNK_SPLITS", 0);
+  int n_splits = c->opt[SV_OPT_CHUNK_SPLITS];
   if (n_splits <= 0) {
-    // fill 256 CUs with 8 wavefronts each (one workgroup of 8 or two of 4)
-    const int slots = 256 * (8 / NW);
-    n_splits = std::max(1, slots / std::max(1, row_tiles * Hkv));
+    // fill the 256 CUs, one workgroup each
+    n_splits = std::max(1, 256 / std::max(1, row_tiles * Hkv));
     n_splits = std::min(n_splits, std::max(1, n_kv / (4 * TK)));
-    // the pipelined kernel keeps the row tiles of a (kv head, key range) pair on one XCD: a pair count that
-    // is a multiple of 8 loads the 8 XCDs evenly
-    if (PIPE)
-      while (n_splits > 1 && (Hkv * n_splits) % 8 != 0) --n_splits;
+    // the row tiles of a (kv head, key range) pair stay on one XCD: a pair count that is a multiple of 8 loads
+    // the 8 XCDs evenly
+    while (n_splits > 1 && (Hkv * n_splits) % 8 != 0) --n_splits;
   }
   n_splits = std::min<int64_t>(n_splits, std::max<int64_t>(1, c->part_rows / n_q));
   n_splits = std::min(n_splits, 64);
   int keys_per_split = ((n_kv + n_splits - 1) / n_splits + TK - 1) / TK * TK;
   n_splits = (n_kv + keys_per_split - 1) / keys_per_split;
   const float c_log2 = 1.4426950408889634f / sqrtf((float)D);
-  dim3 grid(row_tiles, Hkv, n_splits);
-  if constexpr (PIPE) {
-    __hip_bfloat16* vt = (__hip_bfloat16*)(c->vt + (size_t)stream * c->vt_stream_stride);
-    const size_t vt_head_stride = c->vt_stream_stride / 2 / Hkv;
-    if (!vt_ready) {
-      hipError_t ev = launch_vt_build(c, stream, layer, n_kv, s);
-      if (ev != hipSuccess) return ev;
-    }
-    const int pairs_pad = (Hkv * n_splits + 7) / 8 * 8;
-    hipLaunchKernelGGL((k_attn_chunk_pipe<NW, KS, VS, INTER>), dim3(row_tiles * pairs_pad), dim3(NW * 64), kLds, s, (const __hip_bfloat16*)q,
-                       (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 0),
-                       (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 1), (__hip_bfloat16*)o, c->part_o,
-                       c->part_ml, n_q, n_kv, causal ? 1 : 0, n_splits, keys_per_split, c->cfg.n_q_heads, G,
-                       c->head_stride / 2, c_log2, env_int("SV_CHUNK_PHASE", 1), (const __hip_bfloat16*)vt,
-                       vt_head_stride, Hkv, pairs_pad);
-  } else
-    hipLaunchKernelGGL((k_attn_chunk_mfma<NW>), grid, dim3(NW * 64), kLds, s, (const __hip_bfloat16*)q,
-                       (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 0),
-                       (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 1), (__hip_bfloat16*)o, c->part_o,
-                       c->part_ml, n_q, n_kv, causal ? 1 : 0, n_splits, keys_per_split, c->cfg.n_q_heads, G,
-                       c->head_stride / 2, c_log2);
+  __hip_bfloat16* vt = (__hip_bfloat16*)(c->vt + (size_t)stream * c->vt_stream_stride);
+  const size_t vt_head_stride = c->vt_stream_stride / 2 / Hkv;
+  if (!vt_ready) {
+    hipError_t ev = launch_vt_build(c, stream, layer, n_kv, s);
+    if (ev != hipSuccess) return ev;
+  }
+  const int pairs_pad = (Hkv * n_splits + 7) / 8 * 8;
+  hipLaunchKernelGGL((k_attn_chunk_pipe<kNW, kKS, kVS>), dim3(row_tiles * pairs_pad), dim3(kNW * 64), kLds, s,
+                     (const __hip_bfloat16*)q, (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 0),
+                     (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 1), (__hip_bfloat16*)o, c->part_o,
+                     c->part_ml, n_q, n_kv, causal ? 1 : 0, n_splits, keys_per_split, c->cfg.n_q_heads, G,
+                     c->head_stride / 2, c_log2, (const __hip_bfloat16*)vt, vt_head_stride, Hkv, pairs_pad);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || n_splits == 1) return e;
   return launch_attn_combine(c, n_q, n_splits, o, s);
-}
-
-}  // namespace
-
-bool attn_mfma_supported(const sv_cache* c) {
-  return c->cfg.dtype == SV_DTYPE_BF16 && c->cfg.head_dim == 128 && std::getenv("SV_NO_MFMA") == nullptr;
-}
-
-// Which chunk-prefill kernel runs (SV_CHUNK_VARIANT overrides).  4 (default) = pipelined, 8 wavefronts, softmax of a
-// tile interleaved with the output MFMAs of the tile before; 2 = same staging, matrix and softmax phases kept apart,
-// the two wavefronts of a SIMD in opposite phase order; 3 = as 2 with 4 wavefronts and two independent workgroups
-// per CU; 0 / 1 = register-staged kernels.  Measured with merge, 256 / 512 / 1024-token chunk over 5.4k / 9.7k /
-// 18.4k keys: 4: 40.9 / 87.8 / 262 us; 2: 44.0 / 93.8 / 284 us; 3: 44.4 / 95.8 / 291 us.
-static int chunk_variant(int n_q) {
-  (void)n_q;
-  return env_int("SV_CHUNK_VARIANT", 4);
-}
-
-bool attn_chunk_wants_vt(const sv_cache* c, int n_q) { return attn_mfma_supported(c) && chunk_variant(n_q) >= 2; }
-
-hipError_t launch_attn_chunk_mfma(const sv_cache* c, int stream, int layer, const void* q, int n_q, void* o,
-                                  int causal, bool vt_ready, hipStream_t s) {
-  const int variant = chunk_variant(n_q);
-  if (variant == 0) return launch_t<8, false>(c, stream, layer, q, n_q, o, causal, false, s);
-  if (variant == 2) return launch_t<8, true>(c, stream, layer, q, n_q, o, causal, vt_ready, s);
-  if (variant == 3) return launch_t<4, true>(c, stream, layer, q, n_q, o, causal, vt_ready, s);
-  if (variant == 4) return launch_t<8, true, true>(c, stream, layer, q, n_q, o, causal, vt_ready, s);
-  return launch_t<4, false>(c, stream, layer, q, n_q, o, causal, false, s);
 }
 
 }  // namespace sv

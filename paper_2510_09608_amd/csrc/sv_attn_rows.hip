@@ -23,7 +23,6 @@
 #include <hip/hip_bf16.h>
 
 #include <algorithm>
-#include <cstdlib>
 
 #include "sv_internal.h"
 
@@ -400,13 +399,8 @@ __global__ __launch_bounds__(128) void k_attn_combine(const float* __restrict__ 
   }
 }
 
-int env_int(const char* name, int dflt) {
-  const char* v = std::getenv(name);
-  return v && *v ? std::atoi(v) : dflt;
-}
-
 int pick_splits(const sv_cache* c, int n_rows, int max_len) {
-  const int forced = env_int("SV_DECODE_SPLITS", 0);
+  const int forced = c->opt[SV_OPT_DECODE_SPLITS];
   int64_t want = forced > 0 ? forced
                             : (1024 + (int64_t)c->cfg.n_kv_heads * n_rows - 1) / ((int64_t)c->cfg.n_kv_heads * n_rows);
   want = std::min<int64_t>(want, (max_len + 63) / 64);

@@ -68,6 +68,8 @@ struct sv_cache {
   char* vt;                  // device [n_streams][n_kv_heads][ceil(capacity/64)][head_dim][64]  V^T staging of one layer
   size_t vt_stream_stride;   // bytes per stream of vt
   bool host_logic_only = false;   // created with SV_HOST_LOGIC_ONLY: no device work, bookkeeping only
+  bool use_mfma = false;          // bf16, head_dim 128, group <= 8 and no SV_FLAG_GENERIC_KERNELS: matrix-core kernels
+  int opt[SV_OPT_COUNT_] = {};    // sv_cache_set_option values, 0 = automatic
   std::vector<sv::StreamState> st;
 
   char* kv_ptr(int stream, int half, int layer, int which) const {
@@ -113,18 +115,17 @@ hipError_t launch_attn_rows_batch(const sv_cache* c, int layer, const int32_t* s
                                   const void* q, const void* k_new, const void* v_new, void* o, hipStream_t s);
 bool attn_rows_supported(const sv_cache* c);
 
-// Same contract as launch_attn_rows_batch, matrix-core kernel for bf16 / head_dim 128 / group <= 8.
-bool attn_decode_mfma_supported(const sv_cache* c);
+// Same contract as launch_attn_rows_batch, matrix-core kernel (c->use_mfma).
 hipError_t launch_attn_decode_mfma(const sv_cache* c, int layer, const int32_t* streams, int n_list, int fused,
                                    const void* q, const void* k_new, const void* v_new, void* o, hipStream_t s);
 
-bool attn_mfma_supported(const sv_cache* c);
+// Once per process and device, before the first chunk-prefill launch: the kernel's LDS size has to be asked for.
+hipError_t attn_chunk_mfma_init();
 // V^T staging of one layer for the pipelined chunk-prefill kernel, alone or fused with the chunk's append and Q
 // rotation (bf16, head_dim 128); vt_ready tells the attention launch that the staging is already done.
 hipError_t launch_vt_build(const sv_cache* c, int stream, int layer, int n_kv, hipStream_t s);
 hipError_t launch_chunk_prologue(const sv_cache* c, int stream, int layer, int64_t slot0, int n, void* q, const void* k,
                                  const void* v, hipStream_t s);
-bool attn_chunk_wants_vt(const sv_cache* c, int n_q);
 hipError_t launch_attn_chunk_mfma(const sv_cache* c, int stream, int layer, const void* q, int n_q,
                                   void* o, int causal, bool vt_ready, hipStream_t s);
 

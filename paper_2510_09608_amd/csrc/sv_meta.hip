@@ -17,7 +17,7 @@ __global__ void k_meta_append(MetaPtrs m, const int32_t* __restrict__ next_in, i
                               int64_t slot0, int n, int64_t gid0, int64_t rank_text0, int64_t rank_vis0,
                               int type_uniform, TypeMask mask, int rope3d, int blk, int gT, int gH, int gW,
                               float2* __restrict__ last_cs, const double* __restrict__ inv_freq, int half,
-                              int rope_none, int s0, int s01, int f32_data) {
+                              int rope_none, int s0, int s01, int f32_data, int32_t* __restrict__ n_dev) {
   const int j = blockIdx.x * blockDim.x + threadIdx.x;
   const int next = *next_in;
   if (blockIdx.x == 0 && threadIdx.x < half) {
@@ -44,6 +44,7 @@ __global__ void k_meta_append(MetaPtrs m, const int32_t* __restrict__ next_in, i
     else if (blk >= 0) adv = max(gT, max(gH, gW));
     else adv = n;
     *next_out = next + adv;
+    *n_dev = (int32_t)(slot0 + n);   // the device's own token count (cross-checked by sv_cache_retained)
   }
   if (j >= n) return;
   int type;
@@ -197,7 +198,7 @@ hipError_t launch_meta_append(const sv_cache* c, int stream, int next_parity, in
                      rank_vis0, type_uniform, mk, c->cfg.rope_mode == SV_ROPE_3D ? 1 : 0, blk, gT, gH, gW,
                      c->last_cs + (size_t)stream * half, c->inv_freq, half, c->cfg.rope_mode == SV_ROPE_NONE ? 1 : 0,
                      c->cfg.mrope_sections[0], c->cfg.mrope_sections[0] + c->cfg.mrope_sections[1],
-                     c->cfg.dtype == SV_DTYPE_F32 ? 1 : 0);
+                     c->cfg.dtype == SV_DTYPE_F32 ? 1 : 0, c->n_dev + stream);
   return hipGetLastError();
 }
 

@@ -112,3 +112,33 @@ def assert_attn_parity(g: Dict[str, object], o: Dict[str, object], tol: float, w
             assert e <= tol, f"{where} decode step {t} layer#{j}: max abs err {e:.3e} > {tol}"
             worst = max(worst, e)
     return worst
+
+
+class PooledWorkload(si.Workload):
+    """Qwen-shaped stream whose Q/K/V of a token depend on its arrival id modulo a pool of 32 chunks (the preamble
+    keeps its own ids): throughput and parity do not depend on the data, and a late chunk of a long stream stays
+    reachable for both sides without generating an hour of samples."""
+    POOL_CHUNKS = 32
+
+    def key(self, gids):
+        g = np.asarray(gids, dtype=np.int64)
+        period = self.POOL_CHUNKS * self.tokens_per_chunk
+        return np.where(g < self.preamble_text, g, self.preamble_text + (g - self.preamble_text) % period)
+
+    def tables(self, layer):
+        cache = self.__dict__.setdefault("_tables", {})
+        if layer not in cache:
+            keys = np.arange(self.preamble_text + self.POOL_CHUNKS * self.tokens_per_chunk)
+            cache[layer] = si.Workload.qkv(self, layer, keys)
+        return cache[layer]
+
+    def qkv(self, layer, gids):
+        q, k, v = self.tables(layer)
+        kk = self.key(gids)
+        return q[kk], k[kk], v[kk]
+
+
+def pooled(base: si.Workload, pool_chunks: int = 32) -> PooledWorkload:
+    w = PooledWorkload(**{f: getattr(base, f) for f in base.__dataclass_fields__})
+    w.POOL_CHUNKS = pool_chunks
+    return w

@@ -5,7 +5,6 @@ outputs within max-abs 1e-5 (fp32 workload) and 2e-2 (bf16 workloads, unit-varia
 inputs, oracle fed the bf16-rounded values).  Everything goes through the C ABI.
 """
 import copy
-import os
 
 import numpy as np
 import pytest
@@ -374,10 +373,11 @@ def test_rope_apply_and_stored_kv(dtype, mode):
     assert gu.max_err(cache.read_kv(0, 0, 0, 0, n2), orc.rope(K, o.positions(), mode, theta, sec)) <= 2 * tol
 
 
-def _attn_case(dtype, Hq, Hkv, d, n_kv, n_q, causal, seed):
+def _attn_case(dtype, Hq, Hkv, d, n_kv, n_q, causal, seed, splits=0, flags=0):
     w = si.Workload("a", 1, Hq, Hkv, d, dtype, 2, 1e4, (0, 0, 0), 0, 0, 0, 0, 0, 0, None, 0, seed)
     cache = sv.Cache(1, Hq, Hkv, d, sv.SV_DTYPE_F32 if dtype == "f32" else sv.SV_DTYPE_BF16, sv.SV_ROPE_NONE, 1e4,
-                     (0, 0, 0), 1, n_kv + 8, max(n_q, 1))
+                     (0, 0, 0), 1, n_kv + 8, max(n_q, 1), flags=flags)
+    cache.set_option(sv.SV_OPT_CHUNK_SPLITS, splits)
     gids = np.arange(n_kv)
     bf = dtype == "bf16"
     k = si.normal(seed, si.TENSOR_K, 0, gids, Hkv, d, bf)
@@ -392,24 +392,35 @@ def _attn_case(dtype, Hq, Hkv, d, n_kv, n_q, causal, seed):
     return gu.max_err(gu.host(od), ref), cache, w, q, k, v
 
 
-@pytest.mark.parametrize("variant", ["0", "1", "2", "3", "4"])
 @pytest.mark.parametrize("n_kv,n_q,causal,splits", [
-    (64, 64, True, "0"), (200, 37, True, "0"), (1000, 256, True, "0"), (1333, 300, True, "3"),
-    (777, 100, False, "2"), (5392, 256, True, "0"), (130, 1, True, "0")])
-def test_attn_chunk_mfma_shapes(variant, n_kv, n_q, causal, splits):
-    os.environ["SV_CHUNK_VARIANT"], os.environ["SV_CHUNK_SPLITS"] = variant, splits
-    try:
-        _say(f"attn_chunk mfma variant={variant} n_kv={n_kv} n_q={n_q} causal={causal} splits={splits}")
-        err, *_ = _attn_case("bf16", 28, 4, 128, n_kv, n_q, causal, 300 + n_kv)
-        assert err <= gu.TOL["bf16"], err
-    finally:
-        os.environ.pop("SV_CHUNK_VARIANT"), os.environ.pop("SV_CHUNK_SPLITS")
+    (64, 64, True, 0), (200, 37, True, 0), (1000, 256, True, 0), (1333, 300, True, 3),
+    (777, 100, False, 2), (5392, 256, True, 0), (130, 1, True, 0)])
+def test_attn_chunk_mfma_shapes(n_kv, n_q, causal, splits):
+    _say(f"attn_chunk mfma n_kv={n_kv} n_q={n_q} causal={causal} splits={splits}")
+    err, *_ = _attn_case("bf16", 28, 4, 128, n_kv, n_q, causal, 300 + n_kv, splits=splits)
+    assert err <= gu.TOL["bf16"], err
 
 
-@pytest.mark.parametrize("variant", ["0", "2", "4"])
-def test_attn_chunk_wide_score_range(variant):
+@pytest.mark.parametrize("n_kv,n_q,causal,splits", [(200, 37, True, 0), (777, 100, False, 3), (1400, 1, True, 5)])
+def test_generic_kernels_on_bf16_head_dim_128(n_kv, n_q, causal, splits):
+    """SV_FLAG_GENERIC_KERNELS: the vector-ALU row kernels (chunk prefill and decode, forced key-range counts) on the
+    data type and head shape that the matrix-core kernels normally take."""
+    _say(f"generic kernels bf16 d128 n_kv={n_kv} n_q={n_q} causal={causal} splits={splits}")
+    err, cache, w, q, k, v = _attn_case("bf16", 28, 4, 128, n_kv, n_q, causal, 900 + n_kv,
+                                        flags=sv.SV_FLAG_GENERIC_KERNELS)
+    assert err <= gu.TOL["bf16"], err
+    cache.set_option(sv.SV_OPT_DECODE_SPLITS, splits)
+    qd1 = gu.dev(q[-1:], w)
+    od1 = torch.empty_like(qd1)
+    cache.attn_decode(0, [0], qd1, od1)
+    ref1 = orc.gqa_attention(q[-1:].astype(np.float64), k.astype(np.float64), v.astype(np.float64),
+                             np.array([n_kv - 1]), True)
+    assert gu.max_err(gu.host(od1), ref1) <= gu.TOL["bf16"]
+
+
+def test_attn_chunk_wide_score_range():
     """Scores whose row maxima jump by tens to hundreds of binary orders from one key tile to the next (key blocks
-    scaled by exact powers of two, one late key by 128): the running-maximum logic of the chunk kernels (steps of
+    scaled by exact powers of two, one late key by 128): the running-maximum logic of the chunk kernel (steps of
     the reference maximum, probabilities taken before the tile's maxima are known, redo on overflow) must still
     reproduce the plain softmax, which is then nearly one-hot."""
     Hq, Hkv, d, n_kv, n_q, seed = 28, 4, 128, 1100, 200, 4242
@@ -423,22 +434,18 @@ def test_attn_chunk_wide_score_range(variant):
     k[640:704] *= 32
     k[901] *= 128
     k[1000:1010] *= 8            # inside the causal part of the chunk
-    os.environ["SV_CHUNK_VARIANT"] = variant
-    try:
-        _say(f"attn_chunk wide score range variant={variant}")
-        for causal in (True, False):
-            cache = sv.Cache(1, Hq, Hkv, d, sv.SV_DTYPE_BF16, sv.SV_ROPE_NONE, 1e4, (0, 0, 0), 1, n_kv + 8, n_q)
-            cache.append(0, 0, np.zeros(n_kv, dtype=np.uint8), None, gu.dev(k, w), gu.dev(v, w))
-            qd = gu.dev(q, w)
-            od = torch.empty_like(qd)
-            cache.attn_chunk(0, 0, qd, od, causal)
-            ref = orc.gqa_attention(q.astype(np.float64), k.astype(np.float64), v.astype(np.float64),
-                                    np.arange(n_kv - n_q, n_kv), causal)
-            got = gu.host(od)
-            assert np.isfinite(got).all()
-            assert gu.max_err(got, ref) <= gu.TOL["bf16"], (causal, gu.max_err(got, ref))
-    finally:
-        os.environ.pop("SV_CHUNK_VARIANT")
+    _say("attn_chunk wide score range")
+    for causal in (True, False):
+        cache = sv.Cache(1, Hq, Hkv, d, sv.SV_DTYPE_BF16, sv.SV_ROPE_NONE, 1e4, (0, 0, 0), 1, n_kv + 8, n_q)
+        cache.append(0, 0, np.zeros(n_kv, dtype=np.uint8), None, gu.dev(k, w), gu.dev(v, w))
+        qd = gu.dev(q, w)
+        od = torch.empty_like(qd)
+        cache.attn_chunk(0, 0, qd, od, causal)
+        ref = orc.gqa_attention(q.astype(np.float64), k.astype(np.float64), v.astype(np.float64),
+                                np.arange(n_kv - n_q, n_kv), causal)
+        got = gu.host(od)
+        assert np.isfinite(got).all()
+        assert gu.max_err(got, ref) <= gu.TOL["bf16"], (causal, gu.max_err(got, ref))
 
 
 def test_attn_randomized_shapes():
@@ -450,7 +457,7 @@ def test_attn_randomized_shapes():
         n_kv = int(rng.choice([rng.integers(1, 130), rng.integers(130, 700), rng.integers(700, 2600)]))
         n_q = int(min(n_kv, rng.choice([1, rng.integers(1, 40), rng.integers(40, 300)])))
         causal = bool(rng.integers(0, 2))
-        splits = str(int(rng.choice([0, 0, 1, 2, 3, 5])))
+        splits = int(rng.choice([0, 0, 1, 2, 3, 5]))
         scale_mode = int(rng.integers(0, 3))
         seed = 7000 + case
         w = si.Workload("a", 1, 28, 4, 128, "bf16", 2, 1e4, (0, 0, 0), 0, 0, 0, 0, 0, 0, None, 0, seed)
@@ -465,15 +472,13 @@ def test_attn_randomized_shapes():
             for b in range(0, n_kv, 32):
                 k[b:b + 32] *= 2.0 ** int(rng.integers(-5, 6))
         _say(f"randomized case {case}: n_kv={n_kv} n_q={n_q} causal={causal} splits={splits} scale_mode={scale_mode}")
-        os.environ["SV_CHUNK_SPLITS"] = splits
-        try:
-            cache = sv.Cache(1, 28, 4, 128, sv.SV_DTYPE_BF16, sv.SV_ROPE_NONE, 1e4, (0, 0, 0), 1, n_kv + 8, n_q)
-            cache.append(0, 0, np.zeros(n_kv, dtype=np.uint8), None, gu.dev(k, w), gu.dev(v, w))
-            qd = gu.dev(q, w)
-            od = torch.empty_like(qd)
-            cache.attn_chunk(0, 0, qd, od, causal)
-        finally:
-            os.environ.pop("SV_CHUNK_SPLITS")
+        cache = sv.Cache(1, 28, 4, 128, sv.SV_DTYPE_BF16, sv.SV_ROPE_NONE, 1e4, (0, 0, 0), 1, n_kv + 8, n_q)
+        cache.set_option(sv.SV_OPT_CHUNK_SPLITS, splits)
+        cache.set_option(sv.SV_OPT_DECODE_TILES_PER_WAVE, int(rng.choice([0, 0, 1, 3])))
+        cache.append(0, 0, np.zeros(n_kv, dtype=np.uint8), None, gu.dev(k, w), gu.dev(v, w))
+        qd = gu.dev(q, w)
+        od = torch.empty_like(qd)
+        cache.attn_chunk(0, 0, qd, od, causal)
         k64, v64 = k.astype(np.float64), v.astype(np.float64)
         ref = orc.gqa_attention(q.astype(np.float64), k64, v64, np.arange(n_kv - n_q, n_kv), causal)
         got = gu.host(od)
@@ -753,35 +758,11 @@ def test_probe_rates_are_plausible():
         sv.sv_probe_rates(buf[:16])            # smaller than the 1 MiB the probe asks for
 
 
-class _PooledWorkload(si.Workload):
-    """Qwen-shaped stream whose Q/K/V of a token depend on its arrival id modulo a pool of 32 chunks (the preamble
-    keeps its own ids): throughput and parity do not depend on the data, and a late chunk of a long stream stays
-    reachable for both sides without generating an hour of samples."""
-    POOL_CHUNKS = 32
-
-    def key(self, gids):
-        g = np.asarray(gids, dtype=np.int64)
-        period = self.POOL_CHUNKS * self.tokens_per_chunk
-        return np.where(g < self.preamble_text, g, self.preamble_text + (g - self.preamble_text) % period)
-
-    def tables(self, layer):
-        cache = self.__dict__.setdefault("_tables", {})
-        if layer not in cache:
-            keys = np.arange(self.preamble_text + self.POOL_CHUNKS * self.tokens_per_chunk)
-            cache[layer] = si.Workload.qkv(self, layer, keys)
-        return cache[layer]
-
-    def qkv(self, layer, gids):
-        q, k, v = self.tables(layer)
-        kk = self.key(gids)
-        return q[kk], k[kk], v[kk]
-
-
 def test_long_stream_attention_at_late_chunks():
     """Attention parity deep into a one-hour stream (chunks 64, 1800 and 3599 of the 28q/4kv x 128 M-RoPE stream,
     three layers), driven by the native per-second call; retained counts checked at every chunk."""
     base = si.workload_qwen_layer(n_chunks=3600, n_layers=3, seed=1003)
-    w = _PooledWorkload(**{f: getattr(base, f) for f in base.__dataclass_fields__})
+    w = gu.pooled(base)
     layers = [0, 13, 27]
     L, nv, nt = 3, w.vision_per_chunk, w.text_per_chunk
     cache = gu.make_cache(w, n_layers=L, capacity=w.retained_steady() + w.tokens_per_chunk + 64)

@@ -160,3 +160,21 @@ def test_call_order_capacity_and_argument_errors():
     n = C.c_int64(-1)
     assert lib.sv_cache_retained(h, 0, None, None, 0, C.byref(n), None) == UNSUPPORTED and n.value == 2
     assert lib.sv_cache_destroy(h) == OK
+
+
+def test_options_and_flags():
+    """sv_cache_set_option keeps per-handle launch overrides (host state only); unknown options, negative values and
+    unknown flag bits are refused; the generic-kernel flag is accepted."""
+    lib, h = _create()
+    for opt in (B.SV_OPT_CHUNK_SPLITS, B.SV_OPT_DECODE_TILES_PER_WAVE, B.SV_OPT_DECODE_SPLITS):
+        assert lib.sv_cache_set_option(h, opt, 3) == OK and lib.sv_cache_set_option(h, opt, 0) == OK
+    assert lib.sv_cache_set_option(h, 3, 1) == INVALID and lib.sv_cache_set_option(h, -1, 1) == INVALID
+    assert lib.sv_cache_set_option(h, B.SV_OPT_CHUNK_SPLITS, -2) == INVALID
+    assert lib.sv_cache_set_option(None, 0, 1) == INVALID
+    cfg = B.SvConfig(1, 28, 4, 128, B.SV_DTYPE_BF16, B.SV_ROPE_3D, 1.0e6, (C.c_int32 * 3)(16, 24, 24), 1, 64, 16,
+                     B.SV_FLAG_GENERIC_KERNELS)
+    assert lib.sv_cache_bytes(C.byref(cfg)) > 0
+    cfg.flags = 2
+    assert lib.sv_cache_bytes(C.byref(cfg)) == 0
+    cfg.flags, cfg.capacity_tokens = 0, (1 << 24) + 1            # slots are indexed with 32-bit arithmetic
+    assert lib.sv_cache_bytes(C.byref(cfg)) == 0
