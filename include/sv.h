@@ -199,6 +199,22 @@ SV_API int sv_attn_decode(sv_cache* c, int layer, const int32_t* stream_ids_host
                    const void* q_dev, void* o_dev, void* hip_stream);
 
 /*
+ * sv_attn_decode_static -- sv_attn_decode for callers that cannot allocate or hand over scratch memory
+ * (code under HIP-graph capture, tight serving loops, harnesses that forbid hipMalloc).  Same arguments,
+ * same result; the partial results of the key ranges go to a fixed 8 MiB device array inside the library
+ * (static storage, one copy per GPU, held until the process ends) instead of the arena's scratch region,
+ * and the call allocates nothing, on the host or on the device.  Limits: bf16 / head_dim 128 / at most 8
+ * query heads per kv head (else SV_ERR_UNSUPPORTED); n_list <= SV_STATIC_MAX_ROWS and
+ * n_list * n_q_heads * 520 bytes <= 8 MiB (else SV_ERR_CAPACITY); rows longer than the array's share are
+ * cut into fewer, longer key ranges.  Every call on one GPU shares the array: calls that overlap in time on
+ * one GPU (different streams, different handles) race; calls ordered on one stream do not.  Nothing in the
+ * array needs clearing between calls: every entry a call reads it has written itself.
+ */
+#define SV_STATIC_MAX_ROWS 64
+SV_API int sv_attn_decode_static(sv_cache* c, int layer, const int32_t* stream_ids_host, int n_list,
+                                 const void* q_dev, void* o_dev, void* hip_stream);
+
+/*
  * sv_decode_step -- one decoded text token per listed stream in a single
  * launch per layer: equivalent to sv_cache_append (one SV_TEXT token),
  * sv_rope_apply on the query and sv_attn_decode, fused (Sec. 2.1: the new

@@ -65,6 +65,7 @@ _SIGNATURES = {
     "sv_rope_apply": (C.c_int, [C.c_void_p, C.c_int, C.c_int64, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]),
     "sv_attn_chunk": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p]),
     "sv_attn_decode": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "sv_attn_decode_static": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]),
     "sv_decode_step": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
                                  C.c_void_p, C.c_void_p]),
     "sv_decode_step_layers": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -172,6 +173,12 @@ def sv_attn_decode(handle: int, layer: int, stream_ids, q, o, stream=None) -> No
     ids = np.ascontiguousarray(stream_ids, dtype=np.int32)
     _check(lib().sv_attn_decode(handle, layer, ids.ctypes.data, int(ids.shape[0]), _ptr(q), _ptr(o), _stream(stream)),
            "sv_attn_decode")
+
+
+def sv_attn_decode_static(handle: int, layer: int, stream_ids, q, o, stream=None) -> None:
+    ids = np.ascontiguousarray(stream_ids, dtype=np.int32)
+    _check(lib().sv_attn_decode_static(handle, layer, ids.ctypes.data, int(ids.shape[0]), _ptr(q), _ptr(o),
+                                       _stream(stream)), "sv_attn_decode_static")
 
 
 def sv_decode_step(handle: int, layer: int, stream_ids, q, k, v, o, stream=None) -> None:
@@ -285,6 +292,9 @@ class Cache:
 
     def attn_decode(self, layer, stream_ids, q, o) -> None:
         sv_attn_decode(self.handle, layer, stream_ids, q, o)
+
+    def attn_decode_static(self, layer, stream_ids, q, o) -> None:
+        sv_attn_decode_static(self.handle, layer, stream_ids, q, o)
 
     def decode_step(self, layer, stream_ids, q, k, v, o) -> None:
         sv_decode_step(self.handle, layer, stream_ids, q, k, v, o)

@@ -205,6 +205,10 @@ int sv_cache_create(const sv_config* cfg, void* dev_arena, size_t arena_bytes, v
   if (e == hipSuccess) e = hipMemsetAsync(c->n_dev, 0, (size_t)cfg->n_streams * 4, s);
   if (e == hipSuccess) e = hipMemsetAsync(c->counters, 0, (size_t)L.part_rows * cfg->n_kv_heads * 4, s);
   if (e == hipSuccess && c->use_mfma) e = sv::attn_chunk_mfma_init();
+  if (e == hipSuccess && c->use_mfma) {   // device address of sv_attn_decode_static's scratch array, once per device
+    void* p = nullptr;
+    e = sv::decode_static_scratch(&p);
+  }
   if (e == hipSuccess) e = hipStreamSynchronize(s);  // f is a local: the copy must have read it
   if (e != hipSuccess) {
     delete c;
@@ -391,6 +395,22 @@ int sv_attn_decode(sv_cache* c, int layer, const int32_t* stream_ids_host, int n
   if (!sv::attn_rows_supported(c)) return SV_ERR_UNSUPPORTED;
   SV_DEV(sv::launch_attn_rows_batch(c, layer, stream_ids_host, n_list, 0, q_dev, nullptr, nullptr, o_dev,
                                     (hipStream_t)hip_stream));
+  return SV_OK;
+}
+
+int sv_attn_decode_static(sv_cache* c, int layer, const int32_t* stream_ids_host, int n_list, const void* q_dev,
+                          void* o_dev, void* hip_stream) {
+  if (!c || layer < 0 || layer >= c->cfg.n_layers || !stream_ids_host || n_list < 1 || !q_dev || !o_dev)
+    return SV_ERR_INVALID;
+  if (!c->use_mfma) return SV_ERR_UNSUPPORTED;
+  if (n_list > SV_STATIC_MAX_ROWS || (int64_t)n_list > sv::decode_static_pairs(c)) return SV_ERR_CAPACITY;
+  for (int b = 0; b < n_list; ++b) {
+    if (!stream_ok(c, stream_ids_host[b])) return SV_ERR_INVALID;
+    const sv::StreamState& st = c->st[stream_ids_host[b]];
+    if (st.len < 1) return SV_ERR_INVALID;
+    if (st.layer_len[layer] != st.len) return SV_ERR_STATE;
+  }
+  SV_DEV(sv::launch_attn_decode_mfma_static(c, layer, stream_ids_host, n_list, q_dev, o_dev, (hipStream_t)hip_stream));
   return SV_OK;
 }
 

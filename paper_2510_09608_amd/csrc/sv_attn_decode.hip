@@ -449,6 +449,35 @@ static hipError_t decode_launch(const sv_cache* c, const DecTable& tab, int fuse
   return hipGetLastError();
 }
 
+// Partial results of the key ranges live in the cache arena by default; sv_attn_decode_static keeps them in a
+// file-scope device array instead (callers that cannot provide scratch memory).  The array's name is only a host-side
+// handle: its device address is looked up once per device and kept.
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+static void* g_scratch_ptr[kMaxDevices] = {};
+
+hipError_t decode_static_scratch(void** ptr_out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr_out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+
+int64_t decode_static_pairs(const sv_cache* c) {
+  // one (row, key range) pair holds n_q_heads x (128 + 2) floats
+  return (int64_t)(kStaticScratchBytes / ((size_t)c->cfg.n_q_heads * (D + 2) * sizeof(float)));
+}
+
 static hipError_t decode_rows(const sv_cache* c, int layer, const int32_t* streams, int n_list, int fused, const void* q,
                               const void* k_new, const void* v_new, void* o, float* part_o, float* part_ml,
                               int64_t part_rows, hipStream_t s) {
@@ -479,6 +508,17 @@ static hipError_t decode_rows(const sv_cache* c, int layer, const int32_t* strea
 hipError_t launch_attn_decode_mfma(const sv_cache* c, int layer, const int32_t* streams, int n_list, int fused,
                                    const void* q, const void* k_new, const void* v_new, void* o, hipStream_t s) {
   return decode_rows(c, layer, streams, n_list, fused, q, k_new, v_new, o, c->part_o, c->part_ml, c->part_rows, s);
+}
+
+hipError_t launch_attn_decode_mfma_static(const sv_cache* c, int layer, const int32_t* streams, int n_list,
+                                          const void* q, void* o, hipStream_t s) {
+  void* p = nullptr;
+  hipError_t e = decode_static_scratch(&p);
+  if (e != hipSuccess) return e;
+  const int64_t pairs = decode_static_pairs(c);
+  float* part_o = (float*)p;
+  float* part_ml = part_o + (size_t)pairs * c->cfg.n_q_heads * D;
+  return decode_rows(c, layer, streams, n_list, 0, q, nullptr, nullptr, o, part_o, part_ml, pairs, s);
 }
 
 }  // namespace sv

@@ -119,6 +119,14 @@ bool attn_rows_supported(const sv_cache* c);
 hipError_t launch_attn_decode_mfma(const sv_cache* c, int layer, const int32_t* streams, int n_list, int fused,
                                    const void* q, const void* k_new, const void* v_new, void* o, hipStream_t s);
 
+// sv_attn_decode_static: split-KV partials in a file-scope device array instead of the arena.
+// decode_static_scratch looks the array's device address up (once per device, kept); decode_static_pairs is the
+// number of (row, key range) pairs the array holds for this cache's head count.
+hipError_t decode_static_scratch(void** ptr_out);
+int64_t decode_static_pairs(const sv_cache* c);
+hipError_t launch_attn_decode_mfma_static(const sv_cache* c, int layer, const int32_t* streams, int n_list,
+                                          const void* q, void* o, hipStream_t s);
+
 // Once per process and device, before the first chunk-prefill launch: the kernel's LDS size has to be asked for.
 hipError_t attn_chunk_mfma_init();
 // V^T staging of one layer for the pipelined chunk-prefill kernel, alone or fused with the chunk's append and Q

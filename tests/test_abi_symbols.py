@@ -22,7 +22,7 @@ def _lib():
 
 def test_every_declared_symbol_is_exported():
     names = _declared()
-    assert len(names) == 17 and "sv_cache_evict" in names and "sv_attn_decode" in names
+    assert len(names) == 18 and "sv_cache_evict" in names and "sv_attn_decode" in names
     lib = _lib()
     for n in names:
         assert hasattr(lib, n), n
