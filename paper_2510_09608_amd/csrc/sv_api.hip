@@ -43,7 +43,7 @@ bool config_ok(const sv_config* c) {
 // sv_cache_bytes and sv_cache_create cannot disagree.
 struct Layout {
   size_t kv, meta_gid[2], meta_rank[2], meta_pos[2], meta_local[2], meta_blk[2], meta_type[2];
-  size_t src, delta, dtab, next_pos, n_dev, inv_freq, last_cs, part_o, part_ml, counters, vt, total;
+  size_t src, delta, dtab, next_pos, n_dev, inv_freq, last_cs, part_o, part_ml, counters, total;
   int64_t part_rows;
 };
 
@@ -51,13 +51,14 @@ Layout make_layout(const sv_config& c) {
   Layout L{};
   const size_t es = c.dtype == SV_DTYPE_F32 ? 4 : 2;
   const size_t cap = (size_t)c.capacity_tokens, S = (size_t)c.n_streams;
+  const size_t cap_pad = (cap + 63) / 64 * 64;   // K/V planes hold whole 64-key tiles
   size_t off = 0;
   auto take = [&](size_t bytes) {
     size_t o = off;
     off = align_up(off + bytes);
     return o;
   };
-  L.kv = take(S * 2 * (size_t)c.n_layers * 2 * (size_t)c.n_kv_heads * cap * (size_t)c.head_dim * es);
+  L.kv = take(S * 2 * (size_t)c.n_layers * 2 * (size_t)c.n_kv_heads * cap_pad * (size_t)c.head_dim * es);
   for (int h = 0; h < 2; ++h) {
     L.meta_gid[h] = take(S * cap * 8);
     L.meta_rank[h] = take(S * cap * 8);
@@ -77,8 +78,6 @@ Layout make_layout(const sv_config& c) {
   L.part_o = take((size_t)L.part_rows * c.n_q_heads * c.head_dim * 4);
   L.part_ml = take((size_t)L.part_rows * c.n_q_heads * 2 * 4);
   L.counters = take((size_t)L.part_rows * c.n_kv_heads * 4);
-  // V^T staging of one layer per stream (chunk prefill on the matrix cores): blocks of 64 keys, [head_dim][64]
-  L.vt = take(S * (size_t)c.n_kv_heads * ((cap + 63) / 64) * 64 * (size_t)c.head_dim * es);
   L.total = off;
   return L;
 }
@@ -155,7 +154,8 @@ int sv_cache_create(const sv_config* cfg, void* dev_arena, size_t arena_bytes, v
   c->esize = cfg->dtype == SV_DTYPE_F32 ? 4 : 2;
   c->group = cfg->n_q_heads / cfg->n_kv_heads;
   c->row_bytes = (size_t)cfg->head_dim * c->esize;
-  c->head_stride = (size_t)cfg->capacity_tokens * c->row_bytes;
+  c->cap_pad = (cfg->capacity_tokens + 63) / 64 * 64;
+  c->head_stride = (size_t)c->cap_pad * c->row_bytes;
   c->tensor_stride = (size_t)cfg->n_kv_heads * c->head_stride;
   c->layer_stride = 2 * c->tensor_stride;
   c->half_stride = (size_t)cfg->n_layers * c->layer_stride;
@@ -181,12 +181,11 @@ int sv_cache_create(const sv_config* cfg, void* dev_arena, size_t arena_bytes, v
   c->part_ml = (float*)(base + L.part_ml);
   c->part_rows = L.part_rows;
   c->counters = (int32_t*)(base + L.counters);
-  c->vt = base + L.vt;
-  c->vt_stream_stride = (size_t)cfg->n_kv_heads * (((size_t)cfg->capacity_tokens + 63) / 64) * 64 * (size_t)cfg->head_dim * c->esize;
   c->st.resize(cfg->n_streams);
   for (auto& s : c->st) s.layer_len.assign(cfg->n_layers, 0);
   c->use_mfma = cfg->dtype == SV_DTYPE_BF16 && cfg->head_dim == 128 && c->group <= 8 &&
                 !(cfg->flags & SV_FLAG_GENERIC_KERNELS);
+  c->v_blocked = c->use_mfma;
 
   // rotary frequencies theta^(-2i/d), computed once in double
   const int half = cfg->head_dim / 2;
@@ -204,6 +203,10 @@ int sv_cache_create(const sv_config* cfg, void* dev_arena, size_t arena_bytes, v
   if (e == hipSuccess) e = hipMemsetAsync(c->next_pos, 0, (size_t)cfg->n_streams * 2 * 4, s);
   if (e == hipSuccess) e = hipMemsetAsync(c->n_dev, 0, (size_t)cfg->n_streams * 4, s);
   if (e == hipSuccess) e = hipMemsetAsync(c->counters, 0, (size_t)L.part_rows * cfg->n_kv_heads * 4, s);
+  // blocked V^T: slots past a stream's end inside its last block are multiplied by probabilities of zero and must
+  // never hold NaN patterns, so the store starts out cleared
+  if (e == hipSuccess && c->v_blocked)
+    e = hipMemsetAsync(c->kv_base, 0, (size_t)cfg->n_streams * c->stream_kv_stride, s);
   if (e == hipSuccess && c->use_mfma) e = sv::attn_chunk_mfma_init();
   if (e == hipSuccess && c->use_mfma) {   // device address of sv_attn_decode_static's scratch array, once per device
     void* p = nullptr;
@@ -368,7 +371,7 @@ int sv_attn_chunk(sv_cache* c, int stream_id, int layer, const void* q_dev, int 
   if (st.layer_len[layer] != st.len) return SV_ERR_STATE;
   hipStream_t s = (hipStream_t)hip_stream;
   if (c->use_mfma) {
-    SV_DEV(sv::launch_attn_chunk_mfma(c, stream_id, layer, q_dev, n_q, o_dev, causal, false, s));
+    SV_DEV(sv::launch_attn_chunk_mfma(c, stream_id, layer, q_dev, n_q, o_dev, causal, s));
     return SV_OK;
   }
   if (!sv::attn_rows_supported(c)) return SV_ERR_UNSUPPORTED;
@@ -500,8 +503,8 @@ int sv_stream_step(sv_cache* c, int stream_id, int64_t n_sink, int64_t vision_wi
     const int n = io->n_vision;
     std::vector<uint8_t> types((size_t)n, (uint8_t)SV_VISION);
     const bool has_grid = io->grid_thw[0] > 0 || io->grid_thw[1] > 0 || io->grid_thw[2] > 0;
-    // bf16 / head_dim 128: K/V store, Q rotation and V^T staging of a layer go out as ONE launch
-    const bool fused = c->use_mfma && n <= c->cfg.max_q_tokens;
+    // blocked-V^T caches: K/V store and Q rotation of a layer go out as ONE launch
+    const bool fused = c->v_blocked && n <= c->cfg.max_q_tokens;
     for (int l = 0; l < L; ++l) {
       int64_t slot0 = 0;
       char* q = (char*)io->q_vision + (size_t)l * n * qrow;
@@ -512,8 +515,8 @@ int sv_stream_step(sv_cache* c, int stream_id, int64_t n_sink, int64_t vision_wi
                        !fused);
       if (rc != SV_OK) return rc;
       if (fused) {
-        SV_DEV(sv::launch_chunk_prologue(c, stream_id, l, slot0, n, q, k, v, (hipStream_t)hip_stream));
-        SV_DEV(sv::launch_attn_chunk_mfma(c, stream_id, l, q, n, o, 1, true, (hipStream_t)hip_stream));
+        SV_DEV(sv::launch_store_tokens_vt(c, stream_id, l, slot0, n, q, k, v, (hipStream_t)hip_stream));
+        SV_DEV(sv::launch_attn_chunk_mfma(c, stream_id, l, q, n, o, 1, (hipStream_t)hip_stream));
       } else {
         rc = sv_rope_apply(c, stream_id, slot0, n, q, nullptr, hip_stream);
         if (rc != SV_OK) return rc;
@@ -579,6 +582,23 @@ int sv_cache_read_kv(sv_cache* c, int stream_id, int layer, int which, int64_t s
   if (slot0 < 0 || n < 0 || slot0 + n > st.layer_len[layer] || (n > 0 && !dst_host)) return SV_ERR_INVALID;
   if (c->host_logic_only) return SV_ERR_UNSUPPORTED;
   hipStream_t s = (hipStream_t)hip_stream;
+  if (n > 0 && which == 1 && c->v_blocked) {
+    // blocked V^T: fetch the 8-key blocks that cover the rows and pick the elements out on the host
+    const int64_t b0 = slot0 / sv::kVB, nb = (slot0 + n - 1) / sv::kVB - b0 + 1;
+    std::vector<uint16_t> tmp((size_t)c->cfg.n_kv_heads * nb * sv::kVBElems);
+    for (int h = 0; h < c->cfg.n_kv_heads; ++h)
+      SV_HIP(hipMemcpyAsync(tmp.data() + (size_t)h * nb * sv::kVBElems,
+                            c->kv_ptr(stream_id, st.cur, layer, 1) + (size_t)h * c->head_stride + (size_t)b0 * sv::kVBElems * 2,
+                            (size_t)nb * sv::kVBElems * 2, hipMemcpyDeviceToHost, s));
+    SV_HIP(hipStreamSynchronize(s));
+    uint16_t* dst = (uint16_t*)dst_host;
+    for (int64_t i = 0; i < n; ++i)
+      for (int h = 0; h < c->cfg.n_kv_heads; ++h)
+        for (int d = 0; d < c->cfg.head_dim; ++d)
+          dst[((size_t)i * c->cfg.n_kv_heads + h) * c->cfg.head_dim + d] =
+              tmp[(size_t)h * nb * sv::kVBElems + sv::vt_elem(slot0 + i - b0 * sv::kVB, d)];
+    return SV_OK;
+  }
   if (n > 0) {
     const char* src = c->kv_ptr(stream_id, st.cur, layer, which) + (size_t)slot0 * c->row_bytes;
     const size_t dpitch = (size_t)c->cfg.n_kv_heads * c->row_bytes;

@@ -13,12 +13,14 @@
 //   * the rows of the score MFMAs are assigned to keys such that each lane ends up
 //     with 8 consecutive keys, i.e. the probabilities already sit in the B-operand
 //     layout of the second product O^T = V^T P^T;
-//   * V rows are staged row-major in LDS (coalesced 16-byte loads and stores) and read
-//     back as the V^T operand with the LDS transpose read, so keys are contracted
-//     inside the MFMA: about 4 instructions per key in total;
+//   * V is stored in the cache as V^T in blocks of 8 keys ([head dim][key], 2 KB per kv head): a
+//     32-key tile of the second product's A operand is 8 KB contiguous, each lane loads its 8 keys
+//     of one head dim (one block row) with a 16-byte load straight from HBM, and keys are contracted
+//     inside the MFMA: about 3 instructions per key in total, no LDS on the way;
 //   * in the fused form the query and the new token's K are rotated in registers at
 //     the new token's position (cos/sin from a 64-entry table written when the token
-//     was registered), and K/V of the new token are stored by the lanes that hold them;
+//     was registered), and K/V of the new token are stored by the lanes that hold them
+//     (V as one 2-byte element per head dim into its V^T block);
 //   * all global loads of a tile are issued before anything else the wavefront does;
 //   * wavefronts of a workgroup take alternate tiles of the workgroup's key range and
 //     are merged through LDS; key ranges are merged by a second, tiny kernel whose
@@ -88,25 +90,12 @@ __device__ __forceinline__ void rotate_pair_chunks(uint4& lo, uint4& hi, const f
   }
 }
 
-typedef short v4i16 __attribute__((ext_vector_type(4)));
-
-constexpr int VROW = D * 2 + 64;   // bytes per V row in LDS: rows of one transpose read fall in distinct banks
-
-// LDS transpose read (ds_read_b64_tr_b16).  Within each group of 16 lanes, lane j hands in the address of 4
-// consecutive 16-bit elements and receives element (j & 3) of the chunks of lanes (j >> 2) + 4 e, e = 0..3.
-// With lane j pointing at row r0 + (j >> 2), columns c0 + 4 (j & 3) .. + 3 of a row-major tile, it therefore
-// receives column c0 + j of rows r0 .. r0 + 3: a column fragment, which is what an MFMA operand holding
-// V^T wants.  (Layout confirmed with an index pattern on the device.)
-__device__ __forceinline__ v4i16 lds_read_tr(const char* lds_base, int byte_off) {
-  return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-      (v4i16 __attribute__((address_space(3)))*)((__attribute__((address_space(3))) char*)lds_base + byte_off));
-}
 
 // ONE: a single row (one stream).  Its cache pointers, length and everything else needed to issue the first
 // loads are the leading 16 dwords of the argument list, which reach the wavefront in SGPRs at launch (kernel
 // argument preload) instead of through a first dependent fetch; the by-value table, at the end, is not read.
 template <int NW, bool ONE, bool STREAM>
-__global__ __launch_bounds__(NW * 64) void k_decode_mfma(__hip_bfloat16* k0_, __hip_bfloat16* v0_, const float2* cs0_,
+__global__ __launch_bounds__(NW * 64, 2) void k_decode_mfma(__hip_bfloat16* k0_, __hip_bfloat16* v0_, const float2* cs0_,
                                                          int len0_, int keys_per_split,
                                                          const __hip_bfloat16* __restrict__ q,
                                                          const __hip_bfloat16* __restrict__ k_new,
@@ -115,7 +104,6 @@ __global__ __launch_bounds__(NW * 64) void k_decode_mfma(__hip_bfloat16* k0_, __
                                                          __hip_bfloat16* __restrict__ out, float* __restrict__ part_o,
                                                          float* __restrict__ part_ml, int n_splits, int n_q_heads,
                                                          int n_kv_heads, int G, float c_log2, DecTable tab) {
-  __shared__ __attribute__((aligned(16))) char sV[NW][TK * VROW];   // V tile of each wavefront, row-major
   __shared__ float sO[NW][GMAX][D];                                 // wavefront results (merge)
   __shared__ float sML[NW][GMAX][2];
 
@@ -131,7 +119,6 @@ __global__ __launch_bounds__(NW * 64) void k_decode_mfma(__hip_bfloat16* k0_, __
   const __hip_bfloat16* vp = rd.v + (size_t)hk * head_stride_elems;
   const bool rot = fused && rotate;
   const size_t new_off = ((size_t)b * n_kv_heads + hk) * D;
-  char* myV = sV[wave];
 
   // Row m = l16 of score MFMA gi carries key 8 (m >> 2) + 4 gi + (m & 3) of the tile, so that the
   // accumulator of lane group lg holds keys 8 lg + 4 gi + r: eight consecutive keys per lane over the two
@@ -140,10 +127,12 @@ __global__ __launch_bounds__(NW * 64) void k_decode_mfma(__hip_bfloat16* k0_, __
 
   uint4 kreg[2][4];
   uint4 vreg[8];
-  // K: 8 loads per lane straight into the A-operand layout (dims 8 lg + 32 kk + j of key krow[gi]);
-  // V: 8 loads per lane, 16 lanes per row (key 4 st + lg, dims 8 l16 + e).  The token being decoded comes
-  // from the caller's buffers.
-  auto issue_loads = [&](int kt) {
+  // K: 8 loads per lane straight into the A-operand layout (dims 8 lg + 32 kk + j of key krow[gi]); the token
+  // being decoded comes from the caller's buffer.
+  // V^T: 8 loads per lane, again straight into the A-operand layout of the second product: head dim
+  // 16 blk + l16, keys kt + 8 lg .. + 7 = one row of a V^T block.  Whole blocks are read whatever the range's
+  // end: planes hold whole tiles, keys past the range get probability zero, and stale values are finite.
+  auto issue_k = [&](int kt) {
 #pragma unroll
     for (int gi = 0; gi < 2; ++gi) {
       const int key = kt + krow[gi];
@@ -154,18 +143,29 @@ __global__ __launch_bounds__(NW * 64) void k_decode_mfma(__hip_bfloat16* k0_, __
         if constexpr (STREAM) kreg[gi][kk] = key < k1 ? stream_load(src + 32 * kk) : make_uint4(0, 0, 0, 0);
         else kreg[gi][kk] = key < k1 ? *(const uint4*)(src + 32 * kk) : make_uint4(0, 0, 0, 0);
     }
+  };
+  auto issue_v = [&](int kt) {
+    const __hip_bfloat16* vb = vp + vt_elem(kt + 8 * lg, l16);   // block of the lane group's 8 keys, row l16
 #pragma unroll
-    for (int st = 0; st < 8; ++st) {
-      const int key = kt + 4 * st + lg;
-      const bool is_new = fused && key == len - 1;
-      const __hip_bfloat16* src = is_new ? v_new + new_off + 8 * l16 : vp + (size_t)key * D + 8 * l16;
-      if constexpr (STREAM) vreg[st] = key < k1 ? stream_load(src) : make_uint4(0, 0, 0, 0);
-      else vreg[st] = key < k1 ? *(const uint4*)src : make_uint4(0, 0, 0, 0);
+    for (int blk = 0; blk < 8; ++blk) {
+      if constexpr (STREAM) vreg[blk] = stream_load(vb + blk * 16 * kVB);
+      else vreg[blk] = *(const uint4*)(vb + blk * 16 * kVB);
     }
   };
 
   const int n_tiles = k1 > k0 ? (k1 - k0 + TK - 1) / TK : 0;
-  if (wave < n_tiles) issue_loads(k0 + wave * TK);   // memory first: everything below overlaps its latency
+  if (wave < n_tiles) {   // memory first: everything below overlaps its latency
+    issue_k(k0 + wave * TK);
+    issue_v(k0 + wave * TK);
+  }
+  // the wavefront whose tile holds the token being decoded fetches that token's V (one element per head dim for
+  // the lanes that will own it) along with its first loads
+  unsigned short vnew_bits[8] = {};
+  const bool owns_new = fused && len - 1 >= k0 && len - 1 < k1 && ((len - 1 - k0) / TK) % NW == wave;
+  if (owns_new) {
+#pragma unroll
+    for (int blk = 0; blk < 8; ++blk) vnew_bits[blk] = *(const unsigned short*)(v_new + new_off + 16 * blk + l16);
+  }
 
   // cos/sin of the 16 rotary pairs a lane touches (dims 8 lg + 32 kk + j, kk = 0, 1), from the table the
   // token's registration wrote
@@ -217,14 +217,22 @@ __global__ __launch_bounds__(NW * 64) void k_decode_mfma(__hip_bfloat16* k0_, __
 #pragma unroll
           for (int kk = 0; kk < 4; ++kk) *(uint4*)(dst + 32 * kk) = kreg[gi][kk];
         }
+      // V: the lanes of lane group rel / 8 hold the new token as element rel % 8 of each of their 8 head dims:
+      // patch the registers (the cache does not hold the token yet) and store the elements into the block
+      if ((rel >> 3) == lg) {
+        const int wsel = (rel & 7) >> 1, hi = rel & 1;
+        unsigned short* vdst = (unsigned short*)rd.v + (size_t)hk * head_stride_elems + vt_elem(len - 1, l16);
 #pragma unroll
-      for (int st = 0; st < 8; ++st)
-        if (rel == 4 * st + lg)
-          *(uint4*)(rd.v + (size_t)hk * head_stride_elems + (size_t)(len - 1) * D + 8 * l16) = vreg[st];
+        for (int blk = 0; blk < 8; ++blk) {
+          const uint32_t x = vnew_bits[blk];
+          uint32_t* w = (uint32_t*)&vreg[blk];
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            if (i == wsel) w[i] = hi ? (w[i] & 0x0000ffffu) | (x << 16) : (w[i] & 0xffff0000u) | x;
+          vdst[blk * 16 * kVB] = vnew_bits[blk];
+        }
+      }
     }
-    // ---- V tile to LDS, row-major
-#pragma unroll
-    for (int st = 0; st < 8; ++st) *(uint4*)(myV + (4 * st + lg) * VROW + l16 * 16) = vreg[st];
     // ---- scores S^T = K Q^T: register r of MFMA gi is key kt + 8 lg + 4 gi + r, head l16
     f32x4 sacc[2];
 #pragma unroll
@@ -234,9 +242,9 @@ __global__ __launch_bounds__(NW * 64) void k_decode_mfma(__hip_bfloat16* k0_, __
       for (int kk = 0; kk < 4; ++kk)
         sacc[gi] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(bf16x8*)&kreg[gi][kk], qf[kk], sacc[gi], 0, 0, 0);
     }
-    // the registers of this tile are consumed: fetch the wavefront's next tile behind the softmax and
-    // the second product
-    if (t + NW < n_tiles) issue_loads(kt + NW * TK);
+    // the K registers of this tile are consumed: fetch the wavefront's next K tile behind the softmax and the
+    // second product (the next V^T block follows once that product has read this one)
+    if (t + NW < n_tiles) issue_k(kt + NW * TK);
     float mx = -INFINITY;
 #pragma unroll
     for (int gi = 0; gi < 2; ++gi)
@@ -266,19 +274,11 @@ __global__ __launch_bounds__(NW * 64) void k_decode_mfma(__hip_bfloat16* k0_, __
       for (int blk = 0; blk < 8; ++blk) oacc[blk] *= alpha;
     }
     m_run = m_new;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    // ---- O^T += V^T P^T: A operand = V^T[dims 16 blk + l16][keys 8 lg + j] by two transpose reads
+    // ---- O^T += V^T P^T: A operand = V^T[dims 16 blk + l16][keys 8 lg + j], as loaded
 #pragma unroll
-    for (int blk = 0; blk < 8; ++blk) {
-      const int off = (8 * lg + (l16 >> 2)) * VROW + (16 * blk + 4 * (l16 & 3)) * 2;
-      const v4i16 a0 = lds_read_tr(myV, off), a1 = lds_read_tr(myV, off + 4 * VROW);
-      const short __attribute__((ext_vector_type(8))) a8 = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
-      oacc[blk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(const bf16x8*)&a8, pf, oacc[blk], 0, 0, 0);
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();   // the next tile overwrites the V tile
+    for (int blk = 0; blk < 8; ++blk)
+      oacc[blk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(const bf16x8*)&vreg[blk], pf, oacc[blk], 0, 0, 0);
+    if (t + NW < n_tiles) issue_v(kt + NW * TK);
   }
 
   // ---- wavefront result to LDS: head l16 < G, dims 16 blk + 4 lg + r; the sum of a head is spread over

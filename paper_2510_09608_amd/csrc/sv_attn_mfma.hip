@@ -93,7 +93,7 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
     const __hip_bfloat16* __restrict__ q, const __hip_bfloat16* __restrict__ kc, const __hip_bfloat16* __restrict__ vc,
     __hip_bfloat16* __restrict__ out, float* __restrict__ part_o, float* __restrict__ part_ml, int n_q, int n_kv,
     int causal, int n_splits, int keys_per_split, int n_q_heads, int G, size_t head_stride_elems, float c_log2,
-    const __hip_bfloat16* __restrict__ vt, size_t vt_head_stride_elems, int n_kv_heads, int pairs_pad) {
+    int n_kv_heads, int pairs_pad) {
   constexpr int ROWS_WG = NW * 32;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   char* const sKbase = smem;
@@ -126,17 +126,18 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
   }
 
   const __hip_bfloat16* kbase = kc + (size_t)hk * head_stride_elems;
-  const __hip_bfloat16* vtbase = vt + (size_t)hk * vt_head_stride_elems;
+  const __hip_bfloat16* vtbase = vc + (size_t)hk * head_stride_elems;   // V is stored as V^T in blocks of 8 keys
 
   // tile t -> LDS slot t & 3; each tile is 16 / NW direct-load instructions per wavefront, instruction wi
   // filling 1 KB of the slot.  The lane's source offset inside a tile does not depend on the tile:
   //   K:   LDS row m = 4 wi + lane / 16 holds key perm_key(m), its 16-byte chunks XOR-swizzled by m & 15;
   //   V^T: LDS row d = 8 wi + lane / 8 (128 bytes: 8 chunks of 8 keys); chunk c sits at position
   //        c ^ ((d >> 1) & 7), so that 16 lanes reading one chunk index of 16 consecutive rows touch 16
-  //        distinct 16-byte bank groups.
-  // Tiles past the range re-read the last one.  The last K tile may run up to 63 rows past the key range:
-  // those rows are other rows of the cache arena (K is never its last tensor), and their scores are
-  // replaced, not scaled, by the mask.  V^T blocks are zero-padded by the staging pass.
+  //        distinct 16-byte bank groups.  In the cache a 64-key tile is 8 consecutive blocks of
+  //        [128 head dims][8 keys] (2 KB each): chunk c of row d is row d of block c.
+  // Tiles past the range re-read the last one.  The last tile may run up to 63 keys past the key range: those
+  // K rows and V^T columns are other slots of the same head's plane (planes hold whole 64-key tiles); their
+  // scores are replaced, not scaled, by the mask, and stale V values are finite (the store starts out cleared).
   uint32_t k_lane_off[16 / NW], v_lane_off[16 / NW];
 #pragma unroll
   for (int i = 0; i < 16 / NW; ++i) {
@@ -144,10 +145,10 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
     const int m = 4 * wi + (lane >> 4), p = lane & 15;
     k_lane_off[i] = (uint32_t)(perm_key(m) * (D * 2) + ((p ^ (m & 15)) << 4));
     const int dd = 8 * wi + (lane >> 3), c = (lane & 7) ^ ((dd >> 1) & 7);
-    v_lane_off[i] = (uint32_t)(dd * (TK * 2) + (c << 4));
+    v_lane_off[i] = (uint32_t)(c * (kVBElems * 2) + dd * (kVB * 2));
   }
   const char* const k_tiles = (const char*)(kbase + (size_t)k_begin * D);
-  const char* const v_tiles = (const char*)(vtbase + (size_t)(k_begin / TK) * (TK * D));
+  const char* const v_tiles = (const char*)(vtbase + (size_t)(k_begin / TK) * (TK * D));   // k_begin is a multiple of 64
   auto dma_tile = [&](int which, int t) {
     const int te = min(t, n_tiles - 1);
     char* slot = (which ? sVbase : sKbase) + (t % (which ? VS : KS)) * PIPE_TILE;
@@ -437,7 +438,7 @@ hipError_t attn_chunk_mfma_init() {
 }
 
 hipError_t launch_attn_chunk_mfma(const sv_cache* c, int stream, int layer, const void* q, int n_q, void* o,
-                                  int causal, bool vt_ready, hipStream_t s) {
+                                  int causal, hipStream_t s) {
   constexpr int ROWS_WG = kNW * 32;
   const StreamState& st = c->st[stream];
   const int n_kv = (int)st.len, G = c->group, Hkv = c->cfg.n_kv_heads;
@@ -456,18 +457,12 @@ hipError_t launch_attn_chunk_mfma(const sv_cache* c, int stream, int layer, cons
   int keys_per_split = ((n_kv + n_splits - 1) / n_splits + TK - 1) / TK * TK;
   n_splits = (n_kv + keys_per_split - 1) / keys_per_split;
   const float c_log2 = 1.4426950408889634f / sqrtf((float)D);
-  __hip_bfloat16* vt = (__hip_bfloat16*)(c->vt + (size_t)stream * c->vt_stream_stride);
-  const size_t vt_head_stride = c->vt_stream_stride / 2 / Hkv;
-  if (!vt_ready) {
-    hipError_t ev = launch_vt_build(c, stream, layer, n_kv, s);
-    if (ev != hipSuccess) return ev;
-  }
   const int pairs_pad = (Hkv * n_splits + 7) / 8 * 8;
   hipLaunchKernelGGL((k_attn_chunk_pipe<kNW, kKS, kVS>), dim3(row_tiles * pairs_pad), dim3(kNW * 64), kLds, s,
                      (const __hip_bfloat16*)q, (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 0),
                      (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 1), (__hip_bfloat16*)o, c->part_o,
                      c->part_ml, n_q, n_kv, causal ? 1 : 0, n_splits, keys_per_split, c->cfg.n_q_heads, G,
-                     c->head_stride / 2, c_log2, (const __hip_bfloat16*)vt, vt_head_stride, Hkv, pairs_pad);
+                     c->head_stride / 2, c_log2, Hkv, pairs_pad);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || n_splits == 1) return e;
   return launch_attn_combine(c, n_q, n_splits, o, s);

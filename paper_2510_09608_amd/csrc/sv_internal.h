@@ -10,6 +10,19 @@
 
 namespace sv {
 
+// ---- blocked V^T layout (caches with v_blocked: bf16, head_dim 128, matrix-core kernels) -----------------
+// Both attention kernels contract V over keys, so their matrix-core operand is a piece of V^T: one head dim,
+// 8 consecutive keys per lane.  V is therefore STORED transposed in blocks of kVB = 8 keys: per kv head, block b
+// holds keys [8 b, 8 b + 8) as [head dim 0..127][key 0..7] (2 KB), element (key, d) at vt_elem(key, d).  A block
+// row is exactly the 16-byte piece a lane wants; 32- and 64-key tiles are 4 and 8 consecutive blocks (8 / 16 KB
+// contiguous); and a compaction that drops runs of 8 k tokens moves whole blocks.
+constexpr int kVB = 8;
+constexpr int kVD = 128;
+constexpr int kVBElems = kVB * kVD;
+__host__ __device__ inline size_t vt_elem(int64_t key, int d) {
+  return (size_t)(key >> 3) * kVBElems + (size_t)d * kVB + (size_t)(key & 7);
+}
+
 // ---- per-token metadata kept in device memory, structure of arrays -----------------
 // pos4  : (t, h, w, base).  base is the scalar position the token's block starts at
 //         (for text and for 1-D mode it equals t); the shift applied by an eviction
@@ -47,7 +60,8 @@ struct sv_cache {
   int esize;                 // bytes per element
   int group;                 // q heads per kv head
   size_t row_bytes;          // head_dim * esize
-  size_t head_stride;        // capacity * row_bytes           (one kv head of one tensor)
+  int64_t cap_pad;           // capacity rounded up to 64 slots
+  size_t head_stride;        // cap_pad * row_bytes            (one kv head of one tensor)
   size_t tensor_stride;      // n_kv_heads * head_stride       (K or V of one layer)
   size_t layer_stride;       // 2 * tensor_stride
   size_t half_stride;        // n_layers * layer_stride        (one ping-pong half)
@@ -65,10 +79,9 @@ struct sv_cache {
   float* part_ml;            // device split-KV partial (max, sum)
   int64_t part_rows;         // capacity of the partial buffers in (token, split) pairs
   int32_t* counters;         // device [part_rows][n_kv_heads]  arrival counters of the split-KV merge (zero between launches)
-  char* vt;                  // device [n_streams][n_kv_heads][ceil(capacity/64)][head_dim][64]  V^T staging of one layer
-  size_t vt_stream_stride;   // bytes per stream of vt
   bool host_logic_only = false;   // created with SV_HOST_LOGIC_ONLY: no device work, bookkeeping only
   bool use_mfma = false;          // bf16, head_dim 128, group <= 8 and no SV_FLAG_GENERIC_KERNELS: matrix-core kernels
+  bool v_blocked = false;         // V stored as V^T in blocks of 8 keys (exactly the caches with use_mfma), else row-major
   int opt[SV_OPT_COUNT_] = {};    // sv_cache_set_option values, 0 = automatic
   std::vector<sv::StreamState> st;
 
@@ -129,13 +142,12 @@ hipError_t launch_attn_decode_mfma_static(const sv_cache* c, int layer, const in
 
 // Once per process and device, before the first chunk-prefill launch: the kernel's LDS size has to be asked for.
 hipError_t attn_chunk_mfma_init();
-// V^T staging of one layer for the pipelined chunk-prefill kernel, alone or fused with the chunk's append and Q
-// rotation (bf16, head_dim 128); vt_ready tells the attention launch that the staging is already done.
-hipError_t launch_vt_build(const sv_cache* c, int stream, int layer, int n_kv, hipStream_t s);
-hipError_t launch_chunk_prologue(const sv_cache* c, int stream, int layer, int64_t slot0, int n, void* q, const void* k,
-                                 const void* v, hipStream_t s);
+// Caches with blocked V^T (c->v_blocked): store n new tokens of one layer (K rows rotated, V transposed into its
+// blocks) and, if q is not NULL, rotate their Q rows in place, all in one launch.
+hipError_t launch_store_tokens_vt(const sv_cache* c, int stream, int layer, int64_t slot0, int n, void* q, const void* k,
+                                  const void* v, hipStream_t s);
 hipError_t launch_attn_chunk_mfma(const sv_cache* c, int stream, int layer, const void* q, int n_q,
-                                  void* o, int causal, bool vt_ready, hipStream_t s);
+                                  void* o, int causal, hipStream_t s);
 
 hipError_t launch_attn_combine(const sv_cache* c, int n_rows, int n_splits, void* o, hipStream_t s);
 

@@ -148,120 +148,80 @@ __global__ __launch_bounds__(256) void k_rope_rows(T* __restrict__ x, const int4
 }
 
 // ---------------------------------------------------------------------------------
-// V^T staging for the pipelined chunk-prefill kernel (bf16, head_dim 128).  That kernel's second product
-// wants V^T fragments (one head dim, 8 consecutive keys per lane); read from a row-major V tile that costs two
-// half-rate LDS transpose reads per fragment in EVERY wavefront of every workgroup that shares the tile.  This
-// pass transposes each 64-key block of the layer's V once, into vt[kv head][block][head dim][64 keys]; the
-// attention kernel then brings V^T tiles to LDS with direct loads and reads fragments with plain 16-byte
-// reads.  Rows [new0, new0 + n_new) may come from the caller's buffer v_new [n_new][n_kv_heads][128] instead of
-// the cache (they are being appended by other workgroups of the same launch); keys past n_kv are written as
-// zeros (they are masked, but must be finite).  One 256-thread workgroup per (block, kv head).
-//
-// LDS transpose read (ds_read_b64_tr_b16): within each group of 16 lanes, lane j hands in the address of 4
-// consecutive 16-bit elements and receives element (j & 3) of the chunks of lanes (j >> 2) + 4 e, e = 0..3;
-// pointing lane j at row r0 + (j >> 2), columns c0 + 4 (j & 3) .. + 3 of a row-major tile returns column
-// c0 + j of rows r0 .. r0 + 3.
+// Storing V of new tokens into the blocked V^T layout (see sv_internal.h): rows [slot0, slot0 + n) of one kv head
+// that fall into the group of 32 slots [32 grp, 32 grp + 32) are staged row-major in LDS, then every thread
+// collects two pieces of 8 keys x one head dim (a block row) and writes each as 16 bytes, or element by element
+// where a piece is only partly new (its other keys belong to older tokens).  Consecutive lanes write
+// consecutive rows of a block: 1 KB contiguous per store instruction.
+// Slots past the end of a stream inside its last block hold zeros or old values, never NaN patterns (the store is
+// cleared at create time): the attention kernels multiply them by probabilities of exactly zero.
 // ---------------------------------------------------------------------------------
-constexpr int VT_KEYS = 64;              // keys per block
-constexpr int VT_D = 128;
-constexpr int VT_ROW = VT_D * 2 + 64;    // LDS row stride in bytes: transpose reads fall in distinct banks
-constexpr int VT_OROW = VT_KEYS * 2 + 16;   // row stride of the transposed block on its way out
-static_assert(VT_D * VT_OROW <= VT_KEYS * VT_ROW, "the transposed block reuses the staging buffer");
-typedef short v4i16 __attribute__((ext_vector_type(4)));
-typedef short v8i16 __attribute__((ext_vector_type(8)));
+constexpr int VG = 32;                     // slots per workgroup of the V^T store (4 blocks)
+constexpr int VT_D = kVD;
+constexpr int VT_SROW = VT_D * 2 + 16;     // bytes per staged row in LDS
 
-__device__ __forceinline__ void vt_block(char* sT, int blk, int hk, const __hip_bfloat16* __restrict__ v_cache,
-                                         const __hip_bfloat16* __restrict__ v_new, int64_t new0, int n_new, int n_kv,
-                                         int n_kv_heads, size_t head_stride_elems, __hip_bfloat16* __restrict__ vt,
-                                         size_t vt_head_stride_elems) {
+__device__ __forceinline__ void append_v_t_group(char* sT, int grp, int hk, const __hip_bfloat16* __restrict__ v_in,
+                                                 __hip_bfloat16* __restrict__ v_cache, int64_t slot0, int n,
+                                                 int n_kv_heads, size_t head_stride_elems) {
   const int tid = threadIdx.x;
-  const __hip_bfloat16* src = v_cache + (size_t)hk * head_stride_elems;
+  const int64_t key0 = (int64_t)grp * VG;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < 2; ++i) {
     const int cid = tid + 256 * i, key = cid >> 4, c16 = cid & 15;
-    const int64_t kk = (int64_t)blk * VT_KEYS + key;
+    const int64_t kk = key0 + key;
     uint4 v = make_uint4(0, 0, 0, 0);
-    if (kk < n_kv) {
-      const bool fresh = v_new != nullptr && kk >= new0 && kk < new0 + n_new;
-      const __hip_bfloat16* row = fresh ? v_new + ((size_t)(kk - new0) * n_kv_heads + hk) * VT_D : src + (size_t)kk * VT_D;
-      v = *(const uint4*)(row + c16 * 8);
-    }
-    *(uint4*)(sT + key * VT_ROW + c16 * 16) = v;
+    if (kk >= slot0 && kk < slot0 + n) v = *(const uint4*)(v_in + ((size_t)(kk - slot0) * n_kv_heads + hk) * VT_D + c16 * 8);
+    *(uint4*)(sT + key * VT_SROW + c16 * 16) = v;
   }
   __syncthreads();
-  const int wave = tid >> 6, lane = tid & 63, j16 = lane & 15, g = lane >> 4;
-  __hip_bfloat16* dst = vt + (size_t)hk * vt_head_stride_elems + (size_t)blk * VT_KEYS * VT_D;
-  // transposing reads: 8 keys (r0 .. r0 + 7) of head dim c0 + j16 per lane
-  v8i16 a8[2][2];
+  unsigned short* head_base = (unsigned short*)v_cache + (size_t)hk * head_stride_elems;
 #pragma unroll
-  for (int ko = 0; ko < 2; ++ko)
+  for (int i = 0; i < 2; ++i) {
+    const int piece = tid + 256 * i, p = piece >> 7, d = piece & 127;   // block p of the group, head dim d
+    unsigned short e[8];
 #pragma unroll
-    for (int ds = 0; ds < 2; ++ds) {
-      const int r0 = 16 * wave + 8 * ko, c0 = 64 * ds + 16 * g;
-      const int off = (r0 + (j16 >> 2)) * VT_ROW + (c0 + 4 * (j16 & 3)) * 2;
-      auto rd = [&](int o) {
-        return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (v4i16 __attribute__((address_space(3)))*)((__attribute__((address_space(3))) char*)sT + o));
-      };
-      const v4i16 a0 = rd(off), a1 = rd(off + 4 * VT_ROW);
-      a8[ko][ds] = v8i16{a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
+    for (int j = 0; j < 8; ++j) e[j] = *(const unsigned short*)(sT + (8 * p + j) * VT_SROW + d * 2);
+    const int64_t k8 = key0 + 8 * p;
+    unsigned short* dst = head_base + vt_elem(k8, d);
+    if (k8 >= slot0 && k8 + 8 <= slot0 + n) {
+      uint4 w;
+      w.x = e[0] | ((uint32_t)e[1] << 16), w.y = e[2] | ((uint32_t)e[3] << 16);
+      w.z = e[4] | ((uint32_t)e[5] << 16), w.w = e[6] | ((uint32_t)e[7] << 16);
+      *(uint4*)dst = w;
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (k8 + j >= slot0 && k8 + j < slot0 + n) dst[j] = e[j];
     }
-  // A lane's 16 bytes belong to a row of V^T of their own (64 different 128-byte rows per store instruction), so
-  // the block goes back through LDS in V^T layout (rows of 64 keys, 144-byte stride: conflict-free for the 16-byte
-  // writes) and leaves as full 128-byte rows, 8 lanes per row.
-  __syncthreads();
-#pragma unroll
-  for (int ko = 0; ko < 2; ++ko)
-#pragma unroll
-    for (int ds = 0; ds < 2; ++ds) {
-      const int r0 = 16 * wave + 8 * ko, c0 = 64 * ds + 16 * g;
-      *(v8i16*)(sT + (c0 + j16) * VT_OROW + r0 * 2) = a8[ko][ds];
-    }
-  __syncthreads();
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int row = (tid >> 3) + 32 * i, ch = tid & 7;
-    *(uint4*)(dst + (size_t)row * VT_KEYS + ch * 8) = *(const uint4*)(sT + row * VT_OROW + ch * 16);
   }
 }
 
-// grid: (blocks of 64 keys, kv heads)
-__global__ __launch_bounds__(256) void k_vt_build(const __hip_bfloat16* __restrict__ v_cache,
-                                                  __hip_bfloat16* __restrict__ vt, int n_kv, int n_kv_heads,
-                                                  size_t head_stride_elems, size_t vt_head_stride_elems) {
-  __shared__ __attribute__((aligned(16))) char sT[VT_KEYS * VT_ROW];
-  vt_block(sT, blockIdx.x, blockIdx.y, v_cache, nullptr, 0, 0, n_kv, n_kv_heads, head_stride_elems, vt,
-           vt_head_stride_elems);
-}
-
 // ---------------------------------------------------------------------------------
-// Everything a layer needs before the chunk-prefill attention of a new chunk, in ONE launch (bf16, head_dim
-// 128): store the chunk's K (rotated) and V, rotate its Q in place, and stage V^T of the whole layer (old rows
-// from the cache, the chunk's rows from the caller's buffer).  The three jobs are independent; workgroup ids
-// [0, nb_kv) do the first, [nb_kv, nb_kv + nb_q) the second, the rest the third.
+// Everything that stores a run of new tokens of one layer in a blocked-V^T cache, in ONE launch: K rows (rotated
+// at their positions), V into its V^T blocks, and, when q is given, the rotation of the tokens' Q rows in place (the
+// chunk prefill's prologue).  The three jobs are independent; workgroup ids [0, nb_k) do the first,
+// [nb_k, nb_k + nb_q) the second, the rest the third.
 // ---------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_chunk_prologue(
+__global__ __launch_bounds__(256) void k_store_tokens_vt(
     __hip_bfloat16* __restrict__ q, const __hip_bfloat16* __restrict__ k_in, const __hip_bfloat16* __restrict__ v_in,
     __hip_bfloat16* __restrict__ k_cache, __hip_bfloat16* __restrict__ v_cache, const int4* __restrict__ pos4,
     const double* __restrict__ inv_freq, int64_t slot0, int n, int n_q_heads, int n_kv_heads, size_t head_stride_elems,
-    int rope_mode, int s0, int s01, int gx_kv, int nb_kv, int nb_q, __hip_bfloat16* __restrict__ vt,
-    size_t vt_head_stride_elems, int n_blk) {
-  __shared__ __attribute__((aligned(16))) char sT[VT_KEYS * VT_ROW];
+    int rope_mode, int s0, int s01, int gx_k, int nb_k, int nb_q, int blk0, int n_blk) {
+  __shared__ __attribute__((aligned(16))) char sT[VG * VT_SROW];
   using T = __hip_bfloat16;
   int b = blockIdx.x;
-  if (b < nb_kv) {
-    append_rows<T, VT_D>(b % gx_kv, (b / gx_kv) % n_kv_heads, b / (gx_kv * n_kv_heads), k_in, v_in, k_cache, v_cache,
-                         pos4, inv_freq, slot0, n, n_kv_heads, head_stride_elems, rope_mode, s0, s01);
+  if (b < nb_k) {
+    append_rows<T, VT_D>(b % gx_k, b / gx_k, 0, k_in, v_in, k_cache, v_cache, pos4, inv_freq, slot0, n, n_kv_heads,
+                         head_stride_elems, rope_mode, s0, s01);
     return;
   }
-  b -= nb_kv;
+  b -= nb_k;
   if (b < nb_q) {
-    if (rope_mode != SV_ROPE_NONE) rope_rows<T, VT_D>(b, q, pos4, inv_freq, slot0, n, n_q_heads, rope_mode, s0, s01);
+    rope_rows<T, VT_D>(b, q, pos4, inv_freq, slot0, n, n_q_heads, rope_mode, s0, s01);
     return;
   }
   b -= nb_q;
-  vt_block(sT, b % n_blk, b / n_blk, v_cache, v_in, slot0, n, (int)(slot0 + n), n_kv_heads, head_stride_elems, vt,
-           vt_head_stride_elems);
+  append_v_t_group(sT, blk0 + b % n_blk, b / n_blk, v_in, v_cache, slot0, n, n_kv_heads, head_stride_elems);
 }
 
 // ---------------------------------------------------------------------------------
@@ -295,19 +255,61 @@ template <typename T, int D>
 __global__ __launch_bounds__(256) void k_compact(const T* __restrict__ old_base, T* __restrict__ new_base,
                                                  const int32_t* __restrict__ src, const int32_t* __restrict__ delta,
                                                  const float2* __restrict__ dtab, int n_new,
-                                                 size_t head_stride_elems, size_t tensor_stride_elems, int rotate) {
+                                                 size_t head_stride_elems, size_t tensor_stride_elems, int rotate,
+                                                 int v_blocked) {
   using G = RowGeom<T, D>;
+  const int h = blockIdx.y;
+  const int which = blockIdx.z & 1;   // z = 2 * layer + which, tensors are laid out in that order
+  const size_t plane = (size_t)blockIdx.z * tensor_stride_elems + (size_t)h * head_stride_elems;
+  typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4;
+  if constexpr (sizeof(T) == 2 && D == kVD) {
+    if (which == 1 && v_blocked) {
+      // V in the blocked V^T layout.  The workgroup moves the same 32 tokens as a workgroup of K rows: 4 new
+      // blocks of 8 keys, 512 block rows of 16 bytes, two per thread (block p, head dim d), consecutive lanes
+      // on consecutive rows.  A new block whose 8 tokens were consecutive in the old cache and started at a
+      // multiple of 8 is a copy of an old block, 2 KB contiguous on both sides (the rule when runs of 8 k tokens
+      // leave, as in the streaming workloads); otherwise its elements are gathered one by one.
+      static_assert(G::ROWS == 32, "K rows and V^T blocks share the grid: 32 tokens per workgroup");
+      const unsigned short* so = (const unsigned short*)old_base + plane;
+      unsigned short* sn = (unsigned short*)new_base + plane;
+      u32x4 w[2];
+      bool live[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int piece = threadIdx.x + 256 * i, p = piece >> 7, d = piece & 127;
+        const int jc = (int)blockIdx.x * 32 + 8 * p;
+        live[i] = jc < n_new;   // a block wholly past the end: nothing to move
+        if (!live[i]) continue;
+        const int sa = src[jc];
+        if (jc + 7 < n_new && src[jc + 7] == sa + 7 && (sa & 7) == 0) {
+          w[i] = __builtin_nontemporal_load((const u32x4*)(so + vt_elem(sa, d)));
+        } else {
+          unsigned short e[8];
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            e[j] = 0;
+            if (jc + j < n_new) e[j] = so[vt_elem(src[jc + j], d)];
+          }
+          w[i][0] = e[0] | ((uint32_t)e[1] << 16), w[i][1] = e[2] | ((uint32_t)e[3] << 16);
+          w[i][2] = e[4] | ((uint32_t)e[5] << 16), w[i][3] = e[6] | ((uint32_t)e[7] << 16);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int piece = threadIdx.x + 256 * i, p = piece >> 7, d = piece & 127;
+        if (live[i]) *(u32x4*)(sn + vt_elem((int64_t)blockIdx.x * 32 + 8 * p, d)) = w[i];
+      }
+      return;
+    }
+  }
   const int j = blockIdx.x * G::ROWS + threadIdx.x / G::TPR;
   if (j >= n_new) return;
-  const int t = threadIdx.x % G::TPR, h = blockIdx.y;
-  const int which = blockIdx.z & 1;  // z = 2 * layer + which, tensors are laid out in that order
-  const size_t plane = (size_t)blockIdx.z * tensor_stride_elems + (size_t)h * head_stride_elems;
+  const int t = threadIdx.x % G::TPR;
   const T* s = old_base + plane + (size_t)src[j] * D;
   T* d = new_base + plane + (size_t)j * D;
   Vec16<T> lo, hi;
   // the old buffer is read once and dead afterwards: non-temporal loads (16 bytes as a native vector); measured
   // 92.8 -> 90 us for 28 layers at 5.1k retained tokens, non-temporal stores on top of that: no change
-  typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4;
   static_assert(sizeof(lo.raw) == sizeof(u32x4), "16-byte vectors");
   {
     const u32x4 a = __builtin_nontemporal_load((const u32x4*)(s + t * G::EPV));
@@ -381,7 +383,7 @@ hipError_t compact_t(const sv_cache* c, int stream, int64_t n_new, hipStream_t s
   dim3 grid((unsigned)((n_new + G::ROWS - 1) / G::ROWS), c->cfg.n_kv_heads, 2 * c->cfg.n_layers);
   hipLaunchKernelGGL((k_compact<T, D>), grid, dim3(256), 0, s, (const T*)c->kv_ptr(stream, cur, 0, 0),
                      (T*)c->kv_ptr(stream, cur ^ 1, 0, 0), c->src + off, c->delta + off, dtab, (int)n_new,
-                     c->head_stride / sizeof(T), c->tensor_stride / sizeof(T), rotate);
+                     c->head_stride / sizeof(T), c->tensor_stride / sizeof(T), rotate, c->v_blocked ? 1 : 0);
   return hipGetLastError();
 }
 
@@ -396,11 +398,6 @@ hipError_t compact_t(const sv_cache* c, int stream, int64_t n_new, hipStream_t s
                                  : fn<__hip_bfloat16, 128>(__VA_ARGS__);                       \
   } while (0)
 
-hipError_t launch_append_kv(const sv_cache* c, int stream, int layer, int64_t slot0, int n, const void* k,
-                            const void* v, hipStream_t s) {
-  SV_DISPATCH(append_kv_t, c, stream, layer, slot0, n, k, v, s);
-}
-
 hipError_t launch_rope_apply(const sv_cache* c, int stream, int64_t slot0, int n, void* q, void* k,
                              hipStream_t s) {
   SV_DISPATCH(rope_apply_t, c, stream, slot0, n, q, k, s);
@@ -410,29 +407,25 @@ hipError_t launch_compact(const sv_cache* c, int stream, int64_t n_new, hipStrea
   SV_DISPATCH(compact_t, c, stream, n_new, s);
 }
 
-hipError_t launch_vt_build(const sv_cache* c, int stream, int layer, int n_kv, hipStream_t s) {
-  const int Hkv = c->cfg.n_kv_heads;
-  __hip_bfloat16* vt = (__hip_bfloat16*)(c->vt + (size_t)stream * c->vt_stream_stride);
-  hipLaunchKernelGGL(k_vt_build, dim3((n_kv + VT_KEYS - 1) / VT_KEYS, Hkv), dim3(256), 0, s,
-                     (const __hip_bfloat16*)c->kv_ptr(stream, c->st[stream].cur, layer, 1), vt, n_kv, Hkv,
-                     c->head_stride / 2, c->vt_stream_stride / 2 / Hkv);
-  return hipGetLastError();
+hipError_t launch_append_kv(const sv_cache* c, int stream, int layer, int64_t slot0, int n, const void* k,
+                            const void* v, hipStream_t s) {
+  if (c->v_blocked) return launch_store_tokens_vt(c, stream, layer, slot0, n, nullptr, k, v, s);
+  SV_DISPATCH(append_kv_t, c, stream, layer, slot0, n, k, v, s);
 }
 
-hipError_t launch_chunk_prologue(const sv_cache* c, int stream, int layer, int64_t slot0, int n, void* q, const void* k,
-                                 const void* v, hipStream_t s) {
+hipError_t launch_store_tokens_vt(const sv_cache* c, int stream, int layer, int64_t slot0, int n, void* q, const void* k,
+                                  const void* v, hipStream_t s) {
   using G = RowGeom<__hip_bfloat16, VT_D>;
   const int Hq = c->cfg.n_q_heads, Hkv = c->cfg.n_kv_heads, cur = c->st[stream].cur;
   const size_t off = (size_t)stream * (size_t)c->cfg.capacity_tokens;
-  const int gx_kv = (n + G::ROWS - 1) / G::ROWS, nb_kv = gx_kv * Hkv * 2;
-  const int nb_q = (int)(((int64_t)n * Hq + G::ROWS - 1) / G::ROWS);
-  const int n_blk = (int)((slot0 + n + VT_KEYS - 1) / VT_KEYS);
-  hipLaunchKernelGGL(k_chunk_prologue, dim3(nb_kv + nb_q + n_blk * Hkv), dim3(256), 0, s, (__hip_bfloat16*)q,
+  const int gx_k = (n + G::ROWS - 1) / G::ROWS, nb_k = gx_k * Hkv;
+  const int nb_q = q && c->cfg.rope_mode != SV_ROPE_NONE ? (int)(((int64_t)n * Hq + G::ROWS - 1) / G::ROWS) : 0;
+  const int blk0 = (int)(slot0 / VG), n_blk = (int)((slot0 + n - 1) / VG) - blk0 + 1;   // groups of 32 slots
+  hipLaunchKernelGGL(k_store_tokens_vt, dim3(nb_k + nb_q + n_blk * Hkv), dim3(256), 0, s, (__hip_bfloat16*)q,
                      (const __hip_bfloat16*)k, (const __hip_bfloat16*)v, (__hip_bfloat16*)c->kv_ptr(stream, cur, layer, 0),
                      (__hip_bfloat16*)c->kv_ptr(stream, cur, layer, 1), c->meta[cur].pos4 + off, c->inv_freq, slot0, n, Hq,
                      Hkv, c->head_stride / 2, c->cfg.rope_mode, c->cfg.mrope_sections[0],
-                     c->cfg.mrope_sections[0] + c->cfg.mrope_sections[1], gx_kv, nb_kv, nb_q,
-                     (__hip_bfloat16*)(c->vt + (size_t)stream * c->vt_stream_stride), c->vt_stream_stride / 2 / Hkv, n_blk);
+                     c->cfg.mrope_sections[0] + c->cfg.mrope_sections[1], gx_k, nb_k, nb_q, blk0, n_blk);
   return hipGetLastError();
 }
 
