@@ -76,7 +76,7 @@ Layout make_layout(const sv_config& c) {
   L.last_cs = take(S * (size_t)(c.head_dim / 2) * 8);
   L.part_rows = std::max<int64_t>(64 * (int64_t)c.n_streams, std::max<int64_t>(4096, 4 * (int64_t)c.max_q_tokens));
   L.part_o = take((size_t)L.part_rows * c.n_q_heads * c.head_dim * 4);
-  L.part_ml = take((size_t)L.part_rows * c.n_q_heads * 2 * 4);
+  L.part_ml = take((size_t)L.part_rows * c.n_q_heads * 4 * 4);   // up to 4 floats per (row, range, head)
   L.counters = take((size_t)L.part_rows * c.n_kv_heads * 4);
   L.total = off;
   return L;

@@ -51,6 +51,10 @@ struct DecRow {
   __hip_bfloat16* v;
   const float2* cs;          // cos/sin of the query token's rotary angles, [64]
   int32_t len;               // visible keys: slots [0, len), the query token is slot len - 1
+  int32_t kps;               // keys per key range of this row (a multiple of 128); ranges = ceil(len / kps)
+};
+struct RangeCounts {
+  uint8_t n[kMaxRowsD];      // key ranges of each row of a launch
 };
 struct DecTable {
   DecRow r[kMaxRowsD];
@@ -114,7 +118,9 @@ __global__ __launch_bounds__(NW * 64, 2) void k_decode_mfma(__hip_bfloat16* k0_,
   if constexpr (ONE) rd = DecRow{k0_, v0_, cs0_, len0_};
   else rd = tab.r[b];
   const int len = rd.len;
-  const int k0 = sp * keys_per_split, k1 = min(len, k0 + keys_per_split);
+  const int kps = ONE ? keys_per_split : rd.kps;   // rows of a batch are cut into ranges of their own size
+  const int k0 = sp * kps, k1 = min(len, k0 + kps);
+  if (k0 >= len) return;   // a shorter row of the batch has fewer ranges than the grid is wide
   const __hip_bfloat16* kp = rd.k + (size_t)hk * head_stride_elems;
   const __hip_bfloat16* vp = rd.v + (size_t)hk * head_stride_elems;
   const bool rot = fused && rotate;
@@ -332,23 +338,25 @@ __global__ __launch_bounds__(NW * 64, 2) void k_decode_mfma(__hip_bfloat16* k0_,
 // ---------------------------------------------------------------------------------
 __global__ __launch_bounds__(128) void k_decode_merge(const float* __restrict__ part_o,
                                                       const float* __restrict__ part_ml,
-                                                      __hip_bfloat16* __restrict__ out, int n_splits, int n_q_heads) {
+                                                      __hip_bfloat16* __restrict__ out, int n_splits, int n_q_heads,
+                                                      RangeCounts cnt) {
   __shared__ float4 s_acc[4][32];
   __shared__ float2 s_ml[4];
   const int h = blockIdx.x, b = blockIdx.y, g = threadIdx.x >> 5, d4 = threadIdx.x & 31;
   const size_t rbase = (size_t)b * n_splits * n_q_heads + h;   // split s adds s * n_q_heads
+  const int ns = cnt.n[b];                                      // ranges this row really has (<= n_splits)
   const float4* po = (const float4*)(part_o + rbase * D) + d4;
   const float2* pml = (const float2*)part_ml + rbase;
   const size_t ostride = (size_t)n_q_heads * D / 4;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   float lsum = 0.f, m_ref = -INFINITY;
-  for (int s0 = g; s0 < n_splits; s0 += 64) {
+  for (int s0 = g; s0 < ns; s0 += 64) {
     float4 v[16];
     float2 ml[16];
 #pragma unroll
     for (int j = 0; j < 16; ++j) {
       const int sidx = s0 + 4 * j;
-      const bool ok = sidx < n_splits;
+      const bool ok = sidx < ns;
       ml[j] = ok ? pml[(size_t)sidx * n_q_heads] : make_float2(-INFINITY, 0.f);
       v[j] = ok ? po[(size_t)sidx * ostride] : make_float4(0.f, 0.f, 0.f, 0.f);
     }
@@ -397,35 +405,48 @@ static hipError_t decode_launch(const sv_cache* c, const DecTable& tab, int fuse
                          const void* q, const void* k_new, const void* v_new, void* o, size_t r0, float* part_o,
                          float* part_ml, int64_t part_rows, hipStream_t s) {
   const int Hq = c->cfg.n_q_heads, Hkv = c->cfg.n_kv_heads;
-  // Key tiles per wavefront.  A single stream is latency bound: one tile per wavefront spreads its few
-  // hundred tiles over the most CUs and costs one memory round trip.  A large batch is bandwidth bound:
-  // longer key ranges keep the partial results and their merge small.  Two workgroups fit a CU (LDS), so the
-  // smallest count for which all non-empty workgroups are resident at once (<= 512) is taken: one workgroup
-  // more than that and a second, nearly empty round follows the first (measured on 16 ragged rows: 516
-  // workgroups 3.6 TB/s, 440 workgroups 4.2 TB/s).
-  int tiles_per_wave = std::min(c->opt[SV_OPT_DECODE_TILES_PER_WAVE], 16);
-  if (tiles_per_wave <= 0) {
-    for (tiles_per_wave = 1; tiles_per_wave < 16; ++tiles_per_wave) {
-      const int keys = TK * NW * tiles_per_wave;
-      int64_t wgs = 0;
-      for (int b = 0; b < nr; ++b) wgs += (tab.r[b].len + keys - 1) / keys;
-      if (wgs * Hkv <= 512) break;
+  // Key ranges.  A single stream is latency bound: ranges of 128 keys (one 32-key tile per wavefront) spread its
+  // few hundred tiles over the most CUs and cost one memory round trip.  A batch is bandwidth bound: longer ranges
+  // keep the partial results and their merge small, and all workgroups should be resident at once (two fit a CU:
+  // 512), since one workgroup more than that and a second, nearly empty round follows the first (measured on 16
+  // ragged rows: 516 workgroups 3.6 TB/s, 440 workgroups 4.2 TB/s).  So: the smallest target T, a multiple of 128
+  // keys (whole tiles for each of the 4 wavefronts: ranges of 800 keys, 7 tiles for one wavefront and 6 for the
+  // others, measured 6 % slower than ranges of 896), for which sum_b ceil(len_b / T) * kv heads <= 512; then every
+  // row is cut into ceil(len_b / T) ranges of EQUAL size (rounded up to 128 keys), so that a row does not end in a
+  // range much shorter than the others.
+  constexpr int kSlots = 512;
+  const int forced = std::min(c->opt[SV_OPT_DECODE_TILES_PER_WAVE], 64);
+  const int64_t max_pairs = std::max<int64_t>(nr, part_rows);
+  int T = forced > 0 ? TK * NW * forced : TK * NW;
+  for (;; T += TK * NW) {
+    int64_t pairs = 0;
+    int widest = 0;
+    for (int b = 0; b < nr; ++b) {
+      const int nb = (tab.r[b].len + T - 1) / T;
+      pairs += nb;
+      widest = std::max(widest, nb);
     }
+    const bool fits = widest <= kMaxSplitsD && widest * (int64_t)nr <= max_pairs;   // scratch: rows x widest ranges
+    if (fits && (forced > 0 || pairs * Hkv <= kSlots || T >= max_len)) break;
   }
-  int keys_per_split = TK * NW * tiles_per_wave;
-  int n_splits = (max_len + keys_per_split - 1) / keys_per_split;
-  const int cap = (int)std::min<int64_t>(kMaxSplitsD, std::max<int64_t>(1, part_rows / nr));
-  if (n_splits > cap) {
-    keys_per_split = ((max_len + cap - 1) / cap + TK - 1) / TK * TK;
-    n_splits = (max_len + keys_per_split - 1) / keys_per_split;
+  DecTable tabk = tab;
+  RangeCounts cnt = {};
+  int n_splits = 1;
+  for (int b = 0; b < nr; ++b) {
+    const int len = tab.r[b].len, nb = std::max(1, (len + T - 1) / T);
+    const int kps = ((len + nb - 1) / nb + TK * NW - 1) / (TK * NW) * (TK * NW);
+    tabk.r[b].kps = kps;
+    cnt.n[b] = (uint8_t)((len + kps - 1) / kps);
+    n_splits = std::max(n_splits, (int)cnt.n[b]);
   }
+  const int keys_per_split = tabk.r[0].kps;
   const float c_log2 = 1.4426950408889634f / sqrtf((float)D);
   const __hip_bfloat16* qp = (const __hip_bfloat16*)q + r0 * Hq * D;
   const __hip_bfloat16* knp = k_new ? (const __hip_bfloat16*)k_new + r0 * Hkv * D : nullptr;
   const __hip_bfloat16* vnp = v_new ? (const __hip_bfloat16*)v_new + r0 * Hkv * D : nullptr;
   __hip_bfloat16* op = (__hip_bfloat16*)o + r0 * Hq * D;
   const int rotate = c->cfg.rope_mode != SV_ROPE_NONE ? 1 : 0;
-  const DecRow& r = tab.r[0];
+  const DecRow& r = tabk.r[0];
   // More than 96 MB of K and V in this launch, one long stream or many: non-temporal loads (rows that are the layers
   // of ONE stream keep the plain loads: their 308 MB are read again at the next token and the Infinity Cache still
   // holds most of them).
@@ -433,19 +454,19 @@ static hipError_t decode_launch(const sv_cache* c, const DecTable& tab, int fuse
   if (nr == 1 && !stream_loads)
     hipLaunchKernelGGL((k_decode_mfma<NW, true, false>), dim3(n_splits, Hkv, 1), dim3(NW * 64), 0, s, r.k, r.v, r.cs, r.len,
                        keys_per_split, qp, knp, vnp, c->head_stride / 2, fused, rotate, op, part_o, part_ml,
-                       n_splits, Hq, Hkv, c->group, c_log2, tab);
+                       n_splits, Hq, Hkv, c->group, c_log2, tabk);
   else if (stream_loads)
     hipLaunchKernelGGL((k_decode_mfma<NW, false, true>), dim3(n_splits, Hkv, nr), dim3(NW * 64), 0, s, r.k, r.v, r.cs, r.len,
                        keys_per_split, qp, knp, vnp, c->head_stride / 2, fused, rotate, op, part_o, part_ml,
-                       n_splits, Hq, Hkv, c->group, c_log2, tab);
+                       n_splits, Hq, Hkv, c->group, c_log2, tabk);
   else
     hipLaunchKernelGGL((k_decode_mfma<NW, false, false>), dim3(n_splits, Hkv, nr), dim3(NW * 64), 0, s, r.k, r.v, r.cs, r.len,
                        keys_per_split, qp, knp, vnp, c->head_stride / 2, fused, rotate, op, part_o, part_ml,
-                       n_splits, Hq, Hkv, c->group, c_log2, tab);
+                       n_splits, Hq, Hkv, c->group, c_log2, tabk);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || n_splits == 1) return e;
   hipLaunchKernelGGL(k_decode_merge, dim3(Hq, nr), dim3(128), 0, s, part_o, part_ml,
-                     (__hip_bfloat16*)o + r0 * Hq * D, n_splits, Hq);
+                     (__hip_bfloat16*)o + r0 * Hq * D, n_splits, Hq, cnt);
   return hipGetLastError();
 }
 

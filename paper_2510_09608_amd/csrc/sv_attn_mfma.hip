@@ -66,7 +66,7 @@ __device__ __forceinline__ int k_lds_off(int row, int chunk) {  // row: permuted
 //     softmax running in the same iteration; LDS operands are fetched one batch ahead of the MFMAs that use them.
 // ---------------------------------------------------------------------------------
 constexpr int PIPE_TILE = TK * D * 2;   // 16 KB per tile, unpadded
-constexpr int PIPE_OROW = D + 4;         // floats per row of a wavefront's partial result on its way out through LDS
+constexpr int PIPE_HROW = D + 8;         // halves per row of a wavefront's partial result on its way out through LDS
 
 // 16 bytes per lane from global memory straight into LDS: lane L's bytes land at lds_dst + 16 L (lds_dst is
 // uniform over the wavefront and travels in M0).  Written as assembly on purpose: the compiler then does not
@@ -115,12 +115,11 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
   int k_end = min(n_kv, k_begin + keys_per_split);
   if (causal) k_end = min(k_end, slot0 + row_last / G + 1);
   const int n_tiles = k_end > k_begin ? (k_end - k_begin + TK - 1) / TK : 0;
-  if (n_tiles == 0) {   // nothing visible in this key range: an empty partial
+  if (n_tiles == 0) {   // nothing visible in this key range: an empty partial (weight zero, its row is never read)
     const int row = rt * ROWS_WG + wave * 32 + l32;
-    if (row < n_rows && n_splits > 1) {
+    if (row < n_rows && n_splits > 1 && hh == 0) {
       const size_t p = ((size_t)(row / G) * n_splits + sp) * n_q_heads + hk * G + row % G;
-      for (int d = hh * 64; d < hh * 64 + 64; d += 4) *(float4*)(part_o + p * D + d) = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (hh == 0) part_ml[p * 2] = -INFINITY, part_ml[p * 2 + 1] = 0.f;
+      *(float4*)(part_ml + p * 4) = make_float4(-INFINITY, 0.f, 1.f, 0.f);
     }
     return;
   }
@@ -282,7 +281,7 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
             if (key > limit) sacc[kb][r] = -INFINITY;
           }
       }
-      // The probabilities are taken against the reference maximum as it stands (see softmax above: it moves
+      // The probabilities are taken against the reference maximum as it stands (it moves
       // only in steps of more than 8 binary orders), so nothing waits for this tile's row maxima.  They are
       // not even computed unless a row's sum of the tile exceeds 2^8 (no p above 2^8 can hide under that) or a
       // row has no reference yet; then the exact maxima decide, and on a step the tile is redone.
@@ -396,38 +395,114 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
       }
     return;
   }
-  // Partial result: a lane holds one row (512 bytes of fp32) in 16-byte pieces, so stored directly every
-  // instruction would touch 32 rows with 32 bytes each.  The wavefront's 32 rows go through LDS (its own 16.5 KB,
-  // rows padded to 132 floats: conflict-free both ways) and leave as whole rows, 32 lanes per row.
+  // Partial result of a key range.  What leaves is the NORMALISED partial o / l (a convex combination of V rows, so
+  // its magnitude is bounded by the values of V) as fp16 scaled per row by a power of two that brings the row's
+  // largest element into [1/2, 1): half the bytes of fp32 at 11 bits of mantissa relative to the row maximum, and no
+  // fp16 range limit on V.  (max, sum, scale) go along in fp32; the merge weighs the rows by sum * 2^(max - M).
+  // A lane holds one row in 8-byte pieces, so stored directly every instruction would touch 32 rows; the
+  // wavefront's 32 rows go through LDS (its own 8.5 KB, rows padded to 136 halves) and leave as whole 256-byte rows.
+  float amax = 0.f;
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) amax = fmaxf(amax, fabsf(oacc[db][r]));
+  amax = fmaxf(amax, __shfl_xor(amax, 32));
+  const float inv_l = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+  amax *= inv_l;
+  // the power of two above the largest normalised element (1 for an all-zero row); exponent clamped below the top
+  const uint32_t ebits = min((__float_as_uint(amax) & 0x7f800000u) + 0x00800000u, 0x7e800000u);
+  const float scale = amax > 1e-30f ? __uint_as_float(ebits) : 1.f;   // (rows of vanishing magnitude keep scale 1)
+  const float mul = inv_l / scale;
   __syncthreads();   // every wavefront is past its last read of the tile slots
-  float* so = (float*)smem + wave * (32 * PIPE_OROW);
+  _Float16* so = (_Float16*)smem + wave * (32 * PIPE_HROW);
   if (rvalid) {
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
         const int dv = 32 * db + 8 * r4 + 4 * hh;
-        *(float4*)(so + l32 * PIPE_OROW + dv) = make_float4(oacc[db][r4 * 4], oacc[db][r4 * 4 + 1],
-                                                            oacc[db][r4 * 4 + 2], oacc[db][r4 * 4 + 3]);
+        typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+        h4 pk;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) pk[e] = (_Float16)(oacc[db][r4 * 4 + e] * mul);
+        *(h4*)(so + l32 * PIPE_HROW + dv) = pk;
       }
     if (hh == 0) {
       const size_t p = ((size_t)qi * n_splits + sp) * n_q_heads + h;
-      part_ml[p * 2] = m_run == -INFINITY ? -INFINITY : m_run * c_log2;
-      part_ml[p * 2 + 1] = l_tot;
+      *(float4*)(part_ml + p * 4) = make_float4(m_run == -INFINITY ? -INFINITY : m_run * c_log2, l_tot, scale, 0.f);
     }
   }
+  // 16 lanes per row, 16 bytes per lane: four whole rows per store instruction
+  _Float16* part_h = (_Float16*)part_o;
+  const int l16 = lane & 15, rsub = lane >> 4;
 #pragma unroll 4
-  for (int i = 0; i < 16; ++i) {
-    const int r = 2 * i + hh, row2 = rt * ROWS_WG + wave * 32 + r;
+  for (int i = 0; i < 8; ++i) {
+    const int r = 4 * i + rsub, row2 = rt * ROWS_WG + wave * 32 + r;
     if (row2 < n_rows) {
       const size_t p2 = ((size_t)(row2 / G) * n_splits + sp) * n_q_heads + hk * G + row2 % G;
-      *(float4*)(part_o + p2 * D + 4 * l32) = *(const float4*)(so + r * PIPE_OROW + 4 * l32);
+      *(uint4*)(part_h + p2 * D + 8 * l16) = *(const uint4*)(so + r * PIPE_HROW + 8 * l16);
     }
   }
 }
 
+// ---------------------------------------------------------------------------------
+// Merge of the key ranges of a chunk-prefill launch: out = sum_s w_s o_s / sum_s w_s with w_s = l_s 2^(m_s - M)
+// and o_s the normalised partial (fp16 x row scale, see above).  16 lanes per (query, head) row, 8 head dims per
+// lane, all of a lane's loads (one 16-byte piece per key range) issued before any is used; 16 rows per workgroup.
+// Ranges of weight zero (nothing visible) are skipped, their rows are never read.
+// grid: ceil(n_q * n_q_heads / 16), block: 256 threads.
+// ---------------------------------------------------------------------------------
+constexpr int kMaxChunkSplits = 64;
+__global__ __launch_bounds__(256) void k_chunk_combine(const _Float16* __restrict__ part_h,
+                                                       const float* __restrict__ part_ml,
+                                                       __hip_bfloat16* __restrict__ out, int n_rows_total, int n_splits,
+                                                       int n_q_heads) {
+  const int row = blockIdx.x * 16 + (threadIdx.x >> 4), l16 = threadIdx.x & 15;
+  if (row >= n_rows_total) return;
+  const int qi = row / n_q_heads, h = row % n_q_heads;
+  const size_t base = (size_t)qi * n_splits * n_q_heads + h;   // split s adds s * n_q_heads
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  float wsum = 0.f, m_ref = -INFINITY;
+  typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+  for (int s0 = 0; s0 < n_splits; s0 += 8) {
+    float4 ml[8];
+    h8 v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const bool ok = s0 + j < n_splits;
+      const size_t p = base + (size_t)(s0 + j) * n_q_heads;
+      ml[j] = ok ? *(const float4*)(part_ml + p * 4) : make_float4(-INFINITY, 0.f, 1.f, 0.f);
+      if (ok && ml[j].x != -INFINITY) v[j] = *(const h8*)(part_h + p * D + 8 * l16);
+      else v[j] = (h8)(_Float16)0;
+    }
+    float mx = m_ref;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) mx = fmaxf(mx, ml[j].x);
+    const float resc = m_ref == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_ref - mx);
+    wsum *= resc;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] *= resc;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      if (ml[j].x == -INFINITY) continue;
+      const float w = ml[j].y * __builtin_amdgcn_exp2f(ml[j].x - mx);
+      const float ws = w * ml[j].z;
+      wsum += w;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] += ws * (float)v[j][e];
+    }
+    m_ref = mx;
+  }
+  const float inv = 1.0f / wsum;
+  typedef __bf16 b8 __attribute__((ext_vector_type(8)));
+  b8 o8;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o8[e] = (__bf16)(acc[e] * inv);
+  *(b8*)(out + (size_t)row * D + 8 * l16) = o8;
+}
+
 constexpr int kNW = 8, kKS = 4, kVS = 4;   // 8 wavefronts, 4 + 4 tile slots: 128 KB of LDS, one workgroup per CU
-constexpr int kLds = std::max((kKS + kVS) * PIPE_TILE, kNW * 32 * PIPE_OROW * 4);
+constexpr int kLds = std::max((kKS + kVS) * PIPE_TILE, kNW * 32 * PIPE_HROW * 2);
 
 }  // namespace
 
@@ -453,7 +528,7 @@ hipError_t launch_attn_chunk_mfma(const sv_cache* c, int stream, int layer, cons
     while (n_splits > 1 && (Hkv * n_splits) % 8 != 0) --n_splits;
   }
   n_splits = std::min<int64_t>(n_splits, std::max<int64_t>(1, c->part_rows / n_q));
-  n_splits = std::min(n_splits, 64);
+  n_splits = std::min(n_splits, kMaxChunkSplits);
   int keys_per_split = ((n_kv + n_splits - 1) / n_splits + TK - 1) / TK * TK;
   n_splits = (n_kv + keys_per_split - 1) / keys_per_split;
   const float c_log2 = 1.4426950408889634f / sqrtf((float)D);
@@ -465,7 +540,10 @@ hipError_t launch_attn_chunk_mfma(const sv_cache* c, int stream, int layer, cons
                      c->head_stride / 2, c_log2, Hkv, pairs_pad);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || n_splits == 1) return e;
-  return launch_attn_combine(c, n_q, n_splits, o, s);
+  const int rows_total = n_q * c->cfg.n_q_heads;
+  hipLaunchKernelGGL(k_chunk_combine, dim3((rows_total + 15) / 16), dim3(256), 0, s, (const _Float16*)c->part_o,
+                     c->part_ml, (__hip_bfloat16*)o, rows_total, n_splits, c->cfg.n_q_heads);
+  return hipGetLastError();
 }
 
 }  // namespace sv

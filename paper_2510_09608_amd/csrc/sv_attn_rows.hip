@@ -363,42 +363,6 @@ __global__ __launch_bounds__(256) void k_attn_rows(RowTable tab, int chunk_mode,
   }
 }
 
-// ---------------------------------------------------------------------------------
-// Merge of key ranges as a kernel of its own (used by the MFMA chunk kernel):
-// out = sum_s e^(m_s - M) o_s / sum_s e^(m_s - M) l_s.  One workgroup of 128
-// threads per (row, head); the weights are computed once into LDS, then every
-// thread sums its dimension over the splits with independent loads.
-// ---------------------------------------------------------------------------------
-template <typename T, int D>
-__global__ __launch_bounds__(128) void k_attn_combine(const float* __restrict__ part_o,
-                                                      const float* __restrict__ part_ml, T* __restrict__ out,
-                                                      int n_splits, int n_q_heads) {
-  __shared__ float sw[kMaxSplits], sl[kMaxSplits];
-  const int b = blockIdx.x / n_q_heads, h = blockIdx.x % n_q_heads, t = threadIdx.x;
-  const size_t base = (size_t)b * n_splits * n_q_heads + h;
-  if (t < n_splits) {
-    sw[t] = part_ml[(base + (size_t)t * n_q_heads) * 2];
-    sl[t] = part_ml[(base + (size_t)t * n_q_heads) * 2 + 1];
-  }
-  __syncthreads();
-  float mn = -INFINITY;
-  for (int s = 0; s < n_splits; ++s) mn = fmaxf(mn, sw[s]);
-  __syncthreads();
-  if (t < n_splits) sw[t] = sw[t] == -INFINITY ? 0.f : exp_diff<T>(sw[t] - mn);
-  __syncthreads();
-  for (int d = t; d < D; d += 128) {
-    float acc = 0.f, lsum = 0.f;
-#pragma unroll 8
-    for (int s = 0; s < n_splits; ++s) {
-      acc += sw[s] * part_o[(base + (size_t)s * n_q_heads) * D + d];
-      lsum += sw[s] * sl[s];
-    }
-    const float r = acc / lsum;
-    if constexpr (sizeof(T) == 4) out[((size_t)b * n_q_heads + h) * D + d] = r;
-    else out[((size_t)b * n_q_heads + h) * D + d] = __float2bfloat16(r);
-  }
-}
-
 int pick_splits(const sv_cache* c, int n_rows, int max_len) {
   const int forced = c->opt[SV_OPT_DECODE_SPLITS];
   int64_t want = forced > 0 ? forced
@@ -459,23 +423,7 @@ hipError_t rows_dispatch(const sv_cache* c, const RowTable& tab, int chunk_mode,
                                                                       n_splits, q, k_new, v_new, o, row_off, s);
 }
 
-template <typename T, int D>
-hipError_t combine_launch(const sv_cache* c, int n_rows, int n_splits, void* o, hipStream_t s) {
-  hipLaunchKernelGGL((k_attn_combine<T, D>), dim3(n_rows * c->cfg.n_q_heads), dim3(128), 0, s, c->part_o, c->part_ml,
-                     (T*)o, n_splits, c->cfg.n_q_heads);
-  return hipGetLastError();
-}
-
 }  // namespace
-
-hipError_t launch_attn_combine(const sv_cache* c, int n_rows, int n_splits, void* o, hipStream_t s) {
-  if (n_splits > kMaxSplits) return hipErrorInvalidValue;
-  if (c->cfg.dtype == SV_DTYPE_F32)
-    return c->cfg.head_dim == 64 ? combine_launch<float, 64>(c, n_rows, n_splits, o, s)
-                                 : combine_launch<float, 128>(c, n_rows, n_splits, o, s);
-  return c->cfg.head_dim == 64 ? combine_launch<__hip_bfloat16, 64>(c, n_rows, n_splits, o, s)
-                               : combine_launch<__hip_bfloat16, 128>(c, n_rows, n_splits, o, s);
-}
 
 bool attn_rows_supported(const sv_cache* c) {
   const int g = c->group;

@@ -149,6 +149,5 @@ hipError_t launch_store_tokens_vt(const sv_cache* c, int stream, int layer, int6
 hipError_t launch_attn_chunk_mfma(const sv_cache* c, int stream, int layer, const void* q, int n_q,
                                   void* o, int causal, hipStream_t s);
 
-hipError_t launch_attn_combine(const sv_cache* c, int n_rows, int n_splits, void* o, hipStream_t s);
 
 }  // namespace sv

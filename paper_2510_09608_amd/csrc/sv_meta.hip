@@ -81,17 +81,23 @@ __global__ void k_meta_append(MetaPtrs m, const int32_t* __restrict__ next_in, i
 //
 // keep(i)  : text  -> rank < n_sink or rank >= text_lo     (sink + recent text)
 //            vision-> rank >= vis_lo                         (recent vision)
-// dst(i)   : exclusive prefix count of keep  (wavefront ballot + popcount, then a
-//            16-entry scan across wavefronts, then a running carry across tiles)
+// dst(i)   : exclusive prefix count of keep
 // base'(i) : exclusive prefix sum over kept tokens of the position advance, where a
 //            text token advances by 1 and a vision block advances by its extent at
 //            its last retained token.  With every token its own block of extent 1
 //            (1-D mode) base' equals dst.
 // Survivors' metadata is written compacted to `out`; src[dst] = i is the gather
 // list for the K/V move and delta[dst] = base - base' the shift for the re-rotation.
+//
+// A pass covers kScanSub x 1024 tokens: sub-tile k holds tokens base + 1024 k + tid, so every load is coalesced
+// and all loads of a pass are independent and issued together (one memory round trip per 4096 tokens instead of
+// one per 1024).  Within a sub-tile a wavefront's keep count comes from the ballot and a popcount, its advances
+// from a shuffle scan; the 64 (sub-tile, wavefront) totals of a pass go through LDS and are scanned by the first
+// wavefront, and a running carry links the passes.
 // ---------------------------------------------------------------------------------
 constexpr int kScanThreads = 1024;
 constexpr int kScanWaves = kScanThreads / 64;
+constexpr int kScanSub = 4;
 
 __device__ __forceinline__ bool keep_rule(int type, int64_t rank, int64_t n_sink, int64_t text_lo, int64_t vis_lo) {
   return type == SV_TEXT ? (rank < n_sink || rank >= text_lo) : (rank >= vis_lo);
@@ -102,76 +108,104 @@ __global__ __launch_bounds__(kScanThreads) void k_evict_scan(MetaPtrs in, MetaPt
                                                              int32_t* __restrict__ next_out,
                                                              int32_t* __restrict__ n_out, int n_old, int64_t n_sink,
                                                              int64_t text_lo, int64_t vis_lo) {
-  __shared__ int sh_cnt[kScanWaves];
-  __shared__ int sh_adv[kScanWaves];
+  __shared__ int sh_cnt[kScanSub * kScanWaves];
+  __shared__ int sh_adv[kScanSub * kScanWaves];
+  __shared__ int sh_tot[2];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int carry_cnt = 0, carry_adv = 0;
-  for (int base = 0; base < n_old; base += kScanThreads) {
-    const int i = base + tid;
-    const bool valid = i < n_old;
-    int type = 0, blk = -1, old_base = 0;
-    int64_t rank = 0, gid = 0;
-    short4 loc = make_short4(0, 0, 0, 1);
-    bool keep = false;
-    int adv = 0;
-    if (valid) {
-      type = in.type[i];
-      rank = in.rank[i];
-      keep = keep_rule(type, rank, n_sink, text_lo, vis_lo);
-      if (keep) {
-        gid = in.gid[i];
-        blk = in.blk[i];
-        loc = in.local4[i];
-        old_base = in.pos4[i].w;
-        if (type == SV_TEXT) {
-          adv = 1;
+  for (int base = 0; base < n_old; base += kScanThreads * kScanSub) {
+    int type[kScanSub], blk[kScanSub], old_base[kScanSub], type_n[kScanSub], blk_n[kScanSub];
+    int64_t rank[kScanSub], gid[kScanSub], rank_n[kScanSub];
+    short4 loc[kScanSub];
+#pragma unroll
+    for (int k = 0; k < kScanSub; ++k) {   // the token and its successor (the look-ahead for "last of its block")
+      const unsigned i = (unsigned)(base + k * kScanThreads + tid);   // (unsigned: scalar base + 32-bit lane offset)
+      const bool valid = i < (unsigned)n_old, valid_n = i + 1 < (unsigned)n_old;
+      type[k] = valid ? in.type[i] : SV_TEXT;
+      rank[k] = valid ? in.rank[i] : 0;
+      blk[k] = valid ? in.blk[i] : -1;
+      gid[k] = valid ? in.gid[i] : 0;
+      loc[k] = valid ? in.local4[i] : make_short4(0, 0, 0, 1);
+      old_base[k] = valid ? in.pos4[i].w : 0;
+      type_n[k] = valid_n ? in.type[i + 1] : SV_TEXT;
+      rank_n[k] = valid_n ? in.rank[i + 1] : 0;
+      blk_n[k] = valid_n ? in.blk[i + 1] : -2;   // matches no block
+    }
+    bool keep[kScanSub];
+    int adv[kScanSub], lane_cnt[kScanSub], incl[kScanSub];
+#pragma unroll
+    for (int k = 0; k < kScanSub; ++k) {
+      const int i = base + k * kScanThreads + tid;
+      keep[k] = i < n_old && keep_rule(type[k], rank[k], n_sink, text_lo, vis_lo);
+      adv[k] = 0;
+      if (keep[k]) {
+        if (type[k] == SV_TEXT) {
+          adv[k] = 1;
         } else {
-          bool last = true;  // last retained token of its vision block?
-          if (blk >= 0 && i + 1 < n_old && in.blk[i + 1] == blk)
-            last = !keep_rule(in.type[i + 1], in.rank[i + 1], n_sink, text_lo, vis_lo);
-          adv = last ? (int)loc.w : 0;
+          // last retained token of its vision block?  (a token without a block, blk < 0, is its own block)
+          const bool next_stays = blk[k] >= 0 && blk_n[k] == blk[k] && i + 1 < n_old &&
+                                  keep_rule(type_n[k], rank_n[k], n_sink, text_lo, vis_lo);
+          adv[k] = next_stays ? 0 : (int)loc[k].w;
         }
       }
-    }
-    // wavefront level: ballot/popcount for the count, shuffle scan for the advance
-    const unsigned long long bal = __ballot(keep);
-    const int lane_cnt = __popcll(bal & ((1ull << lane) - 1ull));
-    int incl = adv;
+      // wavefront level: ballot/popcount for the count, shuffle scan for the advance
+      const unsigned long long bal = __ballot(keep[k]);
+      lane_cnt[k] = __popcll(bal & ((1ull << lane) - 1ull));
+      incl[k] = adv[k];
 #pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      const int y = __shfl_up(incl, off);
-      if (lane >= off) incl += y;
-    }
-    if (lane == 63) {
-      sh_cnt[wave] = __popcll(bal);
-      sh_adv[wave] = incl;
+      for (int off = 1; off < 64; off <<= 1) {
+        const int y = __shfl_up(incl[k], off);
+        if (lane >= off) incl[k] += y;
+      }
+      if (lane == 63) {
+        sh_cnt[k * kScanWaves + wave] = __popcll(bal);
+        sh_adv[k * kScanWaves + wave] = incl[k];
+      }
     }
     __syncthreads();
-    int wave_cnt = 0, wave_adv = 0, tot_cnt = 0, tot_adv = 0;
+    // exclusive prefix over the kScanSub * 16 = 64 (sub-tile, wavefront) segments in token order (segment
+    // k * 16 + w), by the first wavefront: one segment per lane
+    static_assert(kScanSub * kScanWaves == 64, "one segment per lane of the first wavefront");
+    if (wave == 0) {
+      const int c0 = sh_cnt[lane], a0 = sh_adv[lane];
+      int ci = c0, ai = a0;
 #pragma unroll
-    for (int w = 0; w < kScanWaves; ++w) {
-      const int cw = sh_cnt[w], aw = sh_adv[w];
-      if (w < wave) {
-        wave_cnt += cw;
-        wave_adv += aw;
+      for (int off = 1; off < 64; off <<= 1) {
+        const int yc = __shfl_up(ci, off), ya = __shfl_up(ai, off);
+        if (lane >= off) ci += yc, ai += ya;
       }
-      tot_cnt += cw;
-      tot_adv += aw;
+      sh_cnt[lane] = carry_cnt + ci - c0;
+      sh_adv[lane] = carry_adv + ai - a0;
+      if (lane == 63) {
+        sh_tot[0] = carry_cnt + ci;
+        sh_tot[1] = carry_adv + ai;
+      }
     }
-    if (keep) {
-      const int d = carry_cnt + wave_cnt + lane_cnt;
-      const int nb = carry_adv + wave_adv + (incl - adv);
-      out.gid[d] = gid;
-      out.rank[d] = rank;
-      out.type[d] = (uint8_t)type;
-      out.blk[d] = blk;
-      out.local4[d] = loc;
-      out.pos4[d] = make_int4(nb + loc.x, nb + loc.y, nb + loc.z, nb);
-      src[d] = i;
-      delta[d] = old_base - nb;
+    __syncthreads();
+    int seg_cnt[kScanSub], seg_adv[kScanSub];
+#pragma unroll
+    for (int k = 0; k < kScanSub; ++k) {
+      seg_cnt[k] = sh_cnt[k * kScanWaves + wave];
+      seg_adv[k] = sh_adv[k * kScanWaves + wave];
     }
-    carry_cnt += tot_cnt;
-    carry_adv += tot_adv;
+    const int run_cnt = sh_tot[0], run_adv = sh_tot[1];
+#pragma unroll
+    for (int k = 0; k < kScanSub; ++k) {
+      if (keep[k]) {
+        const int d = seg_cnt[k] + lane_cnt[k];
+        const int nb = seg_adv[k] + (incl[k] - adv[k]);
+        out.gid[d] = gid[k];
+        out.rank[d] = rank[k];
+        out.type[d] = (uint8_t)type[k];
+        out.blk[d] = blk[k];
+        out.local4[d] = loc[k];
+        out.pos4[d] = make_int4(nb + loc[k].x, nb + loc[k].y, nb + loc[k].z, nb);
+        src[d] = base + k * kScanThreads + tid;
+        delta[d] = old_base[k] - nb;
+      }
+    }
+    carry_cnt = run_cnt;
+    carry_adv = run_adv;
     __syncthreads();
   }
   if (tid == 0) {
