@@ -268,7 +268,7 @@ def empirical_ceiling():
 
     import paper_2510_09608_amd as sv
     buf = torch.empty(1 << 29, dtype=torch.float32, device="cuda:0").fill_(1.0)     # 2 GiB
-    tflops, read_gbs = sv.sv_probe_rates(buf)
+    tflops, tflops_rnd, read_gbs = sv.sv_probe_rates(buf)
     half = buf.numel() // 2
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     buf[half:].copy_(buf[:half])
@@ -278,9 +278,10 @@ def empirical_ceiling():
     b.record()
     torch.cuda.synchronize()
     copy_gbs = 4 * 2.0 * half * 4 / (a.elapsed_time(b) * 1e-3) / 1e9
-    return {"mfma_bf16_tflops": round(tflops, 1), "hbm_read_gbs": round(read_gbs, 1), "hbm_copy_gbs": round(copy_gbs, 1),
-            "how": "sv_probe_rates (v_mfma_f32_32x32x16_bf16 from registers on all SIMDs; 2 GiB streaming read) and a "
-                   "1 GiB torch device copy counted as read + write"}
+    return {"mfma_bf16_tflops": round(tflops, 1), "mfma_bf16_tflops_random_operands": round(tflops_rnd, 1),
+            "hbm_read_gbs": round(read_gbs, 1), "hbm_copy_gbs": round(copy_gbs, 1),
+            "how": "sv_probe_rates (v_mfma_f32_32x32x16_bf16 from registers on all SIMDs, constant small-integer operands "
+                   "and pseudo-random operands; 2 GiB streaming read) and a 1 GiB torch device copy counted as read + write"}
 
 
 def decode_batch_bench(args, with_ceiling=True):

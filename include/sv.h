@@ -253,7 +253,7 @@ SV_API int sv_decode_step_layers(sv_cache* c, int stream_id, const void* q_dev, 
  * method (Sec. 2.1) with the projections and MLPs of the model left out: the
  * caller supplies each layer's Q/K/V up front.  Layouts (all device memory,
  * cache dtype, K un-rotated):
- *   q_vision [n_layers][n_vision][n_q_heads][head_dim]   rotated IN PLACE
+ *   q_vision [n_layers][n_vision][n_q_heads][head_dim]   un-rotated; MAY be rotated in place (scratch afterwards)
  *   k_vision, v_vision [n_layers][n_vision][n_kv_heads][head_dim]
  *   o_vision [n_layers][n_vision][n_q_heads][head_dim]   output
  *   q_text [n_text][n_layers][n_q_heads][head_dim], k_text / v_text
@@ -311,14 +311,16 @@ SV_API int sv_cache_read_kv(sv_cache* c, int stream_id, int layer, int which, in
  * paper.  Measures what the device sustains, for setting the attention
  * kernels' roofline fractions (taken against the published peaks) beside the
  * achievable ceilings: *mfma_tflops_out = dense bf16 rate of a register-only
- * v_mfma_f32_32x32x16_bf16 loop on every SIMD (the clock under a full-chip
- * matrix load is well below the boost clock); *hbm_read_gbs_out = rate of a
+ * v_mfma_f32_32x32x16_bf16 loop on every SIMD with constant small-integer
+ * operands, *mfma_tflops_random_out = the same loop on pseudo-random operands
+ * (the clock under a full-chip matrix load is well below the boost clock, and
+ * lower still when the multipliers see real data); *hbm_read_gbs_out = rate of a
  * streaming read of dev_buf[0, bytes) (use a buffer several times the 256 MB
- * memory-side cache).  Either output may be NULL (that probe is skipped).
+ * memory-side cache).  Any output may be NULL (that probe is skipped).
  * dev_buf: device memory, 16-byte aligned, >= 1 MiB, read only (its first
  * word is written only if a data-dependent condition that cannot occur holds).
  */
-SV_API int sv_probe_rates(void* dev_buf, size_t bytes, double* mfma_tflops_out,
+SV_API int sv_probe_rates(void* dev_buf, size_t bytes, double* mfma_tflops_out, double* mfma_tflops_random_out,
                           double* hbm_read_gbs_out, void* hip_stream);
 
 #ifdef __cplusplus

@@ -77,7 +77,8 @@ _SIGNATURES = {
                                     C.c_void_p]),
     "sv_cache_read_kv": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int64, C.c_int64, C.c_void_p,
                                    C.c_void_p]),
-    "sv_probe_rates": (C.c_int, [C.c_void_p, C.c_size_t, C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p]),
+    "sv_probe_rates": (C.c_int, [C.c_void_p, C.c_size_t, C.POINTER(C.c_double), C.POINTER(C.c_double),
+                                 C.POINTER(C.c_double), C.c_void_p]),
 }
 
 
@@ -242,11 +243,12 @@ def sv_cache_read_kv(handle: int, stream_id: int, layer: int, which: int, slot0:
 
 
 def sv_probe_rates(buf, stream=None):
-    """(sustained dense bf16 MFMA TFLOP/s, streaming HBM read GB/s) measured on `buf` (a device tensor)."""
-    t, g = C.c_double(0.0), C.c_double(0.0)
-    _check(lib().sv_probe_rates(_ptr(buf), buf.numel() * buf.element_size(), C.byref(t), C.byref(g), _stream(stream)),
-           "sv_probe_rates")
-    return t.value, g.value
+    """(sustained dense bf16 MFMA TFLOP/s on constant operands, the same on pseudo-random operands, streaming HBM
+    read GB/s) measured on `buf` (a device tensor)."""
+    t, tr, g = C.c_double(0.0), C.c_double(0.0), C.c_double(0.0)
+    _check(lib().sv_probe_rates(_ptr(buf), buf.numel() * buf.element_size(), C.byref(t), C.byref(tr), C.byref(g),
+                                _stream(stream)), "sv_probe_rates")
+    return t.value, tr.value, g.value
 
 
 class Cache:

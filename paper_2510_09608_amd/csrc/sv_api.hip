@@ -43,7 +43,7 @@ bool config_ok(const sv_config* c) {
 // sv_cache_bytes and sv_cache_create cannot disagree.
 struct Layout {
   size_t kv, meta_gid[2], meta_rank[2], meta_pos[2], meta_local[2], meta_blk[2], meta_type[2];
-  size_t src, delta, dtab, next_pos, n_dev, inv_freq, last_cs, part_o, part_ml, counters, total;
+  size_t src, delta, dtab, next_pos, n_dev, inv_freq, last_cs, cs_tab, part_o, part_ml, counters, total;
   int64_t part_rows;
 };
 
@@ -74,6 +74,7 @@ Layout make_layout(const sv_config& c) {
   L.n_dev = take(S * 4);
   L.inv_freq = take((size_t)(c.head_dim / 2) * 8);
   L.last_cs = take(S * (size_t)(c.head_dim / 2) * 8);
+  L.cs_tab = take(S * (size_t)c.max_q_tokens * (size_t)(c.head_dim / 2) * 8);
   L.part_rows = std::max<int64_t>(64 * (int64_t)c.n_streams, std::max<int64_t>(4096, 4 * (int64_t)c.max_q_tokens));
   L.part_o = take((size_t)L.part_rows * c.n_q_heads * c.head_dim * 4);
   L.part_ml = take((size_t)L.part_rows * c.n_q_heads * 4 * 4);   // up to 4 floats per (row, range, head)
@@ -83,6 +84,7 @@ Layout make_layout(const sv_config& c) {
 }
 
 bool stream_ok(const sv_cache* c, int s) { return c && s >= 0 && s < c->cfg.n_streams; }
+bool st_cs_valid(const sv_cache* c, int s) { return c->st[s].cs_tab_valid; }
 
 int64_t iv_count(const std::vector<std::pair<int64_t, int64_t>>& iv) {
   int64_t n = 0;
@@ -177,6 +179,7 @@ int sv_cache_create(const sv_config* cfg, void* dev_arena, size_t arena_bytes, v
   c->n_dev = (int32_t*)(base + L.n_dev);
   c->inv_freq = (double*)(base + L.inv_freq);
   c->last_cs = (float2*)(base + L.last_cs);
+  c->cs_tab = (float2*)(base + L.cs_tab);
   c->part_o = (float*)(base + L.part_o);
   c->part_ml = (float*)(base + L.part_ml);
   c->part_rows = L.part_rows;
@@ -281,13 +284,17 @@ static int append_impl(sv_cache* c, int stream_id, int layer, int n, const uint8
         if (types_host[j] == SV_VISION) mask.w[j >> 5] |= 1u << (j & 31);
     }
     const bool has_blk = grid_thw_host && c->cfg.rope_mode == SV_ROPE_3D;
+    // blocked-V^T caches keep the cos/sin of a run of at most max_q_tokens tokens: every layer's K store and, in
+    // sv_stream_step, the attention kernel's Q rotation read them instead of evaluating sincos again
+    const bool with_cs = c->v_blocked && c->cfg.rope_mode != SV_ROPE_NONE && n <= c->cfg.max_q_tokens;
     SV_DEV(sv::launch_meta_append(c, stream_id, st.next_parity, st.len, n, st.next_gid, st.n_text,
                                   st.n_vis, type_uniform, type_uniform < 0 ? &mask : nullptr,
-                                  has_blk ? st.next_blk : -1, gT, gH, gW, s));
-    if (launch_kv) SV_DEV(sv::launch_append_kv(c, stream_id, 0, st.len, n, k_dev, v_dev, s));
-
+                                  has_blk ? st.next_blk : -1, gT, gH, gW, with_cs, s));
+    st.cs_tab_valid = with_cs;
     st.pending_slot0 = st.len;
     st.pending_n = n;
+    if (launch_kv) SV_DEV(sv::launch_append_kv(c, stream_id, 0, st.len, n, k_dev, v_dev, s));
+
     st.next_parity ^= 1;
     if (has_blk) st.next_blk++;
     st.next_gid += n;
@@ -351,6 +358,7 @@ int sv_cache_evict(sv_cache* c, int stream_id, int64_t n_sink, int64_t vision_wi
   for (int l = 0; l < c->cfg.n_layers; ++l) st.layer_len[l] = n_new;
   st.pending_slot0 = n_new;
   st.pending_n = 0;
+  st.cs_tab_valid = false;
   return SV_OK;
 }
 
@@ -371,7 +379,7 @@ int sv_attn_chunk(sv_cache* c, int stream_id, int layer, const void* q_dev, int 
   if (st.layer_len[layer] != st.len) return SV_ERR_STATE;
   hipStream_t s = (hipStream_t)hip_stream;
   if (c->use_mfma) {
-    SV_DEV(sv::launch_attn_chunk_mfma(c, stream_id, layer, q_dev, n_q, o_dev, causal, s));
+    SV_DEV(sv::launch_attn_chunk_mfma(c, stream_id, layer, q_dev, n_q, o_dev, causal, false, s));
     return SV_OK;
   }
   if (!sv::attn_rows_supported(c)) return SV_ERR_UNSUPPORTED;
@@ -446,7 +454,8 @@ int sv_decode_step(sv_cache* c, int layer, const int32_t* stream_ids_host, int n
     sv::StreamState& st = c->st[sid];
     if (layer == 0) {
       SV_DEV(sv::launch_meta_append(c, sid, st.next_parity, st.len, 1, st.next_gid, st.n_text, st.n_vis, SV_TEXT,
-                                    nullptr, -1, 0, 0, 0, s));
+                                    nullptr, -1, 0, 0, 0, false, s));
+      st.cs_tab_valid = false;
       st.pending_slot0 = st.len;
       st.pending_n = 1;
       st.next_parity ^= 1;
@@ -475,7 +484,8 @@ int sv_decode_step_layers(sv_cache* c, int stream_id, const void* q_dev, const v
   if (st.len + 1 > c->cfg.capacity_tokens) return SV_ERR_CAPACITY;
   hipStream_t s = (hipStream_t)hip_stream;
   SV_DEV(sv::launch_meta_append(c, stream_id, st.next_parity, st.len, 1, st.next_gid, st.n_text, st.n_vis, SV_TEXT,
-                                nullptr, -1, 0, 0, 0, s));
+                                nullptr, -1, 0, 0, 0, false, s));
+  st.cs_tab_valid = false;
   st.pending_slot0 = st.len;
   st.pending_n = 1;
   st.next_parity ^= 1;
@@ -515,8 +525,11 @@ int sv_stream_step(sv_cache* c, int stream_id, int64_t n_sink, int64_t vision_wi
                        !fused);
       if (rc != SV_OK) return rc;
       if (fused) {
-        SV_DEV(sv::launch_store_tokens_vt(c, stream_id, l, slot0, n, q, k, v, (hipStream_t)hip_stream));
-        SV_DEV(sv::launch_attn_chunk_mfma(c, stream_id, l, q, n, o, 1, (hipStream_t)hip_stream));
+        // Q stays as the caller wrote it when the run's cos/sin table exists: the attention kernel rotates it on load
+        const bool q_on_load = st_cs_valid(c, stream_id);
+        SV_DEV(sv::launch_store_tokens_vt(c, stream_id, l, slot0, n, q_on_load ? nullptr : q, k, v,
+                                          (hipStream_t)hip_stream));
+        SV_DEV(sv::launch_attn_chunk_mfma(c, stream_id, l, q, n, o, 1, q_on_load, (hipStream_t)hip_stream));
       } else {
         rc = sv_rope_apply(c, stream_id, slot0, n, q, nullptr, hip_stream);
         if (rc != SV_OK) return rc;

@@ -93,7 +93,7 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
     const __hip_bfloat16* __restrict__ q, const __hip_bfloat16* __restrict__ kc, const __hip_bfloat16* __restrict__ vc,
     __hip_bfloat16* __restrict__ out, float* __restrict__ part_o, float* __restrict__ part_ml, int n_q, int n_kv,
     int causal, int n_splits, int keys_per_split, int n_q_heads, int G, size_t head_stride_elems, float c_log2,
-    int n_kv_heads, int pairs_pad) {
+    int n_kv_heads, int pairs_pad, const float2* __restrict__ cs_tab) {
   constexpr int ROWS_WG = NW * 32;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   char* const sKbase = smem;
@@ -173,6 +173,21 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
     for (int kk = 0; kk < 8; ++kk) {
       uint4 raw = rvalid ? *(const uint4*)(qp + kk * 16) : make_uint4(0, 0, 0, 0);
       qf[kk] = *(bf16x8*)&raw;
+    }
+    if (cs_tab != nullptr) {
+      // Un-rotated queries (the per-second step): rotate them here, with the cos/sin the run's registration
+      // tabulated per (token, pair), and round to bf16 as a rotation pass in memory would have.  The lane holds
+      // dims 16 kk + 8 hh + e, so the pair (i, i + 64) is (kk, kk + 4) of its own registers.
+      const float2* cs = cs_tab + (size_t)qi * (D / 2) + 8 * hh;
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float2 r = cs[16 * kk + e];
+          const float a = (float)qf[kk][e], b = (float)qf[kk + 4][e];
+          qf[kk][e] = (__bf16)(a * r.x - b * r.y);
+          qf[kk + 4][e] = (__bf16)(b * r.x + a * r.y);
+        }
     }
   }
 
@@ -513,7 +528,7 @@ hipError_t attn_chunk_mfma_init() {
 }
 
 hipError_t launch_attn_chunk_mfma(const sv_cache* c, int stream, int layer, const void* q, int n_q, void* o,
-                                  int causal, hipStream_t s) {
+                                  int causal, bool rotate_q, hipStream_t s) {
   constexpr int ROWS_WG = kNW * 32;
   const StreamState& st = c->st[stream];
   const int n_kv = (int)st.len, G = c->group, Hkv = c->cfg.n_kv_heads;
@@ -537,7 +552,8 @@ hipError_t launch_attn_chunk_mfma(const sv_cache* c, int stream, int layer, cons
                      (const __hip_bfloat16*)q, (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 0),
                      (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 1), (__hip_bfloat16*)o, c->part_o,
                      c->part_ml, n_q, n_kv, causal ? 1 : 0, n_splits, keys_per_split, c->cfg.n_q_heads, G,
-                     c->head_stride / 2, c_log2, Hkv, pairs_pad);
+                     c->head_stride / 2, c_log2, Hkv, pairs_pad,
+                     rotate_q ? c->cs_tab + (size_t)stream * c->cfg.max_q_tokens * (D / 2) : nullptr);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || n_splits == 1) return e;
   const int rows_total = n_q * c->cfg.n_q_heads;

@@ -51,6 +51,7 @@ struct StreamState {
   std::vector<int64_t> layer_len;                    // tokens stored per layer
   int64_t pending_slot0 = 0;                         // first slot of the append in flight
   int pending_n = 0;
+  bool cs_tab_valid = false;                         // cs_tab holds the rotary cos/sin of the pending run's tokens
 };
 
 }  // namespace sv
@@ -75,6 +76,8 @@ struct sv_cache {
   int32_t* n_dev;            // device [n_streams]             retained count written by the scan
   double* inv_freq;          // device [head_dim/2]
   float2* last_cs;           // device [n_streams][head_dim/2]  cos/sin at the position of the newest token
+  float2* cs_tab;            // device [n_streams][max_q_tokens][head_dim/2]  cos/sin of the tokens of the last
+                             // registered run (written when it has at most max_q_tokens tokens; blocked-V^T caches)
   float* part_o;             // device split-KV partial outputs
   float* part_ml;            // device split-KV partial (max, sum)
   int64_t part_rows;         // capacity of the partial buffers in (token, split) pairs
@@ -103,9 +106,10 @@ struct TypeMask {
 };
 
 // type_uniform: SV_TEXT / SV_VISION when all n tokens share it, -1 to read `mask`.
+// with_cs_tab: also write the rotary cos/sin of the n tokens to c->cs_tab (n <= max_q_tokens).
 hipError_t launch_meta_append(const sv_cache* c, int stream, int next_parity, int64_t slot0, int n,
                               int64_t gid0, int64_t rank_text0, int64_t rank_vis0, int type_uniform,
-                              const TypeMask* mask, int blk, int gT, int gH, int gW, hipStream_t s);
+                              const TypeMask* mask, int blk, int gT, int gH, int gW, bool with_cs_tab, hipStream_t s);
 
 hipError_t launch_append_kv(const sv_cache* c, int stream, int layer, int64_t slot0, int n,
                             const void* k, const void* v, hipStream_t s);
@@ -143,11 +147,14 @@ hipError_t launch_attn_decode_mfma_static(const sv_cache* c, int layer, const in
 // Once per process and device, before the first chunk-prefill launch: the kernel's LDS size has to be asked for.
 hipError_t attn_chunk_mfma_init();
 // Caches with blocked V^T (c->v_blocked): store n new tokens of one layer (K rows rotated, V transposed into its
-// blocks) and, if q is not NULL, rotate their Q rows in place, all in one launch.
+// blocks) and, if q is not NULL, rotate their Q rows in place, all in one launch.  K takes its cos/sin from
+// c->cs_tab when the stream's table is valid for this run.
 hipError_t launch_store_tokens_vt(const sv_cache* c, int stream, int layer, int64_t slot0, int n, void* q, const void* k,
                                   const void* v, hipStream_t s);
+// rotate_q: q is un-rotated; the kernel rotates it while loading, with c->cs_tab (the queries must be the run the
+// table was written for).
 hipError_t launch_attn_chunk_mfma(const sv_cache* c, int stream, int layer, const void* q, int n_q,
-                                  void* o, int causal, hipStream_t s);
+                                  void* o, int causal, bool rotate_q, hipStream_t s);
 
 
 }  // namespace sv

@@ -17,9 +17,25 @@ __global__ void k_meta_append(MetaPtrs m, const int32_t* __restrict__ next_in, i
                               int64_t slot0, int n, int64_t gid0, int64_t rank_text0, int64_t rank_vis0,
                               int type_uniform, TypeMask mask, int rope3d, int blk, int gT, int gH, int gW,
                               float2* __restrict__ last_cs, const double* __restrict__ inv_freq, int half,
-                              int rope_none, int s0, int s01, int f32_data, int32_t* __restrict__ n_dev) {
+                              int rope_none, int s0, int s01, int f32_data, int32_t* __restrict__ n_dev,
+                              float2* __restrict__ cs_tab) {
   const int j = blockIdx.x * blockDim.x + threadIdx.x;
   const int next = *next_in;
+  if (cs_tab != nullptr && j < n * half) {
+    // cos/sin of every new token's rotary angles (thread = one token, one frequency), as the row movers compute
+    // them: angle in double, sincosf of its float value (the table serves bf16 caches only)
+    const int tok = j / half, i = j % half;
+    int p;
+    if (rope3d && blk >= 0) {
+      const int lt = tok / (gH * gW), lh = (tok / gW) % gH, lw = tok % gW;
+      p = next + (i < s0 ? lt : (i < s01 ? lh : lw));
+    } else {
+      p = rope3d ? next + tok : (int)(slot0 + tok);
+    }
+    float2 cs;
+    sincosf((float)((double)p * inv_freq[i]), &cs.y, &cs.x);
+    cs_tab[j] = cs;
+  }
   if (blockIdx.x == 0 && threadIdx.x < half) {
     // cos/sin of the rotary angles of the LAST token of this append (the decode kernel's query token)
     const int i = threadIdx.x;
@@ -218,21 +234,22 @@ __global__ __launch_bounds__(kScanThreads) void k_evict_scan(MetaPtrs in, MetaPt
 
 hipError_t launch_meta_append(const sv_cache* c, int stream, int next_parity, int64_t slot0, int n,
                               int64_t gid0, int64_t rank_text0, int64_t rank_vis0, int type_uniform,
-                              const TypeMask* mask, int blk, int gT, int gH, int gW, hipStream_t s) {
+                              const TypeMask* mask, int blk, int gT, int gH, int gW, bool with_cs_tab, hipStream_t s) {
   const size_t off = (size_t)stream * (size_t)c->cfg.capacity_tokens;
   MetaPtrs m = c->meta[c->st[stream].cur];
   m.gid += off, m.rank += off, m.pos4 += off, m.local4 += off, m.blk += off, m.type += off;
   TypeMask mk = {};
   if (mask) mk = *mask;
-  const int threads = 256, blocks = (n + threads - 1) / threads;
+  const int half = c->cfg.head_dim / 2;
+  const int threads = 256, blocks = ((with_cs_tab ? n * half : n) + threads - 1) / threads;
   const int32_t* nin = c->next_pos + 2 * stream + next_parity;
   int32_t* nout = c->next_pos + 2 * stream + (next_parity ^ 1);
-  const int half = c->cfg.head_dim / 2;
   hipLaunchKernelGGL(k_meta_append, dim3(blocks), dim3(threads), 0, s, m, nin, nout, slot0, n, gid0, rank_text0,
                      rank_vis0, type_uniform, mk, c->cfg.rope_mode == SV_ROPE_3D ? 1 : 0, blk, gT, gH, gW,
                      c->last_cs + (size_t)stream * half, c->inv_freq, half, c->cfg.rope_mode == SV_ROPE_NONE ? 1 : 0,
                      c->cfg.mrope_sections[0], c->cfg.mrope_sections[0] + c->cfg.mrope_sections[1],
-                     c->cfg.dtype == SV_DTYPE_F32 ? 1 : 0, c->n_dev + stream);
+                     c->cfg.dtype == SV_DTYPE_F32 ? 1 : 0, c->n_dev + stream,
+                     with_cs_tab ? c->cs_tab + (size_t)stream * c->cfg.max_q_tokens * half : nullptr);
   return hipGetLastError();
 }
 

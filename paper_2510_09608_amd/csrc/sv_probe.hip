@@ -16,23 +16,36 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 
-// every wavefront issues 4 * iters independent v_mfma_f32_32x32x16_bf16 (32768 flop each) from registers
-__global__ __launch_bounds__(256) void k_probe_mfma(int iters, float* sink) {
-  bf16x8 a, b;
+// every wavefront issues 4 * iters independent v_mfma_f32_32x32x16_bf16 (32768 flop each) from registers.
+// random_data == 0: every operand element is a small integer, the same in all four products (few bits toggle);
+// random_data != 0: the four products read four different operand pairs of pseudo-random values in (-2, 2), sign and
+// mantissa bits all in use, as attention operands are: the clock the chip sustains depends on what the multipliers
+// switch, so this is the ceiling a kernel with real data can reach.
+__global__ __launch_bounds__(256) void k_probe_mfma(int iters, int random_data, float* sink) {
+  bf16x8 a[4], b[4];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    a[i] = (__bf16)(float)((threadIdx.x + i) & 7);
-    b[i] = (__bf16)(float)(i & 3);
-  }
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      if (random_data) {
+        uint32_t h = (threadIdx.x * 8u + i) * 2654435761u + j * 0x9e3779b9u + blockIdx.x * 40503u;
+        h ^= h >> 15, h *= 0x2c1b3c6du, h ^= h >> 12, h *= 0x297a2d39u, h ^= h >> 15;
+        a[j][i] = (__bf16)(((int)(h & 0xffff) - 32768) * (1.0f / 16384.0f));
+        b[j][i] = (__bf16)(((int)(h >> 16) - 32768) * (1.0f / 16384.0f));
+      } else {
+        a[j][i] = (__bf16)(float)((threadIdx.x + i) & 7);
+        b[j][i] = (__bf16)(float)(i & 3);
+      }
+    }
   f32x16 c0 = {0}, c1 = {0}, c2 = {0}, c3 = {0};
   for (int it = 0; it < iters; ++it) {
-    c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c0, 0, 0, 0);
-    c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c1, 0, 0, 0);
-    c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c2, 0, 0, 0);
-    c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c3, 0, 0, 0);
+    c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], b[0], c0, 0, 0, 0);
+    c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1], b[1], c1, 0, 0, 0);
+    c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2], b[2], c2, 0, 0, 0);
+    c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[3], b[3], c3, 0, 0, 0);
   }
   const float s = c0[0] + c1[1] + c2[2] + c3[3];
-  if (s == -1.0f) sink[0] = s;   // never true: keeps the loop alive
+  if (s == -1.0f) sink[0] = s;   // practically never: keeps the loop alive
 }
 
 // grid-stride read of `n16` 16-byte words; one word per lane and step, 8 steps in flight
@@ -60,7 +73,8 @@ __global__ __launch_bounds__(256) void k_probe_read(const u32x4* __restrict__ sr
 
 extern "C" {
 
-int sv_probe_rates(void* dev_buf, size_t bytes, double* mfma_tflops_out, double* hbm_read_gbs_out, void* hip_stream) {
+int sv_probe_rates(void* dev_buf, size_t bytes, double* mfma_tflops_out, double* mfma_tflops_random_out,
+                   double* hbm_read_gbs_out, void* hip_stream) {
   if (!dev_buf || bytes < (1u << 20) || ((uintptr_t)dev_buf & 15) != 0) return SV_ERR_INVALID;
   hipStream_t s = (hipStream_t)hip_stream;
   hipEvent_t e0, e1;
@@ -68,14 +82,16 @@ int sv_probe_rates(void* dev_buf, size_t bytes, double* mfma_tflops_out, double*
   float* sink = (float*)dev_buf;   // written only if a never-true condition holds
   int rc = SV_OK;
   float ms = 0.f;
-  if (mfma_tflops_out) {
+  for (int random_data = 0; random_data < 2 && rc == SV_OK; ++random_data) {
+    double* out = random_data ? mfma_tflops_random_out : mfma_tflops_out;
+    if (!out) continue;
     const int iters = 20000, wgs = 256 * 8;   // 8 workgroups of 4 wavefronts per CU: 8 wavefronts per SIMD
-    hipLaunchKernelGGL(k_probe_mfma, dim3(wgs), dim3(256), 0, s, 200, sink);   // warm-up
+    hipLaunchKernelGGL(k_probe_mfma, dim3(wgs), dim3(256), 0, s, 200, random_data, sink);   // warm-up
     (void)hipEventRecord(e0, s);
-    hipLaunchKernelGGL(k_probe_mfma, dim3(wgs), dim3(256), 0, s, iters, sink);
+    hipLaunchKernelGGL(k_probe_mfma, dim3(wgs), dim3(256), 0, s, iters, random_data, sink);
     (void)hipEventRecord(e1, s);
     if (hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess) rc = SV_ERR_HIP;
-    else *mfma_tflops_out = (double)wgs * 4 * iters * 4 * 32768.0 / (ms * 1e-3) / 1e12;
+    else *out = (double)wgs * 4 * iters * 4 * 32768.0 / (ms * 1e-3) / 1e12;
   }
   if (rc == SV_OK && hbm_read_gbs_out) {
     const size_t n16 = bytes / 16;

@@ -90,7 +90,7 @@ __device__ __forceinline__ void append_rows(int bx, int h, int which, const T* _
                                             const T* __restrict__ v_in, T* __restrict__ k_cache, T* __restrict__ v_cache,
                                             const int4* __restrict__ pos4, const double* __restrict__ inv_freq,
                                             int64_t slot0, int n, int n_kv_heads, size_t head_stride_elems,
-                                            int rope_mode, int s0, int s01) {
+                                            int rope_mode, int s0, int s01, const float2* __restrict__ cs_tab = nullptr) {
   using G = RowGeom<T, D>;
   const int j = bx * G::ROWS + threadIdx.x / G::TPR;
   if (j >= n) return;
@@ -100,8 +100,20 @@ __device__ __forceinline__ void append_rows(int bx, int h, int which, const T* _
   Vec16<T> lo, hi;
   lo.raw = *(const decltype(lo.raw)*)(src + t * G::EPV);
   hi.raw = *(const decltype(hi.raw)*)(src + D / 2 + t * G::EPV);
-  if (which == 0 && rope_mode != SV_ROPE_NONE)
-    rotate_pair_vec<T, D>(lo, hi, pos4[slot0 + j], t * G::EPV, rope_mode, s0, s01, inv_freq);
+  if (which == 0 && rope_mode != SV_ROPE_NONE) {
+    if (cs_tab != nullptr) {   // cos/sin of the run's tokens were tabulated when it was registered: [token][pair]
+      const float2* cs = cs_tab + (size_t)j * (D / 2) + t * G::EPV;
+#pragma unroll
+      for (int e = 0; e < Vec16<T>::N; ++e) {
+        const float2 r = cs[e];
+        const float a = lo.get(e), b = hi.get(e);
+        lo.set(e, a * r.x - b * r.y);
+        hi.set(e, b * r.x + a * r.y);
+      }
+    } else {
+      rotate_pair_vec<T, D>(lo, hi, pos4[slot0 + j], t * G::EPV, rope_mode, s0, s01, inv_freq);
+    }
+  }
   *(decltype(lo.raw)*)(dst + t * G::EPV) = lo.raw;
   *(decltype(hi.raw)*)(dst + D / 2 + t * G::EPV) = hi.raw;
 }
@@ -206,13 +218,14 @@ __global__ __launch_bounds__(256) void k_store_tokens_vt(
     __hip_bfloat16* __restrict__ q, const __hip_bfloat16* __restrict__ k_in, const __hip_bfloat16* __restrict__ v_in,
     __hip_bfloat16* __restrict__ k_cache, __hip_bfloat16* __restrict__ v_cache, const int4* __restrict__ pos4,
     const double* __restrict__ inv_freq, int64_t slot0, int n, int n_q_heads, int n_kv_heads, size_t head_stride_elems,
-    int rope_mode, int s0, int s01, int gx_k, int nb_k, int nb_q, int blk0, int n_blk) {
+    int rope_mode, int s0, int s01, int gx_k, int nb_k, int nb_q, int blk0, int n_blk,
+    const float2* __restrict__ cs_tab) {
   __shared__ __attribute__((aligned(16))) char sT[VG * VT_SROW];
   using T = __hip_bfloat16;
   int b = blockIdx.x;
   if (b < nb_k) {
     append_rows<T, VT_D>(b % gx_k, b / gx_k, 0, k_in, v_in, k_cache, v_cache, pos4, inv_freq, slot0, n, n_kv_heads,
-                         head_stride_elems, rope_mode, s0, s01);
+                         head_stride_elems, rope_mode, s0, s01, cs_tab);
     return;
   }
   b -= nb_k;
@@ -425,7 +438,10 @@ hipError_t launch_store_tokens_vt(const sv_cache* c, int stream, int layer, int6
                      (const __hip_bfloat16*)k, (const __hip_bfloat16*)v, (__hip_bfloat16*)c->kv_ptr(stream, cur, layer, 0),
                      (__hip_bfloat16*)c->kv_ptr(stream, cur, layer, 1), c->meta[cur].pos4 + off, c->inv_freq, slot0, n, Hq,
                      Hkv, c->head_stride / 2, c->cfg.rope_mode, c->cfg.mrope_sections[0],
-                     c->cfg.mrope_sections[0] + c->cfg.mrope_sections[1], gx_k, nb_k, nb_q, blk0, n_blk);
+                     c->cfg.mrope_sections[0] + c->cfg.mrope_sections[1], gx_k, nb_k, nb_q, blk0, n_blk,
+                     c->st[stream].cs_tab_valid && c->st[stream].pending_slot0 == slot0 && c->st[stream].pending_n == n
+                         ? c->cs_tab + (size_t)stream * c->cfg.max_q_tokens * (VT_D / 2)
+                         : nullptr);
   return hipGetLastError();
 }
 

@@ -751,8 +751,9 @@ def test_budget_sweep_and_no_evict_mode(n_sink, vision_window, text_window):
 def test_probe_rates_are_plausible():
     """The measurement aid returns the device's sustained rates: below the published peaks, well above zero."""
     buf = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0").fill_(1.0)      # 1 GiB
-    tflops, gbs = sv.sv_probe_rates(buf)
+    tflops, tflops_rnd, gbs = sv.sv_probe_rates(buf)
     assert 500.0 < tflops <= 2600.0, tflops
+    assert 500.0 < tflops_rnd <= tflops * 1.05, (tflops_rnd, tflops)
     assert 1000.0 < gbs <= 8200.0, gbs
     with pytest.raises(sv.SvError):
         sv.sv_probe_rates(buf[:16])            # smaller than the 1 MiB the probe asks for
