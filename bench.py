@@ -47,7 +47,7 @@ def parse_args():
                          "default workload), whatever this says")
     ap.add_argument("--workload", default="qwen7b_256v_28L",
                     choices=["qwen7b_256v_28L", "qwen7b_1024v_28L", "decode_ragged16", "decode_noevict32k",
-                             "noevict_growth", "budget_sweep", "overlap_recompute"])
+                             "noevict_growth", "budget_sweep", "overlap_recompute", "decode_timeline"])
     ap.add_argument("--max-tokens", type=int, default=131072, help="noevict_growth: cache length to grow to")
     ap.add_argument("--layers", type=int, default=28)
     ap.add_argument("--pool", type=int, default=6, help="distinct pre-generated chunks cycled through")
@@ -78,6 +78,10 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     dev = "cuda:0"
     torch.cuda.set_device(0)
+
+    if args.workload == "decode_timeline":
+        print(json.dumps(decode_timeline_bench(args)))
+        return
 
     if args.workload.startswith("decode_"):
         print(json.dumps(decode_batch_bench(args)))
@@ -348,6 +352,75 @@ def decode_batch_bench(args, with_ceiling=True):
                      "algorithmic_bytes_per_launch": bytes_layer,
                      "frac_of_measured_ceiling": round(gbs / ceil["hbm_read_gbs"], 4) if ceil else None},
     }
+
+
+def decode_timeline_bench(args):
+    """In-kernel timeline of the single-stream decode step (measurement build libsv_timeline.so: the two decode
+    kernels stamp the 100 MHz real-time counter at entry, when the first tile's loads have landed, after the tile
+    work, and when their stores are acknowledged).  One stream of the default workload's steady-state length, 28
+    layers; the last 8 launches of a 16-step decode sweep are read back and laid out on the common clock."""
+    import ctypes as C
+
+    import numpy as np
+    import torch
+
+    from paper_2510_09608_amd import binding as B
+    B.lib_path = lambda: os.path.join(ROOT, "paper_2510_09608_amd", "libsv_timeline.so")   # before the first call
+    import paper_2510_09608_amd as sv
+    dev = "cuda:0"
+    L, Hq, Hkv, d, N, steps = args.layers, 28, 4, 128, 5376, 16
+    cache = sv.Cache(L, Hq, Hkv, d, sv.SV_DTYPE_BF16, sv.SV_ROPE_3D, 1e6, (16, 24, 24), 1, N + 4096, 256)
+    g = torch.Generator(device=dev).manual_seed(1)
+    rnd = lambda *shape: torch.randn(*shape, device=dev, generator=g).to(torch.bfloat16)
+    ty = np.zeros(N, dtype=np.uint8)
+    for l in range(L):
+        cache.append(0, l, ty if l == 0 else None, None, rnd(N, Hkv, d), rnd(N, Hkv, d))
+    q, kn, vn = rnd(steps, L, 1, Hq, d), rnd(steps, L, 1, Hkv, d), rnd(steps, L, 1, Hkv, d)
+    o = torch.empty(steps, L, Hq, d, device=dev, dtype=torch.bfloat16)
+    INF = sv.SV_WINDOW_INF
+    sweep = lambda: cache.stream_step(0, 512, INF, INF, q_text=q, k_text=kn, v_text=vn, o_text=o)
+    ts = torch.zeros(8 * 2 * 1024 * 8, dtype=torch.int64, device=dev)
+    lib = B.lib()
+    lib.sv_timeline_set.restype, lib.sv_timeline_set.argtypes = C.c_int, [C.c_void_p, C.POINTER(C.c_int)]
+    n0 = C.c_int(0)
+    for _ in range(3):
+        sweep()
+    torch.cuda.synchronize()
+    assert lib.sv_timeline_set(ts.data_ptr(), C.byref(n0)) == 0
+    sweep()
+    torch.cuda.synchronize()
+    n1 = C.c_int(0)
+    assert lib.sv_timeline_set(None, C.byref(n1)) == 0
+    r = ts.cpu().numpy().reshape(8, 2, 1024, 8).astype(np.float64) / 100.0      # microseconds on the device clock
+    launches = [(n1.value - 8 + i) % 8 for i in range(8)]                       # slots of the last 8 launches, in order
+    med = lambda x: float(np.median(x))
+    rows, ends = [], []
+    for idx, sl in enumerate(launches):
+        dk, mk = r[sl, 0], r[sl, 1]
+        dk, mk = dk[dk[:, 0] > 0], mk[mk[:, 0] > 0]
+        work = dk[dk[:, 3] > 0]                                                  # workgroups that had keys
+        t0 = dk[:, 0].min()
+        row = {"decode_workgroups": int(len(work)), "decode_dispatch_spread": dk[:, 0].max() - t0,
+               "decode_entry_to_first_data": med(work[:, 1] - work[:, 0]),
+               "decode_tile_work": med(work[:, 2] - work[:, 1]),
+               "decode_lds_merge_and_stores": med(work[:, 3] - work[:, 2]),
+               "decode_first_entry_to_last_end": work[:, 3].max() - t0,
+               "gap_decode_end_to_merge_entry": mk[:, 0].min() - work[:, 3].max(),
+               "merge_first_entry_to_last_end": mk[:, 1].max() - mk[:, 0].min()}
+        if ends:
+            row["gap_merge_end_to_next_decode_entry"] = t0 - ends[-1][1]
+            row["layer_step_period"] = t0 - ends[-1][0]
+        ends.append((t0, mk[:, 1].max()))
+        rows.append(row)
+    keys = sorted({k for row in rows for k in row})
+    summary = {k: round(med([row[k] for row in rows if k in row]), 2) for k in keys}
+    cache.close()
+    return {"metric": "in-kernel timeline of one decode layer-step", "unit": "us", "value": summary.get("layer_step_period"),
+            "config": {"workload": f"decode_timeline: one stream, {N + 64}-{N + 128} cached tokens, {L} layers, "
+                                   f"{Hq}q/{Hkv}kv heads x {d}; medians over the last 8 launches of a 16-step sweep"},
+            "n_gpus": 1, "dtype": "bf16", "data": "synthetic", "timeline_us": summary, "per_launch": rows,
+            "note": "libsv_timeline.so (same sources, -DSV_TIMELINE); the stamps and the two extra waits cost a few "
+                    "tenths of a microsecond per launch"}
 
 
 def _stream_setup(L, cap, w, n_sink, vision_window, text_window, preamble, pool_n, max_q=None):

@@ -306,23 +306,6 @@ SV_API int sv_cache_retained(sv_cache* c, int stream_id, int64_t* ids_host, int3
 SV_API int sv_cache_read_kv(sv_cache* c, int stream_id, int layer, int which, int64_t slot0,
                      int64_t n, void* dst_host, void* hip_stream);
 
-/*
- * sv_probe_rates -- measurement aid, SYNCHRONOUS; implements no passage of the
- * paper.  Measures what the device sustains, for setting the attention
- * kernels' roofline fractions (taken against the published peaks) beside the
- * achievable ceilings: *mfma_tflops_out = dense bf16 rate of a register-only
- * v_mfma_f32_32x32x16_bf16 loop on every SIMD with constant small-integer
- * operands, *mfma_tflops_random_out = the same loop on pseudo-random operands
- * (the clock under a full-chip matrix load is well below the boost clock, and
- * lower still when the multipliers see real data); *hbm_read_gbs_out = rate of a
- * streaming read of dev_buf[0, bytes) (use a buffer several times the 256 MB
- * memory-side cache).  Any output may be NULL (that probe is skipped).
- * dev_buf: device memory, 16-byte aligned, >= 1 MiB, read only (its first
- * word is written only if a data-dependent condition that cannot occur holds).
- */
-SV_API int sv_probe_rates(void* dev_buf, size_t bytes, double* mfma_tflops_out, double* mfma_tflops_random_out,
-                          double* hbm_read_gbs_out, void* hip_stream);
-
 #ifdef __cplusplus
 }
 #endif

@@ -25,9 +25,12 @@ FLAGS = [
 ]
 
 
-def _compile(src: str) -> str:
-    obj = os.path.join(OBJDIR, os.path.basename(src) + ".o")
-    cmd = [HIPCC, *FLAGS, "-c", src, "-o", obj]
+OUT_TIMELINE = os.path.join(HERE, "libsv_timeline.so")   # measurement build: decode kernels stamp a timeline
+
+
+def _compile(src: str, extra=(), tag: str = "") -> str:
+    obj = os.path.join(OBJDIR, os.path.basename(src) + tag + ".o")
+    cmd = [HIPCC, *FLAGS, *extra, "-c", src, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(l for l in r.stderr.splitlines() if noise not in l)
@@ -38,17 +41,25 @@ def _compile(src: str) -> str:
     return obj
 
 
-def build(verbose: bool = True) -> str:
-    os.makedirs(OBJDIR, exist_ok=True)
-    srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
-    with cf.ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
-        objs = list(ex.map(_compile, srcs))
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", OUT, *objs]
-    r = subprocess.run(cmd, capture_output=True, text=True)
+def _link(out: str, objs) -> None:
+    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out, *objs], capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stderr)
+
+
+def build(verbose: bool = True) -> str:
+    """libsv.so (the product) and libsv_timeline.so (the same sources with -DSV_TIMELINE: only bench.py's
+    decode_timeline workload loads it)."""
+    os.makedirs(OBJDIR, exist_ok=True)
+    srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
+    with cf.ThreadPoolExecutor(max_workers=min(8, len(srcs) + 1)) as ex:
+        objs = list(ex.map(_compile, srcs))
+        dec = [s for s in srcs if s.endswith("sv_attn_decode.hip")][0]
+        dec_tl = ex.submit(_compile, dec, ("-DSV_TIMELINE",), ".timeline").result()
+    _link(OUT, objs)
+    _link(OUT_TIMELINE, [dec_tl if o.endswith("sv_attn_decode.hip.o") else o for o in objs])
     if verbose:
-        print(f"built {OUT} from {len(srcs)} sources")
+        print(f"built {OUT} and {OUT_TIMELINE} from {len(srcs)} sources")
     return OUT
 
 

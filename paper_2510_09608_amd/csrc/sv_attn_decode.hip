@@ -34,6 +34,27 @@
 
 #include "sv_internal.h"
 
+// Measurement build (-DSV_TIMELINE, libsv_timeline.so): the two decode kernels stamp the 100 MHz real-time counter at
+// a few points into a buffer set with sv_timeline_set, so that one decode step can be laid out on a common clock
+// (dispatch, first memory round trip, tile work, merge through LDS, stores, the gap to the merge kernel).  The
+// product build compiles none of it.
+#ifdef SV_TIMELINE
+static __device__ unsigned long long* g_ts = nullptr;   // [8 launch slots][2 kernels][1024 workgroups][8]
+#define SV_TS_PARAM , int ts_slot
+#define SV_TS_ARG(x) , x
+#define SV_TS(kind, wg, i)                                                                                     \
+  do {                                                                                                         \
+    if (g_ts != nullptr && threadIdx.x == 0 && (wg) < 1024)                                                    \
+      g_ts[((((size_t)ts_slot * 2 + (kind)) * 1024 + (wg)) << 3) + (i)] = __builtin_amdgcn_s_memrealtime();     \
+  } while (0)
+#else
+#define SV_TS_PARAM
+#define SV_TS_ARG(x)
+#define SV_TS(kind, wg, i) \
+  do {                     \
+  } while (0)
+#endif
+
 namespace sv {
 namespace {
 
@@ -107,7 +128,9 @@ __global__ __launch_bounds__(NW * 64, 2) void k_decode_mfma(__hip_bfloat16* k0_,
                                                          size_t head_stride_elems, int fused, int rotate,
                                                          __hip_bfloat16* __restrict__ out, float* __restrict__ part_o,
                                                          float* __restrict__ part_ml, int n_splits, int n_q_heads,
-                                                         int n_kv_heads, int G, float c_log2, DecTable tab) {
+                                                         int n_kv_heads, int G, float c_log2, DecTable tab SV_TS_PARAM) {
+  [[maybe_unused]] const int ts_wg = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
+  SV_TS(0, ts_wg, 0);
   __shared__ float sO[NW][GMAX][D];                                 // wavefront results (merge)
   __shared__ float sML[NW][GMAX][2];
 
@@ -207,6 +230,10 @@ __global__ __launch_bounds__(NW * 64, 2) void k_decode_mfma(__hip_bfloat16* k0_,
 #pragma unroll
   for (int blk = 0; blk < 8; ++blk) oacc[blk] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
+#ifdef SV_TIMELINE
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // (measurement build only) the first tile's loads have landed
+  SV_TS(0, ts_wg, 1);
+#endif
   for (int t = wave; t < n_tiles; t += NW) {
     const int kt = k0 + t * TK;
     if (fused && len - 1 >= kt && len - 1 < kt + TK) {
@@ -287,6 +314,7 @@ __global__ __launch_bounds__(NW * 64, 2) void k_decode_mfma(__hip_bfloat16* k0_,
     if (t + NW < n_tiles) issue_v(kt + NW * TK);
   }
 
+  SV_TS(0, ts_wg, 2);
   // ---- wavefront result to LDS: head l16 < G, dims 16 blk + 4 lg + r; the sum of a head is spread over
   // the four lane groups
   l_run += __shfl_xor(l_run, 16);
@@ -327,6 +355,10 @@ __global__ __launch_bounds__(NW * 64, 2) void k_decode_mfma(__hip_bfloat16* k0_,
       }
     }
   }
+#ifdef SV_TIMELINE
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // (measurement build only) the stores have been acknowledged
+  SV_TS(0, ts_wg, 3);
+#endif
 }
 
 // ---------------------------------------------------------------------------------
@@ -339,7 +371,9 @@ __global__ __launch_bounds__(NW * 64, 2) void k_decode_mfma(__hip_bfloat16* k0_,
 __global__ __launch_bounds__(128) void k_decode_merge(const float* __restrict__ part_o,
                                                       const float* __restrict__ part_ml,
                                                       __hip_bfloat16* __restrict__ out, int n_splits, int n_q_heads,
-                                                      RangeCounts cnt) {
+                                                      RangeCounts cnt SV_TS_PARAM) {
+  [[maybe_unused]] const int ts_wg = blockIdx.y * gridDim.x + blockIdx.x;
+  SV_TS(1, ts_wg, 0);
   __shared__ float4 s_acc[4][32];
   __shared__ float2 s_ml[4];
   const int h = blockIdx.x, b = blockIdx.y, g = threadIdx.x >> 5, d4 = threadIdx.x & 31;
@@ -396,7 +430,15 @@ __global__ __launch_bounds__(128) void k_decode_merge(const float* __restrict__ 
   const uint32_t w0 = bf_round_bits(tot.x * inv) | (bf_round_bits(tot.y * inv) << 16);
   const uint32_t w1 = bf_round_bits(tot.z * inv) | (bf_round_bits(tot.w * inv) << 16);
   *(uint2*)op = make_uint2(w0, w1);
+#ifdef SV_TIMELINE
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+  SV_TS(1, ts_wg, 1);
+#endif
 }
+
+#ifdef SV_TIMELINE
+int g_ts_launch = 0;   // host: launches so far; the slot of a launch is this modulo 8
+#endif
 
 }  // namespace
 
@@ -454,19 +496,25 @@ static hipError_t decode_launch(const sv_cache* c, const DecTable& tab, int fuse
   if (nr == 1 && !stream_loads)
     hipLaunchKernelGGL((k_decode_mfma<NW, true, false>), dim3(n_splits, Hkv, 1), dim3(NW * 64), 0, s, r.k, r.v, r.cs, r.len,
                        keys_per_split, qp, knp, vnp, c->head_stride / 2, fused, rotate, op, part_o, part_ml,
-                       n_splits, Hq, Hkv, c->group, c_log2, tabk);
+                       n_splits, Hq, Hkv, c->group, c_log2, tabk SV_TS_ARG(g_ts_launch % 8));
   else if (stream_loads)
     hipLaunchKernelGGL((k_decode_mfma<NW, false, true>), dim3(n_splits, Hkv, nr), dim3(NW * 64), 0, s, r.k, r.v, r.cs, r.len,
                        keys_per_split, qp, knp, vnp, c->head_stride / 2, fused, rotate, op, part_o, part_ml,
-                       n_splits, Hq, Hkv, c->group, c_log2, tabk);
+                       n_splits, Hq, Hkv, c->group, c_log2, tabk SV_TS_ARG(g_ts_launch % 8));
   else
     hipLaunchKernelGGL((k_decode_mfma<NW, false, false>), dim3(n_splits, Hkv, nr), dim3(NW * 64), 0, s, r.k, r.v, r.cs, r.len,
                        keys_per_split, qp, knp, vnp, c->head_stride / 2, fused, rotate, op, part_o, part_ml,
-                       n_splits, Hq, Hkv, c->group, c_log2, tabk);
+                       n_splits, Hq, Hkv, c->group, c_log2, tabk SV_TS_ARG(g_ts_launch % 8));
   hipError_t e = hipGetLastError();
+#ifdef SV_TIMELINE
+  if (e != hipSuccess || n_splits == 1) ++g_ts_launch;
+#endif
   if (e != hipSuccess || n_splits == 1) return e;
   hipLaunchKernelGGL(k_decode_merge, dim3(Hq, nr), dim3(128), 0, s, part_o, part_ml,
-                     (__hip_bfloat16*)o + r0 * Hq * D, n_splits, Hq, cnt);
+                     (__hip_bfloat16*)o + r0 * Hq * D, n_splits, Hq, cnt SV_TS_ARG(g_ts_launch % 8));
+#ifdef SV_TIMELINE
+  ++g_ts_launch;
+#endif
   return hipGetLastError();
 }
 
@@ -543,3 +591,14 @@ hipError_t launch_attn_decode_mfma_static(const sv_cache* c, int layer, const in
 }
 
 }  // namespace sv
+
+#ifdef SV_TIMELINE
+// Measurement build only: where the decode kernels stamp their timeline (device memory of at least
+// SV_TIMELINE_BYTES bytes, zeroed by the caller; NULL switches stamping off), and how many decode launches have
+// been enqueued so far (the slot a launch stamps into is its index modulo 8).
+extern "C" __attribute__((visibility("default"))) int sv_timeline_set(void* dev_buf, int* launches_out) {
+  if (launches_out) *launches_out = sv::g_ts_launch;
+  unsigned long long* p = (unsigned long long*)dev_buf;
+  return hipMemcpyToSymbol(HIP_SYMBOL(g_ts), &p, sizeof(p)) == hipSuccess ? SV_OK : SV_ERR_HIP;
+}
+#endif

@@ -8,7 +8,7 @@
 #include <hip/hip_bf16.h>
 #include <hip/hip_runtime.h>
 
-#include "sv.h"
+#include "sv_probe.h"
 
 namespace {
 

@@ -10,8 +10,12 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _declared():
-    text = open(os.path.join(ROOT, "include", "sv.h")).read()
-    return re.findall(r"SV_API\s+[\w\s\*]+?\b(sv_\w+)\s*\(", text)
+    names = []
+    inc = os.path.join(ROOT, "include")
+    for fn in sorted(os.listdir(inc)):
+        if fn.endswith(".h"):
+            names += re.findall(r"SV_API\s+[\w\s\*]+?\b(sv_\w+)\s*\(", open(os.path.join(inc, fn)).read())
+    return names
 
 
 def _lib():
