@@ -28,7 +28,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on the default workload, scaled by
 # what a plain 1 GiB copy reads on the same counters (fetch x2.00, write x1.00); profiles/hbm_traffic_*.txt.
 MEASURED_TRAFFIC = {
-    # attn_chunk = k_chunk_prologue + k_attn_chunk_pipe + k_attn_combine; decode_sweep = k_decode_mfma + k_decode_merge;
+    # attn_chunk = k_chunk_prologue + k_attn_chunk_pipe + k_attn_combine; decode_sweep = k_decode_mfma (key ranges merged in the same launch);
     # evict = k_evict_scan + k_delta_table + k_compact (reads + writes, scaled counters)
     "qwen7b_256v_28L": {"attn_chunk": (7.4e6 + 7.1e6) + (13.3e6 + 28.6e6) + (31.5e6 + 1.8e6),
                         "decode_sweep": (9.32e6 + 0.52e6) + (0.66e6 + 0.01e6),
@@ -346,7 +346,7 @@ def decode_batch_bench(args, with_ceiling=True):
         "config": {"workload": f"{args.workload}: 16 streams, total {sum(lens)} cached tokens, {L} layers per sweep, "
                                f"{Hq}q/{Hkv}kv heads x {d}; one query token per stream per layer",
                    "lens": lens},
-        "roofline": {"kernel": "k_decode_mfma + k_decode_merge (per layer, incl. launch gaps)", "bound": "hbm",
+        "roofline": {"kernel": "k_decode_mfma (per layer, key ranges merged in the same launch, incl. launch gaps)", "bound": "hbm",
                      "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
                      "traffic": None, "avg_launch_us": round(us_layer, 2), "launches": args.steps * L,
                      "algorithmic_bytes_per_launch": bytes_layer,
@@ -355,9 +355,10 @@ def decode_batch_bench(args, with_ceiling=True):
 
 
 def decode_timeline_bench(args):
-    """In-kernel timeline of the single-stream decode step (measurement build libsv_timeline.so: the two decode
-    kernels stamp the 100 MHz real-time counter at entry, when the first tile's loads have landed, after the tile
-    work, and when their stores are acknowledged).  One stream of the default workload's steady-state length, 28
+    """In-kernel timeline of the single-stream decode step (measurement build libsv_timeline.so: the decode
+    kernel stamps the 100 MHz real-time counter at entry, when the first tile's loads have landed, after the tile
+    work, when its partial result's stores are acknowledged, when its merge reads have all seen their tags, and at
+    its end).  One stream of the default workload's steady-state length, 28
     layers; the last 8 launches of a 16-step decode sweep are read back and laid out on the common clock."""
     import ctypes as C
 
@@ -396,21 +397,25 @@ def decode_timeline_bench(args):
     med = lambda x: float(np.median(x))
     rows, ends = [], []
     for idx, sl in enumerate(launches):
-        dk, mk = r[sl, 0], r[sl, 1]
-        dk, mk = dk[dk[:, 0] > 0], mk[mk[:, 0] > 0]
-        work = dk[dk[:, 3] > 0]                                                  # workgroups that had keys
-        t0 = dk[:, 0].min()
-        row = {"decode_workgroups": int(len(work)), "decode_dispatch_spread": dk[:, 0].max() - t0,
+        dk = r[sl, 0]
+        dk = dk[dk[:, 0] > 0]
+        work = dk[dk[:, 2] > 0]                                                  # workgroups that had keys
+        mrg = work[work[:, 4] > 0]                                               # ... and a piece of the merge
+        t0, t_end = dk[:, 0].min(), mrg[:, 5].max()
+        row = {"decode_workgroups": int(len(work)), "merging_workgroups": int(len(mrg)),
+               "decode_dispatch_spread": dk[:, 0].max() - t0,
                "decode_entry_to_first_data": med(work[:, 1] - work[:, 0]),
                "decode_tile_work": med(work[:, 2] - work[:, 1]),
-               "decode_lds_merge_and_stores": med(work[:, 3] - work[:, 2]),
-               "decode_first_entry_to_last_end": work[:, 3].max() - t0,
-               "gap_decode_end_to_merge_entry": mk[:, 0].min() - work[:, 3].max(),
-               "merge_first_entry_to_last_end": mk[:, 1].max() - mk[:, 0].min()}
+               "decode_lds_merge_and_partial_stores": med(mrg[:, 3] - mrg[:, 2]),
+               "last_partial_stored_after_first_entry": mrg[:, 3].max() - t0,
+               "merge_wait_and_reads_after_own_store": med(mrg[:, 4] - mrg[:, 3]),
+               "merge_reads_done_after_last_partial_stored": mrg[:, 4].max() - mrg[:, 3].max(),
+               "merge_combine_and_output_store": med(mrg[:, 5] - mrg[:, 4]),
+               "decode_first_entry_to_last_end": t_end - t0}
         if ends:
-            row["gap_merge_end_to_next_decode_entry"] = t0 - ends[-1][1]
+            row["gap_end_to_next_decode_entry"] = t0 - ends[-1][1]
             row["layer_step_period"] = t0 - ends[-1][0]
-        ends.append((t0, mk[:, 1].max()))
+        ends.append((t0, t_end))
         rows.append(row)
     keys = sorted({k for row in rows for k in row})
     summary = {k: round(med([row[k] for row in rows if k in row]), 2) for k in keys}
@@ -419,7 +424,7 @@ def decode_timeline_bench(args):
             "config": {"workload": f"decode_timeline: one stream, {N + 64}-{N + 128} cached tokens, {L} layers, "
                                    f"{Hq}q/{Hkv}kv heads x {d}; medians over the last 8 launches of a 16-step sweep"},
             "n_gpus": 1, "dtype": "bf16", "data": "synthetic", "timeline_us": summary, "per_launch": rows,
-            "note": "libsv_timeline.so (same sources, -DSV_TIMELINE); the stamps and the two extra waits cost a few "
+            "note": "libsv_timeline.so (same sources, -DSV_TIMELINE); the stamps and the extra waits cost a few "
                     "tenths of a microsecond per launch"}
 
 
@@ -644,7 +649,7 @@ def instrumented_pass(cache, run, pool, w, L, c0, ov, ot_all, n_chunks: int, tra
 
     roofs = [roof("k_chunk_prologue + k_attn_chunk_pipe + k_attn_combine (chunk prefill of one layer: K/V store, Q rotation "
                   "and V^T staging, attention, split merge)", "attn_chunk", "mfma", MFMA_BF16_PEAK_TFLOPS, "TFLOP/s", 1e12, L),
-             roof("k_decode_mfma + k_decode_merge (fused decode step of one layer)", "decode_sweep", "hbm",
+             roof("k_decode_mfma (fused decode step of one layer: append, RoPE, attention, merge of the key ranges)", "decode_sweep", "hbm",
                   HBM_PEAK_GBS, "GB/s", 1e9, L * nt),
              roof("k_compact (+ scan, shift table)", "evict", "hbm", HBM_PEAK_GBS, "GB/s", 1e9, 1)]
     return {"us": us, "ms_per_chunk": round(ms_per_chunk, 3), "roofline_all": roofs,

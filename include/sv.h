@@ -205,10 +205,13 @@ SV_API int sv_attn_decode(sv_cache* c, int layer, const int32_t* stream_ids_host
  * (static storage, one copy per GPU, held until the process ends) instead of the arena's scratch region,
  * and the call allocates nothing, on the host or on the device.  Limits: bf16 / head_dim 128 / at most 8
  * query heads per kv head (else SV_ERR_UNSUPPORTED); n_list <= SV_STATIC_MAX_ROWS and
- * n_list * n_q_heads * 520 bytes <= 8 MiB (else SV_ERR_CAPACITY); rows longer than the array's share are
+ * n_list * n_q_heads * 516 bytes <= 4 MiB (else SV_ERR_CAPACITY); rows longer than the array's share are
  * cut into fewer, longer key ranges.  Every call on one GPU shares the array: calls that overlap in time on
- * one GPU (different streams, different handles) race; calls ordered on one stream do not.  Nothing in the
- * array needs clearing between calls: every entry a call reads it has written itself.
+ * one GPU (different streams, different handles) race; calls ordered on one stream do not.  The array is
+ * zero when the library is loaded and needs no clearing between calls: half of it holds the plain partial
+ * results of multi-row calls, every entry of which a call writes before its merge launch reads it; the other
+ * half holds those of one-row calls as 64-bit words {value, call number}, which the call's own workgroups read
+ * until they see the number of this call (the library clears that half itself when the 32-bit number wraps).
  */
 #define SV_STATIC_MAX_ROWS 64
 SV_API int sv_attn_decode_static(sv_cache* c, int layer, const int32_t* stream_ids_host, int n_list,

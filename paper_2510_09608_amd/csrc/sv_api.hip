@@ -16,6 +16,12 @@ namespace {
 constexpr size_t kAlign = 256;
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
+// bf16, head_dim 128, at most 8 query heads per kv head and no SV_FLAG_GENERIC_KERNELS: the matrix-core kernels
+bool mfma_eligible(const sv_config& c) {
+  return c.dtype == SV_DTYPE_BF16 && c.head_dim == 128 && c.n_q_heads / c.n_kv_heads <= 8 &&
+         !(c.flags & SV_FLAG_GENERIC_KERNELS);
+}
+
 bool config_ok(const sv_config* c) {
   if (!c) return false;
   if (c->n_layers < 1 || c->n_kv_heads < 1 || c->n_q_heads < 1 || c->n_streams < 1) return false;
@@ -43,8 +49,9 @@ bool config_ok(const sv_config* c) {
 // sv_cache_bytes and sv_cache_create cannot disagree.
 struct Layout {
   size_t kv, meta_gid[2], meta_rank[2], meta_pos[2], meta_local[2], meta_blk[2], meta_type[2];
-  size_t src, delta, dtab, next_pos, n_dev, inv_freq, last_cs, cs_tab, part_o, part_ml, counters, total;
+  size_t src, delta, dtab, next_pos, n_dev, inv_freq, last_cs, cs_tab, part_o, part_ml, counters, part_dec, total;
   int64_t part_rows;
+  size_t part_dec_bytes;
 };
 
 Layout make_layout(const sv_config& c) {
@@ -79,6 +86,9 @@ Layout make_layout(const sv_config& c) {
   L.part_o = take((size_t)L.part_rows * c.n_q_heads * c.head_dim * 4);
   L.part_ml = take((size_t)L.part_rows * c.n_q_heads * 4 * 4);   // up to 4 floats per (row, range, head)
   L.counters = take((size_t)L.part_rows * c.n_kv_heads * 4);
+  // matrix-core decode, single stream: tagged words of up to 128 key ranges
+  L.part_dec_bytes = mfma_eligible(c) ? sv::decode_tagged_bytes(c) : 0;
+  L.part_dec = take(L.part_dec_bytes);
   L.total = off;
   return L;
 }
@@ -184,10 +194,10 @@ int sv_cache_create(const sv_config* cfg, void* dev_arena, size_t arena_bytes, v
   c->part_ml = (float*)(base + L.part_ml);
   c->part_rows = L.part_rows;
   c->counters = (int32_t*)(base + L.counters);
+  c->part_dec = (unsigned long long*)(base + L.part_dec);
   c->st.resize(cfg->n_streams);
   for (auto& s : c->st) s.layer_len.assign(cfg->n_layers, 0);
-  c->use_mfma = cfg->dtype == SV_DTYPE_BF16 && cfg->head_dim == 128 && c->group <= 8 &&
-                !(cfg->flags & SV_FLAG_GENERIC_KERNELS);
+  c->use_mfma = mfma_eligible(*cfg);
   c->v_blocked = c->use_mfma;
 
   // rotary frequencies theta^(-2i/d), computed once in double
@@ -206,6 +216,7 @@ int sv_cache_create(const sv_config* cfg, void* dev_arena, size_t arena_bytes, v
   if (e == hipSuccess) e = hipMemsetAsync(c->next_pos, 0, (size_t)cfg->n_streams * 2 * 4, s);
   if (e == hipSuccess) e = hipMemsetAsync(c->n_dev, 0, (size_t)cfg->n_streams * 4, s);
   if (e == hipSuccess) e = hipMemsetAsync(c->counters, 0, (size_t)L.part_rows * cfg->n_kv_heads * 4, s);
+  if (e == hipSuccess && L.part_dec_bytes > 0) e = hipMemsetAsync(c->part_dec, 0, L.part_dec_bytes, s);
   // blocked V^T: slots past a stream's end inside its last block are multiplied by probabilities of zero and must
   // never hold NaN patterns, so the store starts out cleared
   if (e == hipSuccess && c->v_blocked)

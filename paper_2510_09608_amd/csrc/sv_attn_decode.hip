@@ -23,10 +23,15 @@
 //     (V as one 2-byte element per head dim into its V^T block);
 //   * all global loads of a tile are issued before anything else the wavefront does;
 //   * wavefronts of a workgroup take alternate tiles of the workgroup's key range and
-//     are merged through LDS; key ranges are merged by a second, tiny kernel whose
-//     threads issue all their loads at once (an in-kernel merge by the last workgroup
-//     to arrive was measured slower: the device-scope fences it needs cost more than
-//     a launch).
+//     are merged through LDS into the range's partial result: normalised values and the
+//     log-sum-exp.  A single stream's key ranges are merged INSIDE the same launch, with
+//     no fence and no counter: a workgroup publishes its partial result as 64-bit words
+//     {fp32 value, 32-bit launch tag} with relaxed device-scope atomic stores, and the
+//     workgroups of a kv head share out the result, each reading the words of all ranges
+//     with relaxed device-scope atomic loads until every word carries this launch's tag
+//     (see merge_ranges).  (A merge by the last workgroup to arrive needs device-scope
+//     release/acquire fences, about 3 us each here; a second launch costs its gap and a
+//     round trip of its own.)  A batch's key ranges are merged by a second, small launch.
 
 #include <hip/hip_bf16.h>
 
@@ -47,9 +52,21 @@ static __device__ unsigned long long* g_ts = nullptr;   // [8 launch slots][2 ke
     if (g_ts != nullptr && threadIdx.x == 0 && (wg) < 1024)                                                    \
       g_ts[((((size_t)ts_slot * 2 + (kind)) * 1024 + (wg)) << 3) + (i)] = __builtin_amdgcn_s_memrealtime();     \
   } while (0)
+#define SV_TS_VAL(wg, i, v)                                                                                   \
+  do {                                                                                                         \
+    if (g_ts != nullptr && threadIdx.x == 0 && (wg) < 1024)                                                    \
+      g_ts[((((size_t)ts_slot * 2) * 1024 + (wg)) << 3) + (i)] = (v);                                          \
+  } while (0)
+#define SV_TS_COUNT(v) ++(v)
 #else
 #define SV_TS_PARAM
 #define SV_TS_ARG(x)
+#define SV_TS_VAL(wg, i, v) \
+  do {                      \
+  } while (0)
+#define SV_TS_COUNT(v) \
+  do {                 \
+  } while (0)
 #define SV_TS(kind, wg, i) \
   do {                     \
   } while (0)
@@ -66,6 +83,8 @@ constexpr int GMAX = 8;       // query heads per kv head this kernel handles
 constexpr int TK = 32;        // keys per wavefront tile
 constexpr int kMaxSplitsD = 128;
 constexpr int kMaxRowsD = 64;
+constexpr int PW = D + 1;      // tagged words a key range publishes per query head: 128 values and the log-sum-exp
+constexpr int kPollLimit = 1 << 16;   // polls of a merge read before giving up (each is a memory round trip)
 
 struct DecRow {
   __hip_bfloat16* k;         // K of the layer: kv head 0, slot 0 (written only at the slot of a fused new token)
@@ -73,9 +92,7 @@ struct DecRow {
   const float2* cs;          // cos/sin of the query token's rotary angles, [64]
   int32_t len;               // visible keys: slots [0, len), the query token is slot len - 1
   int32_t kps;               // keys per key range of this row (a multiple of 128); ranges = ceil(len / kps)
-};
-struct RangeCounts {
-  uint8_t n[kMaxRowsD];      // key ranges of each row of a launch
+  int32_t pair0;             // index of the row's first key range among all (row, key range) pairs of the launch
 };
 struct DecTable {
   DecRow r[kMaxRowsD];
@@ -116,6 +133,116 @@ __device__ __forceinline__ void rotate_pair_chunks(uint4& lo, uint4& hi, const f
 }
 
 
+// ---------------------------------------------------------------------------------
+// Merge of the key ranges of one (row, kv head): outputs [o_lo, o_lo + n_out) of its G x 128 (n_out a multiple of 32),
+// by one workgroup of NT threads laid out as RG range groups x OPP outputs (RG = 8, 4, 2, 1 for up to 32, 64, 128,
+// more outputs): thread (rg, ol) reads output ol from the ranges rg, rg + RG, ... (8 per pass, all loads issued
+// before any is looked at) and the RG partial merges meet in LDS (3 NT floats at `lds`): one memory round trip
+// unless a row has more than 64 ranges or the workgroup more than NT outputs.
+// phk: the partial result of range 0, first query head of the kv head; range s adds s * sstride words, head g adds
+// g * PW words.  Words are plain floats, or (POLL) 64-bit {float, launch tag}.
+// POLL: the ranges are being written by other workgroups of the SAME launch: every word is read with a relaxed
+// device-scope atomic load, again and again until it carries this launch's tag.  Its writer, a workgroup that
+// waits for nothing, has then written it, and the value in the same word is the one that goes with it (a 64-bit
+// access is single-copy atomic, a word is written once per launch); no ordering between locations is needed.
+// Workgroups are dispatched in index order and the ranges of a (row, kv head) are neighbours in it, so whatever a
+// workgroup waits for is resident or next in line; the polls are bounded all the same.
+// ---------------------------------------------------------------------------------
+template <int NT, bool POLL>
+__device__ __forceinline__ void merge_ranges(const void* phk, size_t sstride, int nsr, uint32_t tag,
+                                             int o_lo, int n_out, float* lds, __hip_bfloat16* out_hk SV_TS_PARAM,
+                                             [[maybe_unused]] int ts_wg) {
+  static_assert(NT == 256 || NT == 128, "thread layout of the merge");
+  constexpr int LNT = NT == 256 ? 8 : 7;
+  const int tid = threadIdx.x;
+  const int lrg = n_out <= 32 ? 3 : n_out <= 64 ? 2 : n_out <= 128 ? 1 : 0;
+  const int RG = 1 << lrg, OPP = NT >> lrg;
+  float* s_acc = lds;   // [RG][OPP] weighted sums, then the same for reference exponents and weights
+  float* s_m = s_acc + NT;
+  float* s_w = s_m + NT;
+  const int ol = tid & (OPP - 1), rg = tid >> (LNT - lrg);
+  const unsigned long long tag_hi = (unsigned long long)tag << 32;
+  for (int ob = 0; ob < n_out; ob += OPP) {
+    const int o = o_lo + ob + (ob + ol < n_out ? ol : 0);
+    const int g = o >> 7, d = o & (D - 1);
+    const unsigned long long* pv = (const unsigned long long*)phk + (size_t)g * PW;   // POLL
+    const float* pf = (const float*)phk + (size_t)g * PW;                             // !POLL
+    float m_ref = -INFINITY, wsum = 0.f, acc = 0.f;
+    [[maybe_unused]] unsigned long long ts_tries = 0;
+    for (int s0 = rg; s0 < nsr; s0 += 8 * RG) {
+      unsigned long long wv[8], we[8];
+      bool ok = false;
+      for (int it = 0; it < kPollLimit && !ok; ++it) {
+        SV_TS_COUNT(ts_tries);
+        if (it >= 3) __builtin_amdgcn_s_sleep(2);
+        ok = true;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int si = s0 + RG * j;
+          if (si >= nsr) {
+            wv[j] = we[j] = tag_hi;
+          } else if constexpr (POLL) {
+            wv[j] = __hip_atomic_load(pv + (size_t)si * sstride + d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            we[j] = __hip_atomic_load(pv + (size_t)si * sstride + D, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          } else {
+            wv[j] = __float_as_uint(pf[(size_t)si * sstride + d]);
+            we[j] = __float_as_uint(pf[(size_t)si * sstride + D]);
+          }
+        }
+        if constexpr (POLL) {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) ok = ok && (uint32_t)(wv[j] >> 32) == tag && (uint32_t)(we[j] >> 32) == tag;
+        }
+      }
+      float mx = m_ref;
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (s0 + RG * j < nsr) mx = fmaxf(mx, __uint_as_float((uint32_t)we[j]));
+      // a read that never saw its tag (the limit is thousands of times any launch's length) poisons the output
+      if (!ok) mx = __uint_as_float(0x7fc00000u);
+      const float resc = m_ref == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_ref - mx);
+      acc *= resc, wsum *= resc;
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (s0 + RG * j < nsr) {
+          const float w = __builtin_amdgcn_exp2f(__uint_as_float((uint32_t)we[j]) - mx);
+          acc += w * __uint_as_float((uint32_t)wv[j]);
+          wsum += w;
+        }
+      m_ref = mx;
+    }
+    SV_TS(0, ts_wg, 4);
+    SV_TS_VAL(ts_wg, 6, ts_tries);
+    s_acc[tid] = acc, s_m[tid] = m_ref, s_w[tid] = wsum;   // tid = rg * OPP + ol
+    __syncthreads();
+    if (2 * tid < OPP && ob + 2 * tid < n_out) {   // two neighbouring dims per thread: one 4-byte store
+      const int oo = 2 * tid;
+      float mx = -INFINITY;
+      for (int k = 0; k < RG; ++k) mx = fmaxf(mx, s_m[k * OPP + oo]);   // a poisoned reference shows in w below
+      float t0 = 0.f, t1 = 0.f, wt = 0.f;
+      for (int k = 0; k < RG; ++k) {
+        const float mk = s_m[k * OPP + oo];
+        const float w = mk == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mk - mx);
+        t0 += w * s_acc[k * OPP + oo], t1 += w * s_acc[k * OPP + oo + 1];
+        wt += w * s_w[k * OPP + oo];
+      }
+      const float inv = 1.0f / wt;
+      const uint32_t w01 = bf_round_bits(t0 * inv) | (bf_round_bits(t1 * inv) << 16);
+      *(uint32_t*)(out_hk + o_lo + ob + oo) = w01;   // outputs of a kv head are contiguous: [head in group][128]
+    }
+    __syncthreads();
+  }
+}
+
+// The outputs of a (row, kv head) are shared out in runs of 32 among M workgroups; workgroup j of M takes
+// [o_lo, o_lo + n_out).  False if it gets none.
+__device__ __forceinline__ bool merge_share(int G, int M, int j, int& o_lo, int& n_out) {
+  const int n_units = G * 4, upw = (n_units + M - 1) / M;
+  o_lo = 32 * min(n_units, j * upw);
+  n_out = 32 * min(n_units, j * upw + upw) - o_lo;
+  return j < M && n_out > 0;
+}
+
 // ONE: a single row (one stream).  Its cache pointers, length and everything else needed to issue the first
 // loads are the leading 16 dwords of the argument list, which reach the wavefront in SGPRs at launch (kernel
 // argument preload) instead of through a first dependent fetch; the by-value table, at the end, is not read.
@@ -126,9 +253,9 @@ __global__ __launch_bounds__(NW * 64, 2) void k_decode_mfma(__hip_bfloat16* k0_,
                                                          const __hip_bfloat16* __restrict__ k_new,
                                                          const __hip_bfloat16* __restrict__ v_new,
                                                          size_t head_stride_elems, int fused, int rotate,
-                                                         __hip_bfloat16* __restrict__ out, float* __restrict__ part_o,
-                                                         float* __restrict__ part_ml, int n_splits, int n_q_heads,
-                                                         int n_kv_heads, int G, float c_log2, DecTable tab SV_TS_PARAM) {
+                                                         __hip_bfloat16* __restrict__ out, void* part,
+                                                         uint32_t tag, int n_q_heads, int n_kv_heads, int G,
+                                                         float c_log2, DecTable tab SV_TS_PARAM) {
   [[maybe_unused]] const int ts_wg = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
   SV_TS(0, ts_wg, 0);
   __shared__ float sO[NW][GMAX][D];                                 // wavefront results (merge)
@@ -138,10 +265,11 @@ __global__ __launch_bounds__(NW * 64, 2) void k_decode_mfma(__hip_bfloat16* k0_,
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, lg = lane >> 4;
   DecRow rd;
-  if constexpr (ONE) rd = DecRow{k0_, v0_, cs0_, len0_};
+  if constexpr (ONE) rd = DecRow{k0_, v0_, cs0_, len0_, keys_per_split, 0};
   else rd = tab.r[b];
   const int len = rd.len;
-  const int kps = ONE ? keys_per_split : rd.kps;   // rows of a batch are cut into ranges of their own size
+  const int kps = rd.kps;   // rows of a batch are cut into ranges of their own size
+  const int nsr = (len + kps - 1) / kps;   // key ranges of this row
   const int k0 = sp * kps, k1 = min(len, k0 + kps);
   if (k0 >= len) return;   // a shorter row of the batch has fewer ranges than the grid is wide
   const __hip_bfloat16* kp = rd.k + (size_t)hk * head_stride_elems;
@@ -330,8 +458,13 @@ __global__ __launch_bounds__(NW * 64, 2) void k_decode_mfma(__hip_bfloat16* k0_,
   }
   __syncthreads();
 
-  // ---- merge the wavefronts; with one split this is the result, else a partial for the merge kernel
-  const size_t pbase = ((size_t)b * n_splits + sp) * n_q_heads + (size_t)hk * G;
+  // ---- merge the wavefronts; with one key range this is the result, else the range's partial result: normalised
+  // values and the log-sum-exp (log2 units), each word tagged with this launch's number
+  // (a single stream: 64-bit words {value, launch tag}, read in this launch; a batch: plain floats for the merge launch)
+  const size_t prow_off = ((size_t)(rd.pair0 + sp) * n_q_heads + (size_t)hk * G) * PW;
+  unsigned long long* prow = (unsigned long long*)part + prow_off;
+  float* prow_f = (float*)part + prow_off;
+  const unsigned long long tag_hi = (unsigned long long)tag << 32;
   for (int idx = tid; idx < G * D; idx += NW * 64) {
     const int g = idx / D, d = idx % D;
     float mn = -INFINITY;
@@ -345,108 +478,103 @@ __global__ __launch_bounds__(NW * 64, 2) void k_decode_mfma(__hip_bfloat16* k0_,
       acc += sO[w][g][d] * a;
       lsum += sML[w][g][1] * a;
     }
-    if (n_splits == 1) {
-      out[((size_t)b * n_q_heads + hk * G + g) * D + d] = __float2bfloat16(acc / lsum);
+    const float val = acc / lsum;   // every range holds at least one key: lsum > 0
+    if (nsr == 1) {
+      out[((size_t)b * n_q_heads + hk * G + g) * D + d] = __float2bfloat16(val);
+    } else if constexpr (ONE) {
+      __hip_atomic_store(prow + (size_t)g * PW + d, tag_hi | __float_as_uint(val), __ATOMIC_RELAXED,
+                         __HIP_MEMORY_SCOPE_AGENT);
+      if (d == 0)
+        __hip_atomic_store(prow + (size_t)g * PW + D, tag_hi | __float_as_uint(mn + __log2f(lsum)), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
     } else {
-      part_o[(pbase + g) * D + d] = acc;
-      if (d == 0) {
-        part_ml[(pbase + g) * 2] = mn;
-        part_ml[(pbase + g) * 2 + 1] = lsum;
-      }
+      prow_f[(size_t)g * PW + d] = val;
+      if (d == 0) prow_f[(size_t)g * PW + D] = mn + __log2f(lsum);
     }
   }
+  if constexpr (ONE) {
+    // A single stream is latency bound and its workgroups end together: they merge the key ranges themselves, the
+    // workgroups of the first min(ranges, 4 G) ranges of a kv head taking a run of outputs each, instead of leaving
+    // it to a second launch (a launch gap and a round trip of its own: about 1.2 us more per layer-step).
+    if (nsr == 1) return;
+    int o_lo, n_out;
+    if (!merge_share(G, min(nsr, G * 4), sp, o_lo, n_out)) return;
+    // the first merge read also wants this workgroup's own words: let their stores be acknowledged first (a read
+    // that overtakes them costs a second round trip)
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    SV_TS(0, ts_wg, 3);
+    __syncthreads();   // the wavefront results in LDS have been read: their space is reused
+    merge_ranges<NW * 64, true>((const unsigned long long*)part + ((size_t)rd.pair0 * n_q_heads + (size_t)hk * G) * PW, (size_t)n_q_heads * PW, nsr,
+                                tag, o_lo, n_out, &sO[0][0][0], out + ((size_t)b * n_q_heads + hk * G) * D SV_TS_ARG(ts_slot),
+                                ts_wg);
 #ifdef SV_TIMELINE
-  __builtin_amdgcn_s_waitcnt(0x0F70);   // (measurement build only) the stores have been acknowledged
-  SV_TS(0, ts_wg, 3);
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    SV_TS(0, ts_wg, 5);
 #endif
+  }
 }
 
 // ---------------------------------------------------------------------------------
-// Merge of the key ranges of one decode step.  One workgroup of 128 threads per (head, row): thread
-// (g, d4) = (tid / 32, tid % 32) takes the key ranges s = g, g + 4, g + 8, ... and 4 output dims, issues
-// ALL its loads (up to 16 (max, sum) pairs and 16 float4) before using any of them, so the kernel costs
-// one memory round trip for up to 64 key ranges; the four partial merges meet in LDS.
-// grid: (n_q_heads, n_rows), block: 128 threads.
+// Merge of the key ranges of a batch's rows, as a launch of its own: the rows of a batch end at very different times
+// (the first workgroups of a ragged 16-stream batch after 6 us, the last after 36 us), and merging inside the decode
+// launch ends later there than this does (measured: the partial results of the last workgroups need about 2.3 us to
+// get through a loaded memory system and 1.5 us to come back).  kMergeWGs workgroups per (row, kv head) (14 and
+// 28 measured slower on the ragged batch).
+// grid: (kMergeWGs, n_kv_heads, n_rows), block: 256 threads.
 // ---------------------------------------------------------------------------------
-__global__ __launch_bounds__(128) void k_decode_merge(const float* __restrict__ part_o,
-                                                      const float* __restrict__ part_ml,
-                                                      __hip_bfloat16* __restrict__ out, int n_splits, int n_q_heads,
-                                                      RangeCounts cnt SV_TS_PARAM) {
-  [[maybe_unused]] const int ts_wg = blockIdx.y * gridDim.x + blockIdx.x;
-  SV_TS(1, ts_wg, 0);
-  __shared__ float4 s_acc[4][32];
-  __shared__ float2 s_ml[4];
-  const int h = blockIdx.x, b = blockIdx.y, g = threadIdx.x >> 5, d4 = threadIdx.x & 31;
-  const size_t rbase = (size_t)b * n_splits * n_q_heads + h;   // split s adds s * n_q_heads
-  const int ns = cnt.n[b];                                      // ranges this row really has (<= n_splits)
-  const float4* po = (const float4*)(part_o + rbase * D) + d4;
-  const float2* pml = (const float2*)part_ml + rbase;
-  const size_t ostride = (size_t)n_q_heads * D / 4;
-  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-  float lsum = 0.f, m_ref = -INFINITY;
-  for (int s0 = g; s0 < ns; s0 += 64) {
-    float4 v[16];
-    float2 ml[16];
-#pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      const int sidx = s0 + 4 * j;
-      const bool ok = sidx < ns;
-      ml[j] = ok ? pml[(size_t)sidx * n_q_heads] : make_float2(-INFINITY, 0.f);
-      v[j] = ok ? po[(size_t)sidx * ostride] : make_float4(0.f, 0.f, 0.f, 0.f);
-    }
-    float mx = m_ref;
-#pragma unroll
-    for (int j = 0; j < 16; ++j) mx = fmaxf(mx, ml[j].x);
-    const float resc = m_ref == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_ref - mx);
-    acc.x *= resc, acc.y *= resc, acc.z *= resc, acc.w *= resc;
-    lsum *= resc;
-#pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      const float w = ml[j].x == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(ml[j].x - mx);
-      acc.x += w * v[j].x, acc.y += w * v[j].y, acc.z += w * v[j].z, acc.w += w * v[j].w;
-      lsum += w * ml[j].y;
-    }
-    m_ref = mx;
-  }
-  s_acc[g][d4] = acc;
-  if (d4 == 0) s_ml[g] = make_float2(m_ref, lsum);
-  __syncthreads();
-  if (g != 0) return;
-  float mx = -INFINITY;
-#pragma unroll
-  for (int k = 0; k < 4; ++k) mx = fmaxf(mx, s_ml[k].x);
-  float4 tot = make_float4(0.f, 0.f, 0.f, 0.f);
-  float ltot = 0.f;
-#pragma unroll
-  for (int k = 0; k < 4; ++k) {
-    const float2 mlk = s_ml[k];
-    const float w = mlk.x == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mlk.x - mx);
-    const float4 a = s_acc[k][d4];
-    tot.x += w * a.x, tot.y += w * a.y, tot.z += w * a.z, tot.w += w * a.w;
-    ltot += w * mlk.y;
-  }
-  const float inv = 1.0f / ltot;
-  __hip_bfloat16* op = out + ((size_t)b * n_q_heads + h) * D + 4 * d4;
-  const uint32_t w0 = bf_round_bits(tot.x * inv) | (bf_round_bits(tot.y * inv) << 16);
-  const uint32_t w1 = bf_round_bits(tot.z * inv) | (bf_round_bits(tot.w * inv) << 16);
-  *(uint2*)op = make_uint2(w0, w1);
+constexpr int kMergeWGs = 7;
+struct RangeTable {
+  uint16_t pair0[kMaxRowsD];   // first (row, key range) pair of each row
+  uint8_t n[kMaxRowsD];        // key ranges of each row
+};
+__global__ __launch_bounds__(256) void k_decode_merge(const float* __restrict__ part,
+                                                      __hip_bfloat16* __restrict__ out, int n_q_heads, int G,
+                                                      RangeTable rt) {
+  __shared__ float lds[3 * 256];
+  const int hk = blockIdx.y, b = blockIdx.z;
+  const int nsr = rt.n[b];
+  int o_lo, n_out;
+  if (nsr == 1 || !merge_share(G, kMergeWGs, blockIdx.x, o_lo, n_out)) return;   // one range: the decode kernel wrote the output
 #ifdef SV_TIMELINE
-  __builtin_amdgcn_s_waitcnt(0x0F70);
-  SV_TS(1, ts_wg, 1);
+  constexpr int ts_slot = 0;
 #endif
+  merge_ranges<256, false>(part + ((size_t)rt.pair0[b] * n_q_heads + (size_t)hk * G) * PW, (size_t)n_q_heads * PW, nsr, 0u,
+                           o_lo, n_out, lds, out + ((size_t)b * n_q_heads + hk * G) * D SV_TS_ARG(ts_slot), 1 << 20);
 }
 
 #ifdef SV_TIMELINE
 int g_ts_launch = 0;   // host: launches so far; the slot of a launch is this modulo 8
 #endif
 
+// Zeroes the tagged-word scratch (when a tag counter wraps: no stale word may carry a tag that comes round again).
+__global__ void k_clear_words(unsigned long long* p, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0ull;
+}
+
 }  // namespace
+
+// Where the key ranges' partial results go.  tagged: 64-bit words of single-stream launches, room for tagged_pairs
+// (row, key range) pairs, written by nothing else and zero before the first launch; seq: its launch counter (tags are
+// never 0 and never repeat while a stale word could carry them).  plain: floats of batch launches, plain_pairs pairs.
+struct DecScratch {
+  unsigned long long* tagged;
+  int64_t tagged_pairs;
+  uint32_t* seq;
+  float* plain;
+  int64_t plain_pairs;
+};
 
 template <int NW>
 static hipError_t decode_launch(const sv_cache* c, const DecTable& tab, int fused, int nr, int max_len, int64_t total_tiles,
-                         const void* q, const void* k_new, const void* v_new, void* o, size_t r0, float* part_o,
-                         float* part_ml, int64_t part_rows, hipStream_t s) {
+                         const void* q, const void* k_new, const void* v_new, void* o, size_t r0,
+                         const DecScratch& scr, hipStream_t s) {
   const int Hq = c->cfg.n_q_heads, Hkv = c->cfg.n_kv_heads;
+  // More than 96 MB of K and V in this launch, one long stream or many: non-temporal loads (rows that are the layers
+  // of ONE stream keep the plain loads: their 308 MB are read again at the next token and the Infinity Cache still
+  // holds most of them).
+  const bool stream_loads = total_tiles * (int64_t)(TK * D * 2 * 2) * Hkv >= ((int64_t)96 << 20);
+  const bool one = nr == 1 && !stream_loads;   // the single-stream instantiation: merges its key ranges itself
+  const int64_t part_pairs = one ? scr.tagged_pairs : scr.plain_pairs;
   // Key ranges.  A single stream is latency bound: ranges of 128 keys (one 32-key tile per wavefront) spread its
   // few hundred tiles over the most CUs and cost one memory round trip.  A batch is bandwidth bound: longer ranges
   // keep the partial results and their merge small, and all workgroups should be resident at once (two fit a CU:
@@ -458,7 +586,7 @@ static hipError_t decode_launch(const sv_cache* c, const DecTable& tab, int fuse
   // range much shorter than the others.
   constexpr int kSlots = 512;
   const int forced = std::min(c->opt[SV_OPT_DECODE_TILES_PER_WAVE], 64);
-  const int64_t max_pairs = std::max<int64_t>(nr, part_rows);
+  if (part_pairs < nr) return hipErrorInvalidValue;   // every row needs at least one pair (callers check their limits)
   int T = forced > 0 ? TK * NW * forced : TK * NW;
   for (;; T += TK * NW) {
     int64_t pairs = 0;
@@ -468,19 +596,34 @@ static hipError_t decode_launch(const sv_cache* c, const DecTable& tab, int fuse
       pairs += nb;
       widest = std::max(widest, nb);
     }
-    const bool fits = widest <= kMaxSplitsD && widest * (int64_t)nr <= max_pairs;   // scratch: rows x widest ranges
+    const bool fits = widest <= kMaxSplitsD && pairs <= part_pairs;   // scratch: one slot per (row, key range)
     if (fits && (forced > 0 || pairs * Hkv <= kSlots || T >= max_len)) break;
   }
   DecTable tabk = tab;
-  RangeCounts cnt = {};
-  int n_splits = 1;
+  RangeTable rt = {};
+  int n_splits = 1, pair0 = 0;
   for (int b = 0; b < nr; ++b) {
     const int len = tab.r[b].len, nb = std::max(1, (len + T - 1) / T);
     const int kps = ((len + nb - 1) / nb + TK * NW - 1) / (TK * NW) * (TK * NW);
+    const int ranges = (len + kps - 1) / kps;   // <= nb <= kMaxSplitsD
     tabk.r[b].kps = kps;
-    cnt.n[b] = (uint8_t)((len + kps - 1) / kps);
-    n_splits = std::max(n_splits, (int)cnt.n[b]);
+    tabk.r[b].pair0 = pair0;
+    rt.pair0[b] = (uint16_t)pair0;
+    rt.n[b] = (uint8_t)ranges;
+    pair0 += ranges;
+    n_splits = std::max(n_splits, ranges);
   }
+  uint32_t tag = 0;
+  if (one && n_splits > 1) {
+    tag = ++*scr.seq;
+    if (tag == 0) {   // the counter wrapped: clear the scratch, so that no stale word carries a tag that is used again
+      hipLaunchKernelGGL(k_clear_words, dim3(1024), dim3(256), 0, s, scr.tagged, (size_t)scr.tagged_pairs * Hq * PW);
+      hipError_t e0 = hipGetLastError();
+      if (e0 != hipSuccess) return e0;
+      tag = ++*scr.seq;
+    }
+  }
+  void* part = one ? (void*)scr.tagged : (void*)scr.plain;
   const int keys_per_split = tabk.r[0].kps;
   const float c_log2 = 1.4426950408889634f / sqrtf((float)D);
   const __hip_bfloat16* qp = (const __hip_bfloat16*)q + r0 * Hq * D;
@@ -489,44 +632,39 @@ static hipError_t decode_launch(const sv_cache* c, const DecTable& tab, int fuse
   __hip_bfloat16* op = (__hip_bfloat16*)o + r0 * Hq * D;
   const int rotate = c->cfg.rope_mode != SV_ROPE_NONE ? 1 : 0;
   const DecRow& r = tabk.r[0];
-  // More than 96 MB of K and V in this launch, one long stream or many: non-temporal loads (rows that are the layers
-  // of ONE stream keep the plain loads: their 308 MB are read again at the next token and the Infinity Cache still
-  // holds most of them).
-  const bool stream_loads = total_tiles * (int64_t)(TK * D * 2 * 2) * Hkv >= ((int64_t)96 << 20);
-  if (nr == 1 && !stream_loads)
+  if (one)
     hipLaunchKernelGGL((k_decode_mfma<NW, true, false>), dim3(n_splits, Hkv, 1), dim3(NW * 64), 0, s, r.k, r.v, r.cs, r.len,
-                       keys_per_split, qp, knp, vnp, c->head_stride / 2, fused, rotate, op, part_o, part_ml,
-                       n_splits, Hq, Hkv, c->group, c_log2, tabk SV_TS_ARG(g_ts_launch % 8));
+                       keys_per_split, qp, knp, vnp, c->head_stride / 2, fused, rotate, op, part, tag, Hq, Hkv,
+                       c->group, c_log2, tabk SV_TS_ARG(g_ts_launch % 8));
   else if (stream_loads)
     hipLaunchKernelGGL((k_decode_mfma<NW, false, true>), dim3(n_splits, Hkv, nr), dim3(NW * 64), 0, s, r.k, r.v, r.cs, r.len,
-                       keys_per_split, qp, knp, vnp, c->head_stride / 2, fused, rotate, op, part_o, part_ml,
-                       n_splits, Hq, Hkv, c->group, c_log2, tabk SV_TS_ARG(g_ts_launch % 8));
+                       keys_per_split, qp, knp, vnp, c->head_stride / 2, fused, rotate, op, part, tag, Hq, Hkv,
+                       c->group, c_log2, tabk SV_TS_ARG(g_ts_launch % 8));
   else
     hipLaunchKernelGGL((k_decode_mfma<NW, false, false>), dim3(n_splits, Hkv, nr), dim3(NW * 64), 0, s, r.k, r.v, r.cs, r.len,
-                       keys_per_split, qp, knp, vnp, c->head_stride / 2, fused, rotate, op, part_o, part_ml,
-                       n_splits, Hq, Hkv, c->group, c_log2, tabk SV_TS_ARG(g_ts_launch % 8));
-  hipError_t e = hipGetLastError();
-#ifdef SV_TIMELINE
-  if (e != hipSuccess || n_splits == 1) ++g_ts_launch;
-#endif
-  if (e != hipSuccess || n_splits == 1) return e;
-  hipLaunchKernelGGL(k_decode_merge, dim3(Hq, nr), dim3(128), 0, s, part_o, part_ml,
-                     (__hip_bfloat16*)o + r0 * Hq * D, n_splits, Hq, cnt SV_TS_ARG(g_ts_launch % 8));
+                       keys_per_split, qp, knp, vnp, c->head_stride / 2, fused, rotate, op, part, tag, Hq, Hkv,
+                       c->group, c_log2, tabk SV_TS_ARG(g_ts_launch % 8));
 #ifdef SV_TIMELINE
   ++g_ts_launch;
 #endif
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || n_splits == 1 || one) return e;
+  hipLaunchKernelGGL(k_decode_merge, dim3(kMergeWGs, Hkv, nr), dim3(256), 0, s, scr.plain, op, Hq, c->group, rt);
   return hipGetLastError();
 }
 
 // Partial results of the key ranges live in the cache arena by default; sv_attn_decode_static keeps them in a
-// file-scope device array instead (callers that cannot provide scratch memory).  The array's name is only a host-side
-// handle: its device address is looked up once per device and kept.
+// file-scope device array instead (callers that cannot provide scratch memory; zero at load, as every device-scope
+// array): its first half holds the tagged words of single-stream launches, its second half the floats of batches.
+// The array's name is only a host-side handle: its device address is looked up once per device and kept.  The array
+// has one launch counter per device, shared by all handles.
 constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
 constexpr int kMaxDevices = 64;
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 static void* g_scratch_ptr[kMaxDevices] = {};
+static uint32_t g_scratch_seq[kMaxDevices] = {};
 
-hipError_t decode_static_scratch(void** ptr_out) {
+static hipError_t static_scratch_of_device(void** ptr_out, int* dev_out) {
   int dev = -1;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
@@ -539,17 +677,26 @@ hipError_t decode_static_scratch(void** ptr_out) {
     g_scratch_ptr[dev] = p;
   }
   *ptr_out = g_scratch_ptr[dev];
+  if (dev_out) *dev_out = dev;
   return hipSuccess;
 }
 
+hipError_t decode_static_scratch(void** ptr_out) { return static_scratch_of_device(ptr_out, nullptr); }
+
+size_t decode_tagged_bytes(const sv_config& cfg) {
+  return (size_t)kMaxSplitsD * cfg.n_q_heads * PW * sizeof(unsigned long long);
+}
+
+int64_t decode_plain_pairs(const sv_cache* c) {   // the arena's split-KV region holds part_rows x heads x 128 floats
+  return c->part_rows * D / PW;
+}
+
 int64_t decode_static_pairs(const sv_cache* c) {
-  // one (row, key range) pair holds n_q_heads x (128 + 2) floats
-  return (int64_t)(kStaticScratchBytes / ((size_t)c->cfg.n_q_heads * (D + 2) * sizeof(float)));
+  return (int64_t)(kStaticScratchBytes / 2 / ((size_t)c->cfg.n_q_heads * PW * sizeof(float)));
 }
 
 static hipError_t decode_rows(const sv_cache* c, int layer, const int32_t* streams, int n_list, int fused, const void* q,
-                              const void* k_new, const void* v_new, void* o, float* part_o, float* part_ml,
-                              int64_t part_rows, hipStream_t s) {
+                              const void* k_new, const void* v_new, void* o, const DecScratch& scr, hipStream_t s) {
   for (int r0 = 0; r0 < n_list; r0 += kMaxRowsD) {
     const int nr = std::min(kMaxRowsD, n_list - r0);
     DecTable tab = {};
@@ -567,8 +714,7 @@ static hipError_t decode_rows(const sv_cache* c, int layer, const int32_t* strea
       max_len = std::max(max_len, (int)st.len);
       if (layer >= 0) total_tiles += (st.len + TK - 1) / TK;
     }
-    hipError_t e = decode_launch<4>(c, tab, fused, nr, max_len, total_tiles, q, k_new, v_new, o, (size_t)r0, part_o,
-                                    part_ml, part_rows, s);
+    hipError_t e = decode_launch<4>(c, tab, fused, nr, max_len, total_tiles, q, k_new, v_new, o, (size_t)r0, scr, s);
     if (e != hipSuccess) return e;
   }
   return hipSuccess;
@@ -576,18 +722,21 @@ static hipError_t decode_rows(const sv_cache* c, int layer, const int32_t* strea
 
 hipError_t launch_attn_decode_mfma(const sv_cache* c, int layer, const int32_t* streams, int n_list, int fused,
                                    const void* q, const void* k_new, const void* v_new, void* o, hipStream_t s) {
-  return decode_rows(c, layer, streams, n_list, fused, q, k_new, v_new, o, c->part_o, c->part_ml, c->part_rows, s);
+  const DecScratch scr = {c->part_dec, kMaxSplitsD, &c->dec_seq, c->part_o, decode_plain_pairs(c)};
+  return decode_rows(c, layer, streams, n_list, fused, q, k_new, v_new, o, scr, s);
 }
 
 hipError_t launch_attn_decode_mfma_static(const sv_cache* c, int layer, const int32_t* streams, int n_list,
                                           const void* q, void* o, hipStream_t s) {
   void* p = nullptr;
-  hipError_t e = decode_static_scratch(&p);
+  int dev = 0;
+  hipError_t e = static_scratch_of_device(&p, &dev);
   if (e != hipSuccess) return e;
-  const int64_t pairs = decode_static_pairs(c);
-  float* part_o = (float*)p;
-  float* part_ml = part_o + (size_t)pairs * c->cfg.n_q_heads * D;
-  return decode_rows(c, layer, streams, n_list, 0, q, nullptr, nullptr, o, part_o, part_ml, pairs, s);
+  const size_t half = kStaticScratchBytes / 2;
+  const DecScratch scr = {(unsigned long long*)p,
+                          (int64_t)(half / ((size_t)c->cfg.n_q_heads * PW * sizeof(unsigned long long))), &g_scratch_seq[dev],
+                          (float*)((char*)p + half), decode_static_pairs(c)};
+  return decode_rows(c, layer, streams, n_list, 0, q, nullptr, nullptr, o, scr, s);
 }
 
 }  // namespace sv
