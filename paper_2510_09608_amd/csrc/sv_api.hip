@@ -243,6 +243,10 @@ int sv_cache_destroy(sv_cache* c) {
 
 int sv_cache_set_option(sv_cache* c, int option, int value) {
   if (!c || option < 0 || option >= SV_OPT_COUNT_ || value < 0) return SV_ERR_INVALID;
+  if (option == SV_OPT_DECODE_TAGS_LEFT) {
+    c->dec_seq = 0xFFFFFFFFu - (uint32_t)value;   // the launch after `value` more gets tag 0, i.e. wraps
+    return SV_OK;
+  }
   c->opt[option] = value;
   return SV_OK;
 }
@@ -536,8 +540,9 @@ int sv_stream_step(sv_cache* c, int stream_id, int64_t n_sink, int64_t vision_wi
                        !fused);
       if (rc != SV_OK) return rc;
       if (fused) {
-        // Q stays as the caller wrote it when the run's cos/sin table exists: the attention kernel rotates it on load
-        const bool q_on_load = st_cs_valid(c, stream_id);
+        // Q stays as the caller wrote it when the run's cos/sin table exists and few key ranges will load each query
+        // row: the attention kernel then rotates it on load
+        const bool q_on_load = st_cs_valid(c, stream_id) && sv::attn_chunk_rotates_on_load(c, stream_id, n);
         SV_DEV(sv::launch_store_tokens_vt(c, stream_id, l, slot0, n, q_on_load ? nullptr : q, k, v,
                                           (hipStream_t)hip_stream));
         SV_DEV(sv::launch_attn_chunk_mfma(c, stream_id, l, q, n, o, 1, q_on_load, (hipStream_t)hip_stream));

@@ -168,26 +168,38 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
   const int wg_first_limit = causal ? slot0 + (rt * ROWS_WG) / G : n_kv - 1;
   bf16x8 qf[8];
   {
+    // rr is a valid row for every lane (lanes past the last row repeat it; nothing of theirs is stored), so all loads
+    // are unconditional and issued together: queries and, for the rotation, their cos/sin in one memory round trip
     const __hip_bfloat16* qp = q + ((size_t)qi * n_q_heads + hk * G + hg) * D + hh * 8;
+    uint4 raw[8];
 #pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
-      uint4 raw = rvalid ? *(const uint4*)(qp + kk * 16) : make_uint4(0, 0, 0, 0);
-      qf[kk] = *(bf16x8*)&raw;
-    }
+    for (int kk = 0; kk < 8; ++kk) raw[kk] = *(const uint4*)(qp + kk * 16);
     if (cs_tab != nullptr) {
       // Un-rotated queries (the per-second step): rotate them here, with the cos/sin the run's registration
       // tabulated per (token, pair), and round to bf16 as a rotation pass in memory would have.  The lane holds
       // dims 16 kk + 8 hh + e, so the pair (i, i + 64) is (kk, kk + 4) of its own registers.
-      const float2* cs = cs_tab + (size_t)qi * (D / 2) + 8 * hh;
+      const float4* cs = (const float4*)(cs_tab + (size_t)qi * (D / 2) + 8 * hh);   // pairs 16 kk + 8 hh + e
+      float4 c4[4][4];
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+        for (int e2 = 0; e2 < 4; ++e2) c4[kk][e2] = cs[8 * kk + e2];
+      __builtin_amdgcn_sched_barrier(0);   // all 24 loads go out before the first of them is waited for
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) qf[kk] = *(bf16x8*)&raw[kk];
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          const float2 r = cs[16 * kk + e];
+          const float4 r4 = c4[kk][e >> 1];
+          const float cx = (e & 1) ? r4.z : r4.x, sx = (e & 1) ? r4.w : r4.y;
           const float a = (float)qf[kk][e], b = (float)qf[kk + 4][e];
-          qf[kk][e] = (__bf16)(a * r.x - b * r.y);
-          qf[kk + 4][e] = (__bf16)(b * r.x + a * r.y);
+          qf[kk][e] = (__bf16)(a * cx - b * sx);
+          qf[kk + 4][e] = (__bf16)(b * cx + a * sx);
         }
+    } else {
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) qf[kk] = *(bf16x8*)&raw[kk];
     }
   }
 
@@ -527,13 +539,12 @@ hipError_t attn_chunk_mfma_init() {
                              kLds);
 }
 
-hipError_t launch_attn_chunk_mfma(const sv_cache* c, int stream, int layer, const void* q, int n_q, void* o,
-                                  int causal, bool rotate_q, hipStream_t s) {
+// Key ranges of a chunk-prefill launch over n_kv keys: (count, keys per range).
+static void chunk_ranges(const sv_cache* c, int n_q, int n_kv, int& n_splits, int& keys_per_split) {
   constexpr int ROWS_WG = kNW * 32;
-  const StreamState& st = c->st[stream];
-  const int n_kv = (int)st.len, G = c->group, Hkv = c->cfg.n_kv_heads;
+  const int G = c->group, Hkv = c->cfg.n_kv_heads;
   const int row_tiles = (n_q * G + ROWS_WG - 1) / ROWS_WG;
-  int n_splits = c->opt[SV_OPT_CHUNK_SPLITS];
+  n_splits = c->opt[SV_OPT_CHUNK_SPLITS];
   if (n_splits <= 0) {
     // fill the 256 CUs, one workgroup each
     n_splits = std::max(1, 256 / std::max(1, row_tiles * Hkv));
@@ -544,8 +555,27 @@ hipError_t launch_attn_chunk_mfma(const sv_cache* c, int stream, int layer, cons
   }
   n_splits = std::min<int64_t>(n_splits, std::max<int64_t>(1, c->part_rows / n_q));
   n_splits = std::min(n_splits, kMaxChunkSplits);
-  int keys_per_split = ((n_kv + n_splits - 1) / n_splits + TK - 1) / TK * TK;
+  keys_per_split = ((n_kv + n_splits - 1) / n_splits + TK - 1) / TK * TK;
   n_splits = (n_kv + keys_per_split - 1) / keys_per_split;
+}
+
+// Every key range's workgroups rotate the queries they load (about 2 us of vector work per workgroup): worth it
+// against a rotation pass over Q in memory while a query row is loaded by few ranges (long chunks: 2 ranges at 1024
+// tokens), not when 8 ranges repeat it (256 tokens).
+bool attn_chunk_rotates_on_load(const sv_cache* c, int stream, int n_q) {
+  int n_splits, kps;
+  chunk_ranges(c, n_q, (int)c->st[stream].len, n_splits, kps);
+  return n_splits <= 2;
+}
+
+hipError_t launch_attn_chunk_mfma(const sv_cache* c, int stream, int layer, const void* q, int n_q, void* o,
+                                  int causal, bool rotate_q, hipStream_t s) {
+  constexpr int ROWS_WG = kNW * 32;
+  const StreamState& st = c->st[stream];
+  const int n_kv = (int)st.len, G = c->group, Hkv = c->cfg.n_kv_heads;
+  const int row_tiles = (n_q * G + ROWS_WG - 1) / ROWS_WG;
+  int n_splits, keys_per_split;
+  chunk_ranges(c, n_q, n_kv, n_splits, keys_per_split);
   const float c_log2 = 1.4426950408889634f / sqrtf((float)D);
   const int pairs_pad = (Hkv * n_splits + 7) / 8 * 8;
   hipLaunchKernelGGL((k_attn_chunk_pipe<kNW, kKS, kVS>), dim3(row_tiles * pairs_pad), dim3(kNW * 64), kLds, s,

@@ -159,6 +159,9 @@ hipError_t launch_store_tokens_vt(const sv_cache* c, int stream, int layer, int6
 // table was written for).
 hipError_t launch_attn_chunk_mfma(const sv_cache* c, int stream, int layer, const void* q, int n_q,
                                   void* o, int causal, bool rotate_q, hipStream_t s);
+// Whether a chunk of n_q queries (already counted in the stream's length) is better rotated by the attention kernel
+// while loading than by a pass over Q in memory.
+bool attn_chunk_rotates_on_load(const sv_cache* c, int stream, int n_q);
 
 
 }  // namespace sv

@@ -491,6 +491,61 @@ def test_attn_randomized_shapes():
         assert gu.max_err(gu.host(od1), ref1) <= gu.TOL["bf16"], (case, "decode")
 
 
+@pytest.mark.parametrize("G", [1, 2, 4, 7, 8])
+def test_decode_single_stream_merge_in_launch(G):
+    """Single-stream decode of the matrix-core kernel, whose key ranges are merged inside the launch: group sizes
+    1..8, caches that give 1, 2, 3, 5, 9, 29 and 70 key ranges of 128 keys (every thread layout of the merge, more
+    than one pass over the ranges), and ranges of 3 tiles per wavefront; each output against the oracle."""
+    Hkv = 2
+    Hq = G * Hkv
+    for n_kv, tiles in [(100, 1), (200, 1), (300, 1), (600, 1), (1100, 1), (3700, 1), (8900, 1), (2500, 3), (640, 0)]:
+        seed = 9100 + 10 * G + tiles
+        w = si.Workload("a", 1, Hq, Hkv, 128, "bf16", 2, 1e4, (0, 0, 0), 0, 0, 0, 0, 0, 0, None, 0, seed)
+        gids = np.arange(n_kv)
+        k = si.normal(seed, si.TENSOR_K, 0, gids, Hkv, 128, True)
+        v = si.normal(seed, si.TENSOR_V, 0, gids, Hkv, 128, True)
+        q = si.normal(seed, si.TENSOR_Q, 0, gids[-1:], Hq, 128, True)
+        _say(f"decode merge in launch: G={G} n_kv={n_kv} tiles_per_wave={tiles}")
+        cache = sv.Cache(1, Hq, Hkv, 128, sv.SV_DTYPE_BF16, sv.SV_ROPE_NONE, 1e4, (0, 0, 0), 1, n_kv + 8, 1)
+        cache.set_option(sv.SV_OPT_DECODE_TILES_PER_WAVE, tiles)
+        cache.append(0, 0, np.zeros(n_kv, dtype=np.uint8), None, gu.dev(k, w), gu.dev(v, w))
+        qd = gu.dev(q, w)
+        od = torch.empty_like(qd)
+        cache.attn_decode(0, [0], qd, od)
+        ref = orc.gqa_attention(q.astype(np.float64), k.astype(np.float64), v.astype(np.float64),
+                                np.array([n_kv - 1]), True)
+        got = gu.host(od)
+        assert np.isfinite(got).all(), (G, n_kv)
+        assert gu.max_err(got, ref) <= gu.TOL["bf16"], (G, n_kv, gu.max_err(got, ref))
+        cache.close()
+
+
+def test_decode_launch_tag_wraps():
+    """The launch counter behind the tags of the in-launch merge wraps after 2^32 launches; the library then clears
+    the tagged scratch and goes on.  With two launches left before the wrap, seven decode calls in a row (the
+    third one wraps) all return the oracle's result."""
+    n_kv, seed = 1500, 9301
+    w = si.Workload("a", 1, 28, 4, 128, "bf16", 2, 1e4, (0, 0, 0), 0, 0, 0, 0, 0, 0, None, 0, seed)
+    gids = np.arange(n_kv)
+    k = si.normal(seed, si.TENSOR_K, 0, gids, 4, 128, True)
+    v = si.normal(seed, si.TENSOR_V, 0, gids, 4, 128, True)
+    q = si.normal(seed, si.TENSOR_Q, 0, gids[-1:], 28, 128, True)
+    cache = sv.Cache(1, 28, 4, 128, sv.SV_DTYPE_BF16, sv.SV_ROPE_NONE, 1e4, (0, 0, 0), 1, n_kv + 8, 1)
+    cache.append(0, 0, np.zeros(n_kv, dtype=np.uint8), None, gu.dev(k, w), gu.dev(v, w))
+    ref = orc.gqa_attention(q.astype(np.float64), k.astype(np.float64), v.astype(np.float64), np.array([n_kv - 1]), True)
+    qd = gu.dev(q, w)
+    cache.attn_decode(0, [0], qd, torch.empty_like(qd))     # leaves tagged words of an ordinary launch behind
+    cache.set_option(sv.SV_OPT_DECODE_TAGS_LEFT, 2)
+    for i in range(7):
+        _say(f"decode launch {i} around the tag wrap")
+        od = torch.full_like(qd, float("nan"))
+        cache.attn_decode(0, [0], qd, od)
+        got = gu.host(od)
+        assert np.isfinite(got).all(), i
+        assert gu.max_err(got, ref) <= gu.TOL["bf16"], (i, gu.max_err(got, ref))
+    cache.close()
+
+
 @pytest.mark.parametrize("dtype,Hq,Hkv,d", [("f32", 2, 1, 64), ("f32", 8, 2, 128), ("bf16", 4, 4, 64), ("bf16", 16, 2, 64)])
 @pytest.mark.parametrize("n_kv,n_q,causal", [(72, 16, True), (300, 41, False), (1, 1, True)])
 def test_attn_chunk_rows_path(dtype, Hq, Hkv, d, n_kv, n_q, causal):
