@@ -109,9 +109,10 @@ SV_API int sv_cache_destroy(sv_cache* c);
  *   SV_OPT_CHUNK_SPLITS           the number of key ranges of sv_attn_chunk's matrix-core kernel,
  *   SV_OPT_DECODE_TILES_PER_WAVE  the 32-key tiles each wavefront of the decode kernel takes (1..16),
  *   SV_OPT_DECODE_SPLITS          the number of key ranges of the generic row kernel,
- *   SV_OPT_DECODE_TAGS_LEFT       (takes effect at once, is not stored) how many single-stream launches of the
- *                                 matrix-core decode kernel are left before the handle's 32-bit launch counter wraps
- *                                 and the kernel's tagged scratch is cleared: lets a test reach the wrap.
+ *   SV_OPT_TAGS_LEFT              (takes effect at once, is not stored) how many launches are left before the handle's
+ *                                 32-bit launch counters wrap (single-stream launches of the matrix-core decode kernel,
+ *                                 eviction scans), when the library clears the tagged scratch words those kernels
+ *                                 exchange partial results through: lets a test reach the wrap.
  * Forced values are still clamped to what the scratch buffers hold.  Host-side state only: takes effect
  * from the next launch.  Errors: SV_ERR_INVALID (NULL handle, unknown option, negative value).
  */
@@ -119,7 +120,7 @@ enum {
   SV_OPT_CHUNK_SPLITS = 0,
   SV_OPT_DECODE_TILES_PER_WAVE = 1,
   SV_OPT_DECODE_SPLITS = 2,
-  SV_OPT_DECODE_TAGS_LEFT = 3,
+  SV_OPT_TAGS_LEFT = 3,
   SV_OPT_COUNT_ = 4
 };
 SV_API int sv_cache_set_option(sv_cache* c, int option, int value);

@@ -49,7 +49,7 @@ bool config_ok(const sv_config* c) {
 // sv_cache_bytes and sv_cache_create cannot disagree.
 struct Layout {
   size_t kv, meta_gid[2], meta_rank[2], meta_pos[2], meta_local[2], meta_blk[2], meta_type[2];
-  size_t src, delta, dtab, next_pos, n_dev, inv_freq, last_cs, cs_tab, part_o, part_ml, counters, part_dec, total;
+  size_t src, delta, dtab, next_pos, n_dev, inv_freq, last_cs, cs_tab, part_o, part_ml, counters, part_dec, scan_agg, total;
   int64_t part_rows;
   size_t part_dec_bytes;
 };
@@ -89,6 +89,7 @@ Layout make_layout(const sv_config& c) {
   // matrix-core decode, single stream: tagged words of up to 128 key ranges
   L.part_dec_bytes = mfma_eligible(c) ? sv::decode_tagged_bytes(c) : 0;
   L.part_dec = take(L.part_dec_bytes);
+  L.scan_agg = take(S * 2 * sv::kScanMaxWG * 8);
   L.total = off;
   return L;
 }
@@ -195,6 +196,7 @@ int sv_cache_create(const sv_config* cfg, void* dev_arena, size_t arena_bytes, v
   c->part_rows = L.part_rows;
   c->counters = (int32_t*)(base + L.counters);
   c->part_dec = (unsigned long long*)(base + L.part_dec);
+  c->scan_agg = (unsigned long long*)(base + L.scan_agg);
   c->st.resize(cfg->n_streams);
   for (auto& s : c->st) s.layer_len.assign(cfg->n_layers, 0);
   c->use_mfma = mfma_eligible(*cfg);
@@ -217,6 +219,7 @@ int sv_cache_create(const sv_config* cfg, void* dev_arena, size_t arena_bytes, v
   if (e == hipSuccess) e = hipMemsetAsync(c->n_dev, 0, (size_t)cfg->n_streams * 4, s);
   if (e == hipSuccess) e = hipMemsetAsync(c->counters, 0, (size_t)L.part_rows * cfg->n_kv_heads * 4, s);
   if (e == hipSuccess && L.part_dec_bytes > 0) e = hipMemsetAsync(c->part_dec, 0, L.part_dec_bytes, s);
+  if (e == hipSuccess) e = hipMemsetAsync(c->scan_agg, 0, (size_t)cfg->n_streams * 2 * sv::kScanMaxWG * 8, s);
   // blocked V^T: slots past a stream's end inside its last block are multiplied by probabilities of zero and must
   // never hold NaN patterns, so the store starts out cleared
   if (e == hipSuccess && c->v_blocked)
@@ -243,8 +246,8 @@ int sv_cache_destroy(sv_cache* c) {
 
 int sv_cache_set_option(sv_cache* c, int option, int value) {
   if (!c || option < 0 || option >= SV_OPT_COUNT_ || value < 0) return SV_ERR_INVALID;
-  if (option == SV_OPT_DECODE_TAGS_LEFT) {
-    c->dec_seq = 0xFFFFFFFFu - (uint32_t)value;   // the launch after `value` more gets tag 0, i.e. wraps
+  if (option == SV_OPT_TAGS_LEFT) {
+    c->dec_seq = c->scan_seq = 0xFFFFFFFFu - (uint32_t)value;   // the launch after `value` more gets tag 0, i.e. wraps
     return SV_OK;
   }
   c->opt[option] = value;

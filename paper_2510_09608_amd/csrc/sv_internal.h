@@ -16,6 +16,7 @@ namespace sv {
 // holds keys [8 b, 8 b + 8) as [head dim 0..127][key 0..7] (2 KB), element (key, d) at vt_elem(key, d).  A block
 // row is exactly the 16-byte piece a lane wants; 32- and 64-key tiles are 4 and 8 consecutive blocks (8 / 16 KB
 // contiguous); and a compaction that drops runs of 8 k tokens moves whole blocks.
+constexpr int kScanMaxWG = 128;   // workgroups of one eviction scan
 constexpr int kVB = 8;
 constexpr int kVD = 128;
 constexpr int kVBElems = kVB * kVD;
@@ -85,6 +86,9 @@ struct sv_cache {
   unsigned long long* part_dec;   // device: tagged partial results of a single stream's key ranges in the matrix-core
                                   // decode kernel (zero at create, written by nothing else; sv_attn_decode.hip)
   mutable uint32_t dec_seq = 0;   // launches that have used part_dec: the tag of the next one is this + 1
+  unsigned long long* scan_agg;   // device [n_streams][kScanMaxWG][2]: tagged totals of the eviction scan's workgroups
+                                  // (zero at create, written by nothing else; sv_meta.hip)
+  mutable uint32_t scan_seq = 0;  // eviction scans launched: the tag of the next one is this + 1
   bool host_logic_only = false;   // created with SV_HOST_LOGIC_ONLY: no device work, bookkeeping only
   bool use_mfma = false;          // bf16, head_dim 128, group <= 8 and no SV_FLAG_GENERIC_KERNELS: matrix-core kernels
   bool v_blocked = false;         // V stored as V^T in blocks of 8 keys (exactly the caches with use_mfma), else row-major

@@ -93,7 +93,7 @@ __global__ void k_meta_append(MetaPtrs m, const int32_t* __restrict__ next_in, i
 }
 
 // ---------------------------------------------------------------------------------
-// Eviction scan, one workgroup of 16 wavefronts per stream.
+// Eviction scan, several workgroups per stream.
 //
 // keep(i)  : text  -> rank < n_sink or rank >= text_lo     (sink + recent text)
 //            vision-> rank >= vis_lo                         (recent vision)
@@ -103,131 +103,216 @@ __global__ void k_meta_append(MetaPtrs m, const int32_t* __restrict__ next_in, i
 //            its last retained token.  With every token its own block of extent 1
 //            (1-D mode) base' equals dst.
 // Survivors' metadata is written compacted to `out`; src[dst] = i is the gather
-// list for the K/V move and delta[dst] = base - base' the shift for the re-rotation.
+// list for the K/V move, delta[dst] = base - base' the shift for the re-rotation, and
+// dtab[dst][pair] = (cos, -sin) of delta * inv_freq[pair] (rows with delta != 0 only:
+// the mover reads no others), i.e. moving from old to new position turns pair i by
+// -(delta * inv_freq[i]); stored so that the mover applies the formula of a forward
+// rotation.  delta is one scalar per token even in 3-D mode because t, h and w shift together.
 //
-// A pass covers kScanSub x 1024 tokens: sub-tile k holds tokens base + 1024 k + tid, so every load is coalesced
-// and all loads of a pass are independent and issued together (one memory round trip per 4096 tokens instead of
-// one per 1024).  Within a sub-tile a wavefront's keep count comes from the ballot and a popcount, its advances
-// from a shuffle scan; the 64 (sub-tile, wavefront) totals of a pass go through LDS and are scanned by the first
-// wavefront, and a running carry links the passes.
+// Workgroup w owns the tokens [w * span, (w + 1) * span), span = passes x 256, one token per thread and pass.
+//   1. It counts its kept tokens and their advances (within a wavefront: ballot + popcount, shuffle sum) and
+//      publishes the two totals as 64-bit words {value, launch tag} with relaxed device-scope atomic stores.
+//   2. Its first wavefront reads the words of all workgroups before it, again and again until each carries this
+//      launch's tag (a word is its own ready flag: a 64-bit access is single-copy atomic and a word is written once
+//      per launch; the writers wait for nothing and are dispatched earlier), and sums them: the carry.
+//   3. It scans its own tokens (ballot / popcount for the slot, shuffle scan for the advance, four wavefront totals
+//      through LDS) on top of the carry and writes the survivors' metadata.
+//   4. The kept tokens of a wavefront sit in consecutive slots; their shifts are nearly always one value, so a
+//      wavefront evaluates the 64 sincos of a shift once (lane = rotary pair, angle in double) whenever the shift
+//      changes along its tokens and writes a 512-byte table row per token.
+// At most kScanMaxWG workgroups: longer caches take several passes per workgroup.
 // ---------------------------------------------------------------------------------
-constexpr int kScanThreads = 1024;
+constexpr int kScanThreads = 256;
 constexpr int kScanWaves = kScanThreads / 64;
-constexpr int kScanSub = 4;
+constexpr int kScanPollLimit = 1 << 16;
 
-__device__ __forceinline__ bool keep_rule(int type, int64_t rank, int64_t n_sink, int64_t text_lo, int64_t vis_lo) {
-  return type == SV_TEXT ? (rank < n_sink || rank >= text_lo) : (rank >= vis_lo);
-}
+struct ScanTok {
+  int type, blk, old_base, type_n, blk_n;
+  int64_t rank, gid, rank_n;
+  short4 loc;
+};
 
 __global__ __launch_bounds__(kScanThreads) void k_evict_scan(MetaPtrs in, MetaPtrs out, int32_t* __restrict__ src,
-                                                             int32_t* __restrict__ delta,
-                                                             int32_t* __restrict__ next_out,
+                                                             int32_t* __restrict__ delta, float2* __restrict__ dtab,
+                                                             const double* __restrict__ inv_freq, int half,
+                                                             int f32_data, int32_t* __restrict__ next_out,
                                                              int32_t* __restrict__ n_out, int n_old, int64_t n_sink,
-                                                             int64_t text_lo, int64_t vis_lo) {
-  __shared__ int sh_cnt[kScanSub * kScanWaves];
-  __shared__ int sh_adv[kScanSub * kScanWaves];
-  __shared__ int sh_tot[2];
+                                                             int64_t text_lo, int64_t vis_lo, int passes,
+                                                             unsigned long long* agg, uint32_t tag) {
+  __shared__ int sh_cnt[kScanWaves];
+  __shared__ int sh_adv[kScanWaves];
+  __shared__ int sh_carry[2];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  int carry_cnt = 0, carry_adv = 0;
-  for (int base = 0; base < n_old; base += kScanThreads * kScanSub) {
-    int type[kScanSub], blk[kScanSub], old_base[kScanSub], type_n[kScanSub], blk_n[kScanSub];
-    int64_t rank[kScanSub], gid[kScanSub], rank_n[kScanSub];
-    short4 loc[kScanSub];
+  const int w = blockIdx.x, span = passes * kScanThreads;
+  const int first = w * span;
+
+  // The token and its successor (the look-ahead for "last of its block").  Indices are clamped instead of guarded
+  // and the rule below is written without short-circuits, so that every load is unconditional and all nine go out
+  // together: guarded, the compiler sinks each load into the branch that uses it, one memory round trip after another.
+  auto load_tok = [&](int i) {
+    ScanTok t;
+    const int ic = min(i, n_old - 1), in_ = min(i + 1, n_old - 1);
+    t.type = in.type[ic];
+    t.rank = in.rank[ic];
+    t.blk = in.blk[ic];
+    t.gid = in.gid[ic];
+    t.loc = in.local4[ic];
+    t.old_base = in.pos4[ic].w;
+    t.type_n = in.type[in_];
+    t.rank_n = in.rank[in_];
+    t.blk_n = in.blk[in_];
+    return t;
+  };
+  auto kept = [&](int type, int64_t rank) {
+    const bool text_ok = (rank < n_sink) | (rank >= text_lo), vis_ok = rank >= vis_lo;
+    return type == SV_TEXT ? text_ok : vis_ok;
+  };
+  auto eval = [&](const ScanTok& t, int i, bool& keep, int& adv) {
+    keep = (i < n_old) & kept(t.type, t.rank);
+    // last retained token of its vision block?  (a token without a block, blk < 0, is its own block)
+    const bool next_stays = (t.blk >= 0) & (t.blk_n == t.blk) & (i + 1 < n_old) & kept(t.type_n, t.rank_n);
+    const int adv_vis = next_stays ? 0 : (int)t.loc.w;
+    adv = keep ? (t.type == SV_TEXT ? 1 : adv_vis) : 0;
+  };
+  auto wave_sum = [&](int x) {
 #pragma unroll
-    for (int k = 0; k < kScanSub; ++k) {   // the token and its successor (the look-ahead for "last of its block")
-      const unsigned i = (unsigned)(base + k * kScanThreads + tid);   // (unsigned: scalar base + 32-bit lane offset)
-      const bool valid = i < (unsigned)n_old, valid_n = i + 1 < (unsigned)n_old;
-      type[k] = valid ? in.type[i] : SV_TEXT;
-      rank[k] = valid ? in.rank[i] : 0;
-      blk[k] = valid ? in.blk[i] : -1;
-      gid[k] = valid ? in.gid[i] : 0;
-      loc[k] = valid ? in.local4[i] : make_short4(0, 0, 0, 1);
-      old_base[k] = valid ? in.pos4[i].w : 0;
-      type_n[k] = valid_n ? in.type[i + 1] : SV_TEXT;
-      rank_n[k] = valid_n ? in.rank[i + 1] : 0;
-      blk_n[k] = valid_n ? in.blk[i + 1] : -2;   // matches no block
-    }
-    bool keep[kScanSub];
-    int adv[kScanSub], lane_cnt[kScanSub], incl[kScanSub];
-#pragma unroll
-    for (int k = 0; k < kScanSub; ++k) {
-      const int i = base + k * kScanThreads + tid;
-      keep[k] = i < n_old && keep_rule(type[k], rank[k], n_sink, text_lo, vis_lo);
-      adv[k] = 0;
-      if (keep[k]) {
-        if (type[k] == SV_TEXT) {
-          adv[k] = 1;
-        } else {
-          // last retained token of its vision block?  (a token without a block, blk < 0, is its own block)
-          const bool next_stays = blk[k] >= 0 && blk_n[k] == blk[k] && i + 1 < n_old &&
-                                  keep_rule(type_n[k], rank_n[k], n_sink, text_lo, vis_lo);
-          adv[k] = next_stays ? 0 : (int)loc[k].w;
-        }
-      }
-      // wavefront level: ballot/popcount for the count, shuffle scan for the advance
-      const unsigned long long bal = __ballot(keep[k]);
-      lane_cnt[k] = __popcll(bal & ((1ull << lane) - 1ull));
-      incl[k] = adv[k];
-#pragma unroll
-      for (int off = 1; off < 64; off <<= 1) {
-        const int y = __shfl_up(incl[k], off);
-        if (lane >= off) incl[k] += y;
-      }
-      if (lane == 63) {
-        sh_cnt[k * kScanWaves + wave] = __popcll(bal);
-        sh_adv[k * kScanWaves + wave] = incl[k];
-      }
-    }
-    __syncthreads();
-    // exclusive prefix over the kScanSub * 16 = 64 (sub-tile, wavefront) segments in token order (segment
-    // k * 16 + w), by the first wavefront: one segment per lane
-    static_assert(kScanSub * kScanWaves == 64, "one segment per lane of the first wavefront");
-    if (wave == 0) {
-      const int c0 = sh_cnt[lane], a0 = sh_adv[lane];
-      int ci = c0, ai = a0;
-#pragma unroll
-      for (int off = 1; off < 64; off <<= 1) {
-        const int yc = __shfl_up(ci, off), ya = __shfl_up(ai, off);
-        if (lane >= off) ci += yc, ai += ya;
-      }
-      sh_cnt[lane] = carry_cnt + ci - c0;
-      sh_adv[lane] = carry_adv + ai - a0;
-      if (lane == 63) {
-        sh_tot[0] = carry_cnt + ci;
-        sh_tot[1] = carry_adv + ai;
-      }
-    }
-    __syncthreads();
-    int seg_cnt[kScanSub], seg_adv[kScanSub];
-#pragma unroll
-    for (int k = 0; k < kScanSub; ++k) {
-      seg_cnt[k] = sh_cnt[k * kScanWaves + wave];
-      seg_adv[k] = sh_adv[k * kScanWaves + wave];
-    }
-    const int run_cnt = sh_tot[0], run_adv = sh_tot[1];
-#pragma unroll
-    for (int k = 0; k < kScanSub; ++k) {
-      if (keep[k]) {
-        const int d = seg_cnt[k] + lane_cnt[k];
-        const int nb = seg_adv[k] + (incl[k] - adv[k]);
-        out.gid[d] = gid[k];
-        out.rank[d] = rank[k];
-        out.type[d] = (uint8_t)type[k];
-        out.blk[d] = blk[k];
-        out.local4[d] = loc[k];
-        out.pos4[d] = make_int4(nb + loc[k].x, nb + loc[k].y, nb + loc[k].z, nb);
-        src[d] = base + k * kScanThreads + tid;
-        delta[d] = old_base[k] - nb;
-      }
-    }
-    carry_cnt = run_cnt;
-    carry_adv = run_adv;
-    __syncthreads();
+    for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off);
+    return x;
+  };
+
+  // ---- 1. totals of this workgroup's tokens
+  const ScanTok t0 = load_tok(first + tid);   // pass 0 stays in registers for step 3
+  int my_cnt = 0, my_adv = 0;
+  for (int p = 0; p < passes; ++p) {
+    const int i = first + p * kScanThreads + tid;
+    const ScanTok t = p == 0 ? t0 : load_tok(i);
+    bool keep;
+    int adv;
+    eval(t, i, keep, adv);
+    my_cnt += keep ? 1 : 0;
+    my_adv += adv;
   }
+  my_cnt = wave_sum(my_cnt), my_adv = wave_sum(my_adv);
+  if (lane == 0) sh_cnt[wave] = my_cnt, sh_adv[wave] = my_adv;
+  __syncthreads();
+  const unsigned long long tag_hi = (unsigned long long)tag << 32;
   if (tid == 0) {
-    *next_out = carry_adv;
-    *n_out = carry_cnt;
+    int tc = 0, ta = 0;
+#pragma unroll
+    for (int k = 0; k < kScanWaves; ++k) tc += sh_cnt[k], ta += sh_adv[k];
+    __hip_atomic_store(agg + 2 * w, tag_hi | (uint32_t)tc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(agg + 2 * w + 1, tag_hi | (uint32_t)ta, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
+  // ---- 2. carry: totals of all workgroups before this one
+  if (wave == 0) {
+    int cc = 0, ca = 0;
+    bool lost = false;
+    for (int b0 = 0; b0 < w; b0 += 64) {
+      const int b = b0 + lane;
+      unsigned long long wc = tag_hi, wa = tag_hi;
+      for (int it = 0; it < kScanPollLimit; ++it) {
+        if (b < w) {
+          wc = __hip_atomic_load(agg + 2 * b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          wa = __hip_atomic_load(agg + 2 * b + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        if ((uint32_t)(wc >> 32) == tag && (uint32_t)(wa >> 32) == tag) break;
+        if (it == kScanPollLimit - 1) lost = true;
+        __builtin_amdgcn_s_sleep(1);
+      }
+      cc += (int)(uint32_t)wc, ca += (int)(uint32_t)wa;
+    }
+    cc = wave_sum(cc), ca = wave_sum(ca);
+    // a word that never showed its tag (the limit is far beyond any launch's length): this workgroup writes
+    // nothing, and the failure shows in the device's own token count, which sv_cache_retained checks against the host's
+    if (__any(lost)) cc = -1;
+    if (lane == 0) sh_carry[0] = cc, sh_carry[1] = ca;
+  }
+  __syncthreads();
+  int run_cnt = sh_carry[0], run_adv = sh_carry[1];
+  if (run_cnt < 0) {
+    if (tid == 0) *n_out = -1;
+    return;
+  }
+
+  // ---- 3. and 4. scan of the own tokens on top of the carry, survivors out, table rows
+  for (int p = 0; p < passes; ++p) {
+    const int i = first + p * kScanThreads + tid;
+    const ScanTok t = p == 0 ? t0 : load_tok(i);
+    bool keep;
+    int adv;
+    eval(t, i, keep, adv);
+    const unsigned long long bal = __ballot(keep);
+    const int lane_cnt = __popcll(bal & ((1ull << lane) - 1ull));
+    int incl = adv;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int y = __shfl_up(incl, off);
+      if (lane >= off) incl += y;
+    }
+    __syncthreads();   // the totals of the pass before (or of step 1) have been read
+    if (lane == 63) sh_cnt[wave] = __popcll(bal), sh_adv[wave] = incl;
+    __syncthreads();
+    int seg_cnt = run_cnt, seg_adv = run_adv;
+#pragma unroll
+    for (int k = 0; k < kScanWaves; ++k) {
+      if (k < wave) seg_cnt += sh_cnt[k], seg_adv += sh_adv[k];
+      run_cnt += sh_cnt[k], run_adv += sh_adv[k];
+    }
+    const int d = seg_cnt + lane_cnt;
+    const int nb = seg_adv + (incl - adv);
+    const int dlt = t.old_base - nb;
+    if (keep) {
+      out.gid[d] = t.gid;
+      out.rank[d] = t.rank;
+      out.type[d] = (uint8_t)t.type;
+      out.blk[d] = t.blk;
+      out.local4[d] = t.loc;
+      out.pos4[d] = make_int4(nb + t.loc.x, nb + t.loc.y, nb + t.loc.z, nb);
+      src[d] = i;
+      delta[d] = dlt;
+    }
+    if (dtab != nullptr) {
+      const double my_freq = lane < half ? inv_freq[lane] : 0.0;
+      unsigned long long m = __ballot(keep && dlt != 0);
+      int cur = 0;
+      float2 cs = make_float2(1.f, 0.f);
+      while (m) {   // uniform over the wavefront
+        const int l = __ffsll((long long)m) - 1;
+        m &= m - 1;
+        const int dq = __builtin_amdgcn_readlane(dlt, l), dd = __builtin_amdgcn_readlane(d, l);   // l is uniform
+        if (dq != cur) {
+          cur = dq;
+          if (lane < half) {
+            const double ang = (double)dq * my_freq;
+            if (f32_data) {
+              double sd, cd;
+              sincos(ang, &sd, &cd);
+              cs = make_float2((float)cd, (float)-sd);
+            } else {
+              // bf16 rows: float accuracy is ample, and the double-precision sincos with its large-argument reduction
+              // costs microseconds per call; the angle is reduced to [-pi, pi] in double first (error ~1e-13)
+              const double turns = rint(ang * 0.15915494309189535);
+              const float r = (float)fma(turns, -6.283185307179586, ang);
+              float sf, cf;
+              sincosf(r, &sf, &cf);
+              cs = make_float2(cf, -sf);
+            }
+          }
+        }
+        if (lane < half) dtab[(size_t)dd * half + lane] = cs;
+      }
+    }
+  }
+  if (w == (int)gridDim.x - 1 && tid == 0) {
+    *next_out = run_adv;
+    *n_out = run_cnt;
+  }
+}
+
+// Zeroes the scan's tagged words (when the launch counter wraps).
+__global__ void k_clear_agg(unsigned long long* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0ull;
 }
 
 }  // namespace
@@ -260,9 +345,23 @@ hipError_t launch_evict_scan(const sv_cache* c, int stream, int next_parity, int
   MetaPtrs in = c->meta[cur], out = c->meta[cur ^ 1];
   in.gid += off, in.rank += off, in.pos4 += off, in.local4 += off, in.blk += off, in.type += off;
   out.gid += off, out.rank += off, out.pos4 += off, out.local4 += off, out.blk += off, out.type += off;
-  hipLaunchKernelGGL(k_evict_scan, dim3(1), dim3(kScanThreads), 0, s, in, out, c->src + off, c->delta + off,
-                     c->next_pos + 2 * stream + (next_parity ^ 1), c->n_dev + stream, (int)n_old, n_sink, text_lo,
-                     vis_lo);
+  const int half = c->cfg.head_dim / 2;
+  const int tiles = (int)((n_old + kScanThreads - 1) / kScanThreads);
+  const int passes = (tiles + kScanMaxWG - 1) / kScanMaxWG;
+  const int wgs = (tiles + passes - 1) / passes;
+  unsigned long long* agg = c->scan_agg + (size_t)stream * 2 * kScanMaxWG;
+  uint32_t tag = ++c->scan_seq;
+  if (tag == 0) {   // the counter wrapped: no stale word may carry a tag that is used again
+    const int n = c->cfg.n_streams * 2 * kScanMaxWG;
+    hipLaunchKernelGGL(k_clear_agg, dim3((n + 255) / 256), dim3(256), 0, s, c->scan_agg, n);
+    hipError_t e0 = hipGetLastError();
+    if (e0 != hipSuccess) return e0;
+    tag = ++c->scan_seq;
+  }
+  hipLaunchKernelGGL(k_evict_scan, dim3(wgs), dim3(kScanThreads), 0, s, in, out, c->src + off, c->delta + off,
+                     c->cfg.rope_mode != SV_ROPE_NONE ? c->dtab + off * half : nullptr, c->inv_freq, half,
+                     c->cfg.dtype == SV_DTYPE_F32 ? 1 : 0, c->next_pos + 2 * stream + (next_parity ^ 1), c->n_dev + stream, (int)n_old, n_sink, text_lo,
+                     vis_lo, passes, agg, tag);
   return hipGetLastError();
 }
 

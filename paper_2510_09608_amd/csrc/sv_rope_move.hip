@@ -238,27 +238,6 @@ __global__ __launch_bounds__(256) void k_store_tokens_vt(
 }
 
 // ---------------------------------------------------------------------------------
-// cos/sin of the re-rotation of each surviving token: moving from old to new
-// position turns pair i by -(delta * inv_freq[i]); stored as (cos, -sin) so the
-// mover applies the same formula as a forward rotation.  delta is one scalar per
-// token even in 3-D mode because t, h and w shift together.
-// ---------------------------------------------------------------------------------
-__global__ void k_delta_table(const int32_t* __restrict__ delta, const double* __restrict__ inv_freq,
-                              float2* __restrict__ dtab, int n_new, int half) {
-  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= n_new * half) return;
-  const int j = idx / half, i = idx % half;
-  const int d = delta[j];
-  float2 cs = make_float2(1.f, 0.f);
-  if (d != 0) {
-    double sd, cd;
-    sincos((double)d * inv_freq[i], &sd, &cd);
-    cs = make_float2((float)cd, (float)-sd);
-  }
-  dtab[idx] = cs;
-}
-
-// ---------------------------------------------------------------------------------
 // Compaction gather over all layers: new[l][K|V][h][j] = old[l][K|V][h][src[j]],
 // K re-rotated when delta[j] != 0.  old and new are the two halves of the
 // ping-pong store, so no row is overwritten before it is read.
@@ -385,14 +364,7 @@ hipError_t compact_t(const sv_cache* c, int stream, int64_t n_new, hipStream_t s
   const int cur = c->st[stream].cur;
   const size_t off = (size_t)stream * (size_t)c->cfg.capacity_tokens;
   const int rotate = c->cfg.rope_mode != SV_ROPE_NONE;
-  float2* dtab = c->dtab + off * (D / 2);
-  if (rotate) {
-    const int total = (int)n_new * (D / 2);
-    hipLaunchKernelGGL(k_delta_table, dim3((total + 255) / 256), dim3(256), 0, s, c->delta + off, c->inv_freq, dtab,
-                       (int)n_new, D / 2);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-  }
+  float2* dtab = c->dtab + off * (D / 2);   // rows of the tokens with a shift, written by the eviction scan
   dim3 grid((unsigned)((n_new + G::ROWS - 1) / G::ROWS), c->cfg.n_kv_heads, 2 * c->cfg.n_layers);
   hipLaunchKernelGGL((k_compact<T, D>), grid, dim3(256), 0, s, (const T*)c->kv_ptr(stream, cur, 0, 0),
                      (T*)c->kv_ptr(stream, cur ^ 1, 0, 0), c->src + off, c->delta + off, dtab, (int)n_new,

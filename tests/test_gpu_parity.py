@@ -228,6 +228,33 @@ def test_long_stream_integer_state():
     assert cache.len(0) == 5392
 
 
+def test_long_cache_eviction_many_scan_workgroups():
+    """Eviction of caches long enough for the scan's workgroup limit (128 workgroups of 256 tokens, then several
+    passes per workgroup): 40000 and 70000 tokens of mixed vision blocks and text, windows that cut a block; and an
+    eviction right at the wrap of the scan's launch counter.  Retained ids and positions bit-exact against the oracle."""
+    zt = torch.zeros(4096, 1, 64, device="cuda:0")
+    z = lambda n: np.zeros((n, 1, 2))
+    for total, tags_left in [(40000, -1), (70000, -1), (3000, 1)]:
+        _say(f"long-cache eviction: {total} tokens, tags_left={tags_left}")
+        cache = sv.Cache(1, 1, 1, 64, sv.SV_DTYPE_F32, sv.SV_ROPE_3D, 1e4, (8, 12, 12), 1, total + 4096, 4096)
+        o = orc.OracleStream(1, 1, 1, 2, orc.ROPE_3D, 1e4, (1, 0, 0))
+        n = 0
+        while n < total:
+            for ty, cnt, grid in ((orc.VISION, 2 * 12 * 16, (2, 12, 16)), (orc.TEXT, 37, None)):
+                cache.append(0, 0, np.full(cnt, 1 if ty == orc.VISION else 0, dtype=np.uint8), grid, zt[:cnt], zt[:cnt])
+                o.append_meta([ty] * cnt, grid)
+                o.append_kv(0, z(cnt), z(cnt))
+                n += cnt
+        if tags_left >= 0:
+            cache.set_option(sv.SV_OPT_TAGS_LEFT, tags_left)
+        for budgets in [(100, total // 3 + 77, total // 20), (64, 5000, 333), (64, 5000, 333), (0, 100, 0)]:
+            assert cache.evict(0, *budgets) == o.evict(*budgets)
+            ids, pos = cache.retained(0)
+            assert np.array_equal(ids, np.asarray(o.gid, dtype=np.int64))
+            assert np.array_equal(pos.astype(np.int64), o.positions())
+        cache.close()
+
+
 def test_randomized_streams_integer_state():
     """Seeded sweep: streams of random vision grids (1..3 x 1..12 x 1..16) and text runs, random budgets (0, infinite,
     windows that cut blocks in the middle), evictions skipped now and then, 1-D and 3-D positions: retained ids and
@@ -535,7 +562,7 @@ def test_decode_launch_tag_wraps():
     ref = orc.gqa_attention(q.astype(np.float64), k.astype(np.float64), v.astype(np.float64), np.array([n_kv - 1]), True)
     qd = gu.dev(q, w)
     cache.attn_decode(0, [0], qd, torch.empty_like(qd))     # leaves tagged words of an ordinary launch behind
-    cache.set_option(sv.SV_OPT_DECODE_TAGS_LEFT, 2)
+    cache.set_option(sv.SV_OPT_TAGS_LEFT, 2)
     for i in range(7):
         _say(f"decode launch {i} around the tag wrap")
         od = torch.full_like(qd, float("nan"))
