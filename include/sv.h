@@ -108,11 +108,7 @@ SV_API int sv_cache_destroy(sv_cache* c);
  * defaults to 0 = "let the library choose" (what all measurements use); a positive value forces
  *   SV_OPT_CHUNK_SPLITS           the number of key ranges of sv_attn_chunk's matrix-core kernel,
  *   SV_OPT_DECODE_TILES_PER_WAVE  the 32-key tiles each wavefront of the decode kernel takes (1..16),
- *   SV_OPT_DECODE_SPLITS          the number of key ranges of the generic row kernel,
- *   SV_OPT_TAGS_LEFT              (takes effect at once, is not stored) how many launches are left before the handle's
- *                                 32-bit launch counters wrap (single-stream launches of the matrix-core decode kernel,
- *                                 eviction scans), when the library clears the tagged scratch words those kernels
- *                                 exchange partial results through: lets a test reach the wrap.
+ *   SV_OPT_DECODE_SPLITS          the number of key ranges of the generic row kernel.
  * Forced values are still clamped to what the scratch buffers hold.  Host-side state only: takes effect
  * from the next launch.  Errors: SV_ERR_INVALID (NULL handle, unknown option, negative value).
  */
@@ -120,8 +116,7 @@ enum {
   SV_OPT_CHUNK_SPLITS = 0,
   SV_OPT_DECODE_TILES_PER_WAVE = 1,
   SV_OPT_DECODE_SPLITS = 2,
-  SV_OPT_TAGS_LEFT = 3,
-  SV_OPT_COUNT_ = 4
+  SV_OPT_COUNT_ = 3
 };
 SV_API int sv_cache_set_option(sv_cache* c, int option, int value);
 
@@ -220,8 +215,10 @@ SV_API int sv_attn_decode(sv_cache* c, int layer, const int32_t* stream_ids_host
  * one GPU (different streams, different handles) race; calls ordered on one stream do not.  The array is
  * zero when the library is loaded and needs no clearing between calls: half of it holds the plain partial
  * results of multi-row calls, every entry of which a call writes before its merge launch reads it; the other
- * half holds those of one-row calls as 64-bit words {value, call number}, which the call's own workgroups read
- * until they see the number of this call (the library clears that half itself when the 32-bit number wraps).
+ * half holds those of one-row calls as 64-bit words {value, launch tag}, which the call's own workgroups read
+ * until they carry the tag of this launch; the tag is kept in the array itself and moved on by every launch.
+ * Nothing in a launch depends on host state that changes from call to call, so a captured call may be replayed
+ * while the cache is unchanged.
  */
 #define SV_STATIC_MAX_ROWS 64
 SV_API int sv_attn_decode_static(sv_cache* c, int layer, const int32_t* stream_ids_host, int n_list,

@@ -86,10 +86,10 @@ Layout make_layout(const sv_config& c) {
   L.part_o = take((size_t)L.part_rows * c.n_q_heads * c.head_dim * 4);
   L.part_ml = take((size_t)L.part_rows * c.n_q_heads * 4 * 4);   // up to 4 floats per (row, range, head)
   L.counters = take((size_t)L.part_rows * c.n_kv_heads * 4);
-  // matrix-core decode, single stream: tagged words of up to 128 key ranges
-  L.part_dec_bytes = mfma_eligible(c) ? sv::decode_tagged_bytes(c) : 0;
+  // matrix-core decode, single stream: marked words of up to 128 key ranges
+  L.part_dec_bytes = mfma_eligible(c) ? sv::decode_marked_bytes(c) : 0;
   L.part_dec = take(L.part_dec_bytes);
-  L.scan_agg = take(S * 2 * sv::kScanMaxWG * 8);
+  L.scan_agg = take(S * 2 * (sv::kScanMaxWG + 1) * 8);
   L.total = off;
   return L;
 }
@@ -219,7 +219,7 @@ int sv_cache_create(const sv_config* cfg, void* dev_arena, size_t arena_bytes, v
   if (e == hipSuccess) e = hipMemsetAsync(c->n_dev, 0, (size_t)cfg->n_streams * 4, s);
   if (e == hipSuccess) e = hipMemsetAsync(c->counters, 0, (size_t)L.part_rows * cfg->n_kv_heads * 4, s);
   if (e == hipSuccess && L.part_dec_bytes > 0) e = hipMemsetAsync(c->part_dec, 0, L.part_dec_bytes, s);
-  if (e == hipSuccess) e = hipMemsetAsync(c->scan_agg, 0, (size_t)cfg->n_streams * 2 * sv::kScanMaxWG * 8, s);
+  if (e == hipSuccess) e = hipMemsetAsync(c->scan_agg, 0, (size_t)cfg->n_streams * 2 * (sv::kScanMaxWG + 1) * 8, s);
   // blocked V^T: slots past a stream's end inside its last block are multiplied by probabilities of zero and must
   // never hold NaN patterns, so the store starts out cleared
   if (e == hipSuccess && c->v_blocked)
@@ -246,10 +246,6 @@ int sv_cache_destroy(sv_cache* c) {
 
 int sv_cache_set_option(sv_cache* c, int option, int value) {
   if (!c || option < 0 || option >= SV_OPT_COUNT_ || value < 0) return SV_ERR_INVALID;
-  if (option == SV_OPT_TAGS_LEFT) {
-    c->dec_seq = c->scan_seq = 0xFFFFFFFFu - (uint32_t)value;   // the launch after `value` more gets tag 0, i.e. wraps
-    return SV_OK;
-  }
   c->opt[option] = value;
   return SV_OK;
 }

@@ -29,13 +29,15 @@
 //     {fp32 value, 32-bit launch tag} with relaxed device-scope atomic stores, and the
 //     workgroups of a kv head share out the result, each reading the words of all ranges
 //     with relaxed device-scope atomic loads until every word carries this launch's tag
-//     (see merge_ranges).  (A merge by the last workgroup to arrive needs device-scope
-//     release/acquire fences, about 3 us each here; a second launch costs its gap and a
-//     round trip of its own.)  A batch's key ranges are merged by a second, small launch.
+//     (see merge_ranges; the tag lives in device memory, next to the words).  (A merge by the last workgroup to arrive
+//     needs device-scope release/acquire fences, about 3 us each here; a second launch
+//     costs its gap and a round trip of its own.)  A batch's key ranges are merged by a
+//     second, small launch.
 
 #include <hip/hip_bf16.h>
 
 #include <algorithm>
+#include <type_traits>
 
 #include "sv_internal.h"
 
@@ -83,7 +85,9 @@ constexpr int GMAX = 8;       // query heads per kv head this kernel handles
 constexpr int TK = 32;        // keys per wavefront tile
 constexpr int kMaxSplitsD = 128;
 constexpr int kMaxRowsD = 64;
-constexpr int PW = D + 1;      // tagged words a key range publishes per query head: 128 values and the log-sum-exp
+constexpr int PW = D + 1;      // words a key range publishes per query head: 128 values and the log-sum-exp
+// 64-bit header words in front of a tagged region: one per kv head, rounded up to 32
+static inline int hdr_words_of(int n_kv_heads) { return (n_kv_heads + 31) / 32 * 32; }
 constexpr int kPollLimit = 1 << 16;   // polls of a merge read before giving up (each is a memory round trip)
 
 struct DecRow {
@@ -141,12 +145,12 @@ __device__ __forceinline__ void rotate_pair_chunks(uint4& lo, uint4& hi, const f
 // unless a row has more than 64 ranges or the workgroup more than NT outputs.
 // phk: the partial result of range 0, first query head of the kv head; range s adds s * sstride words, head g adds
 // g * PW words.  Words are plain floats, or (POLL) 64-bit {float, launch tag}.
-// POLL: the ranges are being written by other workgroups of the SAME launch: every word is read with a relaxed
-// device-scope atomic load, again and again until it carries this launch's tag.  Its writer, a workgroup that
-// waits for nothing, has then written it, and the value in the same word is the one that goes with it (a 64-bit
-// access is single-copy atomic, a word is written once per launch); no ordering between locations is needed.
-// Workgroups are dispatched in index order and the ranges of a (row, kv head) are neighbours in it, so whatever a
-// workgroup waits for is resident or next in line; the polls are bounded all the same.
+// POLL: the ranges are being written by other workgroups of the SAME launch.  Every word is read with a relaxed
+// device-scope atomic load, again and again until it carries this launch's tag: its writer, a workgroup that waits
+// for nothing, has then written it, and the value in the same word is the one that goes with it (a 64-bit access is
+// single-copy atomic, a word is written once per launch); no ordering between locations is needed.  Workgroups are
+// dispatched in index order and the ranges of a (row, kv head) are neighbours in it, so whatever a workgroup waits
+// for is resident or next in line; the polls are bounded all the same.
 // ---------------------------------------------------------------------------------
 template <int NT, bool POLL>
 __device__ __forceinline__ void merge_ranges(const void* phk, size_t sstride, int nsr, uint32_t tag,
@@ -161,7 +165,6 @@ __device__ __forceinline__ void merge_ranges(const void* phk, size_t sstride, in
   float* s_m = s_acc + NT;
   float* s_w = s_m + NT;
   const int ol = tid & (OPP - 1), rg = tid >> (LNT - lrg);
-  const unsigned long long tag_hi = (unsigned long long)tag << 32;
   for (int ob = 0; ob < n_out; ob += OPP) {
     const int o = o_lo + ob + (ob + ol < n_out ? ol : 0);
     const int g = o >> 7, d = o & (D - 1);
@@ -169,19 +172,22 @@ __device__ __forceinline__ void merge_ranges(const void* phk, size_t sstride, in
     const float* pf = (const float*)phk + (size_t)g * PW;                             // !POLL
     float m_ref = -INFINITY, wsum = 0.f, acc = 0.f;
     [[maybe_unused]] unsigned long long ts_tries = 0;
-    for (int s0 = rg; s0 < nsr; s0 += 8 * RG) {
-      unsigned long long wv[8], we[8];
+    // One pass: U ranges per thread, s0, s0 + RG, ...; all but the last are known to exist, the last may lie past
+    // the end for the higher range groups (it then reads the thread's first range again and is left out).  The
+    // loads are unconditional, so that the compiler issues them together; guarded ones it waits for one by one.
+    auto pass = [&](auto Uc, int s0) {
+      constexpr int U = decltype(Uc)::value;
+      const bool last_ok = s0 + RG * (U - 1) < nsr;
+      unsigned long long wv[U], we[U];
       bool ok = false;
       for (int it = 0; it < kPollLimit && !ok; ++it) {
         SV_TS_COUNT(ts_tries);
         if (it >= 3) __builtin_amdgcn_s_sleep(2);
         ok = true;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const int si = s0 + RG * j;
-          if (si >= nsr) {
-            wv[j] = we[j] = tag_hi;
-          } else if constexpr (POLL) {
+        for (int j = 0; j < U; ++j) {
+          const int si = (j < U - 1 || last_ok) ? s0 + RG * j : s0;
+          if constexpr (POLL) {
             wv[j] = __hip_atomic_load(pv + (size_t)si * sstride + d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             we[j] = __hip_atomic_load(pv + (size_t)si * sstride + D, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
           } else {
@@ -191,25 +197,41 @@ __device__ __forceinline__ void merge_ranges(const void* phk, size_t sstride, in
         }
         if constexpr (POLL) {
 #pragma unroll
-          for (int j = 0; j < 8; ++j) ok = ok && (uint32_t)(wv[j] >> 32) == tag && (uint32_t)(we[j] >> 32) == tag;
+          for (int j = 0; j < U; ++j) ok = ok && (uint32_t)(wv[j] >> 32) == tag && (uint32_t)(we[j] >> 32) == tag;
         }
       }
       float mx = m_ref;
 #pragma unroll
-      for (int j = 0; j < 8; ++j)
-        if (s0 + RG * j < nsr) mx = fmaxf(mx, __uint_as_float((uint32_t)we[j]));
+      for (int j = 0; j < U; ++j)
+        if (j < U - 1 || last_ok) mx = fmaxf(mx, __uint_as_float((uint32_t)we[j]));
       // a read that never saw its tag (the limit is thousands of times any launch's length) poisons the output
       if (!ok) mx = __uint_as_float(0x7fc00000u);
       const float resc = m_ref == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_ref - mx);
       acc *= resc, wsum *= resc;
 #pragma unroll
-      for (int j = 0; j < 8; ++j)
-        if (s0 + RG * j < nsr) {
+      for (int j = 0; j < U; ++j)
+        if (j < U - 1 || last_ok) {
           const float w = __builtin_amdgcn_exp2f(__uint_as_float((uint32_t)we[j]) - mx);
           acc += w * __uint_as_float((uint32_t)wv[j]);
           wsum += w;
         }
       m_ref = mx;
+    };
+    // ranges per thread: ceil(nsr / RG) for the lowest range groups, one less for the others; whole passes of 8,
+    // then ONE pass of exactly what is left
+    int left = (nsr + RG - 1) >> lrg, s0 = rg;
+    for (; left > 8; left -= 8, s0 += 8 * RG) pass(std::integral_constant<int, 8>{}, s0);
+    if (s0 < nsr) {   // (a thread of a higher range group may have nothing at all in the last pass)
+      switch (left) {
+        case 1: pass(std::integral_constant<int, 1>{}, s0); break;
+        case 2: pass(std::integral_constant<int, 2>{}, s0); break;
+        case 3: pass(std::integral_constant<int, 3>{}, s0); break;
+        case 4: pass(std::integral_constant<int, 4>{}, s0); break;
+        case 5: pass(std::integral_constant<int, 5>{}, s0); break;
+        case 6: pass(std::integral_constant<int, 6>{}, s0); break;
+        case 7: pass(std::integral_constant<int, 7>{}, s0); break;
+        default: pass(std::integral_constant<int, 8>{}, s0); break;
+      }
     }
     SV_TS(0, ts_wg, 4);
     SV_TS_VAL(ts_wg, 6, ts_tries);
@@ -254,7 +276,7 @@ __global__ __launch_bounds__(NW * 64, 2) void k_decode_mfma(__hip_bfloat16* k0_,
                                                          const __hip_bfloat16* __restrict__ v_new,
                                                          size_t head_stride_elems, int fused, int rotate,
                                                          __hip_bfloat16* __restrict__ out, void* part,
-                                                         uint32_t tag, int n_q_heads, int n_kv_heads, int G,
+                                                         int hdr_words, int n_q_heads, int n_kv_heads, int G,
                                                          float c_log2, DecTable tab SV_TS_PARAM) {
   [[maybe_unused]] const int ts_wg = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
   SV_TS(0, ts_wg, 0);
@@ -270,6 +292,15 @@ __global__ __launch_bounds__(NW * 64, 2) void k_decode_mfma(__hip_bfloat16* k0_,
   const int len = rd.len;
   const int kps = rd.kps;   // rows of a batch are cut into ranges of their own size
   const int nsr = (len + kps - 1) / kps;   // key ranges of this row
+  // Single stream: the words' header of this kv head, {tag of the launch before, its number of key ranges}, written
+  // by the launch before (read here, used after the tiles).  This launch's tag is the next one, never 0.
+  // Thread 0 reads it, the workgroup takes it from LDS behind the barrier that precedes all its publishing: the
+  // workgroup of range 0 replaces the header once it has seen every range publish, i.e. after all have read it.
+  __shared__ unsigned long long sHdr;
+  // (Every thread issues the load, without a branch: behind `if (tid == 0)` the compiler waits for it on the spot,
+  // and the first wavefront would start its K/V loads a memory round trip late.)
+  [[maybe_unused]] unsigned long long hdr_old = 0;
+  if constexpr (ONE) hdr_old = ((const unsigned long long*)part)[hk];
   const int k0 = sp * kps, k1 = min(len, k0 + kps);
   if (k0 >= len) return;   // a shorter row of the batch has fewer ranges than the grid is wide
   const __hip_bfloat16* kp = rd.k + (size_t)hk * head_stride_elems;
@@ -456,14 +487,22 @@ __global__ __launch_bounds__(NW * 64, 2) void k_decode_mfma(__hip_bfloat16* k0_,
       sML[wave][l16][1] = l_run;
     }
   }
+  if constexpr (ONE) {
+    if (tid == 0) sHdr = hdr_old;
+  }
   __syncthreads();
+  if constexpr (ONE) hdr_old = sHdr;
 
   // ---- merge the wavefronts; with one key range this is the result, else the range's partial result: normalised
-  // values and the log-sum-exp (log2 units), each word tagged with this launch's number
-  // (a single stream: 64-bit words {value, launch tag}, read in this launch; a batch: plain floats for the merge launch)
+  // values and the log-sum-exp (log2 units)
+  // (a single stream: 64-bit words {value, launch tag} behind the headers, read in this launch; a batch: plain floats
+  // for the merge launch)
   const size_t prow_off = ((size_t)(rd.pair0 + sp) * n_q_heads + (size_t)hk * G) * PW;
-  unsigned long long* prow = (unsigned long long*)part + prow_off;
+  unsigned long long* const words = (unsigned long long*)part + hdr_words;
+  unsigned long long* prow = words + prow_off;
   float* prow_f = (float*)part + prow_off;
+  const uint32_t tag_old = __builtin_amdgcn_readfirstlane((uint32_t)(hdr_old >> 32));   // uniform, and known to be
+  const uint32_t tag = tag_old + 1u == 0u ? 1u : tag_old + 1u;
   const unsigned long long tag_hi = (unsigned long long)tag << 32;
   for (int idx = tid; idx < G * D; idx += NW * 64) {
     const int g = idx / D, d = idx % D;
@@ -496,7 +535,19 @@ __global__ __launch_bounds__(NW * 64, 2) void k_decode_mfma(__hip_bfloat16* k0_,
     // A single stream is latency bound and its workgroups end together: they merge the key ranges themselves, the
     // workgroups of the first min(ranges, 4 G) ranges of a kv head taking a run of outputs each, instead of leaving
     // it to a second launch (a launch gap and a round trip of its own: about 1.2 us more per layer-step).
-    if (nsr == 1) return;
+    // Words of ranges that the launch before had and this one has not (the cache shrank) go back to zero, so that no
+    // word is ever older than one launch: a word that does not carry this launch's tag carries the one before or none,
+    // also when the 32-bit tag wraps, and nothing depends on host state (a captured launch can be replayed).
+    const int nsr_old = (int)(uint32_t)hdr_old;
+    for (int r = nsr + sp; r < nsr_old; r += nsr) {
+      unsigned long long* pz = words + ((size_t)r * n_q_heads + (size_t)hk * G) * PW;
+      for (int idx = tid; idx < G * PW; idx += NW * 64)
+        __hip_atomic_store(pz + idx, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (nsr == 1) {
+      if (tid == 0) ((unsigned long long*)part)[hk] = tag_hi | 1ull;
+      return;
+    }
     int o_lo, n_out;
     if (!merge_share(G, min(nsr, G * 4), sp, o_lo, n_out)) return;
     // the first merge read also wants this workgroup's own words: let their stores be acknowledged first (a read
@@ -504,9 +555,11 @@ __global__ __launch_bounds__(NW * 64, 2) void k_decode_mfma(__hip_bfloat16* k0_,
     __builtin_amdgcn_s_waitcnt(0x0F70);
     SV_TS(0, ts_wg, 3);
     __syncthreads();   // the wavefront results in LDS have been read: their space is reused
-    merge_ranges<NW * 64, true>((const unsigned long long*)part + ((size_t)rd.pair0 * n_q_heads + (size_t)hk * G) * PW, (size_t)n_q_heads * PW, nsr,
+    merge_ranges<NW * 64, true>(words + ((size_t)rd.pair0 * n_q_heads + (size_t)hk * G) * PW, (size_t)n_q_heads * PW, nsr,
                                 tag, o_lo, n_out, &sO[0][0][0], out + ((size_t)b * n_q_heads + hk * G) * D SV_TS_ARG(ts_slot),
                                 ts_wg);
+    // the workgroup of range 0 has seen every range of the kv head publish, i.e. read the header: the new one goes in
+    if (sp == 0 && tid == 0) ((unsigned long long*)part)[hk] = tag_hi | (uint32_t)nsr;
 #ifdef SV_TIMELINE
     __builtin_amdgcn_s_waitcnt(0x0F70);
     SV_TS(0, ts_wg, 5);
@@ -546,20 +599,14 @@ __global__ __launch_bounds__(256) void k_decode_merge(const float* __restrict__ 
 int g_ts_launch = 0;   // host: launches so far; the slot of a launch is this modulo 8
 #endif
 
-// Zeroes the tagged-word scratch (when a tag counter wraps: no stale word may carry a tag that comes round again).
-__global__ void k_clear_words(unsigned long long* p, size_t n) {
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0ull;
-}
-
 }  // namespace
 
-// Where the key ranges' partial results go.  tagged: 64-bit words of single-stream launches, room for tagged_pairs
-// (row, key range) pairs, written by nothing else and zero before the first launch; seq: its launch counter (tags are
-// never 0 and never repeat while a stale word could carry them).  plain: floats of batch launches, plain_pairs pairs.
+// Where the key ranges' partial results go.  marked: header words (hdr_words_of), then the 64-bit words of single-stream
+// launches, room for marked_pairs (row, key range) pairs; written by nothing else, zero before the first launch.
+// plain: floats of batch launches, plain_pairs pairs.
 struct DecScratch {
-  unsigned long long* tagged;
-  int64_t tagged_pairs;
-  uint32_t* seq;
+  unsigned long long* marked;
+  int64_t marked_pairs;
   float* plain;
   int64_t plain_pairs;
 };
@@ -574,7 +621,7 @@ static hipError_t decode_launch(const sv_cache* c, const DecTable& tab, int fuse
   // holds most of them).
   const bool stream_loads = total_tiles * (int64_t)(TK * D * 2 * 2) * Hkv >= ((int64_t)96 << 20);
   const bool one = nr == 1 && !stream_loads;   // the single-stream instantiation: merges its key ranges itself
-  const int64_t part_pairs = one ? scr.tagged_pairs : scr.plain_pairs;
+  const int64_t part_pairs = one ? scr.marked_pairs : scr.plain_pairs;
   // Key ranges.  A single stream is latency bound: ranges of 128 keys (one 32-key tile per wavefront) spread its
   // few hundred tiles over the most CUs and cost one memory round trip.  A batch is bandwidth bound: longer ranges
   // keep the partial results and their merge small, and all workgroups should be resident at once (two fit a CU:
@@ -613,17 +660,7 @@ static hipError_t decode_launch(const sv_cache* c, const DecTable& tab, int fuse
     pair0 += ranges;
     n_splits = std::max(n_splits, ranges);
   }
-  uint32_t tag = 0;
-  if (one && n_splits > 1) {
-    tag = ++*scr.seq;
-    if (tag == 0) {   // the counter wrapped: clear the scratch, so that no stale word carries a tag that is used again
-      hipLaunchKernelGGL(k_clear_words, dim3(1024), dim3(256), 0, s, scr.tagged, (size_t)scr.tagged_pairs * Hq * PW);
-      hipError_t e0 = hipGetLastError();
-      if (e0 != hipSuccess) return e0;
-      tag = ++*scr.seq;
-    }
-  }
-  void* part = one ? (void*)scr.tagged : (void*)scr.plain;
+  void* part = one ? (void*)scr.marked : (void*)scr.plain;
   const int keys_per_split = tabk.r[0].kps;
   const float c_log2 = 1.4426950408889634f / sqrtf((float)D);
   const __hip_bfloat16* qp = (const __hip_bfloat16*)q + r0 * Hq * D;
@@ -634,15 +671,15 @@ static hipError_t decode_launch(const sv_cache* c, const DecTable& tab, int fuse
   const DecRow& r = tabk.r[0];
   if (one)
     hipLaunchKernelGGL((k_decode_mfma<NW, true, false>), dim3(n_splits, Hkv, 1), dim3(NW * 64), 0, s, r.k, r.v, r.cs, r.len,
-                       keys_per_split, qp, knp, vnp, c->head_stride / 2, fused, rotate, op, part, tag, Hq, Hkv,
+                       keys_per_split, qp, knp, vnp, c->head_stride / 2, fused, rotate, op, part, hdr_words_of(Hkv), Hq, Hkv,
                        c->group, c_log2, tabk SV_TS_ARG(g_ts_launch % 8));
   else if (stream_loads)
     hipLaunchKernelGGL((k_decode_mfma<NW, false, true>), dim3(n_splits, Hkv, nr), dim3(NW * 64), 0, s, r.k, r.v, r.cs, r.len,
-                       keys_per_split, qp, knp, vnp, c->head_stride / 2, fused, rotate, op, part, tag, Hq, Hkv,
+                       keys_per_split, qp, knp, vnp, c->head_stride / 2, fused, rotate, op, part, hdr_words_of(Hkv), Hq, Hkv,
                        c->group, c_log2, tabk SV_TS_ARG(g_ts_launch % 8));
   else
     hipLaunchKernelGGL((k_decode_mfma<NW, false, false>), dim3(n_splits, Hkv, nr), dim3(NW * 64), 0, s, r.k, r.v, r.cs, r.len,
-                       keys_per_split, qp, knp, vnp, c->head_stride / 2, fused, rotate, op, part, tag, Hq, Hkv,
+                       keys_per_split, qp, knp, vnp, c->head_stride / 2, fused, rotate, op, part, hdr_words_of(Hkv), Hq, Hkv,
                        c->group, c_log2, tabk SV_TS_ARG(g_ts_launch % 8));
 #ifdef SV_TIMELINE
   ++g_ts_launch;
@@ -655,14 +692,12 @@ static hipError_t decode_launch(const sv_cache* c, const DecTable& tab, int fuse
 
 // Partial results of the key ranges live in the cache arena by default; sv_attn_decode_static keeps them in a
 // file-scope device array instead (callers that cannot provide scratch memory; zero at load, as every device-scope
-// array): its first half holds the tagged words of single-stream launches, its second half the floats of batches.
-// The array's name is only a host-side handle: its device address is looked up once per device and kept.  The array
-// has one launch counter per device, shared by all handles.
+// array): its first half holds the marked words of single-stream launches, its second half the floats of batches.
+// The array's name is only a host-side handle: its device address is looked up once per device and kept.
 constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
 constexpr int kMaxDevices = 64;
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 static void* g_scratch_ptr[kMaxDevices] = {};
-static uint32_t g_scratch_seq[kMaxDevices] = {};
 
 static hipError_t static_scratch_of_device(void** ptr_out, int* dev_out) {
   int dev = -1;
@@ -683,8 +718,8 @@ static hipError_t static_scratch_of_device(void** ptr_out, int* dev_out) {
 
 hipError_t decode_static_scratch(void** ptr_out) { return static_scratch_of_device(ptr_out, nullptr); }
 
-size_t decode_tagged_bytes(const sv_config& cfg) {
-  return (size_t)kMaxSplitsD * cfg.n_q_heads * PW * sizeof(unsigned long long);
+size_t decode_marked_bytes(const sv_config& cfg) {
+  return ((size_t)kMaxSplitsD * cfg.n_q_heads * PW + hdr_words_of(cfg.n_kv_heads)) * sizeof(unsigned long long);
 }
 
 int64_t decode_plain_pairs(const sv_cache* c) {   // the arena's split-KV region holds part_rows x heads x 128 floats
@@ -722,7 +757,7 @@ static hipError_t decode_rows(const sv_cache* c, int layer, const int32_t* strea
 
 hipError_t launch_attn_decode_mfma(const sv_cache* c, int layer, const int32_t* streams, int n_list, int fused,
                                    const void* q, const void* k_new, const void* v_new, void* o, hipStream_t s) {
-  const DecScratch scr = {c->part_dec, kMaxSplitsD, &c->dec_seq, c->part_o, decode_plain_pairs(c)};
+  const DecScratch scr = {c->part_dec, kMaxSplitsD, c->part_o, decode_plain_pairs(c)};
   return decode_rows(c, layer, streams, n_list, fused, q, k_new, v_new, o, scr, s);
 }
 
@@ -734,7 +769,7 @@ hipError_t launch_attn_decode_mfma_static(const sv_cache* c, int layer, const in
   if (e != hipSuccess) return e;
   const size_t half = kStaticScratchBytes / 2;
   const DecScratch scr = {(unsigned long long*)p,
-                          (int64_t)(half / ((size_t)c->cfg.n_q_heads * PW * sizeof(unsigned long long))), &g_scratch_seq[dev],
+                          (int64_t)((half - (size_t)hdr_words_of(c->cfg.n_kv_heads) * 8) / ((size_t)c->cfg.n_q_heads * PW * sizeof(unsigned long long))),
                           (float*)((char*)p + half), decode_static_pairs(c)};
   return decode_rows(c, layer, streams, n_list, 0, q, nullptr, nullptr, o, scr, s);
 }

@@ -83,12 +83,11 @@ struct sv_cache {
   float* part_ml;            // device split-KV partial (max, sum)
   int64_t part_rows;         // capacity of the partial buffers in (token, split) pairs
   int32_t* counters;         // device [part_rows][n_kv_heads]  arrival counters of the split-KV merge (zero between launches)
-  unsigned long long* part_dec;   // device: tagged partial results of a single stream's key ranges in the matrix-core
-                                  // decode kernel (zero at create, written by nothing else; sv_attn_decode.hip)
-  mutable uint32_t dec_seq = 0;   // launches that have used part_dec: the tag of the next one is this + 1
-  unsigned long long* scan_agg;   // device [n_streams][kScanMaxWG][2]: tagged totals of the eviction scan's workgroups
-                                  // (zero at create, written by nothing else; sv_meta.hip)
-  mutable uint32_t scan_seq = 0;  // eviction scans launched: the tag of the next one is this + 1
+  unsigned long long* part_dec;   // device: marked partial results of a single stream's key ranges in the matrix-core
+                                  // decode kernel (zero at create and between launches; sv_attn_decode.hip)
+  unsigned long long* scan_agg;   // device [n_streams][kScanMaxWG + 1][2]: tagged totals of the eviction scan's
+                                  // workgroups, then the scan's launch tag (zero at create, written by nothing else;
+                                  // sv_meta.hip)
   bool host_logic_only = false;   // created with SV_HOST_LOGIC_ONLY: no device work, bookkeeping only
   bool use_mfma = false;          // bf16, head_dim 128, group <= 8 and no SV_FLAG_GENERIC_KERNELS: matrix-core kernels
   bool v_blocked = false;         // V stored as V^T in blocks of 8 keys (exactly the caches with use_mfma), else row-major
@@ -148,7 +147,7 @@ hipError_t launch_attn_decode_mfma(const sv_cache* c, int layer, const int32_t* 
 // number of (row, key range) pairs the array holds for this cache's head count.
 hipError_t decode_static_scratch(void** ptr_out);
 int64_t decode_static_pairs(const sv_cache* c);
-size_t decode_tagged_bytes(const sv_config& cfg);   // bytes of sv_cache::part_dec
+size_t decode_marked_bytes(const sv_config& cfg);   // bytes of sv_cache::part_dec
 hipError_t launch_attn_decode_mfma_static(const sv_cache* c, int layer, const int32_t* streams, int n_list,
                                           const void* q, void* o, hipStream_t s);
 

@@ -115,6 +115,10 @@ __global__ void k_meta_append(MetaPtrs m, const int32_t* __restrict__ next_in, i
 //   2. Its first wavefront reads the words of all workgroups before it, again and again until each carries this
 //      launch's tag (a word is its own ready flag: a 64-bit access is single-copy atomic and a word is written once
 //      per launch; the writers wait for nothing and are dispatched earlier), and sums them: the carry.
+//      The tag lives in device memory behind the words: a launch uses the stored value + 1 (never 0), and the last
+//      workgroup, which ends only after every other one has published, i.e. read the tag, stores the new value and
+//      zeroes the words of the workgroups this launch did not have; so a word left over from an earlier launch
+//      carries the tag before this one or none, and nothing depends on host state (a captured launch can be replayed).
 //   3. It scans its own tokens (ballot / popcount for the slot, shuffle scan for the advance, four wavefront totals
 //      through LDS) on top of the carry and writes the survivors' metadata.
 //   4. The kept tokens of a wavefront sit in consecutive slots; their shifts are nearly always one value, so a
@@ -138,13 +142,15 @@ __global__ __launch_bounds__(kScanThreads) void k_evict_scan(MetaPtrs in, MetaPt
                                                              int f32_data, int32_t* __restrict__ next_out,
                                                              int32_t* __restrict__ n_out, int n_old, int64_t n_sink,
                                                              int64_t text_lo, int64_t vis_lo, int passes,
-                                                             unsigned long long* agg, uint32_t tag) {
+                                                             unsigned long long* agg) {
   __shared__ int sh_cnt[kScanWaves];
   __shared__ int sh_adv[kScanWaves];
   __shared__ int sh_carry[2];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int w = blockIdx.x, span = passes * kScanThreads;
   const int first = w * span;
+  const uint32_t tag_old = (uint32_t)agg[2 * kScanMaxWG];   // written by the launch before this one
+  const uint32_t tag = tag_old + 1u == 0u ? 1u : tag_old + 1u;
 
   // The token and its successor (the look-ahead for "last of its block").  Indices are clamped instead of guarded
   // and the rule below is written without short-circuits, so that every load is unconditional and all nine go out
@@ -303,16 +309,14 @@ __global__ __launch_bounds__(kScanThreads) void k_evict_scan(MetaPtrs in, MetaPt
       }
     }
   }
-  if (w == (int)gridDim.x - 1 && tid == 0) {
-    *next_out = run_adv;
-    *n_out = run_cnt;
+  if (w == (int)gridDim.x - 1) {
+    if (tid == 0) {
+      *next_out = run_adv;
+      *n_out = run_cnt;
+      agg[2 * kScanMaxWG] = tag;
+    }
+    for (int b = (int)gridDim.x + tid; b < kScanMaxWG; b += kScanThreads) agg[2 * b] = 0ull, agg[2 * b + 1] = 0ull;
   }
-}
-
-// Zeroes the scan's tagged words (when the launch counter wraps).
-__global__ void k_clear_agg(unsigned long long* p, int n) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = 0ull;
 }
 
 }  // namespace
@@ -349,19 +353,11 @@ hipError_t launch_evict_scan(const sv_cache* c, int stream, int next_parity, int
   const int tiles = (int)((n_old + kScanThreads - 1) / kScanThreads);
   const int passes = (tiles + kScanMaxWG - 1) / kScanMaxWG;
   const int wgs = (tiles + passes - 1) / passes;
-  unsigned long long* agg = c->scan_agg + (size_t)stream * 2 * kScanMaxWG;
-  uint32_t tag = ++c->scan_seq;
-  if (tag == 0) {   // the counter wrapped: no stale word may carry a tag that is used again
-    const int n = c->cfg.n_streams * 2 * kScanMaxWG;
-    hipLaunchKernelGGL(k_clear_agg, dim3((n + 255) / 256), dim3(256), 0, s, c->scan_agg, n);
-    hipError_t e0 = hipGetLastError();
-    if (e0 != hipSuccess) return e0;
-    tag = ++c->scan_seq;
-  }
+  unsigned long long* agg = c->scan_agg + (size_t)stream * 2 * (kScanMaxWG + 1);
   hipLaunchKernelGGL(k_evict_scan, dim3(wgs), dim3(kScanThreads), 0, s, in, out, c->src + off, c->delta + off,
                      c->cfg.rope_mode != SV_ROPE_NONE ? c->dtab + off * half : nullptr, c->inv_freq, half,
                      c->cfg.dtype == SV_DTYPE_F32 ? 1 : 0, c->next_pos + 2 * stream + (next_parity ^ 1), c->n_dev + stream, (int)n_old, n_sink, text_lo,
-                     vis_lo, passes, agg, tag);
+                     vis_lo, passes, agg);
   return hipGetLastError();
 }
 

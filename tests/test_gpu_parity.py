@@ -230,12 +230,13 @@ def test_long_stream_integer_state():
 
 def test_long_cache_eviction_many_scan_workgroups():
     """Eviction of caches long enough for the scan's workgroup limit (128 workgroups of 256 tokens, then several
-    passes per workgroup): 40000 and 70000 tokens of mixed vision blocks and text, windows that cut a block; and an
-    eviction right at the wrap of the scan's launch counter.  Retained ids and positions bit-exact against the oracle."""
+    passes per workgroup): 40000 and 70000 tokens of mixed vision blocks and text, windows that cut a block, four
+    evictions in a row each (the scan's launch tag moves on in device memory, the workgroup count shrinks).  Retained
+    ids and positions bit-exact against the oracle."""
     zt = torch.zeros(4096, 1, 64, device="cuda:0")
     z = lambda n: np.zeros((n, 1, 2))
-    for total, tags_left in [(40000, -1), (70000, -1), (3000, 1)]:
-        _say(f"long-cache eviction: {total} tokens, tags_left={tags_left}")
+    for total in [40000, 70000]:
+        _say(f"long-cache eviction: {total} tokens")
         cache = sv.Cache(1, 1, 1, 64, sv.SV_DTYPE_F32, sv.SV_ROPE_3D, 1e4, (8, 12, 12), 1, total + 4096, 4096)
         o = orc.OracleStream(1, 1, 1, 2, orc.ROPE_3D, 1e4, (1, 0, 0))
         n = 0
@@ -245,8 +246,6 @@ def test_long_cache_eviction_many_scan_workgroups():
                 o.append_meta([ty] * cnt, grid)
                 o.append_kv(0, z(cnt), z(cnt))
                 n += cnt
-        if tags_left >= 0:
-            cache.set_option(sv.SV_OPT_TAGS_LEFT, tags_left)
         for budgets in [(100, total // 3 + 77, total // 20), (64, 5000, 333), (64, 5000, 333), (0, 100, 0)]:
             assert cache.evict(0, *budgets) == o.evict(*budgets)
             ids, pos = cache.retained(0)
@@ -547,29 +546,32 @@ def test_decode_single_stream_merge_in_launch(G):
         cache.close()
 
 
-def test_decode_launch_tag_wraps():
-    """The launch counter behind the tags of the in-launch merge wraps after 2^32 launches; the library then clears
-    the tagged scratch and goes on.  With two launches left before the wrap, seven decode calls in a row (the
-    third one wraps) all return the oracle's result."""
-    n_kv, seed = 1500, 9301
+def test_decode_single_stream_repeated_launches():
+    """The in-launch merge of a single stream's key ranges leaves its scratch words zero: the same decode seven
+    times in a row, between them decodes of a longer and a shorter cache through the same scratch, all equal to the
+    oracle's result."""
+    seed = 9301
     w = si.Workload("a", 1, 28, 4, 128, "bf16", 2, 1e4, (0, 0, 0), 0, 0, 0, 0, 0, 0, None, 0, seed)
-    gids = np.arange(n_kv)
-    k = si.normal(seed, si.TENSOR_K, 0, gids, 4, 128, True)
-    v = si.normal(seed, si.TENSOR_V, 0, gids, 4, 128, True)
-    q = si.normal(seed, si.TENSOR_Q, 0, gids[-1:], 28, 128, True)
-    cache = sv.Cache(1, 28, 4, 128, sv.SV_DTYPE_BF16, sv.SV_ROPE_NONE, 1e4, (0, 0, 0), 1, n_kv + 8, 1)
-    cache.append(0, 0, np.zeros(n_kv, dtype=np.uint8), None, gu.dev(k, w), gu.dev(v, w))
-    ref = orc.gqa_attention(q.astype(np.float64), k.astype(np.float64), v.astype(np.float64), np.array([n_kv - 1]), True)
-    qd = gu.dev(q, w)
-    cache.attn_decode(0, [0], qd, torch.empty_like(qd))     # leaves tagged words of an ordinary launch behind
-    cache.set_option(sv.SV_OPT_TAGS_LEFT, 2)
+    lens = [1500, 4000, 300]
+    cache = sv.Cache(1, 28, 4, 128, sv.SV_DTYPE_BF16, sv.SV_ROPE_NONE, 1e4, (0, 0, 0), len(lens), max(lens) + 8, 1)
+    qs, refs = [], []
+    for s_, n_kv in enumerate(lens):
+        gids = np.arange(n_kv)
+        k = si.normal(seed + s_, si.TENSOR_K, 0, gids, 4, 128, True)
+        v = si.normal(seed + s_, si.TENSOR_V, 0, gids, 4, 128, True)
+        q = si.normal(seed + s_, si.TENSOR_Q, 0, gids[-1:], 28, 128, True)
+        cache.append(s_, 0, np.zeros(n_kv, dtype=np.uint8), None, gu.dev(k, w), gu.dev(v, w))
+        qs.append(gu.dev(q, w))
+        refs.append(orc.gqa_attention(q.astype(np.float64), k.astype(np.float64), v.astype(np.float64),
+                                      np.array([n_kv - 1]), True))
     for i in range(7):
-        _say(f"decode launch {i} around the tag wrap")
-        od = torch.full_like(qd, float("nan"))
-        cache.attn_decode(0, [0], qd, od)
-        got = gu.host(od)
-        assert np.isfinite(got).all(), i
-        assert gu.max_err(got, ref) <= gu.TOL["bf16"], (i, gu.max_err(got, ref))
+        for s_ in (0, 1, 0, 2):
+            _say(f"repeated single-stream decode {i}, stream {s_}")
+            od = torch.full_like(qs[s_], float("nan"))
+            cache.attn_decode(0, [s_], qs[s_], od)
+            got = gu.host(od)
+            assert np.isfinite(got).all(), (i, s_)
+            assert gu.max_err(got, refs[s_]) <= gu.TOL["bf16"], (i, s_, gu.max_err(got, refs[s_]))
     cache.close()
 
 

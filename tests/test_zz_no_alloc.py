@@ -53,7 +53,9 @@ def test_static_scratch_decode_matches_arena_decode_twice():
 
     d1 = both(list(range(S)))            # 8 rows, up to 9000 keys: many key ranges per row
     d2 = both([3, 6, 1])                 # 3 short rows right after: fewer ranges, most of the array untouched
-    print(f"  largest difference to the arena-scratch call: {d1:.3e}, {d2:.3e}", flush=True)
+    d3 = both([0])                       # one row: the instantiation that merges its key ranges inside the launch
+    d4 = both([4])                       # and a shorter one right after it
+    print(f"  largest difference to the arena-scratch call: {d1:.3e}, {d2:.3e}, {d3:.3e}, {d4:.3e}", flush=True)
 
     # limits: too many rows for the array is an error, not a silent clamp
     ids = np.zeros(65, dtype=np.int32)
@@ -68,3 +70,42 @@ def test_static_scratch_decode_matches_arena_decode_twice():
     with pytest.raises(sv.SvError) as e:
         c2.attn_decode_static(0, [0], torch.zeros(1, 2, 64, device=DEV), torch.zeros(1, 2, 64, device=DEV))
     assert e.value.status == -5
+
+
+def test_static_scratch_decode_replayed_from_a_graph():
+    """What the static-scratch call is for: captured once into a graph (nothing in it allocates), replayed several
+    times with eager work of the library and synchronisations between the replays; every replay must give the eager
+    call's result bit for bit (one row, whose key ranges meet inside the launch through words that the launch itself
+    sets back to zero; and a batch of rows with its merge launch)."""
+    lens = [6000, 1300, 2500]
+    S = len(lens)
+    cache = sv.Cache(1, HQ, HKV, D, sv.SV_DTYPE_BF16, sv.SV_ROPE_NONE, 1e6, (0, 0, 0), S, max(lens) + 8, 16)
+    for s_, n in enumerate(lens):
+        gids = np.arange(n)
+        cache.append(s_, 0, np.zeros(n, dtype=np.uint8), None, _bf(si.normal(70 + s_, si.TENSOR_K, 0, gids, HKV, D, True)),
+                     _bf(si.normal(70 + s_, si.TENSOR_V, 0, gids, HKV, D, True)))
+    qd = _bf(si.normal(69, si.TENSOR_Q, 0, np.arange(S), HQ, D, True))
+    for ids in ([0], [0, 1, 2]):
+        print(f"static-scratch decode under graph replay: rows {ids}", flush=True)
+        sel = qd[ids].contiguous()
+        o_eager = torch.empty_like(sel)
+        cache.attn_decode_static(0, ids, sel, o_eager)
+        torch.cuda.synchronize()
+        o_graph = torch.full_like(sel, float("nan"))
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            cache.attn_decode_static(0, ids, sel, o_graph)
+        torch.cuda.synchronize()
+        other = torch.empty_like(qd)
+        for replay in range(4):
+            o_graph.fill_(float("nan"))
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(o_graph, o_eager), (ids, replay)
+            # eager work of the library between the replays: other rows through both scratch regions
+            cache.attn_decode_static(0, [1], qd[1:2].contiguous(), other[1:2])
+            cache.attn_decode(0, list(range(S)), qd, other)
+            torch.cuda.synchronize()
+    cache.close()
