@@ -47,7 +47,7 @@ def parse_args():
                          "default workload), whatever this says")
     ap.add_argument("--workload", default="qwen7b_256v_28L",
                     choices=["qwen7b_256v_28L", "qwen7b_1024v_28L", "decode_ragged16", "decode_noevict32k",
-                             "noevict_growth", "budget_sweep", "overlap_recompute", "decode_timeline"])
+                             "noevict_growth", "budget_sweep", "overlap_recompute", "decode_timeline", "decode_graph"])
     ap.add_argument("--max-tokens", type=int, default=131072, help="noevict_growth: cache length to grow to")
     ap.add_argument("--layers", type=int, default=28)
     ap.add_argument("--pool", type=int, default=6, help="distinct pre-generated chunks cycled through")
@@ -81,6 +81,9 @@ def main():
 
     if args.workload == "decode_timeline":
         print(json.dumps(decode_timeline_bench(args)))
+        return
+    if args.workload == "decode_graph":
+        print(json.dumps(decode_graph_bench(args)))
         return
 
     if args.workload.startswith("decode_"):
@@ -352,6 +355,91 @@ def decode_batch_bench(args, with_ceiling=True):
                      "algorithmic_bytes_per_launch": bytes_layer,
                      "frac_of_measured_ceiling": round(gbs / ceil["hbm_read_gbs"], 4) if ceil else None},
     }
+
+
+def decode_graph_bench(args):
+    """Does replaying the decode launches of a chunk from a captured graph shorten them?  One stream of the default
+    workload's steady-state length, 28 layers; the 16 x 28 single-stream decode launches of a chunk (sv_attn_decode:
+    the same kernel the per-second step launches, without the append, so that the cache and the library's host state
+    do not change and the launches can be replayed) timed by events, enqueued eagerly through the C ABI and replayed
+    from one hipGraph; outputs of the two compared bit for bit."""
+    import numpy as np
+    import torch
+
+    import paper_2510_09608_amd as sv
+    dev = "cuda:0"
+    L, Hq, Hkv, d, N, steps = args.layers, 28, 4, 128, 5392, 16
+    cache = sv.Cache(L, Hq, Hkv, d, sv.SV_DTYPE_BF16, sv.SV_ROPE_3D, 1e6, (16, 24, 24), 1, N + 64, 256)
+    g = torch.Generator(device=dev).manual_seed(1)
+    rnd = lambda *shape: torch.randn(*shape, device=dev, generator=g).to(torch.bfloat16)
+    ty = np.zeros(N, dtype=np.uint8)
+    for l in range(L):
+        cache.append(0, l, ty if l == 0 else None, None, rnd(N, Hkv, d), rnd(N, Hkv, d))
+    q = rnd(steps, L, 1, Hq, d)
+    o_eager, o_graph = torch.empty_like(q), torch.empty_like(q)
+
+    def chunk(o):
+        for t in range(steps):
+            for l in range(L):
+                cache.attn_decode(l, [0], q[t, l], o[t, l])
+
+    def timed(fn, reps):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e3 / (reps * steps * L)
+
+    us_eager = timed(lambda: chunk(o_eager), 20)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        chunk(o_graph)
+    torch.cuda.synchronize()
+    us_graph = timed(graph.replay, 20)
+    same = bool(torch.equal(o_eager, o_graph))
+
+    # The text half of the per-second step itself (16 token registrations + 16 x 28 fused append / RoPE / decode
+    # launches, sequenced natively by sv_stream_step): enqueued eagerly (the cache grows by 16 tokens per call) and
+    # replayed from a graph captured at the same length (a replay registers and stores the same 16 tokens in the same
+    # slots again: the same kernels with the same arguments; as a measurement, not a way to run a stream).
+    INF = sv.SV_WINDOW_INF
+    kn, vn = rnd(steps, L, 1, Hkv, d), rnd(steps, L, 1, Hkv, d)
+    o_step = torch.empty(steps, L, Hq, d, device=dev, dtype=torch.bfloat16)
+    reps = 20
+    big = sv.Cache(L, Hq, Hkv, d, sv.SV_DTYPE_BF16, sv.SV_ROPE_3D, 1e6, (16, 24, 24), 1, N + (reps + 8) * steps, 256)
+    for l in range(L):
+        big.append(0, l, ty if l == 0 else None, None, rnd(N, Hkv, d), rnd(N, Hkv, d))
+    text_half = lambda c: c.stream_step(0, 512, INF, INF, q_text=q, k_text=kn, v_text=vn, o_text=o_step)
+    us_step_eager = timed(lambda: text_half(big), reps)
+    big.close()
+    cache2 = sv.Cache(L, Hq, Hkv, d, sv.SV_DTYPE_BF16, sv.SV_ROPE_3D, 1e6, (16, 24, 24), 1, N + 64, 256)
+    for l in range(L):
+        cache2.append(0, l, ty if l == 0 else None, None, rnd(N, Hkv, d), rnd(N, Hkv, d))
+    torch.cuda.synchronize()
+    side.wait_stream(torch.cuda.current_stream())
+    graph2 = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph2, stream=side):
+        text_half(cache2)
+    torch.cuda.synchronize()
+    us_step_graph = timed(graph2.replay, reps)
+    cache.close()
+    cache2.close()
+    return {"metric": "us per single-stream decode launch, eager and replayed from a graph", "unit": "us",
+            "value": round(us_step_graph, 3),
+            "step_text_half": {"eager_native_us_per_layer_step": round(us_step_eager, 3),
+                               "graph_replay_us_per_layer_step": round(us_step_graph, 3)},
+            "attn_decode_only": {"eager_python_us_per_launch": round(us_eager, 3),
+                                 "graph_replay_us_per_launch": round(us_graph, 3), "outputs_identical": same},
+            "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": f"decode_graph: one stream, {N} cached tokens, {L} layers, {Hq}q/{Hkv}kv heads x {d}; "
+                                   f"{steps} x {L} decode launches per chunk, {reps} chunks timed each way"}}
 
 
 def decode_timeline_bench(args):
