@@ -28,11 +28,11 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on the default workload, scaled by
 # what a plain 1 GiB copy reads on the same counters (fetch x2.00, write x1.00); profiles/hbm_traffic_*.txt.
 MEASURED_TRAFFIC = {
-    # attn_chunk = k_chunk_prologue + k_attn_chunk_pipe + k_attn_combine; decode_sweep = k_decode_mfma (key ranges merged in the same launch);
-    # evict = k_evict_scan + k_delta_table + k_compact (reads + writes, scaled counters)
-    "qwen7b_256v_28L": {"attn_chunk": (7.4e6 + 7.1e6) + (13.3e6 + 28.6e6) + (31.5e6 + 1.8e6),
-                        "decode_sweep": (9.32e6 + 0.52e6) + (0.66e6 + 0.01e6),
-                        "evict": (317.9e6 + 290.6e6) + 3.3e6},
+    # attn_chunk = k_store_tokens_vt + k_attn_chunk_pipe + k_chunk_combine; decode_sweep = k_decode_mfma (key ranges merged
+    # in the same launch); evict = k_evict_scan + k_compact (reads + writes, scaled counters)
+    "qwen7b_256v_28L": {"attn_chunk": (2.68e6 + 2.31e6) + (13.5e6 + 14.9e6) + (15.2e6 + 1.8e6),
+                        "decode_sweep": 11.49e6 + 1.13e6,
+                        "evict": (297.3e6 + 290.9e6) + (0.4e6 + 2.6e6)},
 }
 
 
@@ -235,7 +235,7 @@ def stream_workload(name, L, steps, warmup, pool_n, batched_leg):
 def prefill_1024v_figure(Hq, Hkv, d, n_kv=18432, n_q=1024, layers=4, reps=40):
     """Extra figure, never `value`: chunk-prefill attention alone at the high-frame-rate shape (1024-token chunk over
     a 17.4k-token retained cache, the shape of --workload qwen7b_1024v_28L), where the MFMA kernel has its longest key
-    ranges.  One `sv_attn_chunk` call per layer = V^T staging + attention + split merge, timed with events on the
+    ranges.  One `sv_attn_chunk` call per layer = attention + merge of the key ranges, timed with events on the
     launch stream; the kernel-only duration is in profiles/kernel_trace_qwen7b_1024v_28L.txt."""
     import numpy as np
     import torch
@@ -265,7 +265,7 @@ def prefill_1024v_figure(Hq, Hkv, d, n_kv=18432, n_q=1024, layers=4, reps=40):
     tf = flops / us / 1e6
     return {"shape": f"{n_q}-token chunk, {n_kv} keys, {Hq}q/{Hkv}kv x {d}", "us_per_layer": round(us, 2),
             "tflops": round(tf, 1), "frac_of_peak": round(tf / 2500.0, 4),
-            "includes": "V^T staging + k_attn_chunk_pipe + k_attn_combine and the launch gaps"}
+            "includes": "k_attn_chunk_pipe + k_chunk_combine and the launch gaps"}
 
 
 def empirical_ceiling():
@@ -735,11 +735,12 @@ def instrumented_pass(cache, run, pool, w, L, c0, ov, ot_all, n_chunks: int, tra
                 "avg_launch_us": round(tot[key] / max(n_launch, 1), 2), "launches": n_launch,
                 "total_us_per_chunk": round(tot[key] / n_chunks, 1)}
 
-    roofs = [roof("k_chunk_prologue + k_attn_chunk_pipe + k_attn_combine (chunk prefill of one layer: K/V store, Q rotation "
-                  "and V^T staging, attention, split merge)", "attn_chunk", "mfma", MFMA_BF16_PEAK_TFLOPS, "TFLOP/s", 1e12, L),
+    roofs = [roof("k_store_tokens_vt + k_attn_chunk_pipe + k_chunk_combine (chunk prefill of one layer: K/V store into the "
+                  "cache, Q rotation, attention, merge of the key ranges)", "attn_chunk", "mfma", MFMA_BF16_PEAK_TFLOPS,
+                  "TFLOP/s", 1e12, L),
              roof("k_decode_mfma (fused decode step of one layer: append, RoPE, attention, merge of the key ranges)", "decode_sweep", "hbm",
                   HBM_PEAK_GBS, "GB/s", 1e9, L * nt),
-             roof("k_compact (+ scan, shift table)", "evict", "hbm", HBM_PEAK_GBS, "GB/s", 1e9, 1)]
+             roof("k_evict_scan + k_compact (keep rule, positions, shift table; K/V move with re-rotation)", "evict", "hbm", HBM_PEAK_GBS, "GB/s", 1e9, 1)]
     return {"us": us, "ms_per_chunk": round(ms_per_chunk, 3), "roofline_all": roofs,
             "prefill_attn_tflops": roofs[0]["achieved"], "decode_kv_gbs": roofs[1]["achieved"],
             "compaction_gbs": roofs[2]["achieved"]}
