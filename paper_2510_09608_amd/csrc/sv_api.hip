@@ -563,6 +563,40 @@ int sv_stream_step(sv_cache* c, int stream_id, int64_t n_sink, int64_t vision_wi
     }
     return SV_OK;
   }
+  if (c->use_mfma && io->n_text > 1 && io->n_text <= c->cfg.max_q_tokens) {
+    // The call names its n_text decode steps in advance, and what a decoded text token's registration writes (arrival
+    // id, rank, position, rotary cos/sin) does not depend on the token: the run is registered ONCE, as an append of
+    // n_text text tokens whose K/V arrive later, and the fused decode launch of step t stores token t and attends to
+    // the first len0 + t + 1 slots with the cos/sin row t of the run's table.  Same result as n_text single-token
+    // registrations (the table holds what each of them would have computed), n_text - 1 launches fewer.
+    sv::StreamState& st = c->st[stream_id];
+    const int n = io->n_text;
+    for (int l = 0; l < L; ++l)
+      if (st.layer_len[l] != st.len) return SV_ERR_STATE;
+    if (st.len + n > c->cfg.capacity_tokens) return SV_ERR_CAPACITY;
+    const int64_t len0 = st.len;
+    const bool with_cs = c->cfg.rope_mode != SV_ROPE_NONE;
+    SV_DEV(sv::launch_meta_append(c, stream_id, st.next_parity, len0, n, st.next_gid, st.n_text, st.n_vis, SV_TEXT, nullptr,
+                                  -1, 0, 0, 0, with_cs, (hipStream_t)hip_stream));
+    st.cs_tab_valid = with_cs;
+    st.pending_slot0 = len0;
+    st.pending_n = n;
+    st.next_parity ^= 1;
+    st.next_gid += n;
+    if (!st.text_iv.empty() && st.text_iv.back().second == st.n_text) st.text_iv.back().second += n;
+    else st.text_iv.emplace_back(st.n_text, st.n_text + n);
+    st.n_text += n;
+    st.len += n;
+    for (int t = 0; t < n; ++t)
+      for (int l = 0; l < L; ++l) {
+        const size_t i = (size_t)t * L + l;
+        SV_DEV(sv::launch_decode_step_of_run(c, l, stream_id, len0 + t + 1, t, (const char*)io->q_text + i * qrow,
+                                             (const char*)io->k_text + i * kvrow, (const char*)io->v_text + i * kvrow,
+                                             (char*)io->o_text + i * qrow, (hipStream_t)hip_stream));
+      }
+    for (int l = 0; l < L; ++l) st.layer_len[l] = st.len;
+    return SV_OK;
+  }
   for (int t = 0; t < io->n_text; ++t)
     for (int l = 0; l < L; ++l) {
       const size_t i = (size_t)t * L + l;

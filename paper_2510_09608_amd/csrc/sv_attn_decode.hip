@@ -730,8 +730,11 @@ int64_t decode_static_pairs(const sv_cache* c) {
   return (int64_t)(kStaticScratchBytes / 2 / ((size_t)c->cfg.n_q_heads * PW * sizeof(float)));
 }
 
+// len_one / cs_one (single row only, 0 / NULL = the stream's own): the row's visible length and the cos/sin of its
+// query token, for a token of a run that was registered as a whole and is decoded one token at a time.
 static hipError_t decode_rows(const sv_cache* c, int layer, const int32_t* streams, int n_list, int fused, const void* q,
-                              const void* k_new, const void* v_new, void* o, const DecScratch& scr, hipStream_t s) {
+                              const void* k_new, const void* v_new, void* o, const DecScratch& scr, hipStream_t s,
+                              int64_t len_one = 0, const float2* cs_one = nullptr) {
   for (int r0 = 0; r0 < n_list; r0 += kMaxRowsD) {
     const int nr = std::min(kMaxRowsD, n_list - r0);
     DecTable tab = {};
@@ -744,10 +747,11 @@ static hipError_t decode_rows(const sv_cache* c, int layer, const int32_t* strea
       const StreamState& st = c->st[sid];
       tab.r[b].k = (__hip_bfloat16*)c->kv_ptr(sid, st.cur, lay, 0);
       tab.r[b].v = (__hip_bfloat16*)c->kv_ptr(sid, st.cur, lay, 1);
-      tab.r[b].len = (int)st.len;
-      tab.r[b].cs = c->last_cs + (size_t)sid * (D / 2);
-      max_len = std::max(max_len, (int)st.len);
-      if (layer >= 0) total_tiles += (st.len + TK - 1) / TK;
+      const int64_t len = n_list == 1 && len_one > 0 ? len_one : st.len;
+      tab.r[b].len = (int)len;
+      tab.r[b].cs = n_list == 1 && cs_one ? cs_one : c->last_cs + (size_t)sid * (D / 2);
+      max_len = std::max(max_len, (int)len);
+      if (layer >= 0) total_tiles += (len + TK - 1) / TK;
     }
     hipError_t e = decode_launch<4>(c, tab, fused, nr, max_len, total_tiles, q, k_new, v_new, o, (size_t)r0, scr, s);
     if (e != hipSuccess) return e;
@@ -759,6 +763,14 @@ hipError_t launch_attn_decode_mfma(const sv_cache* c, int layer, const int32_t* 
                                    const void* q, const void* k_new, const void* v_new, void* o, hipStream_t s) {
   const DecScratch scr = {c->part_dec, kMaxSplitsD, c->part_o, decode_plain_pairs(c)};
   return decode_rows(c, layer, streams, n_list, fused, q, k_new, v_new, o, scr, s);
+}
+
+hipError_t launch_decode_step_of_run(const sv_cache* c, int layer, int stream, int64_t len, int run_index, const void* q,
+                                     const void* k_new, const void* v_new, void* o, hipStream_t s) {
+  const DecScratch scr = {c->part_dec, kMaxSplitsD, c->part_o, decode_plain_pairs(c)};
+  const int32_t sid = stream;
+  const float2* cs = c->cs_tab + ((size_t)stream * c->cfg.max_q_tokens + run_index) * (D / 2);
+  return decode_rows(c, layer, &sid, 1, 1, q, k_new, v_new, o, scr, s, len, cs);
 }
 
 hipError_t launch_attn_decode_mfma_static(const sv_cache* c, int layer, const int32_t* streams, int n_list,

@@ -142,6 +142,12 @@ bool attn_rows_supported(const sv_cache* c);
 hipError_t launch_attn_decode_mfma(const sv_cache* c, int layer, const int32_t* streams, int n_list, int fused,
                                    const void* q, const void* k_new, const void* v_new, void* o, hipStream_t s);
 
+// One fused decode step (append + RoPE + attention) for token `run_index` of the stream's last registered run, whose
+// metadata and cos/sin table (c->cs_tab) were written for the whole run at once: the token is slot len - 1, the keys
+// are [0, len).
+hipError_t launch_decode_step_of_run(const sv_cache* c, int layer, int stream, int64_t len, int run_index, const void* q,
+                                     const void* k_new, const void* v_new, void* o, hipStream_t s);
+
 // sv_attn_decode_static: split-KV partials in a file-scope device array instead of the arena.
 // decode_static_scratch looks the array's device address up (once per device, kept); decode_static_pairs is the
 // number of (row, key range) pairs the array holds for this cache's head count.
