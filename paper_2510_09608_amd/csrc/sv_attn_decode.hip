@@ -29,10 +29,10 @@
 //     {fp32 value, 32-bit launch tag} with relaxed device-scope atomic stores, and the
 //     workgroups of a kv head share out the result, each reading the words of all ranges
 //     with relaxed device-scope atomic loads until every word carries this launch's tag
-//     (see merge_ranges; the tag lives in device memory, next to the words).  (A merge by the last workgroup to arrive
-//     needs device-scope release/acquire fences, about 3 us each here; a second launch
-//     costs its gap and a round trip of its own.)  A batch's key ranges are merged by a
-//     second, small launch.
+//     (see merge_ranges; the tag lives in device memory, next to the words).  (A merge
+//     by the last workgroup to arrive needs device-scope release/acquire fences, about
+//     3 us each here; a second launch costs its gap and a round trip of its own.)  A
+//     batch's key ranges are merged by a second, small launch.
 
 #include <hip/hip_bf16.h>
 
@@ -41,10 +41,11 @@
 
 #include "sv_internal.h"
 
-// Measurement build (-DSV_TIMELINE, libsv_timeline.so): the two decode kernels stamp the 100 MHz real-time counter at
+// Measurement build (-DSV_TIMELINE, libsv_timeline.so): the decode kernel stamps the 100 MHz real-time counter at
 // a few points into a buffer set with sv_timeline_set, so that one decode step can be laid out on a common clock
-// (dispatch, first memory round trip, tile work, merge through LDS, stores, the gap to the merge kernel).  The
-// product build compiles none of it.
+// (dispatch, first memory round trip, tile work, merge through LDS and publishing, the reads of the other ranges'
+// words, the output's stores), and counts the read attempts of the in-launch merge.  The product build compiles
+// none of it.
 #ifdef SV_TIMELINE
 static __device__ unsigned long long* g_ts = nullptr;   // [8 launch slots][2 kernels][1024 workgroups][8]
 #define SV_TS_PARAM , int ts_slot
@@ -140,9 +141,10 @@ __device__ __forceinline__ void rotate_pair_chunks(uint4& lo, uint4& hi, const f
 // ---------------------------------------------------------------------------------
 // Merge of the key ranges of one (row, kv head): outputs [o_lo, o_lo + n_out) of its G x 128 (n_out a multiple of 32),
 // by one workgroup of NT threads laid out as RG range groups x OPP outputs (RG = 8, 4, 2, 1 for up to 32, 64, 128,
-// more outputs): thread (rg, ol) reads output ol from the ranges rg, rg + RG, ... (8 per pass, all loads issued
-// before any is looked at) and the RG partial merges meet in LDS (3 NT floats at `lds`): one memory round trip
-// unless a row has more than 64 ranges or the workgroup more than NT outputs.
+// more outputs): thread (rg, ol) reads output ol from the ranges rg, rg + RG, ... (whole passes of 8, then one pass
+// of exactly what is left; all loads of a pass issued before any is looked at) and the RG partial merges meet in
+// LDS (3 NT floats at `lds`): one memory round trip unless a thread has more than 8 ranges or the workgroup more
+// than NT outputs.
 // phk: the partial result of range 0, first query head of the kv head; range s adds s * sstride words, head g adds
 // g * PW words.  Words are plain floats, or (POLL) 64-bit {float, launch tag}.
 // POLL: the ranges are being written by other workgroups of the SAME launch.  Every word is read with a relaxed
@@ -630,7 +632,9 @@ static hipError_t decode_launch(const sv_cache* c, const DecTable& tab, int fuse
   // keys (whole tiles for each of the 4 wavefronts: ranges of 800 keys, 7 tiles for one wavefront and 6 for the
   // others, measured 6 % slower than ranges of 896), for which sum_b ceil(len_b / T) * kv heads <= 512; then every
   // row is cut into ceil(len_b / T) ranges of EQUAL size (rounded up to 128 keys), so that a row does not end in a
-  // range much shorter than the others.
+  // range much shorter than the others.  (Filling the slots left over by moving rows to the next shorter range
+  // length, 508 workgroups on the ragged batch, was measured as well: 54 us instead of 40; the drop sets in before
+  // the 512th workgroup, so the choice errs on the side of longer ranges.)
   constexpr int kSlots = 512;
   const int forced = std::min(c->opt[SV_OPT_DECODE_TILES_PER_WAVE], 64);
   if (part_pairs < nr) return hipErrorInvalidValue;   // every row needs at least one pair (callers check their limits)
