@@ -632,7 +632,12 @@ static hipError_t decode_launch(const sv_cache* c, const DecTable& tab, int fuse
   // keys (whole tiles for each of the 4 wavefronts: ranges of 800 keys, 7 tiles for one wavefront and 6 for the
   // others, measured 6 % slower than ranges of 896), for which sum_b ceil(len_b / T) * kv heads <= 512; then every
   // row is cut into ceil(len_b / T) ranges of EQUAL size (rounded up to 128 keys), so that a row does not end in a
-  // range much shorter than the others.  (Filling the slots left over by moving rows to the next shorter range
+  // range much shorter than the others.  (The grid is rows x kv heads x the widest row's ranges, with empty
+  // workgroups where a row is shorter; ids go to the 8 XCDs in turn, so depending on the grid's width one XCD can run
+  // out of its 64 slots before the launch has 512 workgroups.  A one-dimensional grid over the ranges that exist
+  // removes that, 8 rows at 256 workgroups: 35.6 -> 27.5 us, but finding a workgroup's row costs a second dependent
+  // read of the arguments, +1.3 us on every launch, and nothing at the 16-row shapes measured here; moving rows to
+  // shorter ranges until the slots are full, 508 workgroups on the ragged batch, came out level with 440.)  (Filling the slots left over by moving rows to the next shorter range
   // length, 508 workgroups on the ragged batch, was measured as well: 54 us instead of 40; the drop sets in before
   // the 512th workgroup, so the choice errs on the side of longer ranges.)
   constexpr int kSlots = 512;
