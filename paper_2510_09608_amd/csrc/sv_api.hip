@@ -312,6 +312,8 @@ static int append_impl(sv_cache* c, int stream_id, int layer, int n, const uint8
     st.next_parity ^= 1;
     if (has_blk) st.next_blk++;
     st.next_gid += n;
+    if (st.len == st.front && st.n_text == st.front)   // the cache is the opening text run so far: it may grow
+      for (int j = 0; j < n && types_host[j] == SV_TEXT; ++j) ++st.front;
     const int n_text_new = n - n_vis;
     if (n_text_new > 0) {
       if (!st.text_iv.empty() && st.text_iv.back().second == st.n_text)
@@ -362,8 +364,15 @@ int sv_cache_evict(sv_cache* c, int stream_id, int64_t n_sink, int64_t vision_wi
   if (n_retained_out) *n_retained_out = n_new;
   if (n_new == st.len) return SV_OK;  // nothing to evict: no device work
 
+  // The opening text run: its tokens of rank >= n_sink and < text_lo leave; the slots before the first of them
+  // (all of the run if none leaves) keep place, position and contents.  What the eviction before this one left in
+  // place as well is already in the half this one fills.
+  const int64_t gone = (n_sink < st.front && text_lo > n_sink) ? n_sink : st.front;
+  const int64_t n_still = std::min(st.still[st.cur], gone);
   SV_DEV(sv::launch_evict_scan(c, stream_id, st.next_parity, st.len, n_sink, text_lo, vis_lo, s));
-  if (n_new > 0) SV_DEV(sv::launch_compact(c, stream_id, n_new, s));
+  if (n_new > 0) SV_DEV(sv::launch_compact(c, stream_id, n_new, n_still, s));
+  st.still[st.cur ^ 1] = gone;
+  st.front = gone;
   st.cur ^= 1;
   st.next_parity ^= 1;
   st.text_iv.swap(iv_new);

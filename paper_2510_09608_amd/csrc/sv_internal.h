@@ -53,6 +53,13 @@ struct StreamState {
   int64_t pending_slot0 = 0;                         // first slot of the append in flight
   int pending_n = 0;
   bool cs_tab_valid = false;                         // cs_tab holds the rotary cos/sin of the pending run's tokens
+  // Slots [0, front) hold the text tokens of rank 0 .. front - 1: the stream's opening text run (system prompt and
+  // what follows it before the first vision token), as far as evictions have left it in place.  An eviction leaves
+  // the slots below the run's first leaving token where they are, unshifted; still[h] is that bound for the eviction
+  // that filled K/V half h, so below min(still[0], still[1]) both halves hold the same rows and the next eviction
+  // need not move them again.
+  int64_t front = 0;
+  int64_t still[2] = {0, 0};
 };
 
 }  // namespace sv
@@ -124,7 +131,9 @@ hipError_t launch_append_kv(const sv_cache* c, int stream, int layer, int64_t sl
 hipError_t launch_evict_scan(const sv_cache* c, int stream, int next_parity, int64_t n_old,
                              int64_t n_sink, int64_t text_lo, int64_t vis_lo, hipStream_t s);
 
-hipError_t launch_compact(const sv_cache* c, int stream, int64_t n_new, hipStream_t s);
+// Slots below `n_still` (rounded down to the kernel's token group) are not moved: the caller knows that the other half
+// already holds them.
+hipError_t launch_compact(const sv_cache* c, int stream, int64_t n_new, int64_t n_still, hipStream_t s);
 
 hipError_t launch_rope_apply(const sv_cache* c, int stream, int64_t slot0, int n, void* q, void* k,
                              hipStream_t s);

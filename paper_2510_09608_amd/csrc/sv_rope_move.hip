@@ -241,15 +241,18 @@ __global__ __launch_bounds__(256) void k_store_tokens_vt(
 // Compaction gather over all layers: new[l][K|V][h][j] = old[l][K|V][h][src[j]],
 // K re-rotated when delta[j] != 0.  old and new are the two halves of the
 // ping-pong store, so no row is overwritten before it is read.
-// grid: (ceil(n_new / ROWS), n_kv_heads, 2 * n_layers)
+// Token groups (ROWS tokens) below x0 are not moved: the caller knows that the new half holds them already (tokens
+// that two evictions in a row left in place, unshifted: the sink text at the front of a stream in steady state).
+// grid: (ceil(n_new / ROWS) - x0, n_kv_heads, 2 * n_layers)
 // ---------------------------------------------------------------------------------
 template <typename T, int D>
 __global__ __launch_bounds__(256) void k_compact(const T* __restrict__ old_base, T* __restrict__ new_base,
                                                  const int32_t* __restrict__ src, const int32_t* __restrict__ delta,
                                                  const float2* __restrict__ dtab, int n_new,
                                                  size_t head_stride_elems, size_t tensor_stride_elems, int rotate,
-                                                 int v_blocked) {
+                                                 int v_blocked, int x0) {
   using G = RowGeom<T, D>;
+  const int bx = (int)blockIdx.x + x0;   // token group; the groups below x0 stay where they are
   const int h = blockIdx.y;
   const int which = blockIdx.z & 1;   // z = 2 * layer + which, tensors are laid out in that order
   const size_t plane = (size_t)blockIdx.z * tensor_stride_elems + (size_t)h * head_stride_elems;
@@ -269,7 +272,7 @@ __global__ __launch_bounds__(256) void k_compact(const T* __restrict__ old_base,
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
         const int piece = threadIdx.x + 256 * i, p = piece >> 7, d = piece & 127;
-        const int jc = (int)blockIdx.x * 32 + 8 * p;
+        const int jc = bx * 32 + 8 * p;
         live[i] = jc < n_new;   // a block wholly past the end: nothing to move
         if (!live[i]) continue;
         const int sa = src[jc];
@@ -289,12 +292,12 @@ __global__ __launch_bounds__(256) void k_compact(const T* __restrict__ old_base,
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
         const int piece = threadIdx.x + 256 * i, p = piece >> 7, d = piece & 127;
-        if (live[i]) *(u32x4*)(sn + vt_elem((int64_t)blockIdx.x * 32 + 8 * p, d)) = w[i];
+        if (live[i]) *(u32x4*)(sn + vt_elem((int64_t)bx * 32 + 8 * p, d)) = w[i];
       }
       return;
     }
   }
-  const int j = blockIdx.x * G::ROWS + threadIdx.x / G::TPR;
+  const int j = bx * G::ROWS + threadIdx.x / G::TPR;
   if (j >= n_new) return;
   const int t = threadIdx.x % G::TPR;
   const T* s = old_base + plane + (size_t)src[j] * D;
@@ -359,16 +362,18 @@ hipError_t rope_apply_t(const sv_cache* c, int stream, int64_t slot0, int n, voi
 }
 
 template <typename T, int D>
-hipError_t compact_t(const sv_cache* c, int stream, int64_t n_new, hipStream_t s) {
+hipError_t compact_t(const sv_cache* c, int stream, int64_t n_new, int64_t n_still, hipStream_t s) {
   using G = RowGeom<T, D>;
   const int cur = c->st[stream].cur;
   const size_t off = (size_t)stream * (size_t)c->cfg.capacity_tokens;
   const int rotate = c->cfg.rope_mode != SV_ROPE_NONE;
   float2* dtab = c->dtab + off * (D / 2);   // rows of the tokens with a shift, written by the eviction scan
-  dim3 grid((unsigned)((n_new + G::ROWS - 1) / G::ROWS), c->cfg.n_kv_heads, 2 * c->cfg.n_layers);
+  const int groups = (int)((n_new + G::ROWS - 1) / G::ROWS), x0 = (int)std::min<int64_t>(n_still / G::ROWS, groups);
+  if (x0 == groups) return hipSuccess;
+  dim3 grid((unsigned)(groups - x0), c->cfg.n_kv_heads, 2 * c->cfg.n_layers);
   hipLaunchKernelGGL((k_compact<T, D>), grid, dim3(256), 0, s, (const T*)c->kv_ptr(stream, cur, 0, 0),
                      (T*)c->kv_ptr(stream, cur ^ 1, 0, 0), c->src + off, c->delta + off, dtab, (int)n_new,
-                     c->head_stride / sizeof(T), c->tensor_stride / sizeof(T), rotate, c->v_blocked ? 1 : 0);
+                     c->head_stride / sizeof(T), c->tensor_stride / sizeof(T), rotate, c->v_blocked ? 1 : 0, x0);
   return hipGetLastError();
 }
 
@@ -388,8 +393,8 @@ hipError_t launch_rope_apply(const sv_cache* c, int stream, int64_t slot0, int n
   SV_DISPATCH(rope_apply_t, c, stream, slot0, n, q, k, s);
 }
 
-hipError_t launch_compact(const sv_cache* c, int stream, int64_t n_new, hipStream_t s) {
-  SV_DISPATCH(compact_t, c, stream, n_new, s);
+hipError_t launch_compact(const sv_cache* c, int stream, int64_t n_new, int64_t n_still, hipStream_t s) {
+  SV_DISPATCH(compact_t, c, stream, n_new, n_still, s);
 }
 
 hipError_t launch_append_kv(const sv_cache* c, int stream, int layer, int64_t slot0, int n, const void* k,

@@ -352,6 +352,56 @@ def test_randomized_streams_stored_kv():
     _say(f"stored K worst error {worst}")
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_opening_text_run_left_in_place(dtype):
+    """Streams that open with a run of text (the system prompt): the sink tokens at the front keep slot, position and
+    contents through every eviction, and the compaction does not move what two evictions in a row left in place.
+    Budgets change between evictions (a sink count that shrinks, grows, drops to zero), the opening run is appended
+    in two calls, and after every step V as stored is the appended V bit for bit and K the raw K rotated at the
+    token's current position, on both layers; retained ids and positions bit-exact (Sec. 3.1: sink text, windows)."""
+    rng = np.random.default_rng(25100960)
+    d, Hq, Hkv = (64, 2, 1) if dtype == "f32" else (128, 28, 4)
+    for case, (mode, sinks) in enumerate([(1, [96, 96, 96, 40, 40, 96, 64, 64, 0, 0, 33]),
+                                          (0, [200, 200, 130, 130, 130, 500, 70, 70, 70, 70, 70])]):
+        sec = (0, 0, 0) if mode == 0 else ((8, 12, 12) if d == 64 else (16, 24, 24))
+        theta = 1e4 if dtype == "f32" else 1e6
+        w = si.Workload("t", 2, Hq, Hkv, d, dtype, mode, theta, sec, 0, 0, 0, 0, 0, 0, None, 0, 300 + case)
+        cache = gu.make_cache(w, capacity=2048)
+        o = orc.OracleStream(2, Hq, Hkv, d, mode, theta, sec)
+        _say(f"opening text run {dtype} mode={mode}")
+        g0 = 0
+
+        def append(ty, n, grid):
+            nonlocal g0
+            gids = np.arange(g0, g0 + n)
+            g0 += n
+            o.append_meta([ty] * n, grid)
+            for l in range(2):
+                _, k, v = w.qkv(l, gids)
+                cache.append(0, l, np.full(n, ty, dtype=np.uint8) if l == 0 else None, grid if l == 0 else None,
+                             gu.dev(k, w), gu.dev(v, w))
+                o.append_kv(l, k, v)
+
+        append(orc.TEXT, 150, None)
+        append(orc.TEXT, 75, None)          # the run grows while the cache holds nothing else
+        for c, n_sink in enumerate(sinks):
+            T, H, W = int(rng.integers(1, 3)), int(rng.integers(2, 7)), int(rng.integers(2, 9))
+            append(orc.VISION, T * H * W, (T, H, W))
+            append(orc.TEXT, int(rng.integers(1, 12)), None)
+            vw, tw = int(rng.choice([60, 150])), int(rng.choice([8, 40]))
+            assert cache.evict(0, n_sink, vw, tw) == o.evict(n_sink, vw, tw)
+            n = len(o)
+            gids, pos3 = cache.retained(0) if n else (np.zeros(0), np.zeros((0, 3)))
+            assert np.array_equal(gids, np.asarray(o.gid)) and np.array_equal(pos3, o.positions()), (case, c)
+            pos = o.positions()
+            tol = (1e-5 if dtype == "f32" else 4e-2) * (1 + c)      # one rounding per compaction so far
+            for l in range(2):
+                K, V = np.stack(o.k[l]), np.stack(o.v[l])
+                assert np.array_equal(cache.read_kv(0, l, 1, 0, n).astype(np.float64), V), (case, c, l)
+                e = gu.max_err(cache.read_kv(0, l, 0, 0, n), orc.rope(K, pos, mode, theta, sec))
+                assert e <= tol, (case, c, l, e)
+
+
 # ----------------------------------------------------------------------------
 # single operations
 # ----------------------------------------------------------------------------
