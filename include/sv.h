@@ -70,8 +70,12 @@ typedef struct sv_config {
 /* sv_config.flags.  SV_FLAG_GENERIC_KERNELS: run the generic (vector ALU) attention kernels and keep
  * the row-major V layout even where the matrix-core kernels apply (bf16, head_dim 128, at most 8 query
  * heads per kv head).  Same results to rounding; the parity tests use it to cover the generic kernels
- * on bf16 data. */
-enum { SV_FLAG_GENERIC_KERNELS = 1 };
+ * on bf16 data.
+ * SV_FLAG_HOST_LOGIC_ONLY: a test seam.  The cache launches nothing and never touches the arena: argument
+ * checks, call-order rules, lengths, retained counts and error codes behave as usual (they are host
+ * bookkeeping), attention outputs are not produced, and sv_cache_retained / sv_cache_read_kv return
+ * SV_ERR_UNSUPPORTED.  It exists so that the host logic can be tested on a machine without a GPU. */
+enum { SV_FLAG_GENERIC_KERNELS = 1, SV_FLAG_HOST_LOGIC_ONLY = 2 };
 
 typedef struct sv_cache sv_cache;
 
@@ -90,12 +94,7 @@ SV_API size_t sv_cache_bytes(const sv_config* cfg);
  * Errors: SV_ERR_INVALID (NULLs, n_q_heads % n_kv_heads, head_dim not 64/128,
  * sections not summing to head_dim/2, sizes < 1, capacity_tokens above 2^24, unknown flag bits),
  * SV_ERR_CAPACITY (arena too small).
- * Test seam: if the environment variable SV_HOST_LOGIC_ONLY is set (not "0")
- * when a cache is created, that cache launches nothing and never touches the
- * arena: argument checks, call-order rules, lengths, retained counts and error
- * codes behave as usual (they are host bookkeeping), attention outputs are not
- * produced, and sv_cache_retained / sv_cache_read_kv return SV_ERR_UNSUPPORTED.
- * It exists so that the host logic can be tested on a machine without a GPU.
+ * The library reads no environment variable, here or on any launch path.
  */
 SV_API int sv_cache_create(const sv_config* cfg, void* dev_arena, size_t arena_bytes,
                     void* hip_stream, sv_cache** out);

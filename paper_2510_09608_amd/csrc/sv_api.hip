@@ -3,7 +3,6 @@
 // file holds no arithmetic of the method beyond counting which tokens survive.
 
 #include <algorithm>
-#include <cstdlib>
 #include <cmath>
 #include <cstring>
 #include <limits>
@@ -31,7 +30,7 @@ bool config_ok(const sv_config* c) {
   if (c->rope_mode != SV_ROPE_1D && c->rope_mode != SV_ROPE_3D && c->rope_mode != SV_ROPE_NONE) return false;
   // slot and element indices inside the kernels are 32-bit: 2^24 slots x head_dim 128 stays far below 2^31
   if (c->capacity_tokens < 1 || c->capacity_tokens > (int64_t)1 << 24) return false;
-  if (c->flags & ~(int32_t)SV_FLAG_GENERIC_KERNELS) return false;
+  if (c->flags & ~(int32_t)(SV_FLAG_GENERIC_KERNELS | SV_FLAG_HOST_LOGIC_ONLY)) return false;
   if (c->max_q_tokens < 1) return false;
   if (c->rope_mode != SV_ROPE_NONE && !(c->rope_theta > 0.0)) return false;
   if (c->rope_mode == SV_ROPE_3D) {
@@ -126,7 +125,7 @@ std::vector<std::pair<int64_t, int64_t>> iv_after_evict(
     if (e__ != hipSuccess) return SV_ERR_HIP; \
   } while (0)
 
-// Device work of a call: skipped for a cache created with SV_HOST_LOGIC_ONLY set (see sv_cache_create).
+// Device work of a call: skipped for a cache created with SV_FLAG_HOST_LOGIC_ONLY.
 #define SV_DEV(expr)                 \
   do {                               \
     if (!c->host_logic_only) SV_HIP(expr); \
@@ -208,8 +207,7 @@ int sv_cache_create(const sv_config* cfg, void* dev_arena, size_t arena_bytes, v
   if (cfg->rope_mode != SV_ROPE_NONE)
     for (int i = 0; i < half; ++i) f[i] = std::pow(cfg->rope_theta, -2.0 * (double)i / (double)cfg->head_dim);
   hipStream_t s = (hipStream_t)hip_stream;
-  const char* dry = std::getenv("SV_HOST_LOGIC_ONLY");
-  c->host_logic_only = dry && *dry && *dry != '0';
+  c->host_logic_only = (cfg->flags & SV_FLAG_HOST_LOGIC_ONLY) != 0;
   if (c->host_logic_only) {   // test seam: bookkeeping and checks only, the arena is never touched
     *out = c;
     return SV_OK;

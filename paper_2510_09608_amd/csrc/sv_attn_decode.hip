@@ -636,10 +636,11 @@ static hipError_t decode_launch(const sv_cache* c, const DecTable& tab, int fuse
   // workgroups where a row is shorter; ids go to the 8 XCDs in turn, so depending on the grid's width one XCD can run
   // out of its 64 slots before the launch has 512 workgroups.  A one-dimensional grid over the ranges that exist
   // removes that, 8 rows at 256 workgroups: 35.6 -> 27.5 us, but finding a workgroup's row costs a second dependent
-  // read of the arguments, +1.3 us on every launch, and nothing at the 16-row shapes measured here; moving rows to
-  // shorter ranges until the slots are full, 508 workgroups on the ragged batch, came out level with 440.)  (Filling the slots left over by moving rows to the next shorter range
-  // length, 508 workgroups on the ragged batch, was measured as well: 54 us instead of 40; the drop sets in before
-  // the 512th workgroup, so the choice errs on the side of longer ranges.)
+  // read of the arguments, +1.3 us on every launch, and nothing at the 16-row shapes measured here.  Moving rows to
+  // the next shorter range length until the slots are full, 508 workgroups on the ragged batch, measured 54 us
+  // instead of 40 on this grid (the drop sets in before the 512th workgroup) and level with 440 workgroups on the
+  // one-dimensional grid: the choice errs on the side of longer ranges.  More, shorter workgroups than slots, left
+  // to the dispatcher (3 or 4 tiles per wavefront, 750 to 1000 workgroups): 43.7 us against 39.3.)
   constexpr int kSlots = 512;
   const int forced = std::min(c->opt[SV_OPT_DECODE_TILES_PER_WAVE], 64);
   if (part_pairs < nr) return hipErrorInvalidValue;   // every row needs at least one pair (callers check their limits)

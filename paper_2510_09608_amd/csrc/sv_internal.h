@@ -95,7 +95,7 @@ struct sv_cache {
   unsigned long long* scan_agg;   // device [n_streams][kScanMaxWG + 1][2]: tagged totals of the eviction scan's
                                   // workgroups, then the scan's launch tag (zero at create, written by nothing else;
                                   // sv_meta.hip)
-  bool host_logic_only = false;   // created with SV_HOST_LOGIC_ONLY: no device work, bookkeeping only
+  bool host_logic_only = false;   // created with SV_FLAG_HOST_LOGIC_ONLY: no device work, bookkeeping only
   bool use_mfma = false;          // bf16, head_dim 128, group <= 8 and no SV_FLAG_GENERIC_KERNELS: matrix-core kernels
   bool v_blocked = false;         // V stored as V^T in blocks of 8 keys (exactly the caches with use_mfma), else row-major
   int opt[SV_OPT_COUNT_] = {};    // sv_cache_set_option values, 0 = automatic

@@ -1,10 +1,9 @@
 """Host logic of the C-ABI library, without a GPU: call-order rules, capacity, argument checks, lengths and the
 retained counts of sv_cache_evict (computed on the host from per-type intervals) against the oracle.
 
-The caches are created with SV_HOST_LOGIC_ONLY set, so nothing is launched and the fake arena / tensor addresses
+The caches are created with SV_FLAG_HOST_LOGIC_ONLY, so nothing is launched and the fake arena / tensor addresses
 handed in are never dereferenced."""
 import ctypes as C
-import os
 
 import numpy as np
 import pytest
@@ -17,14 +16,10 @@ FAKE = 0x10000          # a 256-byte aligned, non-NULL "device address" that nob
 OK, INVALID, CAPACITY, STATE, UNSUPPORTED = 0, -1, -2, -3, -5
 
 
-@pytest.fixture(autouse=True)
-def _host_logic_only(monkeypatch):
-    monkeypatch.setenv("SV_HOST_LOGIC_ONLY", "1")
-
-
 def _create(n_layers=1, hq=28, hkv=4, d=128, dtype=B.SV_DTYPE_BF16, rope=B.SV_ROPE_3D, sections=(16, 24, 24),
             n_streams=1, capacity=1024, max_q=256):
-    cfg = B.SvConfig(n_layers, hq, hkv, d, dtype, rope, 1.0e6, (C.c_int32 * 3)(*sections), n_streams, capacity, max_q)
+    cfg = B.SvConfig(n_layers, hq, hkv, d, dtype, rope, 1.0e6, (C.c_int32 * 3)(*sections), n_streams, capacity, max_q,
+                     B.SV_FLAG_HOST_LOGIC_ONLY)
     lib = B.lib()
     h = C.c_void_p()
     assert lib.sv_cache_create(C.byref(cfg), FAKE, 1 << 60, None, C.byref(h)) == OK
@@ -174,7 +169,7 @@ def test_options_and_flags():
     cfg = B.SvConfig(1, 28, 4, 128, B.SV_DTYPE_BF16, B.SV_ROPE_3D, 1.0e6, (C.c_int32 * 3)(16, 24, 24), 1, 64, 16,
                      B.SV_FLAG_GENERIC_KERNELS)
     assert lib.sv_cache_bytes(C.byref(cfg)) > 0
-    cfg.flags = 2
+    cfg.flags = 4
     assert lib.sv_cache_bytes(C.byref(cfg)) == 0
     cfg.flags, cfg.capacity_tokens = 0, (1 << 24) + 1            # slots are indexed with 32-bit arithmetic
     assert lib.sv_cache_bytes(C.byref(cfg)) == 0
