@@ -119,6 +119,19 @@ std::vector<std::pair<int64_t, int64_t>> iv_after_evict(
   return out;
 }
 
+// Host bookkeeping of n text tokens registered at the end of a stream (the metadata launch is the caller's).
+void note_text_registered(sv::StreamState& st, int n, bool cs_tab_valid) {
+  st.cs_tab_valid = cs_tab_valid;
+  st.pending_slot0 = st.len;
+  st.pending_n = n;
+  st.next_parity ^= 1;
+  st.next_gid += n;
+  if (!st.text_iv.empty() && st.text_iv.back().second == st.n_text) st.text_iv.back().second += n;
+  else st.text_iv.emplace_back(st.n_text, st.n_text + n);
+  st.n_text += n;
+  st.len += n;
+}
+
 #define SV_HIP(expr)                         \
   do {                                       \
     hipError_t e__ = (expr);                 \
@@ -254,8 +267,8 @@ int sv_cache_len(sv_cache* c, int stream_id, int64_t* n_out) {
   return SV_OK;
 }
 
-// sv_cache_append, with the option of leaving the K/V store to the caller (the fused chunk prologue of
-// sv_stream_step stores K/V, rotates Q and stages V^T in one launch): all checks and bookkeeping are the same.
+// sv_cache_append, with the option of leaving the K/V store to the caller (sv_stream_step stores a chunk's K rows and
+// V^T blocks and rotates its Q in one launch of its own): all checks and bookkeeping are the same.
 static int append_impl(sv_cache* c, int stream_id, int layer, int n, const uint8_t* types_host,
                        const int32_t* grid_thw_host, const void* k_dev, const void* v_dev,
                        int64_t* slot0_out, void* hip_stream, bool launch_kv) {
@@ -476,15 +489,7 @@ int sv_decode_step(sv_cache* c, int layer, const int32_t* stream_ids_host, int n
     if (layer == 0) {
       SV_DEV(sv::launch_meta_append(c, sid, st.next_parity, st.len, 1, st.next_gid, st.n_text, st.n_vis, SV_TEXT,
                                     nullptr, -1, 0, 0, 0, false, s));
-      st.cs_tab_valid = false;
-      st.pending_slot0 = st.len;
-      st.pending_n = 1;
-      st.next_parity ^= 1;
-      st.next_gid += 1;
-      if (!st.text_iv.empty() && st.text_iv.back().second == st.n_text) st.text_iv.back().second += 1;
-      else st.text_iv.emplace_back(st.n_text, st.n_text + 1);
-      st.n_text += 1;
-      st.len += 1;
+      note_text_registered(st, 1, false);
     }
     st.layer_len[layer] = st.len;
   }
@@ -506,15 +511,7 @@ int sv_decode_step_layers(sv_cache* c, int stream_id, const void* q_dev, const v
   hipStream_t s = (hipStream_t)hip_stream;
   SV_DEV(sv::launch_meta_append(c, stream_id, st.next_parity, st.len, 1, st.next_gid, st.n_text, st.n_vis, SV_TEXT,
                                 nullptr, -1, 0, 0, 0, false, s));
-  st.cs_tab_valid = false;
-  st.pending_slot0 = st.len;
-  st.pending_n = 1;
-  st.next_parity ^= 1;
-  st.next_gid += 1;
-  if (!st.text_iv.empty() && st.text_iv.back().second == st.n_text) st.text_iv.back().second += 1;
-  else st.text_iv.emplace_back(st.n_text, st.n_text + 1);
-  st.n_text += 1;
-  st.len += 1;
+  note_text_registered(st, 1, false);
   for (int l = 0; l < L; ++l) st.layer_len[l] = st.len;
   const int32_t sid = stream_id;
   SV_DEV(sv::launch_attn_decode_mfma(c, -1, &sid, L, 1, q_dev, k_dev, v_dev, o_dev, s));
@@ -585,15 +582,7 @@ int sv_stream_step(sv_cache* c, int stream_id, int64_t n_sink, int64_t vision_wi
     const bool with_cs = c->cfg.rope_mode != SV_ROPE_NONE;
     SV_DEV(sv::launch_meta_append(c, stream_id, st.next_parity, len0, n, st.next_gid, st.n_text, st.n_vis, SV_TEXT, nullptr,
                                   -1, 0, 0, 0, with_cs, (hipStream_t)hip_stream));
-    st.cs_tab_valid = with_cs;
-    st.pending_slot0 = len0;
-    st.pending_n = n;
-    st.next_parity ^= 1;
-    st.next_gid += n;
-    if (!st.text_iv.empty() && st.text_iv.back().second == st.n_text) st.text_iv.back().second += n;
-    else st.text_iv.emplace_back(st.n_text, st.n_text + n);
-    st.n_text += n;
-    st.len += n;
+    note_text_registered(st, n, with_cs);
     for (int t = 0; t < n; ++t)
       for (int l = 0; l < L; ++l) {
         const size_t i = (size_t)t * L + l;

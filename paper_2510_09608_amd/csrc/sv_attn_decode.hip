@@ -111,9 +111,6 @@ __device__ __forceinline__ uint32_t bf_round_bits(float x) {
   return a >> 16;
 }
 
-// Rotate, in place, the two 16-byte chunks a lane holds of one row: `lo` covers
-// dims [i0, i0 + 8), `hi` the partner dims [i0 + 64, i0 + 72); c/s are cos/sin of
-// the 8 pairs.  Result is rounded to bf16, as it would be stored.
 // 16 bytes of K or V for launches that read far more than the caches hold (many long streams), every byte once:
 // a non-temporal load keeps the stream from displacing itself through L2 and the Infinity Cache (measured
 // 16 x 32k tokens: 5.7 -> 6.4 TB/s with merge).  A single stream's 11 MB per layer are partly still cached from
@@ -124,6 +121,9 @@ __device__ __forceinline__ uint4 stream_load(const __hip_bfloat16* p) {
   return make_uint4(v[0], v[1], v[2], v[3]);
 }
 
+// Rotate, in place, the two 16-byte chunks a lane holds of one row: `lo` covers
+// dims [i0, i0 + 8), `hi` the partner dims [i0 + 64, i0 + 72); c/s are cos/sin of
+// the 8 pairs.  Result is rounded to bf16, as it would be stored.
 __device__ __forceinline__ void rotate_pair_chunks(uint4& lo, uint4& hi, const float (&c)[8], const float (&s)[8]) {
   uint32_t* a = (uint32_t*)&lo;
   uint32_t* b = (uint32_t*)&hi;
@@ -136,7 +136,6 @@ __device__ __forceinline__ void rotate_pair_chunks(uint4& lo, uint4& hi, const f
     b[w] = bf_round_bits(rb0) | (bf_round_bits(rb1) << 16);
   }
 }
-
 
 // ---------------------------------------------------------------------------------
 // Merge of the key ranges of one (row, kv head): outputs [o_lo, o_lo + n_out) of its G x 128 (n_out a multiple of 32),
@@ -296,8 +295,9 @@ __global__ __launch_bounds__(NW * 64, 2) void k_decode_mfma(__hip_bfloat16* k0_,
   const int nsr = (len + kps - 1) / kps;   // key ranges of this row
   // Single stream: the words' header of this kv head, {tag of the launch before, its number of key ranges}, written
   // by the launch before (read here, used after the tiles).  This launch's tag is the next one, never 0.
-  // Thread 0 reads it, the workgroup takes it from LDS behind the barrier that precedes all its publishing: the
-  // workgroup of range 0 replaces the header once it has seen every range publish, i.e. after all have read it.
+  // The workgroup uses the value thread 0 read, handed round through LDS behind the barrier that precedes all its
+  // publishing: the workgroup of range 0 replaces the header once it has seen every range publish, i.e. after every
+  // workgroup's thread 0 has read it (a later wavefront of a workgroup might see the new one).
   __shared__ unsigned long long sHdr;
   // (Every thread issues the load, without a branch: behind `if (tid == 0)` the compiler waits for it on the spot,
   // and the first wavefront would start its K/V loads a memory round trip late.)

@@ -97,8 +97,8 @@ def test_default_workload_28_layers_full_budgets_steady_state():
 
 
 def test_high_frame_rate_28_layers_all_rows_of_a_steady_chunk():
-    """bench.py's 1024-token workload: 28-layer cache (arena above 2 GiB), fused chunk prologue with n = 1024,
-    all 1024 query rows of a steady-state chunk (both windows full: chunk 33) on layers 0 and 27, plus the first and
+    """bench.py's 1024-token workload: 28-layer cache (arena above 2 GiB), fused token store (K rows, V^T blocks; Q
+    rotated by the attention kernel while loading) with n = 1024, all 1024 query rows of a steady-state chunk (both windows full: chunk 33) on layers 0 and 27, plus the first and
     last decode step."""
     w = gu.pooled(si.workload_high_fps(n_chunks=34, n_layers=28), 4)
     _say("high-frame-rate workload, 28 layers")
