@@ -136,7 +136,7 @@ __global__ __launch_bounds__(256) void k_append_kv(const T* __restrict__ k_in, c
 template <typename T, int D>
 __device__ __forceinline__ void rope_rows(int bx, T* __restrict__ x, const int4* __restrict__ pos4,
                                           const double* __restrict__ inv_freq, int64_t slot0, int n, int n_heads,
-                                          int rope_mode, int s0, int s01) {
+                                          int rope_mode, int s0, int s01, const float2* __restrict__ cs_tab = nullptr) {
   using G = RowGeom<T, D>;
   const int64_t row = (int64_t)bx * G::ROWS + threadIdx.x / G::TPR;
   if (row >= (int64_t)n * n_heads) return;
@@ -146,7 +146,18 @@ __device__ __forceinline__ void rope_rows(int bx, T* __restrict__ x, const int4*
   Vec16<T> lo, hi;
   lo.raw = *(const decltype(lo.raw)*)(p + t * G::EPV);
   hi.raw = *(const decltype(hi.raw)*)(p + D / 2 + t * G::EPV);
-  rotate_pair_vec<T, D>(lo, hi, pos4[slot0 + j], t * G::EPV, rope_mode, s0, s01, inv_freq);
+  if (cs_tab != nullptr) {   // cos/sin of the run's tokens, tabulated when it was registered: [token][pair]
+    const float2* cs = cs_tab + (size_t)j * (D / 2) + t * G::EPV;
+#pragma unroll
+    for (int e = 0; e < Vec16<T>::N; ++e) {
+      const float2 r = cs[e];
+      const float a = lo.get(e), b = hi.get(e);
+      lo.set(e, a * r.x - b * r.y);
+      hi.set(e, b * r.x + a * r.y);
+    }
+  } else {
+    rotate_pair_vec<T, D>(lo, hi, pos4[slot0 + j], t * G::EPV, rope_mode, s0, s01, inv_freq);
+  }
   *(decltype(lo.raw)*)(p + t * G::EPV) = lo.raw;
   *(decltype(hi.raw)*)(p + D / 2 + t * G::EPV) = hi.raw;
 }
@@ -230,7 +241,7 @@ __global__ __launch_bounds__(256) void k_store_tokens_vt(
   }
   b -= nb_k;
   if (b < nb_q) {
-    rope_rows<T, VT_D>(b, q, pos4, inv_freq, slot0, n, n_q_heads, rope_mode, s0, s01);
+    rope_rows<T, VT_D>(b, q, pos4, inv_freq, slot0, n, n_q_heads, rope_mode, s0, s01, cs_tab);
     return;
   }
   b -= nb_q;
