@@ -93,7 +93,7 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
     const __hip_bfloat16* __restrict__ q, const __hip_bfloat16* __restrict__ kc, const __hip_bfloat16* __restrict__ vc,
     __hip_bfloat16* __restrict__ out, float* __restrict__ part_o, float* __restrict__ part_ml, int n_q, int n_kv,
     int causal, int n_splits, int keys_per_split, int n_q_heads, int G, size_t head_stride_elems, float c_log2,
-    int n_kv_heads, int pairs_pad, const float2* __restrict__ cs_tab) {
+    int n_kv_heads, int row_tiles, const float2* __restrict__ cs_tab) {
   constexpr int ROWS_WG = NW * 32;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   char* const sKbase = smem;
@@ -101,10 +101,14 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hh = lane >> 5;
-  // One-dimensional grid: workgroup id = row tile * pairs_pad + pair, pair = key range * kv heads + kv head.
-  // Consecutive ids go to the 8 XCDs in turn and pairs_pad is a multiple of 8, so all row tiles of one
-  // (kv head, key range) pair run on the same XCD and share its L2 copy of the pair's K and V^T tiles.
-  const int pair = blockIdx.x % pairs_pad, rt = blockIdx.x / pairs_pad;
+  // One-dimensional grid of 8 x ceil(W / 8) workgroups for W = pairs x row tiles units of work, a pair being a
+  // (key range, kv head).  Consecutive workgroup ids go to the 8 XCDs in turn; XCD x takes the units
+  // [x * per_xcd, (x + 1) * per_xcd) in pair-major order, so the row tiles of a pair run on the same XCD (of two, where
+  // a pair straddles the boundary) and share its L2 copy of the pair's K and V^T tiles, and every XCD gets the same
+  // number of workgroups whatever the number of pairs (one workgroup fits a CU: 32 per XCD at most).
+  const int per_xcd = (int)gridDim.x >> 3;
+  const int unit = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
+  const int pair = unit / row_tiles, rt = unit % row_tiles;
   if (pair >= n_kv_heads * n_splits) return;   // padding ids
   const int hk = pair % n_kv_heads, sp = pair / n_kv_heads;
   const int slot0 = n_kv - n_q;
@@ -559,12 +563,13 @@ static void chunk_ranges(const sv_cache* c, int n_q, int n_kv, int& n_splits, in
   const int row_tiles = (n_q * G + ROWS_WG - 1) / ROWS_WG;
   n_splits = c->opt[SV_OPT_CHUNK_SPLITS];
   if (n_splits <= 0) {
-    // fill the 256 CUs, one workgroup each
-    n_splits = std::max(1, 256 / std::max(1, row_tiles * Hkv));
-    n_splits = std::min(n_splits, std::max(1, n_kv / (4 * TK)));
-    // the row tiles of a (kv head, key range) pair stay on one XCD: a pair count that is a multiple of 8 loads
-    // the 8 XCDs evenly
-    while (n_splits > 1 && (Hkv * n_splits) % 8 != 0) --n_splits;
+    // at most one workgroup per CU (256), ranges of at least 4 tiles; among those the count that leaves a workgroup
+    // the fewest tiles, and of equals the smallest (fewer partial results to merge)
+    const int most = std::min(std::max(1, 256 / std::max(1, row_tiles * Hkv)), std::max(1, n_kv / (4 * TK)));
+    const int tiles = (n_kv + TK - 1) / TK;
+    n_splits = 1;
+    for (int s = 2; s <= most; ++s)
+      if ((tiles + s - 1) / s < (tiles + n_splits - 1) / n_splits) n_splits = s;
   }
   n_splits = std::min<int64_t>(n_splits, std::max<int64_t>(1, c->part_rows / n_q));
   n_splits = std::min(n_splits, kMaxChunkSplits);
@@ -590,12 +595,12 @@ hipError_t launch_attn_chunk_mfma(const sv_cache* c, int stream, int layer, cons
   int n_splits, keys_per_split;
   chunk_ranges(c, n_q, n_kv, n_splits, keys_per_split);
   const float c_log2 = 1.4426950408889634f / sqrtf((float)D);
-  const int pairs_pad = (Hkv * n_splits + 7) / 8 * 8;
-  hipLaunchKernelGGL((k_attn_chunk_pipe<kNW, kKS, kVS>), dim3(row_tiles * pairs_pad), dim3(kNW * 64), kLds, s,
+  const int units = row_tiles * Hkv * n_splits;
+  hipLaunchKernelGGL((k_attn_chunk_pipe<kNW, kKS, kVS>), dim3((units + 7) / 8 * 8), dim3(kNW * 64), kLds, s,
                      (const __hip_bfloat16*)q, (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 0),
                      (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 1), (__hip_bfloat16*)o, c->part_o,
                      c->part_ml, n_q, n_kv, causal ? 1 : 0, n_splits, keys_per_split, c->cfg.n_q_heads, G,
-                     c->head_stride / 2, c_log2, Hkv, pairs_pad,
+                     c->head_stride / 2, c_log2, Hkv, row_tiles,
                      rotate_q ? c->cs_tab + (size_t)stream * c->cfg.max_q_tokens * (D / 2) : nullptr);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || n_splits == 1) return e;
