@@ -479,11 +479,11 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
 // ---------------------------------------------------------------------------------
 // Merge of the key ranges of a chunk-prefill launch: out = sum_s w_s o_s / sum_s w_s with w_s = l_s 2^(m_s - M)
 // and o_s the normalised partial (fp16 x row scale, see above).  16 lanes per (query, head) row, 8 head dims per
-// lane; 16 rows per workgroup.  Ranges go in passes of at most 8, the last pass of exactly what is left; within a
-// pass every load (one 16-byte piece and the (max, sum, scale) record per key range) is unconditional and issued
-// before any is used, so a pass costs one memory round trip (guarded by the record's contents, the pieces' loads
-// wait for the records': two).  A range of weight zero (nothing visible to the row: its piece was never written)
-// is read all the same and left out by a select.
+// lane; 16 rows per workgroup.  Ranges go in passes of 8 while more than 12 are left, then one pass of exactly
+// what is left; within a pass every load (one 16-byte piece and the (max, sum, scale) record per key range) is
+// unconditional and issued before any is used, so a pass costs one memory round trip (guarded by the record's
+// contents, the pieces' loads wait for the records': two).  A range of weight zero (nothing visible to the row:
+// its piece was never written) is read all the same and left out by a select.
 // grid: ceil(n_q * n_q_heads / 16), block: 256 threads.
 // ---------------------------------------------------------------------------------
 constexpr int kMaxChunkSplits = 64;
@@ -526,7 +526,7 @@ __global__ __launch_bounds__(256) void k_chunk_combine(const _Float16* __restric
     m_ref = mx;
   };
   int s0 = 0;
-  for (; n_splits - s0 > 8; s0 += 8) pass(std::integral_constant<int, 8>{}, s0);
+  for (; n_splits - s0 > 12; s0 += 8) pass(std::integral_constant<int, 8>{}, s0);
   switch (n_splits - s0) {
     case 1: pass(std::integral_constant<int, 1>{}, s0); break;
     case 2: pass(std::integral_constant<int, 2>{}, s0); break;
@@ -535,7 +535,11 @@ __global__ __launch_bounds__(256) void k_chunk_combine(const _Float16* __restric
     case 5: pass(std::integral_constant<int, 5>{}, s0); break;
     case 6: pass(std::integral_constant<int, 6>{}, s0); break;
     case 7: pass(std::integral_constant<int, 7>{}, s0); break;
-    default: pass(std::integral_constant<int, 8>{}, s0); break;
+    case 8: pass(std::integral_constant<int, 8>{}, s0); break;
+    case 9: pass(std::integral_constant<int, 9>{}, s0); break;
+    case 10: pass(std::integral_constant<int, 10>{}, s0); break;
+    case 11: pass(std::integral_constant<int, 11>{}, s0); break;
+    default: pass(std::integral_constant<int, 12>{}, s0); break;
   }
   const float inv = 1.0f / wsum;
   typedef __bf16 b8 __attribute__((ext_vector_type(8)));
