@@ -30,7 +30,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 MEASURED_TRAFFIC = {
     # attn_chunk = k_store_tokens_vt + k_attn_chunk_pipe + k_chunk_combine; decode_sweep = k_decode_mfma (key ranges merged
     # in the same launch); evict = k_evict_scan + k_compact (reads + writes, scaled counters)
-    "qwen7b_256v_28L": {"attn_chunk": (2.76e6 + 2.31e6) + (13.5e6 + 14.9e6) + (15.3e6 + 1.8e6),
+    "qwen7b_256v_28L": {"attn_chunk": (2.79e6 + 2.34e6) + (25.4e6 + 16.5e6) + (17.1e6 + 1.8e6),
                         "decode_sweep": 11.49e6 + 1.13e6,
                         "evict": (268.2e6 + 262.3e6) + (0.4e6 + 2.6e6)},
 }

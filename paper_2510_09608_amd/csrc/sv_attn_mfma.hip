@@ -110,6 +110,8 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
   const int unit = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
   const int pair = unit / row_tiles, rt = unit % row_tiles;
   if (pair >= n_kv_heads * n_splits) return;   // padding ids
+  // (key range major: an XCD's pairs are one key range of several kv heads.  Kv head major, its pairs then share
+  // their queries, cuts the launch's reads from 25 to 15 MB at 9 ranges and measured 1.7 us slower.)
   const int hk = pair % n_kv_heads, sp = pair / n_kv_heads;
   const int slot0 = n_kv - n_q;
   const int n_rows = n_q * G;
