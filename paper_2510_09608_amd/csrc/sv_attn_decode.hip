@@ -318,7 +318,9 @@ __global__ __launch_bounds__(NW * 64, 2) void k_decode_mfma(__hip_bfloat16* k0_,
   uint4 kreg[2][4];
   uint4 vreg[8];
   // K: 8 loads per lane straight into the A-operand layout (dims 8 lg + 32 kk + j of key krow[gi]); the token
-  // being decoded comes from the caller's buffer.
+  // being decoded comes from the caller's buffer.  Rows past the range's end are loaded like the others (planes hold
+  // whole 64-key tiles, their scores are replaced by the mask below): no load of a tile sits behind a branch, so the
+  // compiler can count the loads issued after the queries' and wait for those alone.
   // V^T: 8 loads per lane, again straight into the A-operand layout of the second product: head dim
   // 16 blk + l16, keys kt + 8 lg .. + 7 = one row of a V^T block.  Whole blocks are read whatever the range's
   // end: planes hold whole tiles, keys past the range get probability zero, and stale values are finite.
@@ -330,8 +332,8 @@ __global__ __launch_bounds__(NW * 64, 2) void k_decode_mfma(__hip_bfloat16* k0_,
       const __hip_bfloat16* src = is_new ? k_new + new_off + 8 * lg : kp + (size_t)key * D + 8 * lg;
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk)
-        if constexpr (STREAM) kreg[gi][kk] = key < k1 ? stream_load(src + 32 * kk) : make_uint4(0, 0, 0, 0);
-        else kreg[gi][kk] = key < k1 ? *(const uint4*)(src + 32 * kk) : make_uint4(0, 0, 0, 0);
+        if constexpr (STREAM) kreg[gi][kk] = stream_load(src + 32 * kk);
+        else kreg[gi][kk] = *(const uint4*)(src + 32 * kk);
     }
   };
   auto issue_v = [&](int kt) {
@@ -344,19 +346,18 @@ __global__ __launch_bounds__(NW * 64, 2) void k_decode_mfma(__hip_bfloat16* k0_,
   };
 
   const int n_tiles = k1 > k0 ? (k1 - k0 + TK - 1) / TK : 0;
-  if (wave < n_tiles) {   // memory first: everything below overlaps its latency
-    issue_k(k0 + wave * TK);
-    issue_v(k0 + wave * TK);
-  }
-  // the wavefront whose tile holds the token being decoded fetches that token's V (one element per head dim for
-  // the lanes that will own it) along with its first loads
-  unsigned short vnew_bits[8] = {};
-  const bool owns_new = fused && len - 1 >= k0 && len - 1 < k1 && ((len - 1 - k0) / TK) % NW == wave;
-  if (owns_new) {
+  // Memory first, everything below overlaps its latency, and in this order: the query heads and the cos/sin of the
+  // rotation, THEN the tile.  Loads return in the order they were issued, so the wavefront can wait for the small ones
+  // alone and rotate the queries while K and V are still on their way; issued after the tile they could only be had
+  // by waiting for the tile as well, with the rotation's vector work behind the data instead of under it.
+  // Query heads of this kv head as the B operand: lane holds head l16, dims 8 lg + 32 kk + j.  Lanes past the group
+  // repeat its last head (their columns of the products are never looked at), so the four loads are unconditional and
+  // go out together.  (Guarded by l16 < G, the compiler branched around each and waited for the first, and with it
+  // for every load before it, to move a register: a memory round trip before the other three were even issued.)
+  uint4 qraw[4];
 #pragma unroll
-    for (int blk = 0; blk < 8; ++blk) vnew_bits[blk] = *(const unsigned short*)(v_new + new_off + 16 * blk + l16);
-  }
-
+  for (int kk = 0; kk < 4; ++kk)
+    qraw[kk] = *(const uint4*)(q + ((size_t)b * n_q_heads + hk * G + min(l16, G - 1)) * D + 8 * lg + 32 * kk);
   // cos/sin of the 16 rotary pairs a lane touches (dims 8 lg + 32 kk + j, kk = 0, 1), from the table the
   // token's registration wrote
   float rc[2][8], rs[2][8];
@@ -369,13 +370,23 @@ __global__ __launch_bounds__(NW * 64, 2) void k_decode_mfma(__hip_bfloat16* k0_,
         rc[kk][j] = t4.x, rs[kk][j] = t4.y, rc[kk][j + 1] = t4.z, rs[kk][j + 1] = t4.w;
       }
   }
-
-  // query heads of this kv head as the B operand: lane holds head l16, dims 8 lg + 32 kk + j
-  uint4 qraw[4];
+  __builtin_amdgcn_sched_barrier(0);
+  {   // (a wavefront without a tile, at the end of a short last range, loads the range's last one and leaves it unused)
+    const int t0 = min(wave, max(n_tiles - 1, 0));
+    issue_k(k0 + t0 * TK);
+    issue_v(k0 + t0 * TK);
+  }
+  // the wavefront whose tile holds the token being decoded fetches that token's V (one element per head dim for
+  // the lanes that will own it) along with its first loads
+  // (one element per 32-bit register: packed two to a register, the compiler waits for the loads inside the branch, and
+  // with them for every load issued before, to do the packing)
+  uint32_t vnew_bits[8] = {};
+  const bool owns_new = fused && len - 1 >= k0 && len - 1 < k1 && ((len - 1 - k0) / TK) % NW == wave;
+  if (owns_new) {
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk)
-    qraw[kk] = l16 < G ? *(const uint4*)(q + ((size_t)b * n_q_heads + hk * G + l16) * D + 8 * lg + 32 * kk)
-                       : make_uint4(0, 0, 0, 0);
+    for (int blk = 0; blk < 8; ++blk) vnew_bits[blk] = *(const unsigned short*)(v_new + new_off + 16 * blk + l16);
+  }
+  __builtin_amdgcn_sched_barrier(0);
   if (rot) {
     rotate_pair_chunks(qraw[0], qraw[2], rc[0], rs[0]);
     rotate_pair_chunks(qraw[1], qraw[3], rc[1], rs[1]);
@@ -423,7 +434,7 @@ __global__ __launch_bounds__(NW * 64, 2) void k_decode_mfma(__hip_bfloat16* k0_,
 #pragma unroll
           for (int i = 0; i < 4; ++i)
             if (i == wsel) w[i] = hi ? (w[i] & 0x0000ffffu) | (x << 16) : (w[i] & 0xffff0000u) | x;
-          vdst[blk * 16 * kVB] = vnew_bits[blk];
+          vdst[blk * 16 * kVB] = (unsigned short)vnew_bits[blk];
         }
       }
     }
