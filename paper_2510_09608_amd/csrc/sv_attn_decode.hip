@@ -406,7 +406,11 @@ __global__ __launch_bounds__(NW * 64, 2) void k_decode_mfma(__hip_bfloat16* k0_,
   __builtin_amdgcn_s_waitcnt(0x0F70);   // (measurement build only) the first tile's loads have landed
   SV_TS(0, ts_wg, 1);
 #endif
-  for (int t = wave; t < n_tiles; t += NW) {
+  // One tile.  MORE: the wavefront has a further tile, whose loads go out from inside this one.  The loop below runs
+  // the tiles with a successor and then the last one by itself, so that in each of the two bodies the loads in flight
+  // are the same on every path and the compiler can wait for K alone while V^T is still on its way (with the
+  // prefetch behind a condition it waited for everything).
+  auto tile = [&](auto MORE, int t) {
     const int kt = k0 + t * TK;
     if (fused && len - 1 >= kt && len - 1 < kt + TK) {
       // this tile holds the token being decoded: rotate its K, store K and V to the cache
@@ -449,7 +453,7 @@ __global__ __launch_bounds__(NW * 64, 2) void k_decode_mfma(__hip_bfloat16* k0_,
     }
     // the K registers of this tile are consumed: fetch the wavefront's next K tile behind the softmax and the
     // second product (the next V^T block follows once that product has read this one)
-    if (t + NW < n_tiles) issue_k(kt + NW * TK);
+    if constexpr (decltype(MORE)::value) issue_k(kt + NW * TK);
     float mx = -INFINITY;
 #pragma unroll
     for (int gi = 0; gi < 2; ++gi)
@@ -483,7 +487,12 @@ __global__ __launch_bounds__(NW * 64, 2) void k_decode_mfma(__hip_bfloat16* k0_,
 #pragma unroll
     for (int blk = 0; blk < 8; ++blk)
       oacc[blk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(const bf16x8*)&vreg[blk], pf, oacc[blk], 0, 0, 0);
-    if (t + NW < n_tiles) issue_v(kt + NW * TK);
+    if constexpr (decltype(MORE)::value) issue_v(kt + NW * TK);
+  };
+  {
+    int t = wave;
+    for (; t + NW < n_tiles; t += NW) tile(std::true_type{}, t);
+    if (t < n_tiles) tile(std::false_type{}, t);
   }
 
   SV_TS(0, ts_wg, 2);
