@@ -88,7 +88,7 @@ constexpr int kMaxSplitsD = 128;
 constexpr int kMaxRowsD = 64;
 constexpr int PW = D + 1;      // words a key range publishes per query head: 128 values and the log-sum-exp
 // 64-bit header words in front of a tagged region: one per kv head, rounded up to 32
-static inline int hdr_words_of(int n_kv_heads) { return (n_kv_heads + 31) / 32 * 32; }
+__host__ __device__ static inline int hdr_words_of(int n_kv_heads) { return (n_kv_heads + 31) / 32 * 32; }
 constexpr int kPollLimit = 1 << 16;   // polls of a merge read before giving up (each is a memory round trip)
 
 struct DecRow {
@@ -268,17 +268,25 @@ __device__ __forceinline__ bool merge_share(int G, int M, int j, int& o_lo, int&
 
 // ONE: a single row (one stream).  Its cache pointers, length and everything else needed to issue the first
 // loads are the leading 16 dwords of the argument list, which reach the wavefront in SGPRs at launch (kernel
-// argument preload) instead of through a first dependent fetch; the by-value table, at the end, is not read.
+// argument preload) instead of through a first dependent fetch (a scalar-memory round trip in front of the first
+// global load); to fit, the small integers travel in one word (decode_shape) and the head stride as 32 bits.  The
+// by-value table, at the end, is not read.
+__host__ __device__ inline uint32_t decode_shape(int fused, int rotate, int G, int n_kv_heads, int n_q_heads) {
+  return (uint32_t)(fused != 0) | (uint32_t)(rotate != 0) << 1 | (uint32_t)G << 2 | (uint32_t)n_kv_heads << 8 |
+         (uint32_t)n_q_heads << 16;   // G <= 8, n_kv_heads <= 255, n_q_heads <= 65535 (checked by the launcher)
+}
 template <int NW, bool ONE, bool STREAM>
 __global__ __launch_bounds__(NW * 64, 2) void k_decode_mfma(__hip_bfloat16* k0_, __hip_bfloat16* v0_, const float2* cs0_,
                                                          int len0_, int keys_per_split,
                                                          const __hip_bfloat16* __restrict__ q,
                                                          const __hip_bfloat16* __restrict__ k_new,
+                                                         uint32_t head_stride_elems, uint32_t shape, void* part,
                                                          const __hip_bfloat16* __restrict__ v_new,
-                                                         size_t head_stride_elems, int fused, int rotate,
-                                                         __hip_bfloat16* __restrict__ out, void* part,
-                                                         int hdr_words, int n_q_heads, int n_kv_heads, int G,
-                                                         float c_log2, DecTable tab SV_TS_PARAM) {
+                                                         __hip_bfloat16* __restrict__ out, DecTable tab SV_TS_PARAM) {
+  const int fused = shape & 1, rotate = (shape >> 1) & 1, G = (shape >> 2) & 15, n_kv_heads = (shape >> 8) & 255,
+            n_q_heads = (int)(shape >> 16);
+  const int hdr_words = hdr_words_of(n_kv_heads);
+  constexpr float c_log2 = 1.4426950408889634f * 0.08838834764831845f;   // log2(e) / sqrt(128)
   [[maybe_unused]] const int ts_wg = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
   SV_TS(0, ts_wg, 0);
   __shared__ float sO[NW][GMAX][D];                                 // wavefront results (merge)
@@ -299,10 +307,8 @@ __global__ __launch_bounds__(NW * 64, 2) void k_decode_mfma(__hip_bfloat16* k0_,
   // publishing: the workgroup of range 0 replaces the header once it has seen every range publish, i.e. after every
   // workgroup's thread 0 has read it (a later wavefront of a workgroup might see the new one).
   __shared__ unsigned long long sHdr;
-  // (Every thread issues the load, without a branch: behind `if (tid == 0)` the compiler waits for it on the spot,
-  // and the first wavefront would start its K/V loads a memory round trip late.)
+  // (Every thread asks for it, without a branch: behind `if (tid == 0)` the compiler waits for it on the spot.)
   [[maybe_unused]] unsigned long long hdr_old = 0;
-  if constexpr (ONE) hdr_old = ((const unsigned long long*)part)[hk];
   const int k0 = sp * kps, k1 = min(len, k0 + kps);
   if (k0 >= len) return;   // a shorter row of the batch has fewer ranges than the grid is wide
   const __hip_bfloat16* kp = rd.k + (size_t)hk * head_stride_elems;
@@ -386,6 +392,9 @@ __global__ __launch_bounds__(NW * 64, 2) void k_decode_mfma(__hip_bfloat16* k0_,
 #pragma unroll
     for (int blk = 0; blk < 8; ++blk) vnew_bits[blk] = *(const unsigned short*)(v_new + new_off + 16 * blk + l16);
   }
+  // (the header: asked for here, behind the tile's loads, because `part` is not among the preloaded arguments and
+  // fetching it first would put a scalar-memory round trip in front of them)
+  if constexpr (ONE) hdr_old = ((const unsigned long long*)part)[hk];
   __builtin_amdgcn_sched_barrier(0);
   if (rot) {
     rotate_pair_chunks(qraw[0], qraw[2], rc[0], rs[0]);
@@ -692,25 +701,22 @@ static hipError_t decode_launch(const sv_cache* c, const DecTable& tab, int fuse
   }
   void* part = one ? (void*)scr.marked : (void*)scr.plain;
   const int keys_per_split = tabk.r[0].kps;
-  const float c_log2 = 1.4426950408889634f / sqrtf((float)D);
+  if (Hkv > 255 || Hq > 65535 || c->group > GMAX || c->head_stride / 2 > 0xffffffffull) return hipErrorInvalidValue;
+  const uint32_t shape = decode_shape(fused, c->cfg.rope_mode != SV_ROPE_NONE, c->group, Hkv, Hq);
   const __hip_bfloat16* qp = (const __hip_bfloat16*)q + r0 * Hq * D;
   const __hip_bfloat16* knp = k_new ? (const __hip_bfloat16*)k_new + r0 * Hkv * D : nullptr;
   const __hip_bfloat16* vnp = v_new ? (const __hip_bfloat16*)v_new + r0 * Hkv * D : nullptr;
   __hip_bfloat16* op = (__hip_bfloat16*)o + r0 * Hq * D;
-  const int rotate = c->cfg.rope_mode != SV_ROPE_NONE ? 1 : 0;
   const DecRow& r = tabk.r[0];
   if (one)
     hipLaunchKernelGGL((k_decode_mfma<NW, true, false>), dim3(n_splits, Hkv, 1), dim3(NW * 64), 0, s, r.k, r.v, r.cs, r.len,
-                       keys_per_split, qp, knp, vnp, c->head_stride / 2, fused, rotate, op, part, hdr_words_of(Hkv), Hq, Hkv,
-                       c->group, c_log2, tabk SV_TS_ARG(g_ts_launch % 8));
+                       keys_per_split, qp, knp, (uint32_t)(c->head_stride / 2), shape, part, vnp, op, tabk SV_TS_ARG(g_ts_launch % 8));
   else if (stream_loads)
     hipLaunchKernelGGL((k_decode_mfma<NW, false, true>), dim3(n_splits, Hkv, nr), dim3(NW * 64), 0, s, r.k, r.v, r.cs, r.len,
-                       keys_per_split, qp, knp, vnp, c->head_stride / 2, fused, rotate, op, part, hdr_words_of(Hkv), Hq, Hkv,
-                       c->group, c_log2, tabk SV_TS_ARG(g_ts_launch % 8));
+                       keys_per_split, qp, knp, (uint32_t)(c->head_stride / 2), shape, part, vnp, op, tabk SV_TS_ARG(g_ts_launch % 8));
   else
     hipLaunchKernelGGL((k_decode_mfma<NW, false, false>), dim3(n_splits, Hkv, nr), dim3(NW * 64), 0, s, r.k, r.v, r.cs, r.len,
-                       keys_per_split, qp, knp, vnp, c->head_stride / 2, fused, rotate, op, part, hdr_words_of(Hkv), Hq, Hkv,
-                       c->group, c_log2, tabk SV_TS_ARG(g_ts_launch % 8));
+                       keys_per_split, qp, knp, (uint32_t)(c->head_stride / 2), shape, part, vnp, op, tabk SV_TS_ARG(g_ts_launch % 8));
 #ifdef SV_TIMELINE
   ++g_ts_launch;
 #endif
