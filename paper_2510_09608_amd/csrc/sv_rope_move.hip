@@ -68,13 +68,16 @@ __device__ __forceinline__ int pos_of_freq(const int4& p, int i, int rope_mode, 
 }
 
 template <typename T, int D>
-__device__ __forceinline__ void rotate_pair_vec(Vec16<T>& lo, Vec16<T>& hi, const int4& p, int i0, int rope_mode,
+__device__ __forceinline__ void rotate_pair_vec(Vec16<T>& lo, Vec16<T>& hi, const int4 p, int i0, int rope_mode,
                                                 int s0, int s01, const double* __restrict__ inv_freq) {
+  double f[Vec16<T>::N];   // all frequencies first: loaded one by one between the sincos evaluations, each is a round trip
+#pragma unroll
+  for (int e = 0; e < Vec16<T>::N; ++e) f[e] = inv_freq[i0 + e];
 #pragma unroll
   for (int e = 0; e < Vec16<T>::N; ++e) {
     const int i = i0 + e;
     float c, s;
-    rot_cs<T>((double)pos_of_freq(p, i, rope_mode, s0, s01) * inv_freq[i], c, s);
+    rot_cs<T>((double)pos_of_freq(p, i, rope_mode, s0, s01) * f[e], c, s);
     const float a = lo.get(e), b = hi.get(e);
     lo.set(e, a * c - b * s);
     hi.set(e, b * c + a * s);
@@ -98,21 +101,28 @@ __device__ __forceinline__ void append_rows(int bx, int h, int which, const T* _
   const T* src = (which == 0 ? k_in : v_in) + ((size_t)j * n_kv_heads + h) * D;
   T* dst = (which == 0 ? k_cache : v_cache) + (size_t)h * head_stride_elems + (size_t)(slot0 + j) * D;
   Vec16<T> lo, hi;
-  lo.raw = *(const decltype(lo.raw)*)(src + t * G::EPV);
-  hi.raw = *(const decltype(hi.raw)*)(src + D / 2 + t * G::EPV);
-  if (which == 0 && rope_mode != SV_ROPE_NONE) {
-    if (cs_tab != nullptr) {   // cos/sin of the run's tokens were tabulated when it was registered: [token][pair]
-      const float2* cs = cs_tab + (size_t)j * (D / 2) + t * G::EPV;
+  // The (uniform) choice of where cos/sin come from is made BEFORE the row's loads, so that on the table's path the
+  // row and its cos/sin go out together: with the choice behind the row's loads the compiler waited for the row
+  // before it issued the table's loads, two memory round trips for a kernel that is little else.
+  if (which == 0 && rope_mode != SV_ROPE_NONE && cs_tab != nullptr) {
+    // cos/sin of the run's tokens were tabulated when it was registered: [token][pair]
+    const float2* cs = cs_tab + (size_t)j * (D / 2) + t * G::EPV;
+    lo.raw = *(const decltype(lo.raw)*)(src + t * G::EPV);
+    hi.raw = *(const decltype(hi.raw)*)(src + D / 2 + t * G::EPV);
+    float2 r[Vec16<T>::N];
 #pragma unroll
-      for (int e = 0; e < Vec16<T>::N; ++e) {
-        const float2 r = cs[e];
-        const float a = lo.get(e), b = hi.get(e);
-        lo.set(e, a * r.x - b * r.y);
-        hi.set(e, b * r.x + a * r.y);
-      }
-    } else {
-      rotate_pair_vec<T, D>(lo, hi, pos4[slot0 + j], t * G::EPV, rope_mode, s0, s01, inv_freq);
+    for (int e = 0; e < Vec16<T>::N; ++e) r[e] = cs[e];
+#pragma unroll
+    for (int e = 0; e < Vec16<T>::N; ++e) {
+      const float a = lo.get(e), b = hi.get(e);
+      lo.set(e, a * r[e].x - b * r[e].y);
+      hi.set(e, b * r[e].x + a * r[e].y);
     }
+  } else {
+    lo.raw = *(const decltype(lo.raw)*)(src + t * G::EPV);
+    hi.raw = *(const decltype(hi.raw)*)(src + D / 2 + t * G::EPV);
+    if (which == 0 && rope_mode != SV_ROPE_NONE)
+      rotate_pair_vec<T, D>(lo, hi, pos4[slot0 + j], t * G::EPV, rope_mode, s0, s01, inv_freq);
   }
   *(decltype(lo.raw)*)(dst + t * G::EPV) = lo.raw;
   *(decltype(hi.raw)*)(dst + D / 2 + t * G::EPV) = hi.raw;
@@ -144,18 +154,22 @@ __device__ __forceinline__ void rope_rows(int bx, T* __restrict__ x, const int4*
   const int j = (int)(row / n_heads);
   T* p = x + row * D;
   Vec16<T> lo, hi;
-  lo.raw = *(const decltype(lo.raw)*)(p + t * G::EPV);
-  hi.raw = *(const decltype(hi.raw)*)(p + D / 2 + t * G::EPV);
   if (cs_tab != nullptr) {   // cos/sin of the run's tokens, tabulated when it was registered: [token][pair]
-    const float2* cs = cs_tab + (size_t)j * (D / 2) + t * G::EPV;
+    const float2* cs = cs_tab + (size_t)j * (D / 2) + t * G::EPV;   // (the row and its cos/sin go out together)
+    lo.raw = *(const decltype(lo.raw)*)(p + t * G::EPV);
+    hi.raw = *(const decltype(hi.raw)*)(p + D / 2 + t * G::EPV);
+    float2 r[Vec16<T>::N];
+#pragma unroll
+    for (int e = 0; e < Vec16<T>::N; ++e) r[e] = cs[e];
 #pragma unroll
     for (int e = 0; e < Vec16<T>::N; ++e) {
-      const float2 r = cs[e];
       const float a = lo.get(e), b = hi.get(e);
-      lo.set(e, a * r.x - b * r.y);
-      hi.set(e, b * r.x + a * r.y);
+      lo.set(e, a * r[e].x - b * r[e].y);
+      hi.set(e, b * r[e].x + a * r[e].y);
     }
   } else {
+    lo.raw = *(const decltype(lo.raw)*)(p + t * G::EPV);
+    hi.raw = *(const decltype(hi.raw)*)(p + D / 2 + t * G::EPV);
     rotate_pair_vec<T, D>(lo, hi, pos4[slot0 + j], t * G::EPV, rope_mode, s0, s01, inv_freq);
   }
   *(decltype(lo.raw)*)(p + t * G::EPV) = lo.raw;
@@ -188,13 +202,21 @@ __device__ __forceinline__ void append_v_t_group(char* sT, int grp, int hk, cons
                                                  int n_kv_heads, size_t head_stride_elems) {
   const int tid = threadIdx.x;
   const int64_t key0 = (int64_t)grp * VG;
+  // both loads of a thread are unconditional (a slot of the group outside the run reads the run's nearest row and
+  // stages zeros) and issued together: guarded, the compiler waited for the first before it issued the second
+  uint4 vin[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int cid = tid + 256 * i, key = cid >> 4, c16 = cid & 15;
+    const int64_t kc = min(max(key0 + key, slot0), slot0 + n - 1);
+    vin[i] = *(const uint4*)(v_in + ((size_t)(kc - slot0) * n_kv_heads + hk) * VT_D + c16 * 8);
+  }
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     const int cid = tid + 256 * i, key = cid >> 4, c16 = cid & 15;
     const int64_t kk = key0 + key;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (kk >= slot0 && kk < slot0 + n) v = *(const uint4*)(v_in + ((size_t)(kk - slot0) * n_kv_heads + hk) * VT_D + c16 * 8);
-    *(uint4*)(sT + key * VT_SROW + c16 * 16) = v;
+    const bool in_run = (kk >= slot0) & (kk < slot0 + n);
+    *(uint4*)(sT + key * VT_SROW + c16 * 16) = in_run ? vin[i] : make_uint4(0, 0, 0, 0);
   }
   __syncthreads();
   unsigned short* head_base = (unsigned short*)v_cache + (size_t)hk * head_stride_elems;
