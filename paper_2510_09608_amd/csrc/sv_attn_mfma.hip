@@ -88,12 +88,23 @@ __device__ __forceinline__ void dma16(const void* base, uint32_t lane_off, char*
 }
 #pragma clang diagnostic pop
 
+// causal 1 bit, key ranges 7 bits (kMaxChunkSplits), group 4 bits, kv heads 8 bits, row tiles 12 bits
+__host__ __device__ inline uint32_t chunk_shape(int causal, int n_splits, int G, int n_kv_heads, int row_tiles) {
+  return (uint32_t)(causal != 0) | (uint32_t)n_splits << 1 | (uint32_t)G << 8 | (uint32_t)n_kv_heads << 12 |
+         (uint32_t)row_tiles << 20;
+}
 template <int NW, int KS, int VS>
 __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
-    const __hip_bfloat16* __restrict__ q, const __hip_bfloat16* __restrict__ kc, const __hip_bfloat16* __restrict__ vc,
-    __hip_bfloat16* __restrict__ out, float* __restrict__ part_o, float* __restrict__ part_ml, int n_q, int n_kv,
-    int causal, int n_splits, int keys_per_split, int n_q_heads, int G, size_t head_stride_elems, float c_log2,
-    int n_kv_heads, int row_tiles, const float2* __restrict__ cs_tab) {
+    const __hip_bfloat16* __restrict__ kc, const __hip_bfloat16* __restrict__ vc, int n_q, int n_kv, int keys_per_split,
+    uint32_t head_stride_elems, uint32_t shape, int n_q_heads, const __hip_bfloat16* __restrict__ q,
+    const float2* __restrict__ cs_tab, __hip_bfloat16* __restrict__ out, float* __restrict__ part_o,
+    float* __restrict__ part_ml) {
+  // (the arguments up to cs_tab are the 14 dwords that reach the wavefront in SGPRs at launch: everything the first
+  // direct loads and the query loads need, the small integers in one word, see chunk_shape; the grid's size, which
+  // would be a fetch of its own, follows from them)
+  const int causal = shape & 1, n_splits = (shape >> 1) & 127, G = (shape >> 8) & 15, n_kv_heads = (shape >> 12) & 255,
+            row_tiles = (int)(shape >> 20);
+  constexpr float c_log2 = 1.4426950408889634f * 0.08838834764831845f;   // log2(e) / sqrt(128)
   constexpr int ROWS_WG = NW * 32;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   char* const sKbase = smem;
@@ -106,7 +117,7 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
   // [x * per_xcd, (x + 1) * per_xcd) in pair-major order, so the row tiles of a pair run on the same XCD (of two, where
   // a pair straddles the boundary) and share its L2 copy of the pair's K and V^T tiles, and every XCD gets the same
   // number of workgroups whatever the number of pairs (one workgroup fits a CU: 32 per XCD at most).
-  const int per_xcd = (int)gridDim.x >> 3;
+  const int per_xcd = (row_tiles * n_kv_heads * n_splits + 7) >> 3;   // = gridDim.x / 8
   const int unit = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
   const int pair = unit / row_tiles, rt = unit % row_tiles;
   if (pair >= n_kv_heads * n_splits) return;   // padding ids
@@ -600,14 +611,16 @@ hipError_t launch_attn_chunk_mfma(const sv_cache* c, int stream, int layer, cons
   const int row_tiles = (n_q * G + ROWS_WG - 1) / ROWS_WG;
   int n_splits, keys_per_split;
   chunk_ranges(c, n_q, n_kv, n_splits, keys_per_split);
-  const float c_log2 = 1.4426950408889634f / sqrtf((float)D);
   const int units = row_tiles * Hkv * n_splits;
+  if (n_splits > 127 || G > 15 || Hkv > 255 || row_tiles > 4095 || c->head_stride / 2 > 0xffffffffull)
+    return hipErrorInvalidValue;   // what chunk_shape and the 32-bit head stride can carry
   hipLaunchKernelGGL((k_attn_chunk_pipe<kNW, kKS, kVS>), dim3((units + 7) / 8 * 8), dim3(kNW * 64), kLds, s,
-                     (const __hip_bfloat16*)q, (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 0),
-                     (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 1), (__hip_bfloat16*)o, c->part_o,
-                     c->part_ml, n_q, n_kv, causal ? 1 : 0, n_splits, keys_per_split, c->cfg.n_q_heads, G,
-                     c->head_stride / 2, c_log2, Hkv, row_tiles,
-                     rotate_q ? c->cs_tab + (size_t)stream * c->cfg.max_q_tokens * (D / 2) : nullptr);
+                     (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 0),
+                     (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 1), n_q, n_kv, keys_per_split,
+                     (uint32_t)(c->head_stride / 2), chunk_shape(causal, n_splits, G, Hkv, row_tiles),
+                     c->cfg.n_q_heads, (const __hip_bfloat16*)q,
+                     rotate_q ? c->cs_tab + (size_t)stream * c->cfg.max_q_tokens * (D / 2) : nullptr,
+                     (__hip_bfloat16*)o, c->part_o, c->part_ml);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || n_splits == 1) return e;
   const int rows_total = n_q * c->cfg.n_q_heads;
