@@ -15,9 +15,10 @@ namespace {
 constexpr size_t kAlign = 256;
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
-// bf16, head_dim 128, at most 8 query heads per kv head and no SV_FLAG_GENERIC_KERNELS: the matrix-core kernels
+// bf16, head_dim 128, at most 8 query heads per kv head (and at most 255 kv heads: the kernels carry the head
+// counts in one packed argument word) and no SV_FLAG_GENERIC_KERNELS: the matrix-core kernels
 bool mfma_eligible(const sv_config& c) {
-  return c.dtype == SV_DTYPE_BF16 && c.head_dim == 128 && c.n_q_heads / c.n_kv_heads <= 8 &&
+  return c.dtype == SV_DTYPE_BF16 && c.head_dim == 128 && c.n_q_heads / c.n_kv_heads <= 8 && c.n_kv_heads <= 255 &&
          !(c.flags & SV_FLAG_GENERIC_KERNELS);
 }
 
