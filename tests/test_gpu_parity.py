@@ -402,6 +402,48 @@ def test_opening_text_run_left_in_place(dtype):
                 assert e <= tol, (case, c, l, e)
 
 
+def test_opening_text_runs_of_two_streams_are_tracked_apart():
+    """Two streams of one cache with opening runs of different lengths, evicted in turn with different sink counts
+    (one of them twice in a row): what an eviction leaves in place is per stream, and every stored K/V row of both
+    streams is what the oracle holds after each step (bf16, 3-D positions; Sec. 3.1)."""
+    rng = np.random.default_rng(96082511)
+    d, Hq, Hkv, mode, sec, theta = 128, 28, 4, 1, (16, 24, 24), 1e6
+    w = si.Workload("t", 1, Hq, Hkv, d, "bf16", mode, theta, sec, 0, 0, 0, 0, 0, 0, None, 0, 400)
+    cache = gu.make_cache(w, capacity=1024, n_streams=2)
+    orcs = [orc.OracleStream(1, Hq, Hkv, d, mode, theta, sec) for _ in range(2)]
+    g0 = [0, 0]
+    n_ev = [0, 0]
+
+    def append(sid, ty, n, grid):
+        gids = np.arange(g0[sid], g0[sid] + n) + 100000 * sid     # different data per stream
+        g0[sid] += n
+        orcs[sid].append_meta([ty] * n, grid)
+        _, k, v = w.qkv(0, gids)
+        cache.append(sid, 0, np.full(n, ty, dtype=np.uint8), grid, gu.dev(k, w), gu.dev(v, w))
+        orcs[sid].append_kv(0, k, v)
+
+    def check(sid, tag):
+        o = orcs[sid]
+        n = len(o)
+        K, V = np.stack(o.k[0]), np.stack(o.v[0])
+        assert np.array_equal(cache.read_kv(sid, 0, 1, 0, n).astype(np.float64), V), (tag, sid)
+        e = gu.max_err(cache.read_kv(sid, 0, 0, 0, n), orc.rope(K, o.positions(), mode, theta, sec))
+        assert e <= 4e-2 * (1 + n_ev[sid]), (tag, sid, e)
+
+    append(0, orc.TEXT, 96, None)
+    append(1, orc.TEXT, 200, None)
+    schedule = [(0, 64), (1, 160), (1, 160), (0, 64), (0, 32), (1, 40), (0, 64), (1, 160), (0, 0), (1, 96)]
+    for step, (sid, n_sink) in enumerate(schedule):
+        for s2 in (0, 1):
+            append(s2, orc.VISION, 2 * 4 * 6, (2, 4, 6))
+            append(s2, orc.TEXT, int(rng.integers(1, 9)), None)
+        _say(f"two streams: step {step}, stream {sid} evicts with {n_sink} sinks")
+        assert cache.evict(sid, n_sink, 100, 12) == orcs[sid].evict(n_sink, 100, 12)
+        n_ev[sid] += 1
+        for s2 in (0, 1):
+            check(s2, step)
+
+
 # ----------------------------------------------------------------------------
 # single operations
 # ----------------------------------------------------------------------------
