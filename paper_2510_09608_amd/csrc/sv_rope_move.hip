@@ -104,7 +104,7 @@ __device__ __forceinline__ void append_rows(int bx, int h, int which, const T* _
   // The (uniform) choice of where cos/sin come from is made BEFORE the row's loads, so that on the table's path the
   // row and its cos/sin go out together: with the choice behind the row's loads the compiler waited for the row
   // before it issued the table's loads, two memory round trips for a kernel that is little else.
-  if (which == 0 && rope_mode != SV_ROPE_NONE && cs_tab != nullptr) {
+  if (which == 0 && cs_tab != nullptr) {   // (a table is only ever given with a rotary mode)
     // cos/sin of the run's tokens were tabulated when it was registered: [token][pair]
     const float2* cs = cs_tab + (size_t)j * (D / 2) + t * G::EPV;
     lo.raw = *(const decltype(lo.raw)*)(src + t * G::EPV);
@@ -247,7 +247,71 @@ __device__ __forceinline__ void append_v_t_group(char* sT, int grp, int hk, cons
 // chunk prefill's prologue).  The three jobs are independent; workgroup ids [0, nb_k) do the first,
 // [nb_k, nb_k + nb_q) the second, the rest the third.
 // ---------------------------------------------------------------------------------
+// All 14 dwords of its arguments reach the wavefront in SGPRs at launch, so no scalar fetch precedes the loads of a
+// kernel that is little more than one memory round trip: the V plane follows the K plane of the layer, the job
+// boundaries follow from n, slot0 and the head counts, and cos/sin come from the run's table only (cs_tab NULL: no
+// rotary embedding, rows are copied; a cache with a rotary mode always has the table for a run this kernel is given).
+// shape: bit 1 = rotate q, bits 8-15 kv heads, bits 16-31 query heads.
 __global__ __launch_bounds__(256) void k_store_tokens_vt(
+    __hip_bfloat16* __restrict__ q, const __hip_bfloat16* __restrict__ k_in, const __hip_bfloat16* __restrict__ v_in,
+    __hip_bfloat16* __restrict__ k_cache, const float2* __restrict__ cs_tab, int slot0, int n, uint32_t head_stride_elems,
+    uint32_t shape) {
+  __shared__ __attribute__((aligned(16))) char sT[VG * VT_SROW];
+  using T = __hip_bfloat16;
+  using G = RowGeom<T, VT_D>;
+  constexpr int D = VT_D;
+  const int n_kv_heads = (shape >> 8) & 255, n_q_heads = (int)(shape >> 16);
+  __hip_bfloat16* const v_cache = k_cache + (size_t)n_kv_heads * head_stride_elems;   // K and V planes of a layer are adjacent
+  const int gx_k = (n + G::ROWS - 1) / G::ROWS, nb_k = gx_k * n_kv_heads;
+  const int nb_q = (shape & 2) ? (n * n_q_heads + G::ROWS - 1) / G::ROWS : 0;
+  const int blk0 = slot0 / VG, n_blk = (slot0 + n - 1) / VG - blk0 + 1;   // groups of 32 slots
+  int b = blockIdx.x;
+  if (b >= nb_k + nb_q) {
+    b -= nb_k + nb_q;
+    append_v_t_group(sT, blk0 + b % n_blk, b / n_blk, v_in, v_cache, slot0, n, n_kv_heads, head_stride_elems);
+    return;
+  }
+  // a K row into the cache, or a Q row in place: the row and its token's cos/sin go out together, one round trip
+  const bool is_k = b < nb_k;
+  const int t = threadIdx.x % G::TPR;
+  int j;
+  const T* src;
+  T* dst;
+  if (is_k) {
+    const int h = b / gx_k;
+    j = (b % gx_k) * G::ROWS + threadIdx.x / G::TPR;
+    if (j >= n) return;
+    src = k_in + ((size_t)j * n_kv_heads + h) * D;
+    dst = k_cache + (size_t)h * head_stride_elems + (size_t)(slot0 + j) * D;
+  } else {
+    const int64_t row = (int64_t)(b - nb_k) * G::ROWS + threadIdx.x / G::TPR;
+    if (row >= (int64_t)n * n_q_heads) return;
+    j = (int)(row / n_q_heads);
+    dst = q + row * D;
+    src = dst;
+  }
+  Vec16<T> lo, hi;
+  lo.raw = *(const decltype(lo.raw)*)(src + t * G::EPV);
+  hi.raw = *(const decltype(hi.raw)*)(src + D / 2 + t * G::EPV);
+  if (cs_tab != nullptr) {   // [token of the run][pair]
+    const float2* cs = cs_tab + (size_t)j * (D / 2) + t * G::EPV;
+    float2 r[Vec16<T>::N];
+#pragma unroll
+    for (int e = 0; e < Vec16<T>::N; ++e) r[e] = cs[e];
+#pragma unroll
+    for (int e = 0; e < Vec16<T>::N; ++e) {
+      const float a = lo.get(e), bb = hi.get(e);
+      lo.set(e, a * r[e].x - bb * r[e].y);
+      hi.set(e, bb * r[e].x + a * r[e].y);
+    }
+  }
+  *(decltype(lo.raw)*)(dst + t * G::EPV) = lo.raw;
+  *(decltype(hi.raw)*)(dst + D / 2 + t * G::EPV) = hi.raw;
+}
+
+// The same three jobs with cos/sin evaluated from the tokens' positions: runs that have no table (longer than the
+// cache's max_q_tokens).
+__global__ __launch_bounds__(256) void k_store_tokens_vt_pos(
     __hip_bfloat16* __restrict__ q, const __hip_bfloat16* __restrict__ k_in, const __hip_bfloat16* __restrict__ v_in,
     __hip_bfloat16* __restrict__ k_cache, __hip_bfloat16* __restrict__ v_cache, const int4* __restrict__ pos4,
     const double* __restrict__ inv_freq, int64_t slot0, int n, int n_q_heads, int n_kv_heads, size_t head_stride_elems,
@@ -440,18 +504,33 @@ hipError_t launch_store_tokens_vt(const sv_cache* c, int stream, int layer, int6
                                   const void* v, hipStream_t s) {
   using G = RowGeom<__hip_bfloat16, VT_D>;
   const int Hq = c->cfg.n_q_heads, Hkv = c->cfg.n_kv_heads, cur = c->st[stream].cur;
-  const size_t off = (size_t)stream * (size_t)c->cfg.capacity_tokens;
   const int gx_k = (n + G::ROWS - 1) / G::ROWS, nb_k = gx_k * Hkv;
-  const int nb_q = q && c->cfg.rope_mode != SV_ROPE_NONE ? (int)(((int64_t)n * Hq + G::ROWS - 1) / G::ROWS) : 0;
+  const bool rot_q = q && c->cfg.rope_mode != SV_ROPE_NONE;
+  const int nb_q = rot_q ? (int)(((int64_t)n * Hq + G::ROWS - 1) / G::ROWS) : 0;
   const int blk0 = (int)(slot0 / VG), n_blk = (int)((slot0 + n - 1) / VG) - blk0 + 1;   // groups of 32 slots
+  // what the kernel's packed arguments can carry, and the layout it relies on (V plane right behind the K plane)
+  if (Hkv > 255 || Hq > 65535 || c->head_stride / 2 > 0xffffffffull || (int64_t)n * Hq > 0x7fffffff ||
+      c->kv_ptr(stream, cur, layer, 1) != c->kv_ptr(stream, cur, layer, 0) + (size_t)Hkv * c->head_stride)
+    return hipErrorInvalidValue;
+  const float2* cs_tab = nullptr;
+  if (c->cfg.rope_mode != SV_ROPE_NONE) {   // the run's cos/sin table, written when the run was registered
+    const StreamState& st = c->st[stream];
+    if (!st.cs_tab_valid || st.pending_slot0 != slot0 || st.pending_n != n) {   // no table: positions and sincos
+      const size_t off = (size_t)stream * (size_t)c->cfg.capacity_tokens;
+      hipLaunchKernelGGL(k_store_tokens_vt_pos, dim3(nb_k + nb_q + n_blk * Hkv), dim3(256), 0, s, (__hip_bfloat16*)q,
+                         (const __hip_bfloat16*)k, (const __hip_bfloat16*)v,
+                         (__hip_bfloat16*)c->kv_ptr(stream, cur, layer, 0), (__hip_bfloat16*)c->kv_ptr(stream, cur, layer, 1),
+                         c->meta[cur].pos4 + off, c->inv_freq, slot0, n, Hq, Hkv, c->head_stride / 2, c->cfg.rope_mode,
+                         c->cfg.mrope_sections[0], c->cfg.mrope_sections[0] + c->cfg.mrope_sections[1], gx_k, nb_k, nb_q,
+                         blk0, n_blk, (const float2*)nullptr);
+      return hipGetLastError();
+    }
+    cs_tab = c->cs_tab + (size_t)stream * c->cfg.max_q_tokens * (VT_D / 2);
+  }
+  const uint32_t shape = (uint32_t)rot_q << 1 | (uint32_t)Hkv << 8 | (uint32_t)Hq << 16;
   hipLaunchKernelGGL(k_store_tokens_vt, dim3(nb_k + nb_q + n_blk * Hkv), dim3(256), 0, s, (__hip_bfloat16*)q,
                      (const __hip_bfloat16*)k, (const __hip_bfloat16*)v, (__hip_bfloat16*)c->kv_ptr(stream, cur, layer, 0),
-                     (__hip_bfloat16*)c->kv_ptr(stream, cur, layer, 1), c->meta[cur].pos4 + off, c->inv_freq, slot0, n, Hq,
-                     Hkv, c->head_stride / 2, c->cfg.rope_mode, c->cfg.mrope_sections[0],
-                     c->cfg.mrope_sections[0] + c->cfg.mrope_sections[1], gx_k, nb_k, nb_q, blk0, n_blk,
-                     c->st[stream].cs_tab_valid && c->st[stream].pending_slot0 == slot0 && c->st[stream].pending_n == n
-                         ? c->cs_tab + (size_t)stream * c->cfg.max_q_tokens * (VT_D / 2)
-                         : nullptr);
+                     cs_tab, (int)slot0, n, (uint32_t)(c->head_stride / 2), shape);
   return hipGetLastError();
 }
 
