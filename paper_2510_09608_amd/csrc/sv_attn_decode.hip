@@ -608,21 +608,24 @@ __global__ __launch_bounds__(NW * 64, 2) void k_decode_mfma(__hip_bfloat16* k0_,
 // ---------------------------------------------------------------------------------
 constexpr int kMergeWGs = 7;
 struct RangeTable {
-  uint16_t pair0[kMaxRowsD];   // first (row, key range) pair of each row
-  uint8_t n[kMaxRowsD];        // key ranges of each row
+  uint32_t row[kMaxRowsD];   // per row: first (row, key range) pair | key ranges << 16.  One 32-bit word, so that the
+                             // lookup by a (uniform) row index is ONE scalar load from the kernel arguments; as bytes and
+                             // halfwords the compiler fetched the two fields with two dependent vector loads, two memory
+                             // round trips in front of the kernel's real loads
 };
 __global__ __launch_bounds__(256) void k_decode_merge(const float* __restrict__ part,
                                                       __hip_bfloat16* __restrict__ out, int n_q_heads, int G,
                                                       RangeTable rt) {
   __shared__ float lds[3 * 256];
   const int hk = blockIdx.y, b = blockIdx.z;
-  const int nsr = rt.n[b];
+  const uint32_t row = rt.row[b];
+  const int nsr = (int)(row >> 16), pair0 = (int)(row & 0xffffu);
   int o_lo, n_out;
   if (nsr == 1 || !merge_share(G, kMergeWGs, blockIdx.x, o_lo, n_out)) return;   // one range: the decode kernel wrote the output
 #ifdef SV_TIMELINE
   constexpr int ts_slot = 0;
 #endif
-  merge_ranges<256, false>(part + ((size_t)rt.pair0[b] * n_q_heads + (size_t)hk * G) * PW, (size_t)n_q_heads * PW, nsr, 0u,
+  merge_ranges<256, false>(part + ((size_t)pair0 * n_q_heads + (size_t)hk * G) * PW, (size_t)n_q_heads * PW, nsr, 0u,
                            o_lo, n_out, lds, out + ((size_t)b * n_q_heads + hk * G) * D SV_TS_ARG(ts_slot), 1 << 20);
 }
 
@@ -694,8 +697,7 @@ static hipError_t decode_launch(const sv_cache* c, const DecTable& tab, int fuse
     const int ranges = (len + kps - 1) / kps;   // <= nb <= kMaxSplitsD
     tabk.r[b].kps = kps;
     tabk.r[b].pair0 = pair0;
-    rt.pair0[b] = (uint16_t)pair0;
-    rt.n[b] = (uint8_t)ranges;
+    rt.row[b] = (uint32_t)pair0 | (uint32_t)ranges << 16;   // pair0 < 2^16: at most kMaxRowsD x kMaxSplitsD pairs
     pair0 += ranges;
     n_splits = std::max(n_splits, ranges);
   }
