@@ -107,7 +107,10 @@ SV_API int sv_cache_destroy(sv_cache* c);
  * defaults to 0 = "let the library choose" (what all measurements use); a positive value forces
  *   SV_OPT_CHUNK_SPLITS           the number of key ranges of sv_attn_chunk's matrix-core kernel,
  *   SV_OPT_DECODE_TILES_PER_WAVE  the 32-key tiles each wavefront of the decode kernel takes (1..16),
- *   SV_OPT_DECODE_SPLITS          the number of key ranges of the generic row kernel.
+ *   SV_OPT_DECODE_SPLITS          the number of key ranges of the generic row kernel,
+ *   SV_OPT_CHUNK_STORE            who stores a chunk's K/V in sv_stream_step on a matrix-core cache: 1 = always a
+ *                                 launch of its own, 2 = the attention launch whenever it can (chunks of at most
+ *                                 512 tokens with a rotary mode); 0 = whichever the library expects to be faster.
  * Forced values are still clamped to what the scratch buffers hold.  Host-side state only: takes effect
  * from the next launch.  Errors: SV_ERR_INVALID (NULL handle, unknown option, negative value).
  */
@@ -115,7 +118,8 @@ enum {
   SV_OPT_CHUNK_SPLITS = 0,
   SV_OPT_DECODE_TILES_PER_WAVE = 1,
   SV_OPT_DECODE_SPLITS = 2,
-  SV_OPT_COUNT_ = 3
+  SV_OPT_CHUNK_STORE = 3,
+  SV_OPT_COUNT_ = 4
 };
 SV_API int sv_cache_set_option(sv_cache* c, int option, int value);
 

@@ -18,7 +18,7 @@ SV_ROPE_1D, SV_ROPE_3D, SV_ROPE_NONE = 0, 1, 2
 SV_TEXT, SV_VISION = 0, 1
 SV_WINDOW_INF = -1
 SV_FLAG_GENERIC_KERNELS, SV_FLAG_HOST_LOGIC_ONLY = 1, 2
-SV_OPT_CHUNK_SPLITS, SV_OPT_DECODE_TILES_PER_WAVE, SV_OPT_DECODE_SPLITS = 0, 1, 2
+SV_OPT_CHUNK_SPLITS, SV_OPT_DECODE_TILES_PER_WAVE, SV_OPT_DECODE_SPLITS, SV_OPT_CHUNK_STORE = 0, 1, 2, 3
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 

@@ -546,6 +546,11 @@ int sv_stream_step(sv_cache* c, int stream_id, int64_t n_sink, int64_t vision_wi
       if (fused) {
         // Q stays as the caller wrote it when the run's cos/sin table exists and few key ranges will load each query
         // row: the attention kernel then rotates it on load
+        // ... and a short chunk's K/V are stored by the attention launch itself
+        if (st_cs_valid(c, stream_id) && sv::attn_chunk_stores_tokens(c, stream_id, n)) {
+          SV_DEV(sv::launch_attn_chunk_mfma(c, stream_id, l, q, n, o, 1, true, (hipStream_t)hip_stream, k, v));
+          continue;
+        }
         const bool q_on_load = st_cs_valid(c, stream_id) && sv::attn_chunk_rotates_on_load(c, stream_id, n);
         SV_DEV(sv::launch_store_tokens_vt(c, stream_id, l, slot0, n, q_on_load ? nullptr : q, k, v,
                                           (hipStream_t)hip_stream));

@@ -93,12 +93,19 @@ __host__ __device__ inline uint32_t chunk_shape(int causal, int n_splits, int G,
   return (uint32_t)(causal != 0) | (uint32_t)n_splits << 1 | (uint32_t)G << 8 | (uint32_t)n_kv_heads << 12 |
          (uint32_t)row_tiles << 20;
 }
-template <int NW, int KS, int VS>
+// STORE: the chunk's own K and V are not in the cache yet.  k_new / v_new hold them as the caller produced them
+// ([n_q][n_kv_heads][128], K un-rotated) and cs_tab their cos/sin; a workgroup first stores, of its kv head, exactly the
+// new keys it is about to read (K rows rotated, V into its V^T blocks), waits for its stores and then proceeds as
+// ever.  Workgroups of different row tiles store the same keys with the same values: each reads what it wrote itself
+// (through its own CU's and XCD's caches), the copies agree, and the last row tile's workgroups write every new key
+// of their ranges, so the cache is complete when the launch ends.  One launch and one pass over the new rows fewer
+// per layer; worth it while the chunk is short, since the store is repeated per row tile.
+template <int NW, int KS, int VS, bool STORE>
 __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
-    const __hip_bfloat16* __restrict__ kc, const __hip_bfloat16* __restrict__ vc, int n_q, int n_kv, int keys_per_split,
+    __hip_bfloat16* kc, __hip_bfloat16* vc, int n_q, int n_kv, int keys_per_split,
     uint32_t head_stride_elems, uint32_t shape, int n_q_heads, const __hip_bfloat16* __restrict__ q,
     const float2* __restrict__ cs_tab, __hip_bfloat16* __restrict__ out, float* __restrict__ part_o,
-    float* __restrict__ part_ml) {
+    float* __restrict__ part_ml, const __hip_bfloat16* __restrict__ k_new, const __hip_bfloat16* __restrict__ v_new) {
   // (the arguments up to cs_tab are the 14 dwords that reach the wavefront in SGPRs at launch: everything the first
   // direct loads and the query loads need, the small integers in one word, see chunk_shape; the grid's size, which
   // would be a fetch of its own, follows from them)
@@ -141,8 +148,89 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_chunk_pipe(
     return;
   }
 
-  const __hip_bfloat16* kbase = kc + (size_t)hk * head_stride_elems;
-  const __hip_bfloat16* vtbase = vc + (size_t)hk * head_stride_elems;   // V is stored as V^T in blocks of 8 keys
+  __hip_bfloat16* const kbase = kc + (size_t)hk * head_stride_elems;
+  __hip_bfloat16* const vtbase = vc + (size_t)hk * head_stride_elems;   // V is stored as V^T in blocks of 8 keys
+
+  if constexpr (STORE) {
+    const int ks0 = max(k_begin, slot0), ks1 = k_end;   // the new keys this workgroup reads
+    if (ks0 < ks1) {
+      // K: 8 lanes per row, a lane owns 16 bytes of the low half and the matching 16 of the high half (the rotary
+      // pairs are lane-local); 64 rows per pass, four passes' loads (row halves and cos/sin) in flight at once,
+      // unconditional on a clamped row
+      const int t8 = tid & 7, r8 = tid >> 3;
+      for (int base = ks0; base < ks1; base += 4 * (NW * 8)) {
+        uint4 lo[4], hi[4];
+        float4 cs[4][4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int j = min(base + i * (NW * 8) + r8, ks1 - 1) - slot0;
+          const __hip_bfloat16* src = k_new + ((size_t)j * n_kv_heads + hk) * D + 8 * t8;
+          lo[i] = *(const uint4*)src;
+          hi[i] = *(const uint4*)(src + D / 2);
+          const float4* c4 = (const float4*)(cs_tab + (size_t)j * (D / 2) + 8 * t8);
+#pragma unroll
+          for (int e2 = 0; e2 < 4; ++e2) cs[i][e2] = c4[e2];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int key = base + i * (NW * 8) + r8;
+          bf16x8 a8 = *(bf16x8*)&lo[i], b8 = *(bf16x8*)&hi[i];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const float4 r4 = cs[i][e >> 1];
+            const float cx = (e & 1) ? r4.z : r4.x, sx = (e & 1) ? r4.w : r4.y;
+            const float a = (float)a8[e], b = (float)b8[e];
+            a8[e] = (__bf16)(a * cx - b * sx);
+            b8[e] = (__bf16)(b * cx + a * sx);
+          }
+          if (key < ks1) {
+            __hip_bfloat16* dst = kbase + (size_t)key * D + 8 * t8;
+            *(bf16x8*)dst = a8;
+            *(bf16x8*)(dst + D / 2) = b8;
+          }
+        }
+      }
+      // V: a lane takes one head dim of the 8 keys of a block (eight 2-byte loads; a wavefront reads 128 contiguous
+      // bytes of a row per instruction) and writes the block row, 16 bytes, consecutive lanes consecutive rows; where
+      // a block is only partly this workgroup's (older tokens below the first new key, keys past its range above),
+      // element by element.  Four blocks per lane in flight.
+      const int dv = tid & (D - 1), bsub = tid / D;
+      constexpr int BP = NW * 64 / D;   // blocks per pass of the workgroup
+      const int b0 = ks0 >> 3, b1 = (ks1 - 1) >> 3;
+      const unsigned short* vsrc = (const unsigned short*)v_new + (size_t)hk * D + dv;
+      for (int base = b0; base <= b1; base += 4 * BP) {
+        unsigned short x[4][8];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int be = min(base + u * BP + bsub, b1);
+#pragma unroll
+          for (int kk = 0; kk < 8; ++kk) {
+            const int j = min(max(8 * be + kk, ks0), ks1 - 1) - slot0;
+            x[u][kk] = vsrc[(size_t)j * n_kv_heads * D];
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int blk = base + u * BP + bsub;
+          if (blk <= b1) {
+            unsigned short* dst = (unsigned short*)vtbase + vt_elem(8 * (int64_t)blk, dv);
+            if (8 * blk >= ks0 && 8 * blk + 8 <= ks1) {
+              *(uint4*)dst = make_uint4(x[u][0] | (uint32_t)x[u][1] << 16, x[u][2] | (uint32_t)x[u][3] << 16,
+                                        x[u][4] | (uint32_t)x[u][5] << 16, x[u][6] | (uint32_t)x[u][7] << 16);
+            } else {
+#pragma unroll
+              for (int kk = 0; kk < 8; ++kk)
+                if (8 * blk + kk >= ks0 && 8 * blk + kk < ks1) dst[kk] = x[u][kk];
+            }
+          }
+        }
+      }
+      __builtin_amdgcn_s_waitcnt(0x0F70);   // this wavefront's stores have reached the L2
+      __syncthreads();                      // ... and everybody's: the tiles may be loaded
+    }
+  }
 
   // tile t -> LDS slot t & 3; each tile is 16 / NW direct-load instructions per wavefront, instruction wi
   // filling 1 KB of the slot.  The lane's source offset inside a tile does not depend on the tile:
@@ -569,8 +657,11 @@ constexpr int kLds = std::max((kKS + kVS) * PIPE_TILE, kNW * 32 * PIPE_HROW * 2)
 
 hipError_t attn_chunk_mfma_init() {
   // more than 64 KB of dynamic LDS has to be asked for, once per device
-  return hipFuncSetAttribute((const void*)k_attn_chunk_pipe<kNW, kKS, kVS>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                             kLds);
+  hipError_t e = hipFuncSetAttribute((const void*)k_attn_chunk_pipe<kNW, kKS, kVS, false>,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute((const void*)k_attn_chunk_pipe<kNW, kKS, kVS, true>,
+                             hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
 }
 
 // Key ranges of a chunk-prefill launch over n_kv keys: (count, keys per range).
@@ -603,8 +694,33 @@ bool attn_chunk_rotates_on_load(const sv_cache* c, int stream, int n_q) {
   return n_splits <= 2;
 }
 
+// Whether the attention launch should store the chunk's K/V itself (see the kernel).  Every workgroup that reads new
+// keys stores them first, the last row tile's all of them, at the pace of ONE CU's memory pipeline (measured: 0.8 us
+// for 64 keys, 3.2 for 256, 6.5 for 384, 9.8 for 512), where a launch of its own spreads that over the device; doing
+// without that launch takes about 3 us off the layer, of which the rotation of the queries on load gives 1.5 back.
+// So it pays when the store hides behind the other workgroups' attention work, i.e. when the key ranges that hold
+// new keys are that much shorter than a full range (at 4096 + 2 x 512 retained tokens and 272 new ones, 8 ranges of
+// 10 tiles hold the retained keys and the ninth, 5 tiles, exactly the chunk: 36.5 -> 35.4 us per layer), or sticks
+// out by no more than a microsecond.
+bool attn_chunk_stores_tokens(const sv_cache* c, int stream, int n_q) {
+  if (!c->use_mfma || n_q > 512 || c->opt[SV_OPT_CHUNK_STORE] == 1) return false;
+  if (c->opt[SV_OPT_CHUNK_STORE] == 2) return true;
+  const int n_kv = (int)c->st[stream].len, slot0 = n_kv - n_q;
+  int n_splits, kps;
+  chunk_ranges(c, n_q, n_kv, n_splits, kps);
+  if (n_splits < 2) return false;
+  const float us_tile = 1.9f;   // a 64-key tile of one workgroup in the steady loop
+  for (int sp = slot0 / kps; sp < n_splits; ++sp) {
+    const int k0 = sp * kps, k1 = std::min(n_kv, k0 + kps), n_new = k1 - std::max(k0, slot0);
+    const float store_us = 0.2f + 0.0125f * (float)n_new + 0.013f * (float)std::max(0, n_new - 256);
+    if ((float)((k1 - k0 + TK - 1) / TK) * us_tile + store_us > (float)(kps / TK) * us_tile + 1.0f) return false;
+  }
+  return true;
+}
+
 hipError_t launch_attn_chunk_mfma(const sv_cache* c, int stream, int layer, const void* q, int n_q, void* o,
-                                  int causal, bool rotate_q, hipStream_t s) {
+                                  int causal, bool rotate_q, hipStream_t s, const void* k_new, const void* v_new) {
+  if ((k_new != nullptr) != (v_new != nullptr) || (k_new != nullptr && !rotate_q)) return hipErrorInvalidValue;
   constexpr int ROWS_WG = kNW * 32;
   const StreamState& st = c->st[stream];
   const int n_kv = (int)st.len, G = c->group, Hkv = c->cfg.n_kv_heads;
@@ -614,13 +730,15 @@ hipError_t launch_attn_chunk_mfma(const sv_cache* c, int stream, int layer, cons
   const int units = row_tiles * Hkv * n_splits;
   if (n_splits > 127 || G > 15 || Hkv > 255 || row_tiles > 4095 || c->head_stride / 2 > 0xffffffffull)
     return hipErrorInvalidValue;   // what chunk_shape and the 32-bit head stride can carry
-  hipLaunchKernelGGL((k_attn_chunk_pipe<kNW, kKS, kVS>), dim3((units + 7) / 8 * 8), dim3(kNW * 64), kLds, s,
-                     (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 0),
-                     (const __hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 1), n_q, n_kv, keys_per_split,
+  auto kernel = k_new != nullptr ? k_attn_chunk_pipe<kNW, kKS, kVS, true> : k_attn_chunk_pipe<kNW, kKS, kVS, false>;
+  hipLaunchKernelGGL(kernel, dim3((units + 7) / 8 * 8), dim3(kNW * 64), kLds, s,
+                     (__hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 0),
+                     (__hip_bfloat16*)c->kv_ptr(stream, st.cur, layer, 1), n_q, n_kv, keys_per_split,
                      (uint32_t)(c->head_stride / 2), chunk_shape(causal, n_splits, G, Hkv, row_tiles),
                      c->cfg.n_q_heads, (const __hip_bfloat16*)q,
                      rotate_q ? c->cs_tab + (size_t)stream * c->cfg.max_q_tokens * (D / 2) : nullptr,
-                     (__hip_bfloat16*)o, c->part_o, c->part_ml);
+                     (__hip_bfloat16*)o, c->part_o, c->part_ml, (const __hip_bfloat16*)k_new,
+                     (const __hip_bfloat16*)v_new);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || n_splits == 1) return e;
   const int rows_total = n_q * c->cfg.n_q_heads;

@@ -175,8 +175,15 @@ hipError_t launch_store_tokens_vt(const sv_cache* c, int stream, int layer, int6
                                   const void* v, hipStream_t s);
 // rotate_q: q is un-rotated; the kernel rotates it while loading, with c->cs_tab (the queries must be the run the
 // table was written for).
+// k_new / v_new not NULL (then rotate_q must be set): the n_q tokens are counted in the stream's length and
+// registered, but their K/V ([n_q][n_kv_heads][head_dim], K un-rotated) are not in the cache yet: the launch stores
+// them (what launch_store_tokens_vt would have) before it reads them.
 hipError_t launch_attn_chunk_mfma(const sv_cache* c, int stream, int layer, const void* q, int n_q,
-                                  void* o, int causal, bool rotate_q, hipStream_t s);
+                                  void* o, int causal, bool rotate_q, hipStream_t s, const void* k_new = nullptr,
+                                  const void* v_new = nullptr);
+// Whether that pays for a chunk of n_q tokens already counted in the stream's length (it does when the workgroups
+// that would store have less attention work than the others).
+bool attn_chunk_stores_tokens(const sv_cache* c, int stream, int n_q);
 // Whether a chunk of n_q queries (already counted in the stream's length) is better rotated by the attention kernel
 // while loading than by a pass over Q in memory.
 bool attn_chunk_rotates_on_load(const sv_cache* c, int stream, int n_q);

@@ -161,9 +161,9 @@ def test_options_and_flags():
     """sv_cache_set_option keeps per-handle launch overrides (host state only); unknown options, negative values and
     unknown flag bits are refused; the generic-kernel flag is accepted."""
     lib, h = _create()
-    for opt in (B.SV_OPT_CHUNK_SPLITS, B.SV_OPT_DECODE_TILES_PER_WAVE, B.SV_OPT_DECODE_SPLITS):
+    for opt in (B.SV_OPT_CHUNK_SPLITS, B.SV_OPT_DECODE_TILES_PER_WAVE, B.SV_OPT_DECODE_SPLITS, B.SV_OPT_CHUNK_STORE):
         assert lib.sv_cache_set_option(h, opt, 3) == OK and lib.sv_cache_set_option(h, opt, 0) == OK
-    assert lib.sv_cache_set_option(h, 3, 1) == INVALID and lib.sv_cache_set_option(h, -1, 1) == INVALID
+    assert lib.sv_cache_set_option(h, 4, 1) == INVALID and lib.sv_cache_set_option(h, -1, 1) == INVALID
     assert lib.sv_cache_set_option(h, B.SV_OPT_CHUNK_SPLITS, -2) == INVALID
     assert lib.sv_cache_set_option(None, 0, 1) == INVALID
     cfg = B.SvConfig(1, 28, 4, 128, B.SV_DTYPE_BF16, B.SV_ROPE_3D, 1.0e6, (C.c_int32 * 3)(16, 24, 24), 1, 64, 16,
