@@ -28,9 +28,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on the default workload, scaled by
 # what a plain 1 GiB copy reads on the same counters (fetch x2.00, write x1.00); profiles/hbm_traffic_*.txt.
 MEASURED_TRAFFIC = {
-    # attn_chunk = k_store_tokens_vt + k_attn_chunk_pipe + k_chunk_combine; decode_sweep = k_decode_mfma (key ranges merged
-    # in the same launch); evict = k_evict_scan + k_compact (reads + writes, scaled counters)
-    "qwen7b_256v_28L": {"attn_chunk": (2.79e6 + 2.34e6) + (25.4e6 + 16.5e6) + (17.1e6 + 1.8e6),
+    # attn_chunk = k_attn_chunk_pipe (which stores the chunk's K/V itself at this workload) + k_chunk_combine; decode_sweep =
+    # k_decode_mfma (key ranges merged in the same launch); evict = k_evict_scan + k_compact (reads + writes, scaled counters)
+    "qwen7b_256v_28L": {"attn_chunk": (29.0e6 + 17.9e6) + (17.1e6 + 1.8e6),
                         "decode_sweep": 11.49e6 + 1.13e6,
                         "evict": (268.2e6 + 262.3e6) + (0.4e6 + 2.6e6)},
 }
@@ -736,8 +736,9 @@ def instrumented_pass(cache, run, pool, w, L, c0, ov, ot_all, n_chunks: int, tra
                 "avg_launch_us": round(tot[key] / max(n_launch, 1), 2), "launches": n_launch,
                 "total_us_per_chunk": round(tot[key] / n_chunks, 1)}
 
-    roofs = [roof("k_store_tokens_vt + k_attn_chunk_pipe + k_chunk_combine (chunk prefill of one layer: K/V store into the "
-                  "cache, Q rotation, attention, merge of the key ranges)", "attn_chunk", "mfma", MFMA_BF16_PEAK_TFLOPS,
+    roofs = [roof("k_attn_chunk_pipe + k_chunk_combine, with k_store_tokens_vt in front where the attention launch does not "
+                  "store the chunk itself (chunk prefill of one layer: K/V store into the cache, Q rotation, attention, "
+                  "merge of the key ranges)", "attn_chunk", "mfma", MFMA_BF16_PEAK_TFLOPS,
                   "TFLOP/s", 1e12, L),
              roof("k_decode_mfma (fused decode step of one layer: append, RoPE, attention, merge of the key ranges)", "decode_sweep", "hbm",
                   HBM_PEAK_GBS, "GB/s", 1e9, L * nt),
