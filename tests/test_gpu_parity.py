@@ -150,18 +150,19 @@ def test_native_stream_step_matches_oracle(layers_batched):
         assert np.array_equal(ids, np.asarray(ro["gids_end"])) and np.array_equal(pos, ro["pos_end"])
 
 
-@pytest.mark.parametrize("preamble,grid,n_text,splits,budgets,store", [
-    (48, (1, 16, 16), 4, 0, (32, 600, 40), 2),     # whole blocks and tiles
-    (51, (1, 7, 5), 3, 0, (9, 100, 11), 2),        # 35-token chunks, the first new key in the middle of a V^T block
-    (13, (1, 1, 1), 1, 0, (2, 5, 3), 2),           # one-token chunks
-    (77, (1, 17, 16), 5, 3, (50, 1000, 21), 2),    # 272 tokens, three forced key ranges: the new keys straddle two
-    (77, (1, 17, 16), 5, 1, (50, 1000, 21), 2),    # ... and no split at all
-    (100, (2, 16, 16), 2, 0, (64, 1100, 30), 2),   # 512 tokens: the longest chunk the attention launch can store
-    (100, (1, 19, 27), 2, 0, (64, 1100, 30), 2),   # 513: stored by the launch of their own whatever the option says
-    (77, (1, 17, 16), 5, 0, (50, 1000, 21), 1),    # the store launch forced
-    (77, (1, 17, 16), 5, 0, (50, 1000, 21), 0),    # the library's own choice, which changes as the cache grows
+@pytest.mark.parametrize("preamble,grid,n_text,splits,budgets,store,sid", [
+    (48, (1, 16, 16), 4, 0, (32, 600, 40), 2, 0),     # whole blocks and tiles
+    (51, (1, 7, 5), 3, 0, (9, 100, 11), 2, 0),        # 35-token chunks, the first new key in the middle of a V^T block
+    (13, (1, 1, 1), 1, 0, (2, 5, 3), 2, 0),           # one-token chunks
+    (77, (1, 17, 16), 5, 3, (50, 1000, 21), 2, 0),    # 272 tokens, three forced key ranges: the new keys straddle two
+    (77, (1, 17, 16), 5, 1, (50, 1000, 21), 2, 0),    # ... and no split at all
+    (100, (2, 16, 16), 2, 0, (64, 1100, 30), 2, 0),   # 512 tokens: the longest chunk the attention launch can store
+    (100, (1, 19, 27), 2, 0, (64, 1100, 30), 2, 0),   # 513: stored by the launch of their own whatever the option says
+    (77, (1, 17, 16), 5, 0, (50, 1000, 21), 1, 0),    # the store launch forced
+    (77, (1, 17, 16), 5, 0, (50, 1000, 21), 0, 0),    # the library's own choice, which changes as the cache grows
+    (51, (1, 7, 5), 3, 0, (9, 100, 11), 2, 1),     # the second stream of a cache (its own cos/sin table and K/V planes)
 ])
-def test_stream_step_chunk_stored_by_attention_launch(preamble, grid, n_text, splits, budgets, store):
+def test_stream_step_chunk_stored_by_attention_launch(preamble, grid, n_text, splits, budgets, store, sid):
     """sv_stream_step on a blocked-V^T cache: a short chunk's K/V can reach the cache inside the attention launch
     (SV_OPT_CHUNK_STORE: forced here, chosen by the balance of the key ranges otherwise).  After every second the
     stored V rows are the appended ones bit for bit, the stored K rows the rotated ones to a bf16 rounding per
@@ -172,14 +173,14 @@ def test_stream_step_chunk_stored_by_attention_launch(preamble, grid, n_text, sp
     w = si.Workload("t", 2, 28, 4, 128, "bf16", 1, 1.0e6, (16, 24, 24), n_sink, vw, tw, preamble, nv, n_text, grid, 6,
                     4242 + preamble + nv)
     layers = [0, 1]
-    cache = gu.make_cache(w, n_layers=2, capacity=w.capacity() + 64)
+    cache = gu.make_cache(w, n_layers=2, capacity=w.capacity() + 64, n_streams=sid + 1)
     if splits:
         cache.set_option(sv.SV_OPT_CHUNK_SPLITS, splits)
     cache.set_option(sv.SV_OPT_CHUNK_STORE, store)
     o = sv_step.new_stream(w, layers)
     sv_step.append_preamble(o, w, layers)
     gids = np.arange(w.preamble_text)
-    run = gu.StreamRunner(cache, w.n_sink, w.vision_window, w.text_window)
+    run = gu.StreamRunner(cache, w.n_sink, w.vision_window, w.text_window, stream_id=sid)
     run.preamble([gu.dev(si.normal(w.seed, si.TENSOR_K, l, gids, 4, 128, True), w) for l in layers],
                  [gu.dev(si.normal(w.seed, si.TENSOR_V, l, gids, 4, 128, True), w) for l in layers])
     stack = lambda which, g, heads: torch.stack([gu.dev(si.normal(w.seed, which, l, g, heads, 128, True), w)
@@ -195,7 +196,7 @@ def test_stream_step_chunk_stored_by_attention_launch(preamble, grid, n_text, sp
         kt = stack(si.TENSOR_K, gt, 4).transpose(0, 1).contiguous()
         vt = stack(si.TENSOR_V, gt, 4).transpose(0, 1).contiguous()
         ov, ot = torch.empty_like(qv), torch.empty_like(qt)
-        n_ret = cache.stream_step(0, w.n_sink, w.vision_window, w.text_window, q_vision=qv, k_vision=kv, v_vision=vv,
+        n_ret = cache.stream_step(sid, w.n_sink, w.vision_window, w.text_window, q_vision=qv, k_vision=kv, v_vision=vv,
                                   o_vision=ov, grid_thw=ch.vision.grid_thw, q_text=qt, k_text=kt, v_text=vt, o_text=ot)
         assert n_ret == ro["n_retained"]
         n = len(o)
@@ -205,10 +206,10 @@ def test_stream_step_chunk_stored_by_attention_launch(preamble, grid, n_text, sp
             for t in range(ch.n_text):
                 assert gu.max_err(gu.host(ot[t, j]), ro["decode"][t][j][0]) <= gu.TOL["bf16"], (c, j, t)
             K, V = np.stack(o.k[j]), np.stack(o.v[j])
-            assert np.array_equal(cache.read_kv(0, j, 1, 0, n).astype(np.float64), V), (c, j)
-            e = gu.max_err(cache.read_kv(0, j, 0, 0, n), orc.rope(K, pos, w.rope_mode, w.rope_theta, w.mrope_sections))
+            assert np.array_equal(cache.read_kv(sid, j, 1, 0, n).astype(np.float64), V), (c, j)
+            e = gu.max_err(cache.read_kv(sid, j, 0, 0, n), orc.rope(K, pos, w.rope_mode, w.rope_theta, w.mrope_sections))
             assert e <= 4e-2 * (1 + c), (c, j, e)
-        ids, p2 = cache.retained(0)
+        ids, p2 = cache.retained(sid)
         assert np.array_equal(ids, np.asarray(ro["gids_end"])) and np.array_equal(p2, ro["pos_end"])
 
 
